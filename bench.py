@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Headline benchmark: tokens/s of the layer-streamed forward at a fixed HBM
+weight budget, on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W
+
+Workload = benchmark configs[1]: the LLaMA-7B-shaped stack (32 layers,
+d 4096, 32 heads x 128, SwiGLU 11008, causal, batch 1 x seq 2048), bf16 weights
+in pinned host memory, HBM weight budget of 4 layer slots, window (k, p) =
+(2, 2).  A step is one sp_forward over the whole stack: every layer is copied
+host-to-device once per step and computed once.  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+LINK_NOMINAL_GBPS = 64.0      # PCIe Gen5 x16, one direction
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def copy_ceiling_gbps(torch, nbytes=1 << 30, reps=3):
+    """Plain pinned hipMemcpyAsync host->device rate, measured in this run."""
+    src = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    src.fill_(1)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    st = torch.cuda.Stream()
+    best = 0.0
+    with torch.cuda.stream(st):
+        dst.copy_(src, non_blocking=True)
+        st.synchronize()
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            dst.copy_(src, non_blocking=True)
+            e1.record(st)
+            st.synchronize()
+            best = max(best, nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del src, dst
+    return best
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama7b")
+    ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--p", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=None, help="run a prefix of the stack (debug)")
+    ap.add_argument("--no-wrap", action="store_true", help="do not prefetch the next call's first layers")
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=2, help="oracle sample: layers at full token count")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build is single-GPU (one process, one device, no collectives); "
+            "run it with --gpus 1.")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2410_08791_amd import binding as sp
+    from paper_2410_08791_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    w = synth.WORKLOADS[args.workload]
+    if args.layers:
+        w = w.with_(n_layers=args.layers)
+    k = args.k or w.k
+    p = args.p or w.p
+    desc = sp.make_desc(w)
+    blob_bytes = sp.sp_layer_blob_bytes(C.byref(desc))
+    budget_layers = w.budget_layers or (k + p)
+    log(f"[bench] {torch.cuda.get_device_name(0)}; host cores {os.cpu_count()}; workload {w.name}: "
+        f"L={w.n_layers} d={w.d_model} T={w.tokens} blob={blob_bytes / 1e6:.1f} MB/layer")
+
+    t0 = time.time()
+    pool = synth.make_pool(16)
+    blobs, views = sp.pinned_blobs(w, desc, pool=pool)
+    pool.shutdown()
+    log(f"[bench] weights generated into pinned memory in {time.time() - t0:.1f} s")
+    x = synth.make_input(w)
+    xd = torch.from_numpy(x).to("cuda:0")
+    yd = torch.empty_like(xd)
+    B, S, T = w.batch, w.seq, w.tokens
+
+    ceiling = copy_ceiling_gbps(torch)
+    log(f"[bench] plain pinned H2D copy ceiling: {ceiling:.1f} GB/s")
+
+    def run(kk, pp, flags, steps, warmup):
+        eng = sp.Engine(desc, blobs, kk, pp, budget_layers=budget_layers, flags=flags)
+        for _ in range(warmup):
+            eng.forward(xd, yd, B, S)
+        eng.sync()
+        eng.stats()                                  # clears the kernel-timing window
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        tw = time.perf_counter()
+        e0.record(eng.compute)
+        for _ in range(steps):
+            eng.forward(xd, yd, B, S)
+        e1.record(eng.compute)
+        eng.sync()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - tw
+        ms = e0.elapsed_time(e1)
+        st = eng.stats()
+        y = yd.cpu().numpy().copy()
+        eng.destroy()
+        return dict(ms_per_step=ms / steps, wall_ms_per_step=wall * 1e3 / steps, stats=st, y=y,
+                    budget=eng.budget_bytes)
+
+    flags = sp.SP_FLAG_TIMING | (0 if args.no_wrap else sp.SP_FLAG_WRAP_PREFETCH)
+    main_run = run(k, p, flags, args.steps, args.warmup)
+    st = main_run["stats"]
+    ms = max(main_run["ms_per_step"], main_run["wall_ms_per_step"])   # host wall covers all streams
+    tokens_s = T / (ms * 1e-3)
+    h2d_gbps_wall = st.last_h2d_bytes / (ms * 1e-3) / 1e9
+    h2d_gbps_busy = st.last_h2d_bytes / (st.copy_busy_ms * 1e-3) / 1e9 if st.copy_busy_ms > 0 else None
+    log(f"[bench] k={k} p={p} slots={st.plan.n_slots}: {ms:.2f} ms/step, {tokens_s:.0f} tokens/s, "
+        f"H2D {h2d_gbps_wall:.1f} GB/s over wall")
+
+    # dominant kernel: the gate/up GEMM with the SwiGLU epilogue
+    gm, gn, gk = st.big_gemm_m, st.big_gemm_n, st.big_gemm_k
+    gemm_ms = st.big_gemm_ms_sum / max(st.big_gemm_launches, 1)
+    gemm_flops = 2.0 * gm * gn * gk
+    achieved_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    roofline = {"bound": "mfma", "kernel": "gemm_kernel<EPI_SWIGLU_BF16> (gate/up projection)",
+                "achieved": round(achieved_tf, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved_tf / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "flops_per_launch": gemm_flops, "avg_launch_ms": round(gemm_ms, 4),
+                "launches_timed": int(st.big_gemm_launches), "shape_mnk": [gm, gn, gk]}
+
+    extra = {
+        "peak_hbm_bytes": int(st.plan.arena_bytes_used), "budget_bytes": int(main_run["budget"]),
+        "h2d_gbps_over_wall": round(h2d_gbps_wall, 2),
+        "h2d_gbps_while_copying": round(h2d_gbps_busy, 2) if h2d_gbps_busy else None,
+        "h2d_ceiling_gbps": round(ceiling, 2),
+        "h2d_frac_of_ceiling": round(h2d_gbps_wall / ceiling, 4) if ceiling else None,
+        "h2d_frac_of_nominal_64": round(h2d_gbps_wall / LINK_NOMINAL_GBPS, 4),
+        "copy_hidden_frac": round(st.copy_hidden_ms / st.copy_busy_ms, 4) if st.copy_busy_ms > 0 else None,
+        "copy_busy_ms": round(st.copy_busy_ms, 3), "compute_busy_ms": round(st.compute_busy_ms, 3),
+        "last_step_wall_ms": round(st.wall_ms, 3),
+        "copy_stream_idle_frac": round(max(0.0, 1 - st.copy_busy_ms / st.wall_ms), 4) if st.wall_ms > 0 else None,
+        "event_ms_per_step": round(main_run["ms_per_step"], 3),
+        "host_wall_ms_per_step": round(main_run["wall_ms_per_step"], 3),
+    }
+
+    # window sweep at the same budget (+ resident and naive comparators), bits must not change
+    sweep = []
+    if not args.no_sweep:
+        base = main_run["y"]
+        for kk in (1, 2, 4):
+            for pp in (1, 2):
+                r = run(kk, pp, flags & ~sp.SP_FLAG_TIMING, 3, 1)
+                m = max(r["ms_per_step"], r["wall_ms_per_step"])
+                sweep.append({"k": kk, "p": pp, "slots": int(r["stats"].plan.n_slots),
+                              "tokens_per_s": round(T / (m * 1e-3), 1),
+                              "bit_identical": bool(np.array_equal(r["y"], base))})
+        r = run(1, 1, sp.SP_FLAG_NO_OVERLAP, 3, 1)
+        m = max(r["ms_per_step"], r["wall_ms_per_step"])
+        sweep.append({"mode": "naive(2 slots, no overlap)", "tokens_per_s": round(T / (m * 1e-3), 1),
+                      "bit_identical": bool(np.array_equal(r["y"], base))})
+        extra["sweep"] = sweep
+        log("[bench] sweep: " + json.dumps(sweep))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+        from oracle import stack_oracle as O
+        n = min(args.cpu_layers, w.n_layers)
+        shape = O.StackShape(w.arch, w.n_layers, w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                             w.d_ffn, w.causal, w.norm_eps)
+        t0 = time.perf_counter()
+        ref = O.stack_forward(x, views, B, S, shape, dtype=np.float32, n_layers=n)
+        dt = time.perf_counter() - t0
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        cpu = {"value": round(T / (dt * w.n_layers / n), 2), "unit": "tokens/s", "cores": int(cores),
+               "kind": "oracle",
+               "sample": f"fp32 numpy oracle on {n} of {w.n_layers} layers at the full {T} tokens "
+                         f"({dt:.1f} s), scaled by {w.n_layers}/{n}"}
+        # parity of the same prefix on the GPU, at the bench's launch configuration
+        sub = sp.make_desc(w, n_layers=n)
+        eng = sp.Engine(sub, blobs[:n], 1, 1)
+        eng.forward(xd, yd, B, S)
+        eng.sync()
+        got = yd.cpu().numpy().reshape(T, -1).astype(np.float64)
+        eng.destroy()
+        extra["parity_prefix_layers"] = n
+        extra["parity_max_rel_err"] = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+        log(f"[bench] oracle {n} layers: {dt:.1f} s on {cores} threads; GPU vs oracle max rel err "
+            f"{extra['parity_max_rel_err']:.3e}")
+
+    out = {
+        "metric": "tokens/sec at fixed HBM weight budget", "value": round(tokens_s, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n_layers} layers d={w.d_model} heads={w.n_q_heads}/{w.n_kv_heads}"
+                               f"x{w.head_dim} ffn={w.d_ffn} causal={w.causal} batch {B} x seq {S}, forward",
+                   "k": k, "p": p, "n_slots": int(st.plan.n_slots), "budget_layers": budget_layers,
+                   "wrap_prefetch": not args.no_wrap, "layer_blob_bytes": int(blob_bytes), "seed": w.seed},
+        "roofline": roofline, "cpu_baseline": cpu, **extra,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,211 @@
+/*
+ * superpipe.h -- C ABI of the MI355X layer-streaming executor.
+ *
+ * The library runs a stack of identical transformer layers whose bf16 weights
+ * live in pinned host memory.  Only a window of layers is resident in HBM; the
+ * next layers are copied host-to-device on a side stream while the resident
+ * ones compute, and a layer's slot is overwritten once it has executed.  This
+ * is the Superpipeline schedule (paper Sec. 1, Fig. 1; Sec. 3.2.2; Sec. 3.3):
+ * partitions = repeated layers (Sec. 3.2.1), k partitions on the device, k'
+ * swapped per group, forward and backward (Sec. 3.3), with results identical
+ * to the fully resident run (Sec. 4.2).  Copying weights back to the host is
+ * replaced by overwriting the slot, the design the paper's Sec. 5 proposes.
+ *
+ * Conventions
+ *  - Every call returns SP_OK (0) or a negative sp_status; nothing aborts or
+ *    throws across the boundary.  sp_last_error() gives a text for the most
+ *    recent failure on a handle (or of sp_create when passed NULL).
+ *  - "host" pointers are CPU addresses, "dev" pointers are HBM addresses on
+ *    the current HIP device.  The library allocates NO device memory: slots
+ *    and workspace are carved from the caller's arena, so peak HBM use is
+ *    arena_bytes_used <= gpu_budget_bytes by construction.
+ *  - Calls only enqueue work.  Outputs are valid after the caller
+ *    synchronises compute_stream (gradient blobs: d2h_stream).
+ *  - One handle = one stack; calls on a handle must not overlap.
+ */
+#ifndef SUPERPIPE_H
+#define SUPERPIPE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sp_engine* sp_handle;
+
+typedef enum {
+    SP_OK = 0,
+    SP_ERR_INVALID_ARG = -1, /* NULL pointer, non-positive size, bad enum, bad struct_size */
+    SP_ERR_BUDGET = -2,      /* arena cannot hold the workspace plus one layer slot          */
+    SP_ERR_NOT_PINNED = -3,  /* a host blob is not page-locked host memory                   */
+    SP_ERR_HIP = -4,         /* a HIP runtime call failed; see sp_last_error                 */
+    SP_ERR_STATE = -5,       /* handle destroyed / created forward-only but asked to train   */
+    SP_ERR_SHAPE = -6        /* B or S outside what the workspace was sized for              */
+} sp_status;
+
+/* Layer kinds.  Decoder: pre-RMSNorm, fused QKV, SwiGLU FFN, no biases.
+ * Encoder: pre-LayerNorm (gain+bias), biased projections, exact-erf GELU MLP. */
+enum { SP_DECODER_SWIGLU_RMS = 0, SP_ENCODER_GELU_LN = 1 };
+
+/* Tensors of one layer, in blob order.  Matrices are row-major [out, in]
+ * (y = x W^T), bf16.  WQKV stacks query rows, key rows, value rows; WGU stacks
+ * gate rows then up rows.  Every tensor starts on a 256-byte boundary. */
+enum {
+    /* decoder */
+    SP_T_G1 = 0, SP_T_WQKV = 1, SP_T_WO = 2, SP_T_G2 = 3, SP_T_WGU = 4, SP_T_WD = 5,
+    SP_DECODER_TENSORS = 6,
+    /* encoder */
+    SP_T_LN1_G = 0, SP_T_LN1_B = 1, SP_T_E_WQKV = 2, SP_T_BQKV = 3, SP_T_E_WO = 4, SP_T_BO = 5,
+    SP_T_LN2_G = 6, SP_T_LN2_B = 7, SP_T_W1 = 8, SP_T_B1 = 9, SP_T_W2 = 10, SP_T_B2 = 11,
+    SP_ENCODER_TENSORS = 12
+};
+
+typedef struct {
+    uint32_t struct_size;   /* = sizeof(sp_stack_desc) */
+    int32_t n_layers;
+    int32_t d_model;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;     /* divides n_q_heads; query head j uses kv head j / (n_q/n_kv) */
+    int32_t head_dim;       /* multiple of 16, <= 128 */
+    int32_t d_ffn;
+    int32_t arch;           /* SP_DECODER_SWIGLU_RMS | SP_ENCODER_GELU_LN */
+    int32_t causal;         /* 1: query i attends keys j <= i */
+    float norm_eps;
+    int32_t max_batch;      /* workspace is sized for max_batch * max_seq tokens */
+    int32_t max_seq;
+} sp_stack_desc;
+
+enum {
+    SP_FLAG_TRAINING = 1u << 0,    /* size the workspace for sp_forward_backward           */
+    SP_FLAG_TIMING = 1u << 1,      /* record per-layer copy/compute events (sp_get_stats)  */
+    SP_FLAG_POISON = 1u << 2,      /* debug: fill a slot with NaN patterns before reuse    */
+    SP_FLAG_NO_OVERLAP = 1u << 3,  /* "Naive" comparator (Sec. 4.2): copies wait for all
+                                      enqueued compute, compute waits for the copies       */
+    SP_FLAG_WRAP_PREFETCH = 1u << 4 /* forward-only: when the tail of a pass frees slots,
+                                      start loading layers 0.. for the next call (the
+                                      consecutive-forward stall of Sec. 5)                 */
+};
+
+typedef struct {
+    uint32_t struct_size;       /* = sizeof(sp_config) */
+    int32_t resident_window_k;  /* layers kept ready to compute            (>= 1) */
+    int32_t prefetch_depth_p;   /* layers in flight / swapped per group    (>= 1) */
+    uint64_t gpu_budget_bytes;  /* size of device_arena; the hard HBM cap        */
+    void* device_arena;         /* dev, caller-owned, 4 KiB aligned              */
+    void* compute_stream;       /* hipStream_t (NULL = default stream)           */
+    void* h2d_stream;           /* hipStream_t, must differ from compute_stream  */
+    void* d2h_stream;           /* hipStream_t, needed only with SP_FLAG_TRAINING */
+    uint32_t flags;
+} sp_config;
+
+/* Slot-count policy (one function decides it).  The requested number of HBM
+ * layer slots is k + p -- the paper's "k partitions on the GPU" with its k' = p
+ * of them being refilled (Fig. 1: k=4, k'=2 is (k,p) = (2,2)) -- clamped by the
+ * layer count and by what the arena holds after the workspace:
+ *   n_slots = min(k + p, L, (budget - workspace) / slot_bytes);  0 -> SP_ERR_BUDGET
+ *   p_eff   = min(p, max(n_slots - 1, 1)),  k_eff = max(n_slots - p_eff, 1).      */
+typedef struct {
+    int32_t n_slots, k_eff, p_eff;
+    int32_t fully_resident;     /* n_slots == n_layers */
+    uint64_t slot_bytes;        /* blob bytes rounded up to 4 KiB */
+    uint64_t workspace_bytes;
+    uint64_t arena_bytes_used;  /* workspace + n_slots * slot_bytes (+ gradient slots) */
+} sp_plan;
+
+#define SP_MAX_TRACE_LAYERS 256
+typedef struct {
+    uint32_t struct_size;
+    sp_plan plan;
+    uint64_t calls;             /* completed sp_forward / sp_forward_backward calls   */
+    uint64_t h2d_copies, h2d_bytes;   /* totals since create                            */
+    uint64_t d2h_copies, d2h_bytes;
+    uint64_t last_h2d_copies, last_h2d_bytes;  /* issued by the most recent call        */
+    /* SP_FLAG_TIMING only; describe the most recent call, valid after its streams
+     * are synchronised.  Times in ms relative to the call's first enqueued op.        */
+    int32_t n_timed;                    /* entries below (forward layers, then backward) */
+    float copy_begin_ms[SP_MAX_TRACE_LAYERS], copy_end_ms[SP_MAX_TRACE_LAYERS]; /* <0: no copy */
+    float comp_begin_ms[SP_MAX_TRACE_LAYERS], comp_end_ms[SP_MAX_TRACE_LAYERS];
+    float copy_busy_ms;         /* sum of copy durations                                */
+    float copy_hidden_ms;       /* part of it that lies under some layer's compute      */
+    float compute_busy_ms;      /* sum of layer compute durations                       */
+    float wall_ms;              /* first op begin -> last op end                        */
+    /* SP_FLAG_TIMING: the layer's largest GEMM (decoder: gate/up with the SwiGLU
+     * epilogue; encoder: the first MLP GEMM), bracketed by events on the compute
+     * stream at every launch since the previous sp_get_stats.                         */
+    uint32_t big_gemm_launches;
+    float big_gemm_ms_sum;
+    int32_t big_gemm_m, big_gemm_n, big_gemm_k;   /* its shape: C[m,n] over k (n counts gate and up) */
+} sp_stats;
+
+/* ---- layout queries (host only, no device needed) ------------------------ */
+
+/* Number of tensors per layer for desc->arch, or a negative sp_status. */
+int sp_num_tensors(const sp_stack_desc* desc);
+/* Byte offset of tensor `tensor_id` inside a layer blob; (size_t)-1 on bad args. */
+size_t sp_tensor_offset(const sp_stack_desc* desc, int tensor_id);
+/* Element count of tensor `tensor_id` (bf16 elements); 0 on bad args. */
+size_t sp_tensor_elems(const sp_stack_desc* desc, int tensor_id);
+/* Bytes of one layer's weight blob (bf16).  0 on bad args. */
+size_t sp_layer_blob_bytes(const sp_stack_desc* desc);
+/* Bytes of one layer's fp32 gradient blob: same tensor order, offsets doubled. */
+size_t sp_layer_grad_bytes(const sp_stack_desc* desc);
+/* Device workspace for max_batch*max_seq tokens (activations, saved layer inputs
+ * and gradient slots when training != 0). */
+size_t sp_workspace_bytes(const sp_stack_desc* desc, int training);
+/* The slot-count policy above as a pure function. */
+int sp_make_plan(const sp_stack_desc* desc, int k, int p, uint64_t budget_bytes, int training,
+                 sp_plan* out);
+
+/* One step of the host-side schedule, for inspection and host-only tests.
+ * sp_trace_schedule writes the ordered op list that `passes` consecutive calls
+ * would enqueue (dir +1 = forward pass over layers 0..L-1, the pattern
+ * forward,backward repeats when training != 0).  Returns the number of ops
+ * (may exceed cap; only cap are written) or a negative sp_status. */
+typedef struct {
+    int32_t kind;    /* 0 = COPY layer->slot (copy stream), 1 = COMPUTE layer (compute stream),
+                        2 = BACKWARD layer (compute stream) */
+    int32_t layer, slot;
+    int32_t wait_layer;  /* COPY: the layer whose compute must finish first (-1 none);
+                            COMPUTE/BACKWARD: 1 if it waits for a copy issued earlier, else 0 */
+    int32_t pass;
+} sp_sched_op;
+int sp_trace_schedule(int n_layers, int n_slots, int p_eff, int training, int wrap_prefetch,
+                      int passes, sp_sched_op* ops, int cap);
+
+/* ---- the four calls ------------------------------------------------------ */
+
+/* Create an executor.  layer_host_blobs[n_layers]: host, pinned, each
+ * sp_layer_blob_bytes long, caller-owned, must stay valid and UNMODIFIED until
+ * sp_destroy (the library never writes them: "no parameter modification",
+ * Sec. 1).  Entries may alias.  On failure *out is NULL. */
+int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* const* layer_host_blobs,
+              const sp_config* cfg);
+
+/* y = stack(x).  x_dev, y_dev: dev, fp32 [B, S, d_model], may be the same
+ * buffer.  1 <= B <= max_batch, 1 <= S <= max_seq. */
+int sp_forward(sp_handle h, const float* x_dev, float* y_dev, int B, int S);
+
+/* One training step's device work (Sec. 3.3): forward, loss =
+ * mean((y - target)^2), backward with each layer's weights re-streamed in
+ * reverse order, fp32 weight gradients written (overwrite, not accumulate) to
+ * grad_host_blobs[l] (host, pinned, sp_layer_grad_bytes each) over d2h_stream.
+ * loss_dev: dev, 1 fp32.  dx_dev: dev fp32 [B,S,d] or NULL.  y_dev may be NULL. */
+int sp_forward_backward(sp_handle h, const float* x_dev, const float* target_dev, float* y_dev,
+                        float* loss_dev, float* dx_dev, void* const* grad_host_blobs, int B, int S);
+
+/* Counters and (with SP_FLAG_TIMING) per-layer timings.  Synchronises the
+ * handle's streams when timing is on. */
+int sp_get_stats(sp_handle h, sp_stats* out);
+
+/* Waits for the handle's streams, destroys its events, frees host bookkeeping.
+ * Frees nothing the caller allocated. */
+int sp_destroy(sp_handle h);
+
+const char* sp_last_error(sp_handle h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SUPERPIPE_H */

@@ -1,0 +1,56 @@
+/*
+ * superpipe_kernels.h -- C ABI test hooks for the individual per-layer kernels.
+ *
+ * These exist so that each kernel can be compared with the CPU oracle's op on
+ * its own; the product path is superpipe.h.  All pointers are device (HBM)
+ * addresses on the current HIP device, 16-byte aligned; `stream` is a
+ * hipStream_t (NULL = default stream).  Calls enqueue and return a sp_status
+ * (SP_ERR_INVALID_ARG when the shape is one the kernel does not take,
+ * SP_ERR_HIP when the launch fails); nothing is allocated.  bf16 buffers hold
+ * raw 16-bit patterns.
+ *
+ * The operations are the per-layer steps of the streamed stack: the paper's
+ * method leaves them unchanged (Sec. 4.2), their definitions are those of a
+ * pre-norm transformer layer.
+ */
+#ifndef SUPERPIPE_KERNELS_H
+#define SUPERPIPE_KERNELS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* out bf16 [T,d] = h * rsqrt(mean(h^2)+eps) * gain          (bias == NULL)
+ *               = (h-mean) * rsqrt(var+eps) * gain + bias   (bias != NULL)
+ * h fp32 [T,d]; gain/bias bf16 [d]; d % 4 == 0, d <= 8192. */
+int spk_norm(void* stream, const float* h, const uint16_t* gain, const uint16_t* bias, uint16_t* out,
+             int T, int d, float eps);
+
+/* C[M,N] = sum_k A(m,k) W(n,k), bf16 inputs, fp32 accumulate.
+ * epilogue: 0 C bf16 = acc (+bias); 1 C fp32 = R + acc (+bias), C may alias R;
+ *           2 C bf16 = gelu(acc + bias); 3 W holds 2N rows [gate; up], C bf16 = silu(gate)*up;
+ *           4 C fp32 = acc (+bias).
+ * a_form / w_form: 0 = contraction index contiguous (A[m*lda+k], W[n*ldw+k]),
+ *                  1 = row index contiguous        (A[k*lda+m], W[k*ldw+n]).
+ * tile: 0 = library heuristic, 1..3 force a block tile.  K % 64 == 0, N % 8 == 0. */
+int spk_gemm(void* stream, int epilogue, const uint16_t* A, int lda, int a_form, const uint16_t* W, int ldw,
+             int w_form, void* C, int ldc, const float* R, int ldr, const uint16_t* bias, int M, int N, int K,
+             int tile);
+
+/* z bf16 [T,f] = silu(gu[:, :f]) * gu[:, f:]; gu bf16 [T,2f]; f % 8 == 0. */
+int spk_swiglu(void* stream, const uint16_t* gu, uint16_t* z, int T, int f);
+
+/* Attention over a fused activation qkv bf16 [B*S, (Hq+2Hkv)*hd] (query heads,
+ * then key heads, then value heads).  vt_scratch: bf16, spk_attention_scratch_elems
+ * elements.  o bf16 [B*S, Hq*hd].  lse fp32 [B,Hq,S] or NULL.  hd in {64,80,128}. */
+size_t spk_attention_scratch_elems(int B, int S, int Hkv, int hd);
+int spk_attention(void* stream, const uint16_t* qkv, uint16_t* vt_scratch, uint16_t* o, float* lse,
+                  int B, int S, int Hq, int Hkv, int hd, int causal);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

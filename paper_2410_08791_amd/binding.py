@@ -1,0 +1,239 @@
+"""ctypes binding of libsuperpipe.so -- argument marshalling only.
+
+Same names as include/superpipe.h and include/superpipe_kernels.h.  torch is
+used here for device memory, pinned host memory and streams, nothing else:
+every step of the path runs in the library's kernels.  There is no fallback:
+if the library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsuperpipe.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first with `python -m paper_2410_08791_amd.build` "
+        "(there is no CPU fallback for the HIP path)")
+lib = C.CDLL(LIB_PATH)
+
+SP_OK, SP_ERR_INVALID_ARG, SP_ERR_BUDGET, SP_ERR_NOT_PINNED, SP_ERR_HIP, SP_ERR_STATE, SP_ERR_SHAPE = 0, -1, -2, -3, -4, -5, -6
+SP_DECODER_SWIGLU_RMS, SP_ENCODER_GELU_LN = 0, 1
+SP_FLAG_TRAINING, SP_FLAG_TIMING, SP_FLAG_POISON, SP_FLAG_NO_OVERLAP, SP_FLAG_WRAP_PREFETCH = 1, 2, 4, 8, 16
+SP_MAX_TRACE_LAYERS = 256
+EPI_BF16, EPI_RESID_F32, EPI_GELU_BF16, EPI_SWIGLU_BF16, EPI_F32 = 0, 1, 2, 3, 4
+
+TENSOR_NAMES = {
+    SP_DECODER_SWIGLU_RMS: ["g1", "wqkv", "wo", "g2", "wgu", "wd"],
+    SP_ENCODER_GELU_LN: ["ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2"],
+}
+
+
+class sp_stack_desc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_layers", C.c_int32), ("d_model", C.c_int32),
+                ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("d_ffn", C.c_int32), ("arch", C.c_int32), ("causal", C.c_int32),
+                ("norm_eps", C.c_float), ("max_batch", C.c_int32), ("max_seq", C.c_int32)]
+
+
+class sp_config(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("resident_window_k", C.c_int32), ("prefetch_depth_p", C.c_int32),
+                ("gpu_budget_bytes", C.c_uint64), ("device_arena", C.c_void_p), ("compute_stream", C.c_void_p),
+                ("h2d_stream", C.c_void_p), ("d2h_stream", C.c_void_p), ("flags", C.c_uint32)]
+
+
+class sp_plan(C.Structure):
+    _fields_ = [("n_slots", C.c_int32), ("k_eff", C.c_int32), ("p_eff", C.c_int32), ("fully_resident", C.c_int32),
+                ("slot_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("arena_bytes_used", C.c_uint64)]
+
+
+_F = C.c_float * SP_MAX_TRACE_LAYERS
+
+
+class sp_stats(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("plan", sp_plan), ("calls", C.c_uint64),
+                ("h2d_copies", C.c_uint64), ("h2d_bytes", C.c_uint64), ("d2h_copies", C.c_uint64),
+                ("d2h_bytes", C.c_uint64), ("last_h2d_copies", C.c_uint64), ("last_h2d_bytes", C.c_uint64),
+                ("n_timed", C.c_int32), ("copy_begin_ms", _F), ("copy_end_ms", _F), ("comp_begin_ms", _F),
+                ("comp_end_ms", _F), ("copy_busy_ms", C.c_float), ("copy_hidden_ms", C.c_float),
+                ("compute_busy_ms", C.c_float), ("wall_ms", C.c_float),
+                ("big_gemm_launches", C.c_uint32), ("big_gemm_ms_sum", C.c_float),
+                ("big_gemm_m", C.c_int32), ("big_gemm_n", C.c_int32), ("big_gemm_k", C.c_int32)]
+
+
+class sp_sched_op(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("layer", C.c_int32), ("slot", C.c_int32), ("wait_layer", C.c_int32),
+                ("pass_", C.c_int32)]
+
+
+_P = C.POINTER
+_sig = {
+    "sp_num_tensors": (C.c_int, [_P(sp_stack_desc)]),
+    "sp_tensor_offset": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
+    "sp_tensor_elems": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
+    "sp_layer_blob_bytes": (C.c_size_t, [_P(sp_stack_desc)]),
+    "sp_layer_grad_bytes": (C.c_size_t, [_P(sp_stack_desc)]),
+    "sp_workspace_bytes": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
+    "sp_make_plan": (C.c_int, [_P(sp_stack_desc), C.c_int, C.c_int, C.c_uint64, C.c_int, _P(sp_plan)]),
+    "sp_trace_schedule": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P(sp_sched_op), C.c_int]),
+    "sp_create": (C.c_int, [_P(C.c_void_p), _P(sp_stack_desc), _P(C.c_void_p), _P(sp_config)]),
+    "sp_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
+    "sp_forward_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      _P(C.c_void_p), C.c_int, C.c_int]),
+    "sp_get_stats": (C.c_int, [C.c_void_p, _P(sp_stats)]),
+    "sp_destroy": (C.c_int, [C.c_void_p]),
+    "sp_last_error": (C.c_char_p, [C.c_void_p]),
+    "spk_norm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float]),
+    "spk_gemm": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                           C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]),
+    "spk_swiglu": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
+    "spk_attention_scratch_elems": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int]),
+    "spk_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                C.c_int, C.c_int, C.c_int, C.c_int]),
+}
+for _n, (_r, _a) in _sig.items():
+    _f = getattr(lib, _n)          # AttributeError here = header/library mismatch
+    _f.restype, _f.argtypes = _r, _a
+    globals()[_n] = _f
+EXPORTS = sorted(_sig)
+
+
+class SuperpipeError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"sp_status {code}: {msg}")
+        self.code = code
+
+
+def make_desc(w, max_batch=None, max_seq=None, n_layers=None):
+    """sp_stack_desc from a synth.Workload-like object."""
+    arch = SP_DECODER_SWIGLU_RMS if w.arch == "decoder" else SP_ENCODER_GELU_LN
+    return sp_stack_desc(C.sizeof(sp_stack_desc), w.n_layers if n_layers is None else n_layers, w.d_model,
+                         w.n_q_heads, w.n_kv_heads, w.head_dim, w.d_ffn, arch, int(w.causal), w.norm_eps,
+                         w.batch if max_batch is None else max_batch, w.seq if max_seq is None else max_seq)
+
+
+def blob_views(desc, blob_u8: np.ndarray):
+    """{tensor name: uint16 view} into one layer blob (a uint8 numpy array)."""
+    names = TENSOR_NAMES[desc.arch]
+    out = {}
+    for i, n in enumerate(names):
+        off = sp_tensor_offset(C.byref(desc), i)
+        cnt = sp_tensor_elems(C.byref(desc), i)
+        out[n] = blob_u8[off:off + 2 * cnt].view(np.uint16)
+    return out
+
+
+def grad_views(desc, gblob_u8: np.ndarray):
+    """{tensor name: float32 view} into one layer's fp32 gradient blob."""
+    names = TENSOR_NAMES[desc.arch]
+    out = {}
+    for i, n in enumerate(names):
+        off = 2 * sp_tensor_offset(C.byref(desc), i)
+        cnt = sp_tensor_elems(C.byref(desc), i)
+        out[n] = gblob_u8[off:off + 4 * cnt].view(np.float32)
+    return out
+
+
+def plan(desc, k, p, budget, training=False):
+    pl = sp_plan()
+    rc = sp_make_plan(C.byref(desc), k, p, budget, int(training), C.byref(pl))
+    return rc, pl
+
+
+def trace_schedule(n_layers, n_slots, p_eff, training=False, wrap=False, passes=1):
+    n = sp_trace_schedule(n_layers, n_slots, p_eff, int(training), int(wrap), passes, None, 0)
+    if n < 0:
+        raise SuperpipeError(n, "sp_trace_schedule")
+    ops = (sp_sched_op * n)()
+    sp_trace_schedule(n_layers, n_slots, p_eff, int(training), int(wrap), passes, ops, n)
+    return [(o.kind, o.layer, o.slot, o.wait_layer, o.pass_) for o in ops]
+
+
+def pinned_blobs(w, desc, n_layers=None, pool=None):
+    """Seeded weights straight into pinned host blobs.  Returns (torch tensors, per-layer views)."""
+    import torch
+    from . import synth
+    nbytes = sp_layer_blob_bytes(C.byref(desc))
+    L = desc.n_layers if n_layers is None else n_layers
+    blobs, views = [], []
+    for l in range(L):
+        t = torch.zeros(nbytes, dtype=torch.uint8, pin_memory=True)
+        v = blob_views(desc, t.numpy())
+        synth.fill_layer(v, w, l, pool=pool)
+        blobs.append(t)
+        views.append(v)
+    return blobs, views
+
+
+class Engine:
+    """Owns an sp_handle plus the torch-allocated arena and streams it runs on."""
+
+    def __init__(self, desc, blobs, k, p, budget_bytes=None, budget_layers=None, flags=0, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.desc = desc
+        self.blobs = blobs                      # keep the pinned tensors alive
+        training = bool(flags & SP_FLAG_TRAINING)
+        ws = sp_workspace_bytes(C.byref(desc), int(training))
+        slot = (sp_layer_blob_bytes(C.byref(desc)) + 4095) // 4096 * 4096
+        if budget_bytes is None:
+            nl = budget_layers if budget_layers else min(k + p, desc.n_layers)
+            budget_bytes = ws + nl * slot
+        self.budget_bytes = int(budget_bytes)
+        self.device = torch.device(device)
+        with torch.cuda.device(self.device):
+            self.arena = torch.empty(self.budget_bytes, dtype=torch.uint8, device=self.device)
+            self.compute = torch.cuda.Stream(device=self.device)
+            self.h2d = torch.cuda.Stream(device=self.device)
+            self.d2h = torch.cuda.Stream(device=self.device) if training else None
+        assert self.arena.data_ptr() % 4096 == 0
+        ptrs = (C.c_void_p * len(blobs))(*[b.data_ptr() for b in blobs])
+        cfg = sp_config(C.sizeof(sp_config), k, p, self.budget_bytes, self.arena.data_ptr(),
+                        self.compute.cuda_stream, self.h2d.cuda_stream,
+                        self.d2h.cuda_stream if training else None, flags)
+        self.handle = C.c_void_p()
+        rc = sp_create(C.byref(self.handle), C.byref(desc), ptrs, C.byref(cfg))
+        if rc != SP_OK:
+            raise SuperpipeError(rc, sp_last_error(None).decode())
+
+    def _check(self, rc):
+        if rc != SP_OK:
+            raise SuperpipeError(rc, sp_last_error(self.handle).decode())
+
+    def forward(self, x, y, B, S):
+        """x, y: fp32 cuda tensors [B,S,d]; enqueues on self.compute."""
+        self._check(sp_forward(self.handle, x.data_ptr(), y.data_ptr(), B, S))
+
+    def forward_backward(self, x, target, y, loss, dx, grad_blobs, B, S):
+        ptrs = (C.c_void_p * len(grad_blobs))(*[g.data_ptr() for g in grad_blobs])
+        self._check(sp_forward_backward(self.handle, x.data_ptr(), target.data_ptr(),
+                                        y.data_ptr() if y is not None else None, loss.data_ptr(),
+                                        dx.data_ptr() if dx is not None else None, ptrs, B, S))
+
+    def sync(self):
+        self.compute.synchronize()
+        self.h2d.synchronize()
+        if self.d2h is not None:
+            self.d2h.synchronize()
+
+    def stats(self):
+        st = sp_stats()
+        self._check(sp_get_stats(self.handle, C.byref(st)))
+        return st
+
+    def destroy(self):
+        if self.handle:
+            rc = sp_destroy(self.handle)
+            self.handle = C.c_void_p()
+            return rc
+        return SP_ERR_STATE
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

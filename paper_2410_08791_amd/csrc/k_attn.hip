@@ -1,0 +1,237 @@
+// Attention forward: o = softmax(q k^T / sqrt(hd) + mask) v per (batch, head),
+// causal or bidirectional, grouped-query heads, head_dim in {64, 80, 128}.
+//
+// One work-group (4 waves) handles 128 queries of one head; a wave owns 32 of
+// them.  Keys/values stream through LDS in tiles of 64.  Scores are computed
+// TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: in the accumulator
+// layout a lane then holds ONE query (its column) and 16 keys of each 32-key
+// tile, so the softmax row maximum and sum are in-lane reductions plus one
+// exchange between the two half-waves, and the probabilities -- rounded to
+// bf16 in place -- already sit in the B-operand layout of the second product
+// O^T = V^T P^T.  (The contraction order over keys inside a 16-key MFMA step is
+// a fixed permutation; V^T fragments are fetched with the same permutation.)
+// V is needed with keys contiguous, so a small pass transposes it once per
+// layer into [B][Hkv][hd_pad][S_pad], zero padded.
+#include "sp_kernels.h"
+
+namespace {
+
+constexpr int QB = 128;   // queries per work-group
+constexpr int KB = 64;    // keys per LDS tile
+
+template <int HD>
+struct AttnCfg {
+    static constexpr int NKS = HD / 16;             // MFMA k-steps over head_dim
+    static constexpr int NMT = (HD + 31) / 32;      // 32-row tiles of O^T
+    static constexpr int HDP = NMT * 32;
+    static constexpr int K_STRIDE = HD * 2 + 16;    // bytes per key row in LDS (padded)
+    static constexpr int V_STRIDE = KB * 2 + 8;     // bytes per V^T row in LDS (padded)
+    static constexpr int K_BYTES = KB * K_STRIDE;
+    static constexpr int V_BYTES = HDP * V_STRIDE;
+    static constexpr int CHUNKS_K = KB * (HD / 8);  // 16-byte chunks of a K tile
+    static constexpr int CHUNKS_V = HDP * (KB / 8);
+};
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
+                                                       const bf16_t* __restrict__ vt,
+                                                       bf16_t* __restrict__ o, float* __restrict__ lse,
+                                                       int S, int S_pad, int Hq, int Hkv, int ld_qkv,
+                                                       int causal, float scale_log2e) {
+    typedef AttnCfg<HD> C;
+    __shared__ __attribute__((aligned(16))) unsigned char sK[C::K_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char sV[C::V_BYTES];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    // heavy (late) query blocks first when causal
+    const int nqb = gridDim.x;
+    const int qb = causal ? nqb - 1 - blockIdx.x : blockIdx.x;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int kvh = h / (Hq / Hkv);
+    const int q0 = qb * QB;
+    const int wq0 = q0 + wave * 32;          // this wave's first query
+    const int qi = wq0 + l32;                // this lane's query
+    const size_t tok0 = (size_t)b * S;
+
+    // Q fragments: B operand, column = query, 8 contiguous head_dim elements.
+    bf16x8_t qf[C::NKS];
+    {
+        const int qr = min(qi, S - 1);
+        const bf16_t* qp = qkv + (tok0 + qr) * ld_qkv + h * HD + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < C::NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16);
+    }
+    const bf16_t* kbase = qkv + tok0 * ld_qkv + (size_t)Hq * HD + (size_t)kvh * HD;
+    const bf16_t* vbase = vt + ((size_t)b * Hkv + kvh) * C::HDP * S_pad;
+
+    f32x16_t oacc[C::NMT];
+#pragma unroll
+    for (int t = 0; t < C::NMT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[t][e] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int k_end = causal ? min(S, q0 + QB) : S;
+    const int ntiles = (k_end + KB - 1) / KB;
+    const int wq_last = wq0 + 31;
+
+    for (int kt = 0; kt < ntiles; ++kt) {
+        const int key0 = kt * KB;
+        __syncthreads();  // previous tile fully consumed
+        for (int c = threadIdx.x; c < C::CHUNKS_K; c += 256) {
+            const int r = c / (HD / 8), cc = c % (HD / 8);
+            const int kr = min(key0 + r, S - 1);
+            *reinterpret_cast<u32x4_t*>(sK + r * C::K_STRIDE + cc * 16) =
+                *reinterpret_cast<const u32x4_t*>(kbase + (size_t)kr * ld_qkv + cc * 8);
+        }
+        for (int c = threadIdx.x; c < C::CHUNKS_V; c += 256) {
+            const int r = c / (KB / 8), cc = c % (KB / 8);
+            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)r * S_pad + key0 + cc * 8);
+            u32x2_t* d = reinterpret_cast<u32x2_t*>(sV + r * C::V_STRIDE + cc * 16);
+            d[0] = u32x2_t{v[0], v[1]};
+            d[1] = u32x2_t{v[2], v[3]};
+        }
+        __syncthreads();
+        if (causal && key0 > wq_last) continue;  // wave-uniform: nothing visible to this wave
+
+        // ---- S^T = K Q^T for two 32-key tiles
+        f32x16_t sacc[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sacc[t][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < C::NKS; ++ks) {
+                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(
+                    sK + (t * 32 + l32) * C::K_STRIDE + (ks * 2 + half) * 16);
+                sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[t], 0, 0, 0);
+            }
+        }
+        // ---- scale, mask, online softmax (base 2)
+        const bool need_mask = (causal && key0 + KB - 1 > wq0) || (key0 + KB > S);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float s = sacc[t][e] * scale_log2e;
+                if (need_mask) {
+                    const int key = key0 + t * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+                    if (key >= S || (causal && key > qi)) s = -INFINITY;
+                }
+                sacc[t][e] = s;
+                mx = fmaxf(mx, s);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);   // finite: key 0 is visible to every query
+        const float alpha = exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+        bf16x8_t pf[2][2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float pv = exp2f(sacc[t][j * 8 + e] - m_new);
+                    psum += pv;
+                    pf[t][j][e] = (__bf16)pv;
+                }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int t = 0; t < C::NMT; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+        // ---- O^T += V^T P^T.  Step (t, j) contracts keys
+        //      t*32 + 16j + {half*4 + 0..3, 8 + half*4 + 0..3}.
+#pragma unroll
+        for (int mt = 0; mt < C::NMT; ++mt)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const unsigned char* vp = sV + (mt * 32 + l32) * C::V_STRIDE + (t * 32 + 16 * j + half * 4) * 2;
+                    const u32x2_t lo = *reinterpret_cast<const u32x2_t*>(vp);
+                    const u32x2_t hi = *reinterpret_cast<const u32x2_t*>(vp + 16);
+                    const u32x4_t both = u32x4_t{lo[0], lo[1], hi[0], hi[1]};
+                    oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, both),
+                                                                       pf[t][j], oacc[mt], 0, 0, 0);
+                }
+    }
+
+    // ---- finish: denominators, write o (and the log-sum-exp for the backward)
+    l_run += __shfl_xor(l_run, 32, 64);
+    if (qi < S) {
+        const float inv = 1.0f / l_run;
+        bf16_t* op = o + (tok0 + qi) * (size_t)(Hq * HD) + h * HD;
+#pragma unroll
+        for (int mt = 0; mt < C::NMT; ++mt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int e0 = mt * 32 + g * 8 + half * 4;
+                if (e0 < HD)
+                    *reinterpret_cast<uint2*>(op + e0) =
+                        make_uint2(pack_bf2(oacc[mt][g * 4] * inv, oacc[mt][g * 4 + 1] * inv),
+                                   pack_bf2(oacc[mt][g * 4 + 2] * inv, oacc[mt][g * 4 + 3] * inv));
+            }
+        if (lse && half == 0)
+            lse[((size_t)b * Hq + h) * S + qi] = m_run * 0.69314718055994530942f + logf(l_run);
+    }
+}
+
+// vt[b][kvh][e][s] = v[b*S+s][kvh*hd+e]: 64x64 tiles through LDS.
+__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ vt,
+                                                          int S, int S_pad, int Hq, int Hkv, int hd, int hdp,
+                                                          int ld_qkv) {
+    __shared__ bf16_t tile[64][66];
+    const int s0 = blockIdx.x * 64, e0 = blockIdx.y * 64;
+    const int bh = blockIdx.z, b = bh / Hkv, kvh = bh % Hkv;
+    const bf16_t* src = qkv + (size_t)b * S * ld_qkv + (size_t)(Hq + Hkv) * hd + (size_t)kvh * hd;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) {
+        const int s = s0 + r, e = e0 + tx;
+        tile[r][tx] = (s < S && e < hd) ? src[(size_t)s * ld_qkv + e] : (bf16_t)0;
+    }
+    __syncthreads();
+    bf16_t* dst = vt + ((size_t)b * Hkv + kvh) * hdp * S_pad;
+    for (int r = ty; r < 64; r += 4) {
+        const int e = e0 + r, s = s0 + tx;
+        if (e < hdp && s < S_pad) dst[(size_t)e * S_pad + s] = tile[tx][r];
+    }
+}
+
+}  // namespace
+
+hipError_t spk_launch_transpose_v(hipStream_t st, const bf16_t* qkv, bf16_t* vt, const AttnShape& a) {
+    if (a.B <= 0 || a.S <= 0) return hipSuccess;
+    const int hdp = attn_hd_pad(a.hd), sp = attn_s_pad(a.S);
+    dim3 grid(sp / 64, (hdp + 63) / 64, a.B * a.Hkv);
+    transpose_v_kernel<<<grid, 256, 0, st>>>(qkv, vt, a.S, sp, a.Hq, a.Hkv, a.hd, hdp, a.ld_qkv);
+    return hipGetLastError();
+}
+
+hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, const bf16_t* vt, bf16_t* o, float* lse,
+                                const AttnShape& a) {
+    if (a.B <= 0 || a.S <= 0) return hipSuccess;
+    if (a.Hkv <= 0 || a.Hq % a.Hkv || a.ld_qkv % 8 || a.B > 65535 || a.Hq > 65535) return hipErrorInvalidValue;
+    if (((uintptr_t)qkv | (uintptr_t)vt | (uintptr_t)o) & 15) return hipErrorInvalidValue;
+    const float sl2 = 1.4426950408889634f / sqrtf((float)a.hd);
+    dim3 grid((a.S + QB - 1) / QB, a.Hq, a.B);
+    const int sp = attn_s_pad(a.S);
+    switch (a.hd) {
+        case 64:
+            attn_fwd_kernel<64><<<grid, 256, 0, st>>>(qkv, vt, o, lse, a.S, sp, a.Hq, a.Hkv, a.ld_qkv, a.causal, sl2);
+            break;
+        case 80:
+            attn_fwd_kernel<80><<<grid, 256, 0, st>>>(qkv, vt, o, lse, a.S, sp, a.Hq, a.Hkv, a.ld_qkv, a.causal, sl2);
+            break;
+        case 128:
+            attn_fwd_kernel<128><<<grid, 256, 0, st>>>(qkv, vt, o, lse, a.S, sp, a.Hq, a.Hkv, a.ld_qkv, a.causal, sl2);
+            break;
+        default:
+            return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}

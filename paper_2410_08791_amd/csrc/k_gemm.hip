@@ -1,0 +1,363 @@
+// bf16 GEMM on the gfx950 matrix cores: C[M,N] = sum_k A(m,k) W(n,k), fp32
+// accumulate, used for every dense projection of a layer (QKV, O, gate/up,
+// down) and for the backward contractions.
+//
+// Work-group = 256 threads = 4 waves in a 2x2 grid; block tile BM x BN x 64,
+// each wave owns (BM/2) x (BN/2) as 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16).
+// Both operand tiles are staged in LDS with the contraction index contiguous
+// (128-byte rows, 16-byte chunks XOR-swizzled so that both the 16-byte stores
+// and the per-lane 16-byte fragment loads spread over all banks), double
+// buffered: global loads for tile t+1 are issued before the MFMAs of tile t and
+// stored to the other buffer afterwards, one barrier per tile.
+//
+// The MFMA is issued "transposed" (weights as the A operand, activations as B)
+// so that a lane's four consecutive accumulator registers are four consecutive
+// n of one row m: the epilogue then writes 8-byte (bf16) or 16-byte (fp32)
+// pieces of a row instead of single elements.
+//
+// An operand whose contraction index is NOT contiguous in memory (the backward
+// GEMMs) is transposed on the way in: a thread loads an 8x8 bf16 block with
+// eight 16-byte loads, transposes it in registers with byte permutes and
+// stores eight 16-byte chunks.
+#include "sp_kernels.h"
+
+namespace {
+
+constexpr int BK = 64;
+constexpr int ROW_BYTES = BK * 2;  // 128
+
+struct GemmDev {
+    const bf16_t* A; const bf16_t* W; void* C; const float* R; const bf16_t* bias;
+    int lda, ldw, ldc, ldr;
+    int M, N, K;
+    int tilesM, tilesN;
+};
+
+__device__ __forceinline__ int lds_off(int row, int chunk) {
+    return row * ROW_BYTES + ((chunk ^ ((row >> 1) & 7)) << 4);
+}
+
+__device__ __forceinline__ float gelu_erf(float x) {
+    return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+}
+
+// ---- tile loaders -----------------------------------------------------------
+// K-major source: rows of 64 contiguous k. ROWS*8 16-byte chunks over 256 threads.
+template <int ROWS>
+struct LoaderK {
+    static constexpr int ITERS = ROWS * 8 / 256;
+    const bf16_t* src[ITERS];
+    int dst[ITERS];
+    u32x4_t regs[ITERS];
+    // row_of(r) maps a tile row to a (clamped) global row.
+    template <class RowMap>
+    __device__ __forceinline__ void init(const bf16_t* base, int ld, RowMap row_of) {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            const int q = threadIdx.x + i * 256;
+            const int row = q >> 3, c = q & 7;
+            src[i] = base + (size_t)row_of(row) * ld + c * 8;
+            dst[i] = lds_off(row, c);
+        }
+    }
+    __device__ __forceinline__ void fetch(int k0) {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) regs[i] = *reinterpret_cast<const u32x4_t*>(src[i] + k0);
+    }
+    __device__ __forceinline__ void store(unsigned char* lds) {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) *reinterpret_cast<u32x4_t*>(lds + dst[i]) = regs[i];
+    }
+};
+
+// Row-major source (element (r,k) at base[k*ld + r]): per thread one 8(k) x 8(r)
+// block per 256 tile rows.  Lane -> (k block = t & 7, row chunk = t >> 3): a
+// global row k gets 128 contiguous bytes from 8 lanes, and the 16-byte LDS
+// stores of 8 lanes fill one 128-byte tile row.
+template <int ROWS>
+struct LoaderR {
+    static constexpr int ITERS = ROWS / 256 > 0 ? ROWS / 256 : 1;
+    static constexpr bool PARTIAL = ROWS < 256;
+    const bf16_t* src[ITERS];
+    int ld_;
+    int rc_[ITERS], kb_;
+    u32x4_t regs[ITERS][8];
+    template <class ColMap>
+    __device__ __forceinline__ void init(const bf16_t* base, int ld, ColMap col_of) {
+        ld_ = ld;
+        kb_ = threadIdx.x & 7;
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            rc_[i] = (threadIdx.x >> 3) + i * 32;  // 8-row chunk index inside the tile
+            src[i] = base + (size_t)(kb_ * 8) * ld + col_of(rc_[i] * 8);
+        }
+    }
+    __device__ __forceinline__ bool active(int i) const { return !PARTIAL || rc_[i] * 8 < ROWS; }
+    __device__ __forceinline__ void fetch(int k0) {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i)
+            if (active(i)) {
+                const bf16_t* p = src[i] + (size_t)k0 * ld_;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) regs[i][e] = *reinterpret_cast<const u32x4_t*>(p + (size_t)e * ld_);
+            }
+    }
+    __device__ __forceinline__ void store(unsigned char* lds) {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i)
+            if (active(i)) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    u32x4_t o;
+#pragma unroll
+                    for (int ee = 0; ee < 4; ++ee) {
+                        const uint32_t lo = regs[i][2 * ee][j >> 1], hi = regs[i][2 * ee + 1][j >> 1];
+                        o[ee] = (j & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
+                                        : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                    }
+                    *reinterpret_cast<u32x4_t*>(lds + lds_off(rc_[i] * 8 + j, kb_)) = o;
+                }
+            }
+    }
+};
+
+template <int ROWS, int FORM>
+struct LoaderSel { typedef LoaderK<ROWS> type; };
+template <int ROWS>
+struct LoaderSel<ROWS, OP_RMAJOR> { typedef LoaderR<ROWS> type; };
+
+// ---- the kernel ---------------------------------------------------------------
+template <int BM, int BN, int EPI, int AFORM, int WFORM>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 tiles per wave
+    constexpr int A_BYTES = BM * ROW_BYTES, W_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + W_BYTES;
+    constexpr bool SWIGLU = (EPI == EPI_SWIGLU_BF16);
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;  // output columns per block
+    static_assert(!SWIGLU || (TN % 2 == 0), "gate and up tiles pair up inside a wave");
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    // XCD-aware, grouped tile order: 8 m-tiles share each n-tile back to back.
+    int pid = xcd_remap(blockIdx.x, gridDim.x);
+    constexpr int GM = 8;
+    const int group = GM * p.tilesN;
+    const int first_m = (pid / group) * GM;
+    const int gm = min(p.tilesM - first_m, GM);
+    const int tm = first_m + (pid % group) % gm;
+    const int tn = (pid % group) / gm;
+    const int m0 = tm * BM, n0 = tn * BN_OUT;
+
+    typename LoaderSel<BM, AFORM>::type la;
+    typename LoaderSel<BN, WFORM>::type lw;
+    {
+        const int M = p.M, N = p.N;
+        if (AFORM == OP_KMAJOR)
+            la.init(p.A, p.lda, [=](int r) { return min(m0 + r, M - 1); });
+        else
+            la.init(p.A, p.lda, [=](int r) { return min(m0 + r, M - 8); });
+        if (SWIGLU) {
+            // tile row r -> wave column wr, 32-row tile j; first half of a wave's
+            // tiles are gate rows, second half the matching up rows (offset N).
+            lw.init(p.W, p.ldw, [=](int r) {
+                const int wr = r / (BN / 2), j = (r % (BN / 2)) >> 5, rr = r & 31;
+                const int isup = j >= TN / 2;
+                const int col = n0 + wr * (BN / 4) + (isup ? j - TN / 2 : j) * 32 + rr;
+                return min(col, N - 1) + (isup ? N : 0);
+            });
+        } else if (WFORM == OP_KMAJOR) {
+            lw.init(p.W, p.ldw, [=](int r) { return min(n0 + r, N - 1); });
+        } else {
+            lw.init(p.W, p.ldw, [=](int r) { return min(n0 + r, N - 8); });
+        }
+    }
+
+    f32x16_t acc[TN][TM];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+
+    // per-lane fragment offsets: row l32 of a 32-row tile, chunk 2*ks + half
+    const int sw = (l32 >> 1) & 7;
+    int foff[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) foff[ks] = l32 * ROW_BYTES + (((2 * ks + half) ^ sw) << 4);
+    const int a_base = wm * (BM / 2) * ROW_BYTES;
+    const int w_base = A_BYTES + wn * (BN / 2) * ROW_BYTES;
+
+    const int KT = p.K / BK;
+    la.fetch(0);
+    lw.fetch(0);
+    la.store(smem);
+    lw.store(smem + A_BYTES);
+    __syncthreads();
+
+    for (int kt = 0; kt < KT; ++kt) {
+        unsigned char* cur = smem + (kt & 1) * STAGE;
+        unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+        const bool more = kt + 1 < KT;
+        if (more) {
+            la.fetch((kt + 1) * BK);
+            lw.fetch((kt + 1) * BK);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8_t af[TM], wf[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[i] = *reinterpret_cast<const bf16x8_t*>(cur + a_base + i * 32 * ROW_BYTES + foff[ks]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                wf[j] = *reinterpret_cast<const bf16x8_t*>(cur + w_base + j * 32 * ROW_BYTES + foff[ks]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[j][i], 0, 0, 0);
+        }
+        if (more) {
+            la.store(nxt);
+            lw.store(nxt + A_BYTES);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane holds row m (l32), register e of tile j = column
+    //      j*32 + (e/4)*8 + half*4 + e%4 of the wave's n range.
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + wm * (BM / 2) + i * 32 + l32;
+        if (m >= p.M) continue;
+        if (SWIGLU) {
+#pragma unroll
+            for (int j = 0; j < TN / 2; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wn * (BN / 4) + j * 32 + g * 8 + half * 4;
+                    if (n >= p.N) continue;
+                    float z[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float gv = acc[j][i][g * 4 + e], uv = acc[j + TN / 2][i][g * 4 + e];
+                        z[e] = gv / (1.0f + __expf(-gv)) * uv;
+                    }
+                    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n) =
+                        make_uint2(pack_bf2(z[0], z[1]), pack_bf2(z[2], z[3]));
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wn * (BN / 2) + j * 32 + g * 8 + half * 4;
+                    if (n >= p.N) continue;
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = acc[j][i][g * 4 + e];
+                    if (p.bias) {
+                        const uint2 b = *reinterpret_cast<const uint2*>(p.bias + n);
+                        v[0] += bf_lo(b.x); v[1] += bf_hi(b.x); v[2] += bf_lo(b.y); v[3] += bf_hi(b.y);
+                    }
+                    if (EPI == EPI_RESID_F32) {
+                        const float4 r = *reinterpret_cast<const float4*>(p.R + (size_t)m * p.ldr + n);
+                        *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (size_t)m * p.ldc + n) =
+                            make_float4(r.x + v[0], r.y + v[1], r.z + v[2], r.w + v[3]);
+                    } else if (EPI == EPI_F32) {
+                        *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (size_t)m * p.ldc + n) =
+                            make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+                        if (EPI == EPI_GELU_BF16) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
+                        }
+                        *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n) =
+                            make_uint2(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]));
+                    }
+                }
+        }
+    }
+}
+
+template <int BM, int BN, int EPI, int AFORM, int WFORM>
+hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
+    constexpr int LDS = 2 * (BM + BN) * ROW_BYTES;
+    constexpr int BN_OUT = (EPI == EPI_SWIGLU_BF16) ? BN / 2 : BN;
+    static bool attr_set = false;  // per instantiation; a benign race sets it twice at worst
+    auto kern = gemm_kernel<BM, BN, EPI, AFORM, WFORM>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    GemmDev d;
+    d.A = g.A; d.W = g.W; d.C = g.C; d.R = g.R; d.bias = g.bias;
+    d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc; d.ldr = g.ldr;
+    d.M = g.M; d.N = g.N; d.K = g.K;
+    d.tilesM = (g.M + BM - 1) / BM;
+    d.tilesN = (g.N + BN_OUT - 1) / BN_OUT;
+    const int nblocks = d.tilesM * d.tilesN;
+    gemm_kernel<BM, BN, EPI, AFORM, WFORM><<<nblocks, 256, LDS, st>>>(d);
+    return hipGetLastError();
+}
+
+// Tile shapes: 1 = 128x128, 2 = 128x256 (BM x BN), 3 = 256x256.
+// The heuristic wants at least ~2 work-groups per CU's worth of tiles before it
+// moves to a larger tile (256 CUs; the 256x256 tile runs one group per CU).
+int pick_tile(int M, int N, int epi) {
+    const int n_out_256 = (epi == EPI_SWIGLU_BF16) ? 128 : 256;
+    const long t256 = (long)((M + 255) / 256) * ((N + n_out_256 - 1) / n_out_256);
+    const long t128x256 = (long)((M + 127) / 128) * ((N + n_out_256 - 1) / n_out_256);
+    if (t256 >= 480) return 3;
+    if (t128x256 >= 480) return 2;
+    return 1;
+}
+
+template <int EPI, int AFORM, int WFORM>
+hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
+    int tile = g.tile ? g.tile : pick_tile(g.M, g.N, EPI);
+    switch (tile) {
+        case 1: return launch_one<128, 128, EPI, AFORM, WFORM>(st, g);
+        case 2: return launch_one<128, 256, EPI, AFORM, WFORM>(st, g);
+        case 3: return launch_one<256, 256, EPI, AFORM, WFORM>(st, g);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t spk_launch_gemm(hipStream_t st, int epi, const GemmArgs& g) {
+    if (g.M <= 0 || g.N <= 0) return hipSuccess;
+    if (g.K <= 0 || g.K % BK || g.N % 8 || g.lda % 8 || g.ldw % 8 || !g.A || !g.W || !g.C) return hipErrorInvalidValue;
+    if (((uintptr_t)g.A | (uintptr_t)g.W | (uintptr_t)g.C | (uintptr_t)g.R | (uintptr_t)g.bias) & 15) return hipErrorInvalidValue;
+    if (g.ldc % 4 || (epi == EPI_RESID_F32 && (!g.R || g.ldr % 4))) return hipErrorInvalidValue;
+    if (g.a_form == OP_RMAJOR && (g.M < 8 || g.M % 8)) return hipErrorInvalidValue;
+    if (g.w_form == OP_RMAJOR && (g.N < 8 || g.N % 8)) return hipErrorInvalidValue;
+    const int forms = g.a_form * 2 + g.w_form;
+    switch (epi) {
+        case EPI_BF16:
+            if (forms == 0) return launch_tile<EPI_BF16, OP_KMAJOR, OP_KMAJOR>(st, g);
+            if (forms == 1) return launch_tile<EPI_BF16, OP_KMAJOR, OP_RMAJOR>(st, g);
+            break;
+        case EPI_RESID_F32:
+            if (forms == 0) return launch_tile<EPI_RESID_F32, OP_KMAJOR, OP_KMAJOR>(st, g);
+            if (forms == 1) return launch_tile<EPI_RESID_F32, OP_KMAJOR, OP_RMAJOR>(st, g);
+            break;
+        case EPI_GELU_BF16:
+            if (forms == 0 && g.bias) return launch_tile<EPI_GELU_BF16, OP_KMAJOR, OP_KMAJOR>(st, g);
+            break;
+        case EPI_SWIGLU_BF16:
+            if (forms == 0 && !g.bias) return launch_tile<EPI_SWIGLU_BF16, OP_KMAJOR, OP_KMAJOR>(st, g);
+            break;
+        case EPI_F32:
+            if (forms == 3) return launch_tile<EPI_F32, OP_RMAJOR, OP_RMAJOR>(st, g);
+            if (forms == 0) return launch_tile<EPI_F32, OP_KMAJOR, OP_KMAJOR>(st, g);
+            break;
+    }
+    return hipErrorInvalidValue;
+}

@@ -1,0 +1,69 @@
+// Engine state behind an sp_handle (internal).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+#include "sp_host.h"
+#include "sp_kernels.h"
+
+struct sp_engine {
+    sp_stack_desc desc;
+    uint32_t flags = 0;
+    sp_plan plan;
+    sp::Layout lay;
+    sp::Workspace ws;
+    sp::Scheduler sched;
+    unsigned char* arena = nullptr;   // caller's device arena: [workspace | slot 0 | slot 1 | ...]
+    unsigned char* slots = nullptr;
+    hipStream_t compute = nullptr, h2d = nullptr, d2h = nullptr;
+    std::vector<const void*> blobs;   // pinned host weight blobs (never written)
+    std::vector<hipEvent_t> loaded, done;          // per layer: copy landed / compute finished
+    std::vector<char> loaded_recorded, done_recorded;
+    hipEvent_t ev_sync_c = nullptr, ev_sync_h = nullptr;
+    hipEvent_t grad_ready[2] = {nullptr, nullptr}, gslot_free[2] = {nullptr, nullptr};
+    char gslot_used[2] = {0, 0};
+    int gslot_next = 0;
+    // per-call trace (SP_FLAG_TIMING)
+    hipEvent_t t0 = nullptr;
+    hipEvent_t t_copy_begin[SP_MAX_TRACE_LAYERS] = {}, t_copy_end[SP_MAX_TRACE_LAYERS] = {};
+    hipEvent_t t_comp_begin[SP_MAX_TRACE_LAYERS] = {}, t_comp_end[SP_MAX_TRACE_LAYERS] = {};
+    int trace_layer[SP_MAX_TRACE_LAYERS] = {};
+    int copy_layer[SP_MAX_TRACE_LAYERS] = {};
+    int trace_n = 0, copy_n = 0;
+    std::vector<hipEvent_t> kt_begin, kt_end;   // ring of event pairs around the largest GEMM
+    uint32_t kt_count = 0;                      // pairs recorded since the last sp_get_stats
+    int kt_m = 0, kt_n = 0, kt_k = 0;
+    // counters
+    uint64_t calls = 0, stats_h2d_copies = 0, stats_h2d_bytes = 0, stats_d2h_copies = 0, stats_d2h_bytes = 0;
+    uint64_t call_h2d_copies = 0, call_h2d_bytes = 0;
+    // kernel selection (fixed at create; never depends on the window or the slot)
+    int gemm_tile = 0;
+    bool fuse_swiglu = true;
+    // training call context
+    void* const* grad_blobs = nullptr;
+    float* y_out = nullptr;
+    std::string error;
+
+    template <class T>
+    T* wsp(size_t off) const { return reinterpret_cast<T*>(arena + off); }
+};
+
+// One layer forward, residual stream h (fp32 [B*S, d]) updated in place.
+int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int S);
+// Training forward of layer l: reads its saved input, writes the next layer's.
+int sp_layer_forward_train(sp_engine* e, int layer, const unsigned char* w, int B, int S);
+// Recompute + backward of layer l; leaves dL/d(input) in the stream-gradient buffer
+// and hands the layer's fp32 weight gradients to the device-to-host stream.
+int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, int S);
+
+int sp_fail(sp_engine* e, int code, const char* fmt, ...);
+
+#define SP_HIP(e, call)                                                                          \
+    do {                                                                                         \
+        hipError_t _err = (call);                                                                \
+        if (_err != hipSuccess)                                                                  \
+            return sp_fail((e), SP_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(_err), \
+                           __FILE__, __LINE__);                                                  \
+    } while (0)

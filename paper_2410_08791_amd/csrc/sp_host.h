@@ -1,0 +1,86 @@
+// Host-side logic shared by the engine and the layout/plan queries:
+// blob layout, workspace carving, slot-count policy and the window scheduler.
+// Pure C++ (no HIP calls) so that it can be exercised without a device.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/superpipe.h"
+
+namespace sp {
+
+constexpr size_t kTensorAlign = 256;
+constexpr size_t kSlotAlign = 4096;
+constexpr int kMaxTensors = 12;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct TensorInfo {
+    size_t offset;  // bytes inside the bf16 weight blob
+    size_t elems;
+    int rows, cols;  // vectors: rows = 1
+};
+
+struct Layout {
+    int n_tensors = 0;
+    TensorInfo t[kMaxTensors];
+    size_t blob_bytes = 0;   // bf16 weights
+    size_t grad_bytes = 0;   // fp32 gradients: offsets doubled
+};
+
+// Returns SP_OK or SP_ERR_INVALID_ARG (why: optional text).
+int validate_desc(const sp_stack_desc* d, const char** why);
+int make_layout(const sp_stack_desc* d, Layout* out);
+
+// Device workspace, as byte offsets from its base (all 256-byte aligned).
+struct Workspace {
+    size_t a, qkv, vt, o, gu, z;           // forward activations (bf16)
+    // training only
+    size_t xs;                             // layer inputs fp32 [L][T, d], kept for the backward
+    size_t m;                              // second normed activation bf16 [Tp, d]
+    size_t h1;                             // residual after attention fp32 [T, d]
+    size_t lse, delta;                     // softmax log-sum-exp, rowsum(dO*O): fp32 [B, Hq, S]
+    size_t dh, da;                         // fp32 [T, d]: stream gradient, norm-output gradient
+    size_t dhb;                            // bf16 [Tp, d] copy of dh (GEMM operand)
+    size_t dqkv, dob, dz;                  // bf16 gradients of qkv, attention output, SwiGLU output
+    size_t part;                           // fp32 [kNormBwdBlocks, d] gain-gradient partials (+ loss partials)
+    size_t gslot[2];                       // fp32 gradient slots
+    size_t total;
+    int t_pad;                             // token rows padded to 64 (training)
+};
+void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Workspace* ws);
+
+int make_plan(const sp_stack_desc* d, int k, int p, uint64_t budget, int training, sp_plan* out);
+
+// ---- window scheduler --------------------------------------------------------
+// Decides, in host order, which layer is copied into which slot and when a
+// slot may be reused; the engine turns each decision into stream operations,
+// the tracer records them.  Residency survives across passes.
+struct SchedSink {
+    virtual ~SchedSink() {}
+    // copy `layer` into `slot`; it must start after the compute of `wait_layer` (-1: none)
+    virtual int copy(int layer, int slot, int wait_layer) = 0;
+    // run `layer` (dir +1 forward, -1 backward) out of `slot`
+    virtual int compute(int layer, int slot, int dir, bool copied_since_last_use) = 0;
+};
+
+class Scheduler {
+public:
+    void reset(int n_layers, int n_slots, int group);
+    // One pass over all layers: dir +1 = 0..L-1, dir -1 = L-1..0.  With wrap
+    // (forward-only use) slots freed at the tail are refilled with the first layers.
+    int run_pass(int dir, bool wrap, SchedSink& sink);
+    int n_slots() const { return n_slots_; }
+    const std::vector<int>& layer_slot() const { return layer_slot_; }
+
+private:
+    int n_layers_ = 0, n_slots_ = 0, group_ = 1;
+    std::vector<int> slot_layer_;   // layer occupying (or being copied into) a slot, -1 = empty
+    std::vector<int> slot_last_;    // last layer computed out of a slot, -1 = none
+    std::vector<int> layer_slot_;   // slot of a resident layer, -1 = not on the device
+    std::vector<char> fresh_;       // copied since last compute
+};
+
+}  // namespace sp

@@ -1,0 +1,273 @@
+// Layout, workspace, slot-count policy, window scheduler and the host-only
+// C entry points (no device needed for anything in this file).
+#include "sp_host.h"
+
+#include <string.h>
+
+#include <algorithm>
+
+namespace sp {
+
+constexpr int kNormBwdBlocks = 256;
+
+int validate_desc(const sp_stack_desc* d, const char** why) {
+    const char* w = nullptr;
+    if (!d) w = "desc is NULL";
+    else if (d->struct_size != sizeof(sp_stack_desc)) w = "desc.struct_size mismatch";
+    else if (d->arch != SP_DECODER_SWIGLU_RMS && d->arch != SP_ENCODER_GELU_LN) w = "unknown arch";
+    else if (d->n_layers < 1) w = "n_layers < 1";
+    else if (d->d_model < 64 || d->d_model % 64 || d->d_model > 8192) w = "d_model must be a multiple of 64 in [64, 8192]";
+    else if (d->head_dim != 64 && d->head_dim != 80 && d->head_dim != 128) w = "head_dim must be 64, 80 or 128";
+    else if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_q_heads % d->n_kv_heads) w = "n_kv_heads must divide n_q_heads";
+    else if ((d->n_q_heads * d->head_dim) % 64) w = "n_q_heads*head_dim must be a multiple of 64";
+    else if (d->d_ffn < 64 || d->d_ffn % 64) w = "d_ffn must be a multiple of 64";
+    else if (d->max_batch < 1 || d->max_seq < 1) w = "max_batch/max_seq < 1";
+    else if ((int64_t)d->max_batch * d->max_seq > (1 << 24)) w = "max_batch*max_seq too large";
+    else if (!(d->norm_eps > 0.f)) w = "norm_eps must be positive";
+    else if (d->arch == SP_ENCODER_GELU_LN && d->causal) w = "encoder layers are bidirectional";
+    if (why) *why = w;
+    return w ? SP_ERR_INVALID_ARG : SP_OK;
+}
+
+int make_layout(const sp_stack_desc* d, Layout* out) {
+    int rc = validate_desc(d, nullptr);
+    if (rc != SP_OK) return rc;
+    const int dm = d->d_model, f = d->d_ffn;
+    const int nq = d->n_q_heads * d->head_dim, nkv = d->n_kv_heads * d->head_dim;
+    const int nqkv = nq + 2 * nkv;
+    struct RC { int r, c; };
+    RC shapes[kMaxTensors];
+    int n;
+    if (d->arch == SP_DECODER_SWIGLU_RMS) {
+        const RC s[] = {{1, dm}, {nqkv, dm}, {dm, nq}, {1, dm}, {2 * f, dm}, {dm, f}};
+        n = SP_DECODER_TENSORS;
+        memcpy(shapes, s, sizeof(s));
+    } else {
+        const RC s[] = {{1, dm}, {1, dm}, {nqkv, dm}, {1, nqkv}, {dm, nq}, {1, dm},
+                        {1, dm}, {1, dm}, {f, dm},    {1, f},    {dm, f},  {1, dm}};
+        n = SP_ENCODER_TENSORS;
+        memcpy(shapes, s, sizeof(s));
+    }
+    size_t off = 0;
+    out->n_tensors = n;
+    for (int i = 0; i < n; ++i) {
+        out->t[i].offset = off;
+        out->t[i].rows = shapes[i].r;
+        out->t[i].cols = shapes[i].c;
+        out->t[i].elems = (size_t)shapes[i].r * shapes[i].c;
+        off = align_up(off + out->t[i].elems * 2, kTensorAlign);
+    }
+    out->blob_bytes = off;
+    out->grad_bytes = off * 2;
+    return SP_OK;
+}
+
+void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Workspace* ws) {
+    memset(ws, 0, sizeof(*ws));
+    const size_t T = (size_t)d->max_batch * d->max_seq;
+    const size_t Tp = training ? align_up(T, 64) : T;
+    ws->t_pad = (int)Tp;
+    const size_t dm = d->d_model, f = d->d_ffn;
+    const size_t nq = (size_t)d->n_q_heads * d->head_dim, nkv = (size_t)d->n_kv_heads * d->head_dim;
+    const size_t nqkv = nq + 2 * nkv;
+    const size_t hdp = (d->head_dim + 31) / 32 * 32, sp = align_up(d->max_seq, 64);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, kTensorAlign); return o; };
+    ws->a = take(Tp * dm * 2);
+    ws->qkv = take(Tp * nqkv * 2);
+    ws->vt = take((size_t)d->max_batch * d->n_kv_heads * hdp * sp * 2);
+    ws->o = take(Tp * nq * 2);
+    ws->gu = take(Tp * (d->arch == SP_DECODER_SWIGLU_RMS ? 2 * f : f) * 2);
+    ws->z = take(Tp * f * 2);
+    if (training) {
+        ws->xs = take((size_t)d->n_layers * T * dm * 4);
+        ws->m = take(Tp * dm * 2);
+        ws->h1 = take(T * dm * 4);
+        ws->lse = take((size_t)d->max_batch * d->n_q_heads * d->max_seq * 4);
+        ws->delta = take((size_t)d->max_batch * d->n_q_heads * d->max_seq * 4);
+        ws->dh = take(T * dm * 4);
+        ws->da = take(T * dm * 4);
+        ws->dhb = take(Tp * dm * 2);
+        ws->dqkv = take(Tp * nqkv * 2);
+        ws->dob = take(Tp * nq * 2);
+        ws->dz = take(Tp * f * 2);
+        ws->part = take(((size_t)kNormBwdBlocks * dm + 1024) * 4);
+        off = align_up(off, kSlotAlign);
+        ws->gslot[0] = take(align_up(lay.grad_bytes, kSlotAlign));
+        ws->gslot[1] = take(align_up(lay.grad_bytes, kSlotAlign));
+    }
+    ws->total = align_up(off, kSlotAlign);
+}
+
+int make_plan(const sp_stack_desc* d, int k, int p, uint64_t budget, int training, sp_plan* out) {
+    if (!out) return SP_ERR_INVALID_ARG;
+    memset(out, 0, sizeof(*out));
+    Layout lay;
+    int rc = make_layout(d, &lay);
+    if (rc != SP_OK) return rc;
+    if (k < 1 || p < 1) return SP_ERR_INVALID_ARG;
+    Workspace ws;
+    make_workspace(d, lay, training, &ws);
+    out->slot_bytes = align_up(lay.blob_bytes, kSlotAlign);
+    out->workspace_bytes = ws.total;
+    if (budget < ws.total + out->slot_bytes) return SP_ERR_BUDGET;
+    const uint64_t fit = (budget - ws.total) / out->slot_bytes;
+    int64_t want = (int64_t)k + p;
+    int64_t n = std::min<int64_t>(want, d->n_layers);
+    n = std::min<int64_t>(n, (int64_t)std::min<uint64_t>(fit, 1u << 30));
+    out->n_slots = (int)n;
+    out->p_eff = (int)std::min<int64_t>(p, std::max<int64_t>(n - 1, 1));
+    out->k_eff = (int)std::max<int64_t>(n - out->p_eff, 1);
+    out->fully_resident = n == d->n_layers;
+    out->arena_bytes_used = ws.total + (uint64_t)n * out->slot_bytes;
+    return SP_OK;
+}
+
+// ---- scheduler ---------------------------------------------------------------
+void Scheduler::reset(int n_layers, int n_slots, int group) {
+    n_layers_ = n_layers;
+    n_slots_ = n_slots;
+    group_ = std::max(1, group);
+    slot_layer_.assign(n_slots, -1);
+    slot_last_.assign(n_slots, -1);
+    layer_slot_.assign(n_layers, -1);
+    fresh_.assign(n_layers, 0);
+}
+
+int Scheduler::run_pass(int dir, bool wrap, SchedSink& sink) {
+    const int L = n_layers_, N = n_slots_;
+    auto at = [&](int i) { return dir > 0 ? i : L - 1 - i; };  // i-th layer of this pass
+    int rc;
+    // Initial load (Sec. 1: "load k units into GPU memory initially"): the first
+    // N layers of the pass, except those still resident from the previous pass.
+    const int first = std::min(N, L);
+    std::vector<char> keep(N, 0);
+    for (int i = 0; i < first; ++i)
+        if (layer_slot_[at(i)] >= 0) keep[layer_slot_[at(i)]] = 1;
+    int scan = 0;
+    for (int i = 0; i < first; ++i) {
+        const int l = at(i);
+        if (layer_slot_[l] >= 0) continue;
+        while (scan < N && keep[scan]) ++scan;
+        if (scan >= N) return SP_ERR_STATE;  // cannot happen: first <= N
+        const int s = scan;
+        keep[s] = 1;
+        if (slot_layer_[s] >= 0) layer_slot_[slot_layer_[s]] = -1;
+        slot_layer_[s] = l;
+        layer_slot_[l] = s;
+        fresh_[l] = 1;
+        if ((rc = sink.copy(l, s, slot_last_[s])) != SP_OK) return rc;
+    }
+    // Steady state (Sec. 3.3, Fig. 1): after each group of `group_` executed
+    // layers, their slots are refilled with the next layers of the pass.
+    int next = first;          // position in the pass of the next layer to fetch
+    int wrapped = 0;           // layers of the NEXT pass already fetched (wrap)
+    int gbegin = 0;
+    for (int i = 0; i < L; ++i) {
+        const int l = at(i);
+        const int s = layer_slot_[l];
+        if (s < 0) return SP_ERR_STATE;
+        if ((rc = sink.compute(l, s, dir, fresh_[l] != 0)) != SP_OK) return rc;
+        fresh_[l] = 0;
+        slot_last_[s] = l;
+        if (i + 1 - gbegin == group_ || i == L - 1) {
+            for (int j = gbegin; j <= i; ++j) {
+                const int done = at(j);
+                int t = -1;
+                while (next < L && layer_slot_[at(next)] >= 0) ++next;  // already on the device
+                if (next < L) {
+                    t = at(next++);
+                } else if (wrap && N < L) {
+                    while (wrapped < N && layer_slot_[at(wrapped)] >= 0) ++wrapped;
+                    if (wrapped < N) t = at(wrapped++);
+                }
+                if (t < 0) break;
+                const int sl = layer_slot_[done];
+                layer_slot_[done] = -1;
+                slot_layer_[sl] = t;
+                layer_slot_[t] = sl;
+                fresh_[t] = 1;
+                if ((rc = sink.copy(t, sl, done)) != SP_OK) return rc;
+            }
+            gbegin = i + 1;
+        }
+    }
+    return SP_OK;
+}
+
+}  // namespace sp
+
+// ---- host-only C entry points ---------------------------------------------------
+using namespace sp;
+
+extern "C" int sp_num_tensors(const sp_stack_desc* desc) {
+    Layout lay;
+    int rc = make_layout(desc, &lay);
+    return rc == SP_OK ? lay.n_tensors : rc;
+}
+
+extern "C" size_t sp_tensor_offset(const sp_stack_desc* desc, int tensor_id) {
+    Layout lay;
+    if (make_layout(desc, &lay) != SP_OK || tensor_id < 0 || tensor_id >= lay.n_tensors) return (size_t)-1;
+    return lay.t[tensor_id].offset;
+}
+
+extern "C" size_t sp_tensor_elems(const sp_stack_desc* desc, int tensor_id) {
+    Layout lay;
+    if (make_layout(desc, &lay) != SP_OK || tensor_id < 0 || tensor_id >= lay.n_tensors) return 0;
+    return lay.t[tensor_id].elems;
+}
+
+extern "C" size_t sp_layer_blob_bytes(const sp_stack_desc* desc) {
+    Layout lay;
+    return make_layout(desc, &lay) == SP_OK ? lay.blob_bytes : 0;
+}
+
+extern "C" size_t sp_layer_grad_bytes(const sp_stack_desc* desc) {
+    Layout lay;
+    return make_layout(desc, &lay) == SP_OK ? lay.grad_bytes : 0;
+}
+
+extern "C" size_t sp_workspace_bytes(const sp_stack_desc* desc, int training) {
+    Layout lay;
+    if (make_layout(desc, &lay) != SP_OK) return 0;
+    Workspace ws;
+    make_workspace(desc, lay, training, &ws);
+    return ws.total;
+}
+
+extern "C" int sp_make_plan(const sp_stack_desc* desc, int k, int p, uint64_t budget_bytes, int training,
+                            sp_plan* out) {
+    return make_plan(desc, k, p, budget_bytes, training, out);
+}
+
+namespace {
+struct TraceSink : SchedSink {
+    sp_sched_op* ops;
+    int cap, n = 0, pass = 0;
+    void push(int kind, int layer, int slot, int w) {
+        if (n < cap) ops[n] = sp_sched_op{kind, layer, slot, w, pass};
+        ++n;
+    }
+    int copy(int layer, int slot, int wait_layer) override { push(0, layer, slot, wait_layer); return SP_OK; }
+    int compute(int layer, int slot, int dir, bool fresh) override { push(dir > 0 ? 1 : 2, layer, slot, fresh ? 1 : 0); return SP_OK; }
+};
+}  // namespace
+
+extern "C" int sp_trace_schedule(int n_layers, int n_slots, int p_eff, int training, int wrap_prefetch, int passes,
+                                 sp_sched_op* ops, int cap) {
+    if (n_layers < 1 || n_slots < 1 || n_slots > n_layers || p_eff < 1 || passes < 1 || cap < 0 || (cap && !ops))
+        return SP_ERR_INVALID_ARG;
+    Scheduler sch;
+    sch.reset(n_layers, n_slots, p_eff);
+    TraceSink sink;
+    sink.ops = ops;
+    sink.cap = cap;
+    for (int ps = 0; ps < passes; ++ps) {
+        sink.pass = ps;
+        const int dir = (training && (ps & 1)) ? -1 : +1;
+        int rc = sch.run_pass(dir, !training && wrap_prefetch, sink);
+        if (rc != SP_OK) return rc;
+    }
+    return sink.n;
+}

@@ -1,0 +1,58 @@
+// Host-side launchers of the per-layer kernels (internal to the library).
+// Every launcher validates what its kernel and grid assume, enqueues on `st`
+// and returns the launch status; none synchronises or allocates.
+#pragma once
+#include "sp_common.h"
+
+enum GemmEpilogue {
+    EPI_BF16 = 0,        // C bf16 [M,N]  = acc (+ bias)
+    EPI_RESID_F32 = 1,   // C fp32 [M,N]  = R + acc (+ bias); C may alias R
+    EPI_GELU_BF16 = 2,   // C bf16 [M,N]  = gelu(acc + bias), exact erf form
+    EPI_SWIGLU_BF16 = 3, // W = [gate rows; up rows] (2N x K); C bf16 [M,N] = silu(gate) * up
+    EPI_F32 = 4          // C fp32 [M,N]  = acc (+ bias)   (weight gradients)
+};
+
+// Operand forms: which index is contiguous in memory.
+//   OP_KMAJOR: element (row r, contraction index k) at ptr[r * ld + k]
+//   OP_RMAJOR: element (r, k) at ptr[k * ld + r]   (transposed on the way into LDS)
+enum GemmOperand { OP_KMAJOR = 0, OP_RMAJOR = 1 };
+
+struct GemmArgs {
+    const bf16_t* A; int lda; int a_form;   // "activation" operand, rows = M
+    const bf16_t* W; int ldw; int w_form;   // "weight" operand, rows = N
+    void* C; int ldc;
+    const float* R; int ldr;                // EPI_RESID_F32
+    const bf16_t* bias;                     // [N] or nullptr
+    int M, N, K;
+    int tile;                               // 0 = heuristic, else 1..3 = forced tile shape
+};
+
+// C[M,N] = sum_k A(m,k) W(n,k), bf16 operands, fp32 accumulate on MFMA.
+// Needs K % 64 == 0, N % 8 == 0, leading dimensions % 8 == 0, 16-byte aligned bases.
+hipError_t spk_launch_gemm(hipStream_t st, int epilogue, const GemmArgs& g);
+
+// out bf16 [T,d] = norm(h fp32 [T,d]); bias == nullptr -> RMSNorm, else LayerNorm.
+hipError_t spk_launch_norm(hipStream_t st, const float* h, const bf16_t* gain, const bf16_t* bias,
+                           bf16_t* out, int T, int d, float eps);
+
+// z bf16 [T,f] = silu(gu[:, :f]) * gu[:, f:], gu bf16 [T,2f].
+hipError_t spk_launch_swiglu(hipStream_t st, const bf16_t* gu, bf16_t* z, int T, int f);
+
+struct AttnShape {
+    int B, S, Hq, Hkv, hd, causal;
+    int ld_qkv;      // row stride (elements) of the fused [q | k | v] activation
+};
+// Rounded-up sizes of the transposed V scratch: [B][Hkv][hd_pad][S_pad] bf16.
+static inline int attn_hd_pad(int hd) { return (hd + 31) / 32 * 32; }
+static inline int attn_s_pad(int S) { return (S + 63) / 64 * 64; }
+
+// vt[b][kvh][e][s] = v[b*S+s][kvh*hd+e]; rows e >= hd and columns s >= S are zero.
+hipError_t spk_launch_transpose_v(hipStream_t st, const bf16_t* qkv, bf16_t* vt, const AttnShape& a);
+
+// o bf16 [B*S, Hq*hd] = softmax(q k^T / sqrt(hd) + mask) v per (batch, head);
+// lse (nullable) fp32 [B, Hq, S] = log of the softmax denominator incl. the row max.
+hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, const bf16_t* vt, bf16_t* o,
+                                float* lse, const AttnShape& a);
+
+hipError_t spk_launch_copy_f32(hipStream_t st, const float* src, float* dst, size_t n);
+hipError_t spk_launch_fill_u32(hipStream_t st, uint32_t* dst, uint32_t v, size_t n);

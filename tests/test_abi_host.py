@@ -1,0 +1,146 @@
+"""The C-ABI library loads on a CPU-only box, exports every symbol the headers
+declare, and its host-only entry points (layout, plan, schedule trace, argument
+checks) behave as documented.  No compute calls here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2410_08791_amd import binding as sp
+from paper_2410_08791_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        text = open(os.path.join(ROOT, "include", fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(spk?_[a-z0-9_]+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"sp_create", "sp_forward", "sp_forward_backward", "sp_destroy"} <= names
+    for n in names:
+        assert hasattr(sp.lib, n), f"{n} declared in include/ but not exported"
+    assert names == set(sp.EXPORTS), names ^ set(sp.EXPORTS)
+
+
+@pytest.mark.parametrize("name,blob_bytes", [("tiny", 2098176), ("llama7b", 404766720),
+                                             ("vith", 39354880), ("llama70b", 1711308800),
+                                             ("train1p3b", 101195776)])
+def test_blob_layout(name, blob_bytes):
+    w = synth.WORKLOADS[name]
+    d = sp.make_desc(w)
+    assert sp.sp_layer_blob_bytes(C.byref(d)) == blob_bytes
+    assert sp.sp_layer_grad_bytes(C.byref(d)) == 2 * blob_bytes
+    specs = synth.tensor_specs(w)
+    assert sp.sp_num_tensors(C.byref(d)) == len(specs)
+    assert [n for n, _, _ in specs] == sp.TENSOR_NAMES[d.arch]
+    prev_end = 0
+    for i, (n, shape, _) in enumerate(specs):
+        off = sp.sp_tensor_offset(C.byref(d), i)
+        cnt = sp.sp_tensor_elems(C.byref(d), i)
+        assert cnt == int(np.prod(shape))
+        assert off % 256 == 0 and off >= prev_end
+        prev_end = off + 2 * cnt
+    assert prev_end <= blob_bytes
+    assert sp.sp_tensor_offset(C.byref(d), len(specs)) == C.c_size_t(-1).value
+    assert sp.sp_tensor_elems(C.byref(d), -1) == 0
+
+
+def test_blob_views_cover_disjoint_ranges():
+    w = synth.WORKLOADS["tiny"]
+    d = sp.make_desc(w)
+    blob = np.zeros(sp.sp_layer_blob_bytes(C.byref(d)), dtype=np.uint8)
+    v = sp.blob_views(d, blob)
+    for i, (n, a) in enumerate(v.items()):
+        a[:] = i + 1
+    for i, (n, a) in enumerate(v.items()):
+        assert np.all(a == i + 1), n
+
+
+def test_bad_descs_are_rejected():
+    w = synth.WORKLOADS["tiny"]
+    for field, val in [("struct_size", 4), ("n_layers", 0), ("d_model", 100), ("head_dim", 48),
+                       ("n_kv_heads", 3), ("d_ffn", 1000), ("arch", 7), ("max_batch", 0), ("norm_eps", 0.0)]:
+        d = sp.make_desc(w)
+        setattr(d, field, val)
+        assert sp.sp_layer_blob_bytes(C.byref(d)) == 0, field
+        assert sp.sp_num_tensors(C.byref(d)) == sp.SP_ERR_INVALID_ARG, field
+        rc, _ = sp.plan(d, 1, 1, 1 << 40)
+        assert rc == sp.SP_ERR_INVALID_ARG, field
+    assert sp.sp_layer_blob_bytes(None) == 0
+
+
+def test_slot_count_policy():
+    w = synth.WORKLOADS["llama7b"]
+    d = sp.make_desc(w)
+    slot = 404766720  # already a multiple of 4096
+    ws = sp.sp_workspace_bytes(C.byref(d), 0)
+    assert ws > 0 and ws % 4096 == 0
+    budget = ws + 4 * slot                      # "HBM budget capped at 4 resident layers"
+    got = {}
+    for k in (1, 2, 4):
+        for p in (1, 2):
+            rc, pl = sp.plan(d, k, p, budget)
+            assert rc == sp.SP_OK
+            got[(k, p)] = (pl.n_slots, pl.k_eff, pl.p_eff)
+            assert pl.arena_bytes_used == ws + pl.n_slots * slot <= budget
+            assert pl.slot_bytes == slot and pl.workspace_bytes == ws and not pl.fully_resident
+    assert got == {(1, 1): (2, 1, 1), (1, 2): (3, 1, 2), (2, 1): (3, 2, 1), (2, 2): (4, 2, 2),
+                   (4, 1): (4, 3, 1), (4, 2): (4, 2, 2)}
+    # budget below workspace + one slot
+    rc, _ = sp.plan(d, 1, 1, ws + slot - 1)
+    assert rc == sp.SP_ERR_BUDGET
+    # exactly one slot: serialised, p_eff = k_eff = 1
+    rc, pl = sp.plan(d, 2, 2, ws + slot)
+    assert rc == sp.SP_OK and (pl.n_slots, pl.k_eff, pl.p_eff) == (1, 1, 1)
+    # plenty of memory: clamped by the layer count -> fully resident
+    rc, pl = sp.plan(d, 40, 2, 1 << 45)
+    assert rc == sp.SP_OK and pl.n_slots == 32 and pl.fully_resident
+    for k, p in [(0, 1), (1, 0), (-1, 1)]:
+        assert sp.plan(d, k, p, budget)[0] == sp.SP_ERR_INVALID_ARG
+    # training workspace is larger (saved inputs, gradient slots)
+    wt = synth.WORKLOADS["train1p3b"]
+    dt = sp.make_desc(wt)
+    assert sp.sp_workspace_bytes(C.byref(dt), 1) > sp.sp_workspace_bytes(C.byref(dt), 0) + 24 * 8192 * 2048 * 4
+
+
+def test_create_argument_errors_without_a_device():
+    w = synth.WORKLOADS["tiny"]
+    d = sp.make_desc(w)
+    h = C.c_void_p()
+    blob = np.zeros(sp.sp_layer_blob_bytes(C.byref(d)), dtype=np.uint8)
+    ptrs = (C.c_void_p * 4)(*[blob.ctypes.data] * 4)
+    cfg = sp.sp_config(C.sizeof(sp.sp_config), 1, 1, 1 << 30, 4096, None, 8, None, 0)
+    assert sp.sp_create(None, C.byref(d), ptrs, C.byref(cfg)) == sp.SP_ERR_INVALID_ARG
+    assert sp.sp_create(C.byref(h), None, ptrs, C.byref(cfg)) == sp.SP_ERR_INVALID_ARG
+    assert b"desc" in sp.sp_last_error(None)
+    assert sp.sp_create(C.byref(h), C.byref(d), None, C.byref(cfg)) == sp.SP_ERR_INVALID_ARG
+    assert sp.sp_create(C.byref(h), C.byref(d), ptrs, None) == sp.SP_ERR_INVALID_ARG
+    bad = sp.sp_config(C.sizeof(sp.sp_config), 0, 1, 1 << 30, 4096, None, 8, None, 0)
+    assert sp.sp_create(C.byref(h), C.byref(d), ptrs, C.byref(bad)) == sp.SP_ERR_INVALID_ARG
+    bad = sp.sp_config(C.sizeof(sp.sp_config), 1, 1, 1 << 30, 4097, None, 8, None, 0)       # misaligned arena
+    assert sp.sp_create(C.byref(h), C.byref(d), ptrs, C.byref(bad)) == sp.SP_ERR_INVALID_ARG
+    bad = sp.sp_config(C.sizeof(sp.sp_config), 1, 1, 1 << 30, 4096, None, None, None, 0)    # same streams
+    assert sp.sp_create(C.byref(h), C.byref(d), ptrs, C.byref(bad)) == sp.SP_ERR_INVALID_ARG
+    bad = sp.sp_config(C.sizeof(sp.sp_config), 1, 1, 1 << 30, 4096, None, 8, None, sp.SP_FLAG_TRAINING)
+    assert sp.sp_create(C.byref(h), C.byref(d), ptrs, C.byref(bad)) == sp.SP_ERR_INVALID_ARG  # no d2h stream
+    small = sp.sp_config(C.sizeof(sp.sp_config), 1, 1, 4096, 4096, None, 8, None, 0)
+    assert sp.sp_create(C.byref(h), C.byref(d), ptrs, C.byref(small)) == sp.SP_ERR_BUDGET
+    assert b"budget" in sp.sp_last_error(None)
+    # pageable numpy memory is not pinned host memory
+    assert sp.sp_create(C.byref(h), C.byref(d), ptrs, C.byref(cfg)) == sp.SP_ERR_NOT_PINNED
+    assert not h.value
+    # calls on a handle that was never created
+    assert sp.sp_destroy(None) == sp.SP_ERR_INVALID_ARG
+    fake = C.c_void_p(0x1000)
+    assert sp.sp_destroy(fake) == sp.SP_ERR_STATE
+    assert sp.sp_forward(fake, 16, 16, 1, 1) == sp.SP_ERR_STATE
+    assert sp.sp_get_stats(fake, C.byref(sp.sp_stats())) == sp.SP_ERR_STATE

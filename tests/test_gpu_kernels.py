@@ -1,0 +1,172 @@
+"""Each HIP kernel against the oracle's op, through the C ABI, element by
+element on seeded inputs: sizes span several tiles and a ragged tail."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from oracle import stack_oracle as O  # noqa: E402
+from paper_2410_08791_amd import binding as sp  # noqa: E402
+from tests.gpu_util import (DEV, bf16_vals, dev_f32, dev_u16, host_u16, max_rel, ptr, rand_bf16,  # noqa: E402
+                            stream_ptr)
+
+BF16_EPS = 2.0 ** -8     # half an ulp of bf16, relative
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("T,d", [(37, 256), (5, 4096), (3, 8192), (7, 1280), (1, 64)])
+@pytest.mark.parametrize("ln", [False, True])
+def test_norm(T, d, ln):
+    rng = np.random.default_rng(T * 7 + d + ln)
+    h = (rng.standard_normal((T, d)) * 2 + (0.5 if ln else 0)).astype(np.float32)
+    gb, g = rand_bf16(rng, d, 0.3)
+    g = g + 1.0
+    gb = __import__("paper_2410_08791_amd.synth", fromlist=["x"]).f32_to_bf16_bits(g.astype(np.float32))
+    g = bf16_vals(gb)
+    bb, b = rand_bf16(rng, d, 0.3)
+    out = torch.zeros((T, d), dtype=torch.int16, device=DEV)
+    rc = sp.spk_norm(stream_ptr(), ptr(dev_f32(h)), ptr(dev_u16(gb)), ptr(dev_u16(bb)) if ln else None, ptr(out),
+                     T, d, 1e-5)
+    assert rc == sp.SP_OK
+    sync()
+    got = bf16_vals(host_u16(out))
+    h64 = h.astype(np.float64)
+    ref = O.layernorm(h64, g, b, 1e-5) if ln else O.rmsnorm(h64, g, 1e-5)
+    assert np.all(np.abs(got - ref) <= BF16_EPS * np.abs(ref) + 1e-5)
+
+
+def gemm_ref(A, W, epi, R=None, bias=None, N=None):
+    acc = A @ W.T
+    if bias is not None:
+        acc = acc + bias
+    if epi == sp.EPI_RESID_F32:
+        return R + acc
+    if epi == sp.EPI_GELU_BF16:
+        return O.gelu(acc)
+    if epi == sp.EPI_SWIGLU_BF16:
+        return O.silu(acc[:, :N]) * acc[:, N:]
+    return acc
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3, 0])
+@pytest.mark.parametrize("M,N,K", [(200, 328, 128), (257, 296, 64), (300, 520, 256), (64, 128, 1024)])
+@pytest.mark.parametrize("epi", [sp.EPI_BF16, sp.EPI_RESID_F32, sp.EPI_GELU_BF16, sp.EPI_SWIGLU_BF16, sp.EPI_F32])
+def test_gemm_kmajor(epi, M, N, K, tile):
+    rng = np.random.default_rng(M + N * 3 + K * 5 + epi)
+    Ab, A = rand_bf16(rng, (M, K))
+    nw = 2 * N if epi == sp.EPI_SWIGLU_BF16 else N
+    Wb, W = rand_bf16(rng, (nw, K), 0.1)
+    bias_b, bias = (rand_bf16(rng, N, 0.5) if epi in (sp.EPI_GELU_BF16, sp.EPI_BF16, sp.EPI_RESID_F32) else (None, None))
+    R = rng.standard_normal((M, N)).astype(np.float32)
+    f32out = epi in (sp.EPI_RESID_F32, sp.EPI_F32)
+    Cd = dev_f32(R) if epi == sp.EPI_RESID_F32 else torch.zeros((M, N), dtype=torch.float32 if f32out else torch.int16, device=DEV)
+    Ad, Wd = dev_u16(Ab), dev_u16(Wb)
+    bd = dev_u16(bias_b) if bias_b is not None else None
+    rc = sp.spk_gemm(stream_ptr(), epi, ptr(Ad), K, 0, ptr(Wd), K, 0, ptr(Cd), N,
+                     ptr(Cd) if epi == sp.EPI_RESID_F32 else None, N, ptr(bd), M, N, K, tile)
+    assert rc == sp.SP_OK
+    sync()
+    ref = gemm_ref(A, W, epi, R.astype(np.float64), bias, N)
+    got = Cd.cpu().numpy().astype(np.float64) if f32out else bf16_vals(host_u16(Cd))
+    scale = np.max(np.abs(ref))
+    tol = 2e-6 * np.sqrt(K) * scale + (0 if f32out else BF16_EPS * np.abs(ref))
+    assert np.all(np.abs(got - ref) <= tol + 1e-6), float(np.max(np.abs(got - ref)))
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("M,N,K", [(200, 328, 128), (264, 520, 192)])
+def test_gemm_transposed_operands(M, N, K, tile):
+    """The backward forms: dX = dY W (weight read with its row index contiguous) and
+    dW = dY^T X (both operands transposed on the way in)."""
+    rng = np.random.default_rng(M * 3 + N + K + tile)
+    Ab, A = rand_bf16(rng, (M, K))
+    Wb, W = rand_bf16(rng, (N, K), 0.1)
+    # (0,1): W given as [K, N]
+    WbT = np.ascontiguousarray(Wb.T)
+    C1 = torch.zeros((M, N), dtype=torch.int16, device=DEV)
+    rc = sp.spk_gemm(stream_ptr(), sp.EPI_BF16, ptr(dev_u16(Ab)), K, 0, ptr(dev_u16(WbT)), N, 1, ptr(C1), N,
+                     None, 0, None, M, N, K, tile)
+    assert rc == sp.SP_OK
+    # (1,1): both given transposed, fp32 output
+    AbT = np.ascontiguousarray(Ab.T)
+    C2 = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    rc = sp.spk_gemm(stream_ptr(), sp.EPI_F32, ptr(dev_u16(AbT)), M, 1, ptr(dev_u16(WbT)), N, 1, ptr(C2), N,
+                     None, 0, None, M, N, K, tile)
+    assert rc == sp.SP_OK
+    sync()
+    ref = A @ W.T
+    scale = np.max(np.abs(ref))
+    assert np.all(np.abs(bf16_vals(host_u16(C1)) - ref) <= BF16_EPS * np.abs(ref) + 2e-6 * np.sqrt(K) * scale)
+    assert np.all(np.abs(C2.cpu().numpy() - ref) <= 2e-6 * np.sqrt(K) * scale)
+
+
+def test_gemm_rejects_shapes_it_cannot_take():
+    z = torch.zeros(1 << 16, dtype=torch.int16, device=DEV)
+    args = lambda M, N, K, lda=64, ldw=64, ldc=64: sp.spk_gemm(  # noqa: E731
+        stream_ptr(), sp.EPI_BF16, ptr(z), lda, 0, ptr(z), ldw, 0, ptr(z), ldc, None, 0, None, M, N, K, 0)
+    assert args(8, 8, 63) == sp.SP_ERR_INVALID_ARG        # K not a multiple of 64
+    assert args(8, 7, 64) == sp.SP_ERR_INVALID_ARG        # N not a multiple of 8
+    assert args(8, 8, 64, lda=60) == sp.SP_ERR_INVALID_ARG
+    assert args(0, 8, 64) == sp.SP_OK                     # empty problem: nothing to do
+    assert sp.spk_gemm(stream_ptr(), 9, ptr(z), 64, 0, ptr(z), 64, 0, ptr(z), 64, None, 0, None, 8, 8, 64, 0) == sp.SP_ERR_INVALID_ARG
+    sync()
+
+
+@pytest.mark.parametrize("T,f", [(33, 1024), (7, 11008), (1, 8)])
+def test_swiglu(T, f):
+    rng = np.random.default_rng(T + f)
+    gb, g = rand_bf16(rng, (T, 2 * f), 2.0)
+    z = torch.zeros((T, f), dtype=torch.int16, device=DEV)
+    assert sp.spk_swiglu(stream_ptr(), ptr(dev_u16(gb)), ptr(z), T, f) == sp.SP_OK
+    sync()
+    ref = O.silu(g[:, :f]) * g[:, f:]
+    assert np.all(np.abs(bf16_vals(host_u16(z)) - ref) <= BF16_EPS * np.abs(ref) + 1e-6)
+
+
+@pytest.mark.parametrize("B,S,Hq,Hkv,hd,causal", [
+    (2, 128, 4, 4, 64, 1),      # the tiny workload's shape
+    (3, 257, 4, 4, 80, 0),      # ViT-like: ragged S, head_dim 80, bidirectional
+    (1, 300, 8, 2, 128, 1),     # grouped-query heads, ragged S
+    (2, 64, 2, 1, 128, 0),
+    (1, 1, 2, 2, 64, 1),        # a single token attends to itself
+    (1, 129, 2, 2, 64, 1),      # one query past a block boundary
+])
+def test_attention(B, S, Hq, Hkv, hd, causal):
+    rng = np.random.default_rng(B + S + Hq + hd + causal)
+    nqkv = (Hq + 2 * Hkv) * hd
+    qb, qkv = rand_bf16(rng, (B * S, nqkv))
+    sh = O.StackShape(O.DECODER, 1, Hq * hd, Hq, Hkv, hd, 64, bool(causal))
+    nq, nk = Hq * hd, Hkv * hd
+    q, k, v = qkv[:, :nq], qkv[:, nq:nq + nk], qkv[:, nq + nk:]
+    ref = O.attention(q, k, v, B, S, sh)
+    vt = torch.zeros(sp.spk_attention_scratch_elems(B, S, Hkv, hd), dtype=torch.int16, device=DEV)
+    o = torch.zeros((B * S, nq), dtype=torch.int16, device=DEV)
+    lse = torch.zeros((B, Hq, S), dtype=torch.float32, device=DEV)
+    rc = sp.spk_attention(stream_ptr(), ptr(dev_u16(qb)), ptr(vt), ptr(o), ptr(lse), B, S, Hq, Hkv, hd, causal)
+    assert rc == sp.SP_OK
+    sync()
+    got = bf16_vals(host_u16(o))
+    # probabilities and the output are each rounded to bf16 once
+    assert np.max(np.abs(got - ref)) <= 3 * BF16_EPS * np.max(np.abs(ref))
+    # log-sum-exp of the scaled, masked scores
+    want = np.empty((B, Hq, S))
+    for b in range(B):
+        qb_ = q[b * S:(b + 1) * S].reshape(S, Hq, hd)
+        kb_ = np.repeat(k[b * S:(b + 1) * S].reshape(S, Hkv, hd), Hq // Hkv, axis=1)
+        s = np.einsum("ihd,jhd->hij", qb_, kb_) / np.sqrt(hd)
+        if causal:
+            s = np.where(np.arange(S)[None, :] <= np.arange(S)[:, None], s, -np.inf)
+        m = s.max(-1)
+        want[b] = m + np.log(np.exp(s - m[..., None]).sum(-1))
+    np.testing.assert_allclose(lse.cpu().numpy(), want, rtol=0, atol=2e-4 * max(1.0, np.abs(want).max()))
+
+
+def test_attention_rejects_unsupported_head_dim():
+    z = torch.zeros(1 << 16, dtype=torch.int16, device=DEV)
+    assert sp.spk_attention(stream_ptr(), ptr(z), ptr(z), ptr(z), None, 1, 8, 2, 2, 48, 1) == sp.SP_ERR_INVALID_ARG
+    assert sp.spk_attention(stream_ptr(), ptr(z), ptr(z), ptr(z), None, 1, 8, 3, 2, 64, 1) == sp.SP_ERR_INVALID_ARG
+    sync()

@@ -1,0 +1,114 @@
+"""The window schedule (Sec. 1, Fig. 1, Sec. 3.3) as the library issues it,
+checked on the host: the Fig. 1 worked setting, and by simulating the two
+streams with random durations -- every layer is computed once per pass in
+order, from a slot that holds exactly that layer for the whole compute, with
+at most n_slots layers on the device."""
+import os
+import random
+
+import pytest
+
+from paper_2410_08791_amd import binding as sp
+
+COPY, FWD, BWD = 0, 1, 2
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "fig1_schedule.txt")
+
+
+def test_fig1_setting_matches_the_paper():
+    want = [tuple(l.split()) for l in open(GOLDEN) if l.strip() and not l.startswith("#")]
+    ops = sp.trace_schedule(8, 4, 2)
+    got = [("L" if k == COPY else "X", str(layer)) for k, layer, *_ in ops]
+    assert got == want
+    # never more than k = 4 layers on the device: slots are 0..3
+    assert {s for _, _, s, _, _ in ops} == {0, 1, 2, 3}
+
+
+def simulate(ops, n_layers, n_slots, seed):
+    """Run the op list on a copy stream and a compute stream with random durations."""
+    rnd = random.Random(seed)
+    t_copy = t_comp = 0.0
+    last_copy_end = {}      # layer -> end time of its most recent copy (in issue order)
+    last_comp_end = {}      # layer -> end time of its most recent compute
+    slot_events = {s: [] for s in range(n_slots)}   # (begin, end, kind, layer)
+    computes = []
+    for kind, layer, slot, wait, ps in ops:
+        assert 0 <= slot < n_slots and 0 <= layer < n_layers
+        if kind == COPY:
+            start = t_copy
+            if wait >= 0:
+                start = max(start, last_comp_end.get(wait, 0.0))
+            end = start + rnd.uniform(0.1, 3.0)
+            t_copy = end
+            last_copy_end[layer] = end
+            slot_events[slot].append((start, end, "copy", layer))
+        else:
+            start = max(t_comp, last_copy_end.get(layer, 0.0))
+            end = start + rnd.uniform(0.1, 3.0)
+            t_comp = end
+            last_comp_end[layer] = end
+            slot_events[slot].append((start, end, "comp", layer))
+            computes.append((ps, kind, layer))
+    # per slot: events in issue order must not overlap in time, and every compute
+    # must follow a copy of the same layer with no other copy in between
+    for s, evs in slot_events.items():
+        content = None
+        t = 0.0
+        for b, e, kind, layer in evs:
+            assert b >= t - 1e-12, f"slot {s}: {kind} of layer {layer} starts before the previous op ended"
+            t = e
+            if kind == "copy":
+                content = layer
+            else:
+                assert content == layer, f"slot {s} holds {content}, computing {layer}"
+    return computes
+
+
+@pytest.mark.parametrize("training", [False, True])
+def test_schedule_invariants_over_a_grid(training):
+    for L in range(1, 10):
+        for N in range(1, L + 1):
+            for p in range(1, max(N, 2)):
+                for wrap in ([False, True] if not training else [False]):
+                    passes = 4
+                    ops = sp.trace_schedule(L, N, p, training=training, wrap=wrap, passes=passes)
+                    computes = simulate(ops, L, N, seed=L * 1000 + N * 100 + p * 10 + wrap)
+                    # every layer once per pass, in order (reverse order on backward passes)
+                    for ps in range(passes):
+                        seq = [l for q, k, l in computes if q == ps]
+                        bwd = training and ps % 2 == 1
+                        assert seq == (list(range(L - 1, -1, -1)) if bwd else list(range(L))), (L, N, p, ps)
+                        kinds = {k for q, k, l in computes if q == ps}
+                        assert kinds == ({BWD} if bwd else {FWD})
+                    copies = [(ps, l) for k, l, s, w, ps in ops if k == COPY]
+                    if N == L:      # fully resident: L copies in all, none after the first pass
+                        assert len(copies) == L and all(ps == 0 for ps, _ in copies)
+                    elif training:  # the turn re-uses the N layers still resident
+                        per_pass = [sum(1 for ps, _ in copies if ps == q) for q in range(passes)]
+                        assert per_pass[0] == L and all(c == L - N for c in per_pass[1:]), per_pass
+                    elif wrap:      # steady state: L copies per call, none at the start of a call
+                        per_pass = [sum(1 for ps, _ in copies if ps == q) for q in range(passes)]
+                        assert per_pass[0] == L + N and all(c == L for c in per_pass[1:]), per_pass
+                        for q in range(1, passes):
+                            first = next(i for i, o in enumerate(ops) if o[4] == q)
+                            assert ops[first][0] == FWD
+                    else:           # each layer copied at most once per pass; only layers
+                        for q in range(passes):   # left over from the previous pass are skipped
+                            got = sorted(l for ps, l in copies if ps == q)
+                            assert len(set(got)) == len(got) and L - N <= len(got) <= L
+                        assert sorted(l for ps, l in copies if ps == 0) == list(range(L))
+
+
+def test_refill_happens_in_groups_of_p():
+    ops = sp.trace_schedule(12, 5, 3)
+    kinds = "".join("L" if k == COPY else "X" for k, *_ in ops)
+    assert kinds == "LLLLL" + "XXX" + "LLL" + "XXX" + "LLL" + "XXX" + "L" + "XXX"
+    # a refill waits for exactly the layer it replaces
+    for k, layer, slot, wait, _ in ops:
+        if k == COPY and layer >= 5:
+            assert wait == layer - 5
+
+
+def test_trace_argument_errors():
+    for args in [(0, 1, 1), (4, 0, 1), (4, 5, 1), (4, 2, 0)]:
+        with pytest.raises(sp.SuperpipeError):
+            sp.trace_schedule(*args)
