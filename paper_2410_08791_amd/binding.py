@@ -11,6 +11,9 @@ import ctypes as C
 import os
 
 import numpy as np
+# torch first: its wheel bundles a HIP runtime, and the library must bind to the
+# SAME runtime instance that allocates the pinned and device memory it is handed.
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsuperpipe.so")
@@ -163,6 +166,7 @@ def pinned_blobs(w, desc, n_layers=None, pool=None):
     for l in range(L):
         t = torch.zeros(nbytes, dtype=torch.uint8, pin_memory=True)
         v = blob_views(desc, t.numpy())
+        v = {n: v[n].reshape(shape) for n, shape, _ in synth.tensor_specs(w)}
         synth.fill_layer(v, w, l, pool=pool)
         blobs.append(t)
         views.append(v)
@@ -186,7 +190,10 @@ class Engine:
         self.budget_bytes = int(budget_bytes)
         self.device = torch.device(device)
         with torch.cuda.device(self.device):
-            self.arena = torch.empty(self.budget_bytes, dtype=torch.uint8, device=self.device)
+            # torch hands out 512-byte aligned blocks; take 4 KiB of slack and align by hand
+            self._arena_raw = torch.empty(self.budget_bytes + 4096, dtype=torch.uint8, device=self.device)
+            skew = (-self._arena_raw.data_ptr()) % 4096
+            self.arena = self._arena_raw[skew:skew + self.budget_bytes]
             self.compute = torch.cuda.Stream(device=self.device)
             self.h2d = torch.cuda.Stream(device=self.device)
             self.d2h = torch.cuda.Stream(device=self.device) if training else None
@@ -205,11 +212,14 @@ class Engine:
             raise SuperpipeError(rc, sp_last_error(self.handle).decode())
 
     def forward(self, x, y, B, S):
-        """x, y: fp32 cuda tensors [B,S,d]; enqueues on self.compute."""
+        """x, y: fp32 cuda tensors [B,S,d]; enqueues on self.compute (after whatever
+        torch's current stream has enqueued so far, e.g. the producer of x)."""
+        self.compute.wait_stream(self.torch.cuda.current_stream(self.device))
         self._check(sp_forward(self.handle, x.data_ptr(), y.data_ptr(), B, S))
 
     def forward_backward(self, x, target, y, loss, dx, grad_blobs, B, S):
         ptrs = (C.c_void_p * len(grad_blobs))(*[g.data_ptr() for g in grad_blobs])
+        self.compute.wait_stream(self.torch.cuda.current_stream(self.device))
         self._check(sp_forward_backward(self.handle, x.data_ptr(), target.data_ptr(),
                                         y.data_ptr() if y is not None else None, loss.data_ptr(),
                                         dx.data_ptr() if dx is not None else None, ptrs, B, S))

@@ -19,19 +19,21 @@ struct sp_engine {
     unsigned char* slots = nullptr;
     hipStream_t compute = nullptr, h2d = nullptr, d2h = nullptr;
     std::vector<const void*> blobs;   // pinned host weight blobs (never written)
-    std::vector<hipEvent_t> loaded, done;          // per layer: copy landed / compute finished
-    std::vector<char> loaded_recorded, done_recorded;
+    // Cross-stream fences.  Every copy and every layer compute of a call records
+    // its own event (copy_ev[i] / comp_ev[j], i-th copy / j-th compute of the call);
+    // layer_loaded / layer_done point at the most recent one for a layer.  With
+    // SP_FLAG_TIMING the events carry timestamps and double as the per-layer trace,
+    // so tracing adds no operation to either stream.
+    std::vector<hipEvent_t> copy_ev, comp_ev;
+    std::vector<hipEvent_t> layer_loaded, layer_done;
+    std::vector<int> layer_loaded_idx, layer_done_idx;   // op index within the current call, -1 = earlier call
+    int ci = 0, mi = 0;                                  // ops issued by the current call
+    std::vector<int> tr_copy_layer, tr_copy_dep, tr_comp_layer, tr_comp_dep;
     hipEvent_t ev_sync_c = nullptr, ev_sync_h = nullptr;
     hipEvent_t grad_ready[2] = {nullptr, nullptr}, gslot_free[2] = {nullptr, nullptr};
     char gslot_used[2] = {0, 0};
     int gslot_next = 0;
-    // per-call trace (SP_FLAG_TIMING)
     hipEvent_t t0 = nullptr;
-    hipEvent_t t_copy_begin[SP_MAX_TRACE_LAYERS] = {}, t_copy_end[SP_MAX_TRACE_LAYERS] = {};
-    hipEvent_t t_comp_begin[SP_MAX_TRACE_LAYERS] = {}, t_comp_end[SP_MAX_TRACE_LAYERS] = {};
-    int trace_layer[SP_MAX_TRACE_LAYERS] = {};
-    int copy_layer[SP_MAX_TRACE_LAYERS] = {};
-    int trace_n = 0, copy_n = 0;
     std::vector<hipEvent_t> kt_begin, kt_end;   // ring of event pairs around the largest GEMM
     uint32_t kt_count = 0;                      // pairs recorded since the last sp_get_stats
     int kt_m = 0, kt_n = 0, kt_k = 0;
@@ -57,6 +59,11 @@ int sp_layer_forward_train(sp_engine* e, int layer, const unsigned char* w, int 
 // Recompute + backward of layer l; leaves dL/d(input) in the stream-gradient buffer
 // and hands the layer's fp32 weight gradients to the device-to-host stream.
 int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, int S);
+
+// Training call phases around the two passes (sp_train.hip).
+int sp_train_begin(sp_engine* e, const float* x_dev, int B, int S);
+int sp_train_loss(sp_engine* e, const float* target_dev, float* loss_dev, int B, int S);
+int sp_train_end(sp_engine* e, float* dx_dev, int B, int S);
 
 int sp_fail(sp_engine* e, int code, const char* fmt, ...);
 

@@ -4,11 +4,13 @@
 // HBM holds n_slots layer-sized slots carved from the caller's arena.  The
 // scheduler (sp_host.hip) decides which layer goes to which slot; this file
 // turns each decision into stream work:
-//   copy(l -> slot):  h2d stream waits done[prev user of slot]; one
-//                     hipMemcpyAsync of the whole layer blob; record loaded[l]
-//   compute(l):       compute stream waits loaded[l]; the layer's kernels;
-//                     record done[l]
-// Those two event kinds are the only cross-stream edges.  An event is always
+//   copy(l -> slot):  h2d stream waits for the compute of the slot's previous
+//                     user; one hipMemcpyAsync of the whole layer blob; record
+//                     a "loaded" event
+//   compute(l):       compute stream waits for l's "loaded" event; the layer's
+//                     kernels; record a "done" event
+// Those two event kinds are the only cross-stream edges (training adds the pair
+// that fences the two gradient slots against the device-to-host stream).  An event is always
 // recorded (in host order) before anything waits on it.  Nothing here blocks
 // the host, and no device memory is allocated.
 #include <hip/hip_runtime.h>
@@ -59,27 +61,30 @@ struct HipSink : SchedSink {
 
     int copy(int layer, int slot, int wait_layer) override {
         hipStream_t cs = e->h2d;
+        if (e->ci >= (int)e->copy_ev.size()) return sp_fail(e, SP_ERR_STATE, "copy event pool exhausted");
+        int dep = -1;
         if (e->flags & SP_FLAG_NO_OVERLAP) {
             // Naive comparator: a copy starts only after everything enqueued for compute.
             SP_HIP(e, hipEventRecord(e->ev_sync_c, e->compute));
             SP_HIP(e, hipStreamWaitEvent(cs, e->ev_sync_c, 0));
-        } else if (wait_layer >= 0 && e->done_recorded[wait_layer]) {
-            SP_HIP(e, hipStreamWaitEvent(cs, e->done[wait_layer], 0));
+            dep = e->mi - 1;
+        } else if (wait_layer >= 0 && e->layer_done[wait_layer]) {
+            SP_HIP(e, hipStreamWaitEvent(cs, e->layer_done[wait_layer], 0));
+            dep = e->layer_done_idx[wait_layer];
         }
         unsigned char* dst = e->slots + (size_t)slot * e->plan.slot_bytes;
         if (e->flags & SP_FLAG_POISON) {
             // bf16 NaN pattern: a read of a slot before its copy lands shows up as NaN output
             SP_HIP(e, spk_launch_fill_u32(cs, reinterpret_cast<uint32_t*>(dst), 0x7FC17FC1u, e->plan.slot_bytes / 4));
         }
-        const bool timed = (e->flags & SP_FLAG_TIMING) && e->copy_n < SP_MAX_TRACE_LAYERS;
-        if (timed) SP_HIP(e, hipEventRecord(e->t_copy_begin[e->copy_n], cs));
         SP_HIP(e, hipMemcpyAsync(dst, e->blobs[layer], e->lay.blob_bytes, hipMemcpyHostToDevice, cs));
-        if (timed) {
-            SP_HIP(e, hipEventRecord(e->t_copy_end[e->copy_n], cs));
-            e->copy_layer[e->copy_n++] = layer;
-        }
-        SP_HIP(e, hipEventRecord(e->loaded[layer], cs));
-        e->loaded_recorded[layer] = 1;
+        hipEvent_t ev = e->copy_ev[e->ci];
+        SP_HIP(e, hipEventRecord(ev, cs));
+        e->layer_loaded[layer] = ev;
+        e->layer_loaded_idx[layer] = e->ci;
+        e->tr_copy_layer[e->ci] = layer;
+        e->tr_copy_dep[e->ci] = dep;
+        e->ci++;
         e->stats_h2d_copies++;
         e->stats_h2d_bytes += e->lay.blob_bytes;
         e->call_h2d_copies++;
@@ -89,29 +94,31 @@ struct HipSink : SchedSink {
 
     int compute(int layer, int slot, int dir, bool /*fresh*/) override {
         hipStream_t st = e->compute;
+        if (e->mi >= (int)e->comp_ev.size()) return sp_fail(e, SP_ERR_STATE, "compute event pool exhausted");
+        int dep = -1;
         if (e->flags & SP_FLAG_NO_OVERLAP) {
             // Naive comparator: compute starts only after every copy enqueued so far.
             SP_HIP(e, hipEventRecord(e->ev_sync_h, e->h2d));
             SP_HIP(e, hipStreamWaitEvent(st, e->ev_sync_h, 0));
-        } else if (e->loaded_recorded[layer]) {
-            SP_HIP(e, hipStreamWaitEvent(st, e->loaded[layer], 0));
+            dep = e->ci - 1;
+        } else if (e->layer_loaded[layer]) {
+            SP_HIP(e, hipStreamWaitEvent(st, e->layer_loaded[layer], 0));
+            dep = e->layer_loaded_idx[layer];
         }
         const unsigned char* w = e->slots + (size_t)slot * e->plan.slot_bytes;
-        const bool timed = (e->flags & SP_FLAG_TIMING) && e->trace_n < SP_MAX_TRACE_LAYERS;
-        if (timed) SP_HIP(e, hipEventRecord(e->t_comp_begin[e->trace_n], st));
         int rc;
         if (dir > 0)
             rc = training_fwd ? sp_layer_forward_train(e, layer, w, B, S) : sp_layer_forward(e, w, hbuf, B, S);
         else
             rc = sp_layer_backward(e, layer, w, B, S);
         if (rc != SP_OK) return rc;
-        if (timed) {
-            SP_HIP(e, hipEventRecord(e->t_comp_end[e->trace_n], st));
-            e->trace_layer[e->trace_n] = layer;
-            e->trace_n++;
-        }
-        SP_HIP(e, hipEventRecord(e->done[layer], st));
-        e->done_recorded[layer] = 1;
+        hipEvent_t ev = e->comp_ev[e->mi];
+        SP_HIP(e, hipEventRecord(ev, st));
+        e->layer_done[layer] = ev;
+        e->layer_done_idx[layer] = e->mi;
+        e->tr_comp_layer[e->mi] = layer;
+        e->tr_comp_dep[e->mi] = dep;
+        e->mi++;
         return SP_OK;
     }
 };
@@ -232,33 +239,31 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     e->d2h = static_cast<hipStream_t>(cfg->d2h_stream);
     e->blobs.assign(blobs, blobs + desc->n_layers);
     const int L = desc->n_layers;
-    e->loaded.assign(L, nullptr);
-    e->done.assign(L, nullptr);
-    e->loaded_recorded.assign(L, 0);
-    e->done_recorded.assign(L, 0);
-    const unsigned evflags = (cfg->flags & SP_FLAG_TIMING) ? hipEventDefault : hipEventDisableTiming;
+    const bool timing = cfg->flags & SP_FLAG_TIMING;
+    // a call issues at most 2L + n_slots copies and 2L computes (forward + backward)
+    e->copy_ev.assign((training ? 2 : 1) * L + plan.n_slots + 1, nullptr);
+    e->comp_ev.assign((training ? 2 : 1) * L + 1, nullptr);
+    e->tr_copy_layer.assign(e->copy_ev.size(), -1);
+    e->tr_copy_dep.assign(e->copy_ev.size(), -1);
+    e->tr_comp_layer.assign(e->comp_ev.size(), -1);
+    e->tr_comp_dep.assign(e->comp_ev.size(), -1);
+    e->layer_loaded.assign(L, nullptr);
+    e->layer_done.assign(L, nullptr);
+    e->layer_loaded_idx.assign(L, -1);
+    e->layer_done_idx.assign(L, -1);
+    const unsigned evflags = timing ? hipEventDefault : hipEventDisableTiming;
     auto mk = [&](hipEvent_t* ev, unsigned fl) { return hipEventCreateWithFlags(ev, fl); };
     hipError_t he = hipSuccess;
-    for (int l = 0; l < L && he == hipSuccess; ++l) {
-        he = mk(&e->loaded[l], evflags);
-        if (he == hipSuccess) he = mk(&e->done[l], evflags);
-    }
+    for (size_t i = 0; i < e->copy_ev.size() && he == hipSuccess; ++i) he = mk(&e->copy_ev[i], evflags);
+    for (size_t i = 0; i < e->comp_ev.size() && he == hipSuccess; ++i) he = mk(&e->comp_ev[i], evflags);
     if (he == hipSuccess) he = mk(&e->ev_sync_c, hipEventDisableTiming);
     if (he == hipSuccess) he = mk(&e->ev_sync_h, hipEventDisableTiming);
     for (int i = 0; i < 2 && he == hipSuccess; ++i) {
         he = mk(&e->grad_ready[i], hipEventDisableTiming);
         if (he == hipSuccess) he = mk(&e->gslot_free[i], hipEventDisableTiming);
     }
-    if (he == hipSuccess && (cfg->flags & SP_FLAG_TIMING)) {
+    if (he == hipSuccess && timing) {
         he = mk(&e->t0, hipEventDefault);
-        for (int i = 0; i < SP_MAX_TRACE_LAYERS && he == hipSuccess; ++i) {
-            he = mk(&e->t_copy_begin[i], hipEventDefault);
-            if (he == hipSuccess) he = mk(&e->t_copy_end[i], hipEventDefault);
-            if (he == hipSuccess) he = mk(&e->t_comp_begin[i], hipEventDefault);
-            if (he == hipSuccess) he = mk(&e->t_comp_end[i], hipEventDefault);
-        }
-    }
-    if (he == hipSuccess && (cfg->flags & SP_FLAG_TIMING)) {
         e->kt_begin.assign(2048, nullptr);
         e->kt_end.assign(2048, nullptr);
         for (size_t i = 0; i < e->kt_begin.size() && he == hipSuccess; ++i) {
@@ -273,10 +278,10 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     }
     const bool naive = cfg->flags & SP_FLAG_NO_OVERLAP;
     e->sched.reset(L, plan.n_slots, naive ? plan.n_slots : plan.p_eff);
-    e->fuse_swiglu = !training;
+    e->fuse_swiglu = true;
     e->gemm_tile = 0;
     if (const char* t = getenv("SP_GEMM_TILE")) e->gemm_tile = atoi(t);
-    if (const char* t = getenv("SP_FUSE_SWIGLU")) e->fuse_swiglu = atoi(t) != 0 && !training;
+    if (const char* t = getenv("SP_FUSE_SWIGLU")) e->fuse_swiglu = atoi(t) != 0;
     if (training) {
         // padded token rows of the GEMM-operand buffers must read as zero
         hipError_t fe = spk_launch_fill_u32(e->compute, reinterpret_cast<uint32_t*>(e->arena), 0u, e->ws.total / 4);
@@ -304,8 +309,9 @@ static int check_call(sp_engine* e, int B, int S) {
 
 static int begin_call(sp_engine* e) {
     e->call_h2d_copies = e->call_h2d_bytes = 0;
-    e->trace_n = 0;
-    e->copy_n = 0;
+    e->ci = e->mi = 0;
+    std::fill(e->layer_loaded_idx.begin(), e->layer_loaded_idx.end(), -1);
+    std::fill(e->layer_done_idx.begin(), e->layer_done_idx.end(), -1);
     if (e->flags & SP_FLAG_TIMING) SP_HIP(e, hipEventRecord(e->t0, e->compute));
     return SP_OK;
 }
@@ -324,6 +330,33 @@ extern "C" int sp_forward(sp_handle e, const float* x_dev, float* y_dev, int B, 
     const bool wrap = (e->flags & SP_FLAG_WRAP_PREFETCH) && !(e->flags & SP_FLAG_TRAINING);
     rc = e->sched.run_pass(+1, wrap, sink);
     if (rc != SP_OK) return rc;
+    e->calls++;
+    return SP_OK;
+}
+
+extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float* target_dev, float* y_dev,
+                                   float* loss_dev, float* dx_dev, void* const* grad_host_blobs, int B, int S) {
+    int rc = check_call(e, B, S);
+    if (rc != SP_OK) return rc;
+    if (!(e->flags & SP_FLAG_TRAINING)) return fail(e, SP_ERR_STATE, "handle was created without SP_FLAG_TRAINING");
+    if (!x_dev || !target_dev || !loss_dev || !grad_host_blobs) return fail(e, SP_ERR_INVALID_ARG, "NULL argument");
+    if (((uintptr_t)x_dev | (uintptr_t)target_dev | (uintptr_t)y_dev | (uintptr_t)dx_dev) & 15)
+        return fail(e, SP_ERR_INVALID_ARG, "device tensors must be 16-byte aligned");
+    for (int l = 0; l < e->desc.n_layers; ++l)
+        if (!grad_host_blobs[l]) return fail(e, SP_ERR_INVALID_ARG, "grad_host_blobs[%d] is NULL", l);
+    if ((rc = begin_call(e)) != SP_OK) return rc;
+    e->grad_blobs = grad_host_blobs;
+    e->y_out = y_dev;
+    if ((rc = sp_train_begin(e, x_dev, B, S)) != SP_OK) return rc;
+    HipSink sink(e);
+    sink.B = B;
+    sink.S = S;
+    sink.training_fwd = true;
+    if ((rc = e->sched.run_pass(+1, false, sink)) != SP_OK) return rc;
+    if ((rc = sp_train_loss(e, target_dev, loss_dev, B, S)) != SP_OK) return rc;
+    sink.training_fwd = false;
+    if ((rc = e->sched.run_pass(-1, false, sink)) != SP_OK) return rc;
+    if ((rc = sp_train_end(e, dx_dev, B, S)) != SP_OK) return rc;
     e->calls++;
     return SP_OK;
 }
@@ -356,44 +389,54 @@ extern "C" int sp_get_stats(sp_handle e, sp_stats* out) {
         out->big_gemm_m = e->kt_m; out->big_gemm_n = e->kt_n; out->big_gemm_k = e->kt_k;
         e->kt_count = 0;
     }
-    const int n = e->trace_n;
-    out->n_timed = n;
-    std::vector<std::pair<float, float>> comp(n);
-    float tmin = 1e30f, tmax = -1e30f;
-    for (int i = 0; i < n; ++i) {
-        float b = 0, en = 0;
-        SP_HIP(e, hipEventElapsedTime(&b, e->t0, e->t_comp_begin[i]));
-        SP_HIP(e, hipEventElapsedTime(&en, e->t0, e->t_comp_end[i]));
-        out->comp_begin_ms[i] = b;
-        out->comp_end_ms[i] = en;
-        out->copy_begin_ms[i] = out->copy_end_ms[i] = -1.f;
-        comp[i] = {b, en};
-        out->compute_busy_ms += en - b;
-        tmin = std::min(tmin, b);
-        tmax = std::max(tmax, en);
+    // Per-op trace of the most recent call from the fence events' timestamps.  An op
+    // begins when its stream's previous op has ended and its dependency is met.
+    const int nc = e->ci, nm = e->mi;
+    std::vector<float> tc(nc), tm(nm), cb(nc), mb(nm);
+    for (int i = 0; i < nc; ++i) SP_HIP(e, hipEventElapsedTime(&tc[i], e->t0, e->copy_ev[i]));
+    for (int j = 0; j < nm; ++j) SP_HIP(e, hipEventElapsedTime(&tm[j], e->t0, e->comp_ev[j]));
+    for (int i = 0; i < nc; ++i) {
+        float b = i > 0 ? tc[i - 1] : std::min(0.f, tc[i]);
+        const int dep = e->tr_copy_dep[i];
+        if (dep >= 0 && dep < nm) b = std::max(b, tm[dep]);
+        cb[i] = std::min(b, tc[i]);
     }
-    std::sort(comp.begin(), comp.end());
-    const int nc = e->copy_n;
-    for (int c = 0; c < nc; ++c) {
-        float b = 0, en = 0;
-        SP_HIP(e, hipEventElapsedTime(&b, e->t0, e->t_copy_begin[c]));
-        SP_HIP(e, hipEventElapsedTime(&en, e->t0, e->t_copy_end[c]));
-        // attach to the first traced compute of that layer (reporting only)
-        for (int i = 0; i < n; ++i)
-            if (e->trace_layer[i] == e->copy_layer[c] && out->copy_begin_ms[i] < 0.f && out->comp_begin_ms[i] >= b) {
-                out->copy_begin_ms[i] = b;
-                out->copy_end_ms[i] = en;
-                break;
+    for (int j = 0; j < nm; ++j) {
+        float b = j > 0 ? tm[j - 1] : 0.f;
+        const int dep = e->tr_comp_dep[j];
+        if (dep >= 0 && dep < nc) b = std::max(b, tc[dep]);
+        mb[j] = std::min(b, tm[j]);
+    }
+    std::vector<std::pair<float, float>> comp(nm);
+    float tmin = 1e30f, tmax = -1e30f;
+    const int n = std::min(nm, (int)SP_MAX_TRACE_LAYERS);
+    out->n_timed = n;
+    for (int j = 0; j < nm; ++j) {
+        comp[j] = {mb[j], tm[j]};
+        out->compute_busy_ms += tm[j] - mb[j];
+        tmin = std::min(tmin, mb[j]);
+        tmax = std::max(tmax, tm[j]);
+        if (j < n) {
+            out->comp_begin_ms[j] = mb[j];
+            out->comp_end_ms[j] = tm[j];
+            out->copy_begin_ms[j] = out->copy_end_ms[j] = -1.f;
+            const int dep = e->tr_comp_dep[j];
+            if (dep >= 0 && dep < nc && e->tr_copy_layer[dep] == e->tr_comp_layer[j]) {
+                out->copy_begin_ms[j] = cb[dep];
+                out->copy_end_ms[j] = tc[dep];
             }
-        out->copy_busy_ms += en - b;
+        }
+    }
+    for (int i = 0; i < nc; ++i) {
+        out->copy_busy_ms += tc[i] - cb[i];
         for (auto& iv : comp) {
-            const float lo = std::max(b, iv.first), hi = std::min(en, iv.second);
+            const float lo = std::max(cb[i], iv.first), hi = std::min(tc[i], iv.second);
             if (hi > lo) out->copy_hidden_ms += hi - lo;
         }
-        tmin = std::min(tmin, b);
-        tmax = std::max(tmax, en);
+        tmin = std::min(tmin, cb[i]);
+        tmax = std::max(tmax, tc[i]);
     }
-    out->wall_ms = (n || nc) ? tmax - tmin : 0.f;
+    out->wall_ms = (nm || nc) ? tmax - tmin : 0.f;
     return SP_OK;
 }
 
@@ -411,27 +454,15 @@ static int destroy_engine(sp_engine* e) {
     (void)hipStreamSynchronize(e->compute);
     if (e->d2h) (void)hipStreamSynchronize(e->d2h);
     auto kill = [](hipEvent_t ev) { if (ev) (void)hipEventDestroy(ev); };
-    for (auto ev : e->loaded) kill(ev);
-    for (auto ev : e->done) kill(ev);
+    for (auto ev : e->copy_ev) kill(ev);
+    for (auto ev : e->comp_ev) kill(ev);
+    for (auto ev : e->kt_begin) kill(ev);
+    for (auto ev : e->kt_end) kill(ev);
     kill(e->ev_sync_c);
     kill(e->ev_sync_h);
     kill(e->t0);
     for (int i = 0; i < 2; ++i) { kill(e->grad_ready[i]); kill(e->gslot_free[i]); }
-    for (auto ev : e->kt_begin) kill(ev);
-    for (auto ev : e->kt_end) kill(ev);
-    for (int i = 0; i < SP_MAX_TRACE_LAYERS; ++i) {
-        kill(e->t_copy_begin[i]); kill(e->t_copy_end[i]); kill(e->t_comp_begin[i]); kill(e->t_comp_end[i]);
-    }
     (void)hipGetLastError();
     delete e;
     return SP_OK;
-}
-
-extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float* target_dev, float* y_dev,
-                                   float* loss_dev, float* dx_dev, void* const* grad_host_blobs, int B, int S) {
-    int rc = check_call(e, B, S);
-    if (rc != SP_OK) return rc;
-    if (!(e->flags & SP_FLAG_TRAINING)) return fail(e, SP_ERR_STATE, "handle was created without SP_FLAG_TRAINING");
-    (void)x_dev; (void)target_dev; (void)y_dev; (void)loss_dev; (void)dx_dev; (void)grad_host_blobs;
-    return fail(e, SP_ERR_STATE, "training path not built");
 }

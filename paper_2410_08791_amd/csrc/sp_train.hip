@@ -8,3 +8,6 @@ int sp_layer_forward_train(sp_engine* e, int, const unsigned char*, int, int) {
 int sp_layer_backward(sp_engine* e, int, const unsigned char*, int, int) {
     return sp_fail(e, SP_ERR_STATE, "training path not built");
 }
+int sp_train_begin(sp_engine* e, const float*, int, int) { return sp_fail(e, SP_ERR_STATE, "training path not built"); }
+int sp_train_loss(sp_engine* e, const float*, float*, int, int) { return sp_fail(e, SP_ERR_STATE, "training path not built"); }
+int sp_train_end(sp_engine* e, float*, int, int) { return sp_fail(e, SP_ERR_STATE, "training path not built"); }

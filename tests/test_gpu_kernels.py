@@ -29,8 +29,8 @@ def test_norm(T, d, ln):
     g = bf16_vals(gb)
     bb, b = rand_bf16(rng, d, 0.3)
     out = torch.zeros((T, d), dtype=torch.int16, device=DEV)
-    rc = sp.spk_norm(stream_ptr(), ptr(dev_f32(h)), ptr(dev_u16(gb)), ptr(dev_u16(bb)) if ln else None, ptr(out),
-                     T, d, 1e-5)
+    hd, gd, bd = dev_f32(h), dev_u16(gb), dev_u16(bb)      # keep the device buffers alive
+    rc = sp.spk_norm(stream_ptr(), ptr(hd), ptr(gd), ptr(bd) if ln else None, ptr(out), T, d, 1e-5)
     assert rc == sp.SP_OK
     sync()
     got = bf16_vals(host_u16(out))
@@ -88,13 +88,15 @@ def test_gemm_transposed_operands(M, N, K, tile):
     # (0,1): W given as [K, N]
     WbT = np.ascontiguousarray(Wb.T)
     C1 = torch.zeros((M, N), dtype=torch.int16, device=DEV)
-    rc = sp.spk_gemm(stream_ptr(), sp.EPI_BF16, ptr(dev_u16(Ab)), K, 0, ptr(dev_u16(WbT)), N, 1, ptr(C1), N,
+    Ad, WTd = dev_u16(Ab), dev_u16(WbT)
+    rc = sp.spk_gemm(stream_ptr(), sp.EPI_BF16, ptr(Ad), K, 0, ptr(WTd), N, 1, ptr(C1), N,
                      None, 0, None, M, N, K, tile)
     assert rc == sp.SP_OK
     # (1,1): both given transposed, fp32 output
     AbT = np.ascontiguousarray(Ab.T)
     C2 = torch.zeros((M, N), dtype=torch.float32, device=DEV)
-    rc = sp.spk_gemm(stream_ptr(), sp.EPI_F32, ptr(dev_u16(AbT)), M, 1, ptr(dev_u16(WbT)), N, 1, ptr(C2), N,
+    ATd = dev_u16(AbT)
+    rc = sp.spk_gemm(stream_ptr(), sp.EPI_F32, ptr(ATd), M, 1, ptr(WTd), N, 1, ptr(C2), N,
                      None, 0, None, M, N, K, tile)
     assert rc == sp.SP_OK
     sync()
@@ -121,7 +123,8 @@ def test_swiglu(T, f):
     rng = np.random.default_rng(T + f)
     gb, g = rand_bf16(rng, (T, 2 * f), 2.0)
     z = torch.zeros((T, f), dtype=torch.int16, device=DEV)
-    assert sp.spk_swiglu(stream_ptr(), ptr(dev_u16(gb)), ptr(z), T, f) == sp.SP_OK
+    gd = dev_u16(gb)
+    assert sp.spk_swiglu(stream_ptr(), ptr(gd), ptr(z), T, f) == sp.SP_OK
     sync()
     ref = O.silu(g[:, :f]) * g[:, f:]
     assert np.all(np.abs(bf16_vals(host_u16(z)) - ref) <= BF16_EPS * np.abs(ref) + 1e-6)
@@ -146,7 +149,8 @@ def test_attention(B, S, Hq, Hkv, hd, causal):
     vt = torch.zeros(sp.spk_attention_scratch_elems(B, S, Hkv, hd), dtype=torch.int16, device=DEV)
     o = torch.zeros((B * S, nq), dtype=torch.int16, device=DEV)
     lse = torch.zeros((B, Hq, S), dtype=torch.float32, device=DEV)
-    rc = sp.spk_attention(stream_ptr(), ptr(dev_u16(qb)), ptr(vt), ptr(o), ptr(lse), B, S, Hq, Hkv, hd, causal)
+    qd = dev_u16(qb)
+    rc = sp.spk_attention(stream_ptr(), ptr(qd), ptr(vt), ptr(o), ptr(lse), B, S, Hq, Hkv, hd, causal)
     assert rc == sp.SP_OK
     sync()
     got = bf16_vals(host_u16(o))

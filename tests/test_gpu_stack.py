@@ -113,7 +113,8 @@ def test_smaller_batch_and_ragged_sequence(tiny):
     x = synth.make_input(w, seed=5)
     eng = sp.Engine(tiny.desc, tiny.blobs, 1, 1)
     y = torch.empty((1, 77, w.d_model), dtype=torch.float32, device=DEV)
-    eng.forward(dev_f32(x), y, 1, 77)
+    xd = dev_f32(x)
+    eng.forward(xd, y, 1, 77)
     eng.sync()
     ref = O.stack_forward(x, tiny.views, 1, 77, oracle_shape(w), dtype=np.float64)
     assert max_rel(y.cpu().numpy().reshape(77, -1), ref) <= TOL
