@@ -50,6 +50,28 @@ size_t spk_attention_scratch_elems(int B, int S, int Hkv, int hd);
 int spk_attention(void* stream, const uint16_t* qkv, uint16_t* vt_scratch, uint16_t* o, float* lse,
                   int B, int S, int Hq, int Hkv, int hd, int causal);
 
+/* ---- backward steps (training, Sec. 3.3) ---- */
+
+/* loss[0] = mean((y-t)^2) over n fp32 elements; dy fp32 [n] = 2 (y-t)/n; dy_bf16 the same rounded.
+ * scratch: 1024 floats. */
+int spk_mse(void* stream, const float* y, const float* t, float* dy, uint16_t* dy_bf16, float* scratch,
+            float* loss, size_t n);
+
+/* gu = [g | u] bf16 [T,2f] is overwritten by [dL/dg | dL/du] given dz bf16 [T,f]. */
+int spk_swiglu_bwd(void* stream, const uint16_t* dz, uint16_t* gu, int T, int f);
+
+/* RMSNorm backward.  da fp32 [T,d] = gradient w.r.t. the normed output, h fp32 [T,d] the norm
+ * input, gain bf16 [d].  dh_io fp32 [T,d] += gradient w.r.t. h; dh_bf16 = bf16(dh_io);
+ * dgain fp32 [d] = sum_t da*h*rsqrt(mean(h^2)+eps).  scratch: 256*d floats. */
+int spk_rmsnorm_bwd(void* stream, const float* da, const float* h, const uint16_t* gain, float* dh_io,
+                    uint16_t* dh_bf16, float* scratch, float* dgain, int T, int d, float eps);
+
+/* Attention backward.  qkv as in spk_attention, o and lse its outputs, dO bf16 [B*S, Hq*hd].
+ * dqkv bf16 (layout of qkv) receives dq, dk, dv.  scratch: spk_attention_bwd_scratch_bytes bytes. */
+size_t spk_attention_bwd_scratch_bytes(int B, int S, int Hq, int Hkv, int hd);
+int spk_attention_bwd(void* stream, const uint16_t* qkv, const uint16_t* o, const uint16_t* dO, const float* lse,
+                      void* scratch, uint16_t* dqkv, int B, int S, int Hq, int Hkv, int hd, int causal);
+
 #ifdef __cplusplus
 }
 #endif

@@ -236,6 +236,12 @@ def _layernorm_bwd(da, h, g, eps):
     return dh, dg, db
 
 
+def _swiglu_bwd(dz, g, u):
+    """z = silu(g) * u  ->  dg = dz u silu'(g), du = dz silu(g); silu'(g) = s (1 + g (1 - s)), s = sigmoid(g)."""
+    s = 1.0 / (1.0 + np.exp(-g))
+    return dz * u * (s * (1.0 + g * (1.0 - s))), dz * (g * s)
+
+
 def _linear_bwd(dy, x, w):
     """y = x W^T + b  ->  dx = dy W, dW = dy^T x, db = column sums of dy."""
     return dy @ w, dy.T @ x, np.sum(dy, axis=0)
@@ -274,10 +280,7 @@ def layer_backward(dh2, c, w, B, S, shape: StackShape):
     gr = {}
     if shape.arch == DECODER:
         dz, gr["wd"], _ = _linear_bwd(dh2, c["z"], w["wd"])
-        g, u = c["g"], c["u"]
-        s = 1.0 / (1.0 + np.exp(-g))
-        dg = dz * u * (s * (1.0 + g * (1.0 - s)))
-        du = dz * (g * s)
+        dg, du = _swiglu_bwd(dz, c["g"], c["u"])
         dgu = np.concatenate([dg, du], axis=1)
         dm, gr["wgu"], _ = _linear_bwd(dgu, c["m"], w["wgu"])
         dh1n, gr["g2"] = _rmsnorm_bwd(dm, c["h1"], w["g2"], eps)

@@ -97,6 +97,11 @@ _sig = {
     "spk_attention_scratch_elems": (C.c_size_t, [C.c_int, C.c_int, C.c_int, C.c_int]),
     "spk_attention": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                 C.c_int, C.c_int, C.c_int, C.c_int]),
+    "spk_mse": (C.c_int, [C.c_void_p] * 7 + [C.c_size_t]),
+    "spk_swiglu_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
+    "spk_rmsnorm_bwd": (C.c_int, [C.c_void_p] * 8 + [C.c_int, C.c_int, C.c_float]),
+    "spk_attention_bwd_scratch_bytes": (C.c_size_t, [C.c_int] * 5),
+    "spk_attention_bwd": (C.c_int, [C.c_void_p] * 7 + [C.c_int] * 6),
 }
 for _n, (_r, _a) in _sig.items():
     _f = getattr(lib, _n)          # AttributeError here = header/library mismatch

@@ -181,35 +181,41 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
     }
 }
 
-// vt[b][kvh][e][s] = v[b*S+s][kvh*hd+e]: 64x64 tiles through LDS.
-__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ vt,
-                                                          int S, int S_pad, int Hq, int Hkv, int hd, int hdp,
-                                                          int ld_qkv) {
+// dst[b][h][e][s] = src[(b*S+s)*ld + col0 + h*hd + e]: 64x64 tiles through LDS.
+__global__ __launch_bounds__(256) void transpose_heads_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                                                              int S, int S_pad, int nheads, int hd, int hdp, int ld,
+                                                              int col0) {
     __shared__ bf16_t tile[64][66];
     const int s0 = blockIdx.x * 64, e0 = blockIdx.y * 64;
-    const int bh = blockIdx.z, b = bh / Hkv, kvh = bh % Hkv;
-    const bf16_t* src = qkv + (size_t)b * S * ld_qkv + (size_t)(Hq + Hkv) * hd + (size_t)kvh * hd;
+    const int bh = blockIdx.z, b = bh / nheads, hh = bh % nheads;
+    const bf16_t* sp = src + (size_t)b * S * ld + col0 + (size_t)hh * hd;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int r = ty; r < 64; r += 4) {
         const int s = s0 + r, e = e0 + tx;
-        tile[r][tx] = (s < S && e < hd) ? src[(size_t)s * ld_qkv + e] : (bf16_t)0;
+        tile[r][tx] = (s < S && e < hd) ? sp[(size_t)s * ld + e] : (bf16_t)0;
     }
     __syncthreads();
-    bf16_t* dst = vt + ((size_t)b * Hkv + kvh) * hdp * S_pad;
+    bf16_t* dp = dst + (size_t)bh * hdp * S_pad;
     for (int r = ty; r < 64; r += 4) {
         const int e = e0 + r, s = s0 + tx;
-        if (e < hdp && s < S_pad) dst[(size_t)e * S_pad + s] = tile[tx][r];
+        if (e < hdp && s < S_pad) dp[(size_t)e * S_pad + s] = tile[tx][r];
     }
 }
 
 }  // namespace
 
-hipError_t spk_launch_transpose_v(hipStream_t st, const bf16_t* qkv, bf16_t* vt, const AttnShape& a) {
-    if (a.B <= 0 || a.S <= 0) return hipSuccess;
-    const int hdp = attn_hd_pad(a.hd), sp = attn_s_pad(a.S);
-    dim3 grid(sp / 64, (hdp + 63) / 64, a.B * a.Hkv);
-    transpose_v_kernel<<<grid, 256, 0, st>>>(qkv, vt, a.S, sp, a.Hq, a.Hkv, a.hd, hdp, a.ld_qkv);
+hipError_t spk_launch_transpose_heads(hipStream_t st, const bf16_t* src, int ld, int col0, int nheads, int B, int S,
+                                      int hd, bf16_t* dst) {
+    if (B <= 0 || S <= 0 || nheads <= 0) return hipSuccess;
+    if ((size_t)B * nheads > 65535) return hipErrorInvalidValue;
+    const int hdp = attn_hd_pad(hd), sp = attn_s_pad(S);
+    dim3 grid(sp / 64, (hdp + 63) / 64, B * nheads);
+    transpose_heads_kernel<<<grid, 256, 0, st>>>(src, dst, S, sp, nheads, hd, hdp, ld, col0);
     return hipGetLastError();
+}
+
+hipError_t spk_launch_transpose_v(hipStream_t st, const bf16_t* qkv, bf16_t* vt, const AttnShape& a) {
+    return spk_launch_transpose_heads(st, qkv, a.ld_qkv, (a.Hq + a.Hkv) * a.hd, a.Hkv, a.B, a.S, a.hd, vt);
 }
 
 hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, const bf16_t* vt, bf16_t* o, float* lse,

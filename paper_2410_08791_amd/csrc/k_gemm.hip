@@ -355,6 +355,7 @@ hipError_t spk_launch_gemm(hipStream_t st, int epi, const GemmArgs& g) {
             if (forms == 0 && !g.bias) return launch_tile<EPI_SWIGLU_BF16, OP_KMAJOR, OP_KMAJOR>(st, g);
             break;
         case EPI_F32:
+            if (forms == 1) return launch_tile<EPI_F32, OP_KMAJOR, OP_RMAJOR>(st, g);
             if (forms == 3) return launch_tile<EPI_F32, OP_RMAJOR, OP_RMAJOR>(st, g);
             if (forms == 0) return launch_tile<EPI_F32, OP_KMAJOR, OP_KMAJOR>(st, g);
             break;

@@ -1,6 +1,7 @@
 // Layout, workspace, slot-count policy, window scheduler and the host-only
 // C entry points (no device needed for anything in this file).
 #include "sp_host.h"
+#include "sp_limits.h"
 
 #include <string.h>
 
@@ -8,7 +9,8 @@
 
 namespace sp {
 
-constexpr int kNormBwdBlocks = 256;
+constexpr int kNormBwdBlocks = SPK_NORM_BWD_BLOCKS;
+static_assert(SPK_MSE_PARTS <= 1024, "loss partials share the tail of the partial-sum buffer");
 
 int validate_desc(const sp_stack_desc* d, const char** why) {
     const char* w = nullptr;
@@ -91,6 +93,9 @@ void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Wor
         ws->dqkv = take(Tp * nqkv * 2);
         ws->dob = take(Tp * nq * 2);
         ws->dz = take(Tp * f * 2);
+        ws->kt = take((size_t)d->max_batch * d->n_kv_heads * hdp * sp * 2);
+        ws->qt = take((size_t)d->max_batch * d->n_q_heads * hdp * sp * 2);
+        ws->dot = take((size_t)d->max_batch * d->n_q_heads * hdp * sp * 2);
         ws->part = take(((size_t)kNormBwdBlocks * dm + 1024) * 4);
         off = align_up(off, kSlotAlign);
         ws->gslot[0] = take(align_up(lay.grad_bytes, kSlotAlign));

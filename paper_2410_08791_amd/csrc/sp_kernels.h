@@ -3,6 +3,8 @@
 // and returns the launch status; none synchronises or allocates.
 #pragma once
 #include "sp_common.h"
+#include "sp_limits.h"
+#include <algorithm>
 
 enum GemmEpilogue {
     EPI_BF16 = 0,        // C bf16 [M,N]  = acc (+ bias)
@@ -46,7 +48,11 @@ struct AttnShape {
 static inline int attn_hd_pad(int hd) { return (hd + 31) / 32 * 32; }
 static inline int attn_s_pad(int S) { return (S + 63) / 64 * 64; }
 
-// vt[b][kvh][e][s] = v[b*S+s][kvh*hd+e]; rows e >= hd and columns s >= S are zero.
+// dst[b][h][e][s] = src[(b*S+s)*ld + col0 + h*hd + e] for h < nheads; rows e >= hd (up to
+// hd_pad) and columns s >= S (up to S_pad) are written as zero.
+hipError_t spk_launch_transpose_heads(hipStream_t st, const bf16_t* src, int ld, int col0, int nheads, int B, int S,
+                                      int hd, bf16_t* dst);
+// vt[b][kvh][e][s] = v[b*S+s][kvh*hd+e]: the V part of the fused activation.
 hipError_t spk_launch_transpose_v(hipStream_t st, const bf16_t* qkv, bf16_t* vt, const AttnShape& a);
 
 // o bf16 [B*S, Hq*hd] = softmax(q k^T / sqrt(hd) + mask) v per (batch, head);
@@ -56,3 +62,27 @@ hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, const bf16_t*
 
 hipError_t spk_launch_copy_f32(hipStream_t st, const float* src, float* dst, size_t n);
 hipError_t spk_launch_fill_u32(hipStream_t st, uint32_t* dst, uint32_t v, size_t n);
+
+// ---- backward ---------------------------------------------------------------------
+// loss = mean((y-t)^2) over n elements; dy = 2(y-t)/n as fp32 and as bf16.  part: SPK_MSE_PARTS floats.
+hipError_t spk_launch_mse(hipStream_t st, const float* y, const float* t, float* dy, bf16_t* dyb, float* part,
+                          float* loss, size_t n);
+// gu = [g | u] bf16 [T,2f] is overwritten by [dg | du] given dz bf16 [T,f].
+hipError_t spk_launch_swiglu_bwd(hipStream_t st, const bf16_t* dz, bf16_t* gu, int T, int f);
+// RMSNorm backward: dh_io (fp32 [T,d]) += d(norm)/dh applied to da; dhb = bf16(dh_io);
+// dgain fp32 [d] = sum_t da*h*r.  part: SPK_NORM_BWD_BLOCKS * d floats.
+hipError_t spk_launch_rmsnorm_bwd(hipStream_t st, const float* da, const float* h, const bf16_t* gain, float* dh_io,
+                                  bf16_t* dhb, float* part, float* dgain, int T, int d, float eps);
+hipError_t spk_launch_f32_to_bf16(hipStream_t st, const float* src, bf16_t* dst, size_t n);
+// delta fp32 [B,Hq,S] = rowsum(dO * O), both bf16 [B*S, Hq*hd].
+hipError_t spk_launch_attn_delta(hipStream_t st, const bf16_t* dO, const bf16_t* O, float* delta, int B, int S,
+                                 int Hq, int hd);
+// Attention backward.  qkv, dO, lse, delta as produced by the forward / the launchers above;
+// kt, qt, dot: K, Q and dO transposed per head (spk_launch_transpose_heads).  Writes dq, dk, dv
+// into dqkv (same layout as qkv, bf16).
+struct AttnBwdArgs {
+    const bf16_t* qkv; const bf16_t* dO; const float* lse; const float* delta;
+    const bf16_t* kt; const bf16_t* qt; const bf16_t* dot;
+    bf16_t* dqkv;
+};
+hipError_t spk_launch_attention_bwd(hipStream_t st, const AttnBwdArgs& g, const AttnShape& a);

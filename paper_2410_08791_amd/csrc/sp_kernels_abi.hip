@@ -41,3 +41,54 @@ extern "C" int spk_attention(void* stream, const uint16_t* qkv, uint16_t* vt, ui
     if (e != hipSuccess) return st(e);
     return st(spk_launch_attention((hipStream_t)stream, qkv, vt, o, lse, a));
 }
+
+extern "C" int spk_mse(void* stream, const float* y, const float* t, float* dy, uint16_t* dyb, float* scratch,
+                       float* loss, size_t n) {
+    if (!y || !t || !dy || !dyb || !scratch || !loss || n == 0) return SP_ERR_INVALID_ARG;
+    return st(spk_launch_mse((hipStream_t)stream, y, t, dy, dyb, scratch, loss, n));
+}
+
+extern "C" int spk_swiglu_bwd(void* stream, const uint16_t* dz, uint16_t* gu, int T, int f) {
+    if (!dz || !gu) return SP_ERR_INVALID_ARG;
+    return st(spk_launch_swiglu_bwd((hipStream_t)stream, dz, gu, T, f));
+}
+
+extern "C" int spk_rmsnorm_bwd(void* stream, const float* da, const float* h, const uint16_t* gain, float* dh_io,
+                               uint16_t* dhb, float* scratch, float* dgain, int T, int d, float eps) {
+    if (!da || !h || !gain || !dh_io || !dhb || !scratch || !dgain) return SP_ERR_INVALID_ARG;
+    return st(spk_launch_rmsnorm_bwd((hipStream_t)stream, da, h, gain, dh_io, dhb, scratch, dgain, T, d, eps));
+}
+
+static size_t al256(size_t v) { return (v + 255) / 256 * 256; }
+
+extern "C" size_t spk_attention_bwd_scratch_bytes(int B, int S, int Hq, int Hkv, int hd) {
+    if (B < 1 || S < 1 || Hq < 1 || Hkv < 1 || hd < 1) return 0;
+    const size_t per = (size_t)attn_hd_pad(hd) * attn_s_pad(S) * 2;
+    return al256((size_t)B * Hq * S * 4) + al256(B * Hkv * per) + 2 * al256(B * Hq * per);
+}
+
+extern "C" int spk_attention_bwd(void* stream, const uint16_t* qkv, const uint16_t* o, const uint16_t* dO,
+                                 const float* lse, void* scratch, uint16_t* dqkv, int B, int S, int Hq, int Hkv,
+                                 int hd, int causal) {
+    if (!qkv || !o || !dO || !lse || !scratch || !dqkv || B < 1 || S < 1 || Hq < 1 || Hkv < 1) return SP_ERR_INVALID_ARG;
+    if (hd != 64 && hd != 80 && hd != 128) return SP_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const int nq = Hq * hd, nqkv = (Hq + 2 * Hkv) * hd;
+    const size_t per = (size_t)attn_hd_pad(hd) * attn_s_pad(S) * 2;
+    unsigned char* p = static_cast<unsigned char*>(scratch);
+    float* delta = reinterpret_cast<float*>(p);
+    p += al256((size_t)B * Hq * S * 4);
+    bf16_t* kt = reinterpret_cast<bf16_t*>(p);
+    p += al256(B * Hkv * per);
+    bf16_t* qt = reinterpret_cast<bf16_t*>(p);
+    p += al256(B * Hq * per);
+    bf16_t* dot = reinterpret_cast<bf16_t*>(p);
+    AttnShape a{B, S, Hq, Hkv, hd, causal, nqkv};
+    hipError_t e = spk_launch_attn_delta(s, dO, o, delta, B, S, Hq, hd);
+    if (e == hipSuccess) e = spk_launch_transpose_heads(s, qkv, nqkv, nq, Hkv, B, S, hd, kt);
+    if (e == hipSuccess) e = spk_launch_transpose_heads(s, qkv, nqkv, 0, Hq, B, S, hd, qt);
+    if (e == hipSuccess) e = spk_launch_transpose_heads(s, dO, nq, 0, Hq, B, S, hd, dot);
+    if (e != hipSuccess) return st(e);
+    AttnBwdArgs g{qkv, dO, lse, delta, kt, qt, dot, dqkv};
+    return st(spk_launch_attention_bwd(s, g, a));
+}

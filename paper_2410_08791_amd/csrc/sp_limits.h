@@ -1,0 +1,4 @@
+// Sizes shared by the workspace carving and the backward kernels' launchers.
+#pragma once
+#define SPK_NORM_BWD_BLOCKS 256   // partial rows of the gain-gradient reduction
+#define SPK_MSE_PARTS 1024        // partial sums of the loss reduction

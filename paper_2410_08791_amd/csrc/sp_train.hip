@@ -1,13 +1,199 @@
-// Training step: forward that keeps each layer's input, MSE loss, and the
-// backward pass with weights re-streamed in reverse order (paper Sec. 3.3).
+// Training step (paper Sec. 3.3: the window mechanism repeated for the backward
+// pass).  Forward keeps every layer's fp32 input; the backward walks the layers
+// in reverse, and when layer l's weights are back in a slot it recomputes the
+// layer's internals from the saved input and runs the backward of every op.
+// fp32 weight gradients are written into one of two device gradient slots (same
+// tensor order as the weight blob, offsets doubled) and streamed to the caller's
+// pinned host blob on the device-to-host stream, fenced by two event pairs:
+//   grad_ready[g]  compute -> d2h   (gradients of a layer complete)
+//   gslot_free[g]  d2h -> compute   (slot g has been copied out, may be rewritten)
 #include "sp_engine.h"
 
-int sp_layer_forward_train(sp_engine* e, int, const unsigned char*, int, int) {
-    return sp_fail(e, SP_ERR_STATE, "training path not built");
+using namespace sp;
+
+namespace {
+
+struct LayerBufs {
+    const float* h_in;   // layer input  fp32 [T,d]
+    float* h_mid;        // after the attention residual
+    float* h_out;        // layer output (nullptr: stop after the SwiGLU, recompute mode)
+    float* lse;          // nullptr: not needed
+};
+
+// Decoder layer with every intermediate kept in the workspace (a, qkv, o, m, gu, z).
+int decoder_layer_keep(sp_engine* e, const unsigned char* w, const LayerBufs& b, int B, int S) {
+    const sp_stack_desc& d = e->desc;
+    const Layout& L = e->lay;
+    hipStream_t st = e->compute;
+    const int T = B * S, dm = d.d_model, f = d.d_ffn;
+    const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, nqkv = nq + 2 * nkv;
+    auto W = [&](int t) { return reinterpret_cast<const bf16_t*>(w + L.t[t].offset); };
+    bf16_t* a = e->wsp<bf16_t>(e->ws.a);
+    bf16_t* m = e->wsp<bf16_t>(e->ws.m);
+    bf16_t* qkv = e->wsp<bf16_t>(e->ws.qkv);
+    bf16_t* vt = e->wsp<bf16_t>(e->ws.vt);
+    bf16_t* o = e->wsp<bf16_t>(e->ws.o);
+    bf16_t* gu = e->wsp<bf16_t>(e->ws.gu);
+    bf16_t* z = e->wsp<bf16_t>(e->ws.z);
+    AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
+    GemmArgs g;
+    SP_HIP(e, spk_launch_norm(st, b.h_in, W(SP_T_G1), nullptr, a, T, dm, d.norm_eps));
+    g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0, nullptr, T, nqkv, dm, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+    SP_HIP(e, spk_launch_transpose_v(st, qkv, vt, as));
+    SP_HIP(e, spk_launch_attention(st, qkv, vt, o, b.lse, as));
+    g = GemmArgs{o, nq, OP_KMAJOR, W(SP_T_WO), nq, OP_KMAJOR, b.h_mid, dm, b.h_in, dm, nullptr, T, dm, nq, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+    SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_G2), nullptr, m, T, dm, d.norm_eps));
+    g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, gu, 2 * f, nullptr, 0, nullptr, T, 2 * f, dm, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+    SP_HIP(e, spk_launch_swiglu(st, gu, z, T, f));
+    if (b.h_out) {
+        g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_WD), f, OP_KMAJOR, b.h_out, dm, b.h_mid, dm, nullptr, T, dm, f, e->gemm_tile};
+        SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+    }
+    return SP_OK;
 }
-int sp_layer_backward(sp_engine* e, int, const unsigned char*, int, int) {
-    return sp_fail(e, SP_ERR_STATE, "training path not built");
+
+float* saved_input(sp_engine* e, int layer, int T) {
+    return e->wsp<float>(e->ws.xs) + (size_t)layer * T * e->desc.d_model;
 }
-int sp_train_begin(sp_engine* e, const float*, int, int) { return sp_fail(e, SP_ERR_STATE, "training path not built"); }
-int sp_train_loss(sp_engine* e, const float*, float*, int, int) { return sp_fail(e, SP_ERR_STATE, "training path not built"); }
-int sp_train_end(sp_engine* e, float*, int, int) { return sp_fail(e, SP_ERR_STATE, "training path not built"); }
+
+}  // namespace
+
+int sp_train_begin(sp_engine* e, const float* x_dev, int B, int S) {
+    const sp_stack_desc& d = e->desc;
+    const int T = B * S;
+    const int Tp = (T + 63) / 64 * 64;
+    hipStream_t st = e->compute;
+    if (Tp != T) {
+        // token rows [T, Tp) of the buffers that feed the weight-gradient GEMMs (contraction
+        // over tokens, padded to a multiple of 64) must read as zero
+        const int nq = d.n_q_heads * d.head_dim, nqkv = nq + 2 * d.n_kv_heads * d.head_dim;
+        struct { size_t off; int cols; } bufs[] = {{e->ws.a, d.d_model}, {e->ws.m, d.d_model}, {e->ws.o, nq},
+                                                   {e->ws.gu, 2 * d.d_ffn}, {e->ws.z, d.d_ffn},
+                                                   {e->ws.dhb, d.d_model}, {e->ws.dqkv, nqkv}};
+        for (auto& bf : bufs) {
+            uint32_t* p = reinterpret_cast<uint32_t*>(e->arena + bf.off + (size_t)T * bf.cols * 2);
+            SP_HIP(e, spk_launch_fill_u32(st, p, 0u, (size_t)(Tp - T) * bf.cols / 2));
+        }
+    }
+    SP_HIP(e, spk_launch_copy_f32(st, x_dev, saved_input(e, 0, T), (size_t)T * d.d_model));
+    return SP_OK;
+}
+
+int sp_layer_forward_train(sp_engine* e, int layer, const unsigned char* w, int B, int S) {
+    const int T = B * S, L = e->desc.n_layers;
+    // the last layer writes y (the caller's buffer, or the stream-gradient buffer that the
+    // loss kernel then turns into dy in place)
+    float* out = layer + 1 < L ? saved_input(e, layer + 1, T) : (e->y_out ? e->y_out : e->wsp<float>(e->ws.dh));
+    LayerBufs b{saved_input(e, layer, T), e->wsp<float>(e->ws.h1), out, nullptr};
+    return decoder_layer_keep(e, w, b, B, S);
+}
+
+int sp_train_loss(sp_engine* e, const float* target_dev, float* loss_dev, int B, int S) {
+    const size_t n = (size_t)B * S * e->desc.d_model;
+    float* dh = e->wsp<float>(e->ws.dh);
+    const float* y = e->y_out ? e->y_out : dh;
+    SP_HIP(e, spk_launch_mse(e->compute, y, target_dev, dh, e->wsp<bf16_t>(e->ws.dhb), e->wsp<float>(e->ws.part),
+                             loss_dev, n));
+    return SP_OK;
+}
+
+int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, int S) {
+    const sp_stack_desc& d = e->desc;
+    const Layout& L = e->lay;
+    hipStream_t st = e->compute;
+    const int T = B * S, Tp = (T + 63) / 64 * 64, dm = d.d_model, f = d.d_ffn;
+    const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, nqkv = nq + 2 * nkv;
+    auto W = [&](int t) { return reinterpret_cast<const bf16_t*>(w + L.t[t].offset); };
+    const int gs = e->gslot_next;
+    e->gslot_next ^= 1;
+    unsigned char* gslot = e->arena + e->ws.gslot[gs];
+    auto G = [&](int t) { return reinterpret_cast<float*>(gslot + 2 * L.t[t].offset); };
+    if (e->gslot_used[gs]) SP_HIP(e, hipStreamWaitEvent(st, e->gslot_free[gs], 0));
+
+    float* x_l = saved_input(e, layer, T);
+    float* h1 = e->wsp<float>(e->ws.h1);
+    float* lse = e->wsp<float>(e->ws.lse);
+    float* delta = e->wsp<float>(e->ws.delta);
+    float* dh = e->wsp<float>(e->ws.dh);
+    float* da = e->wsp<float>(e->ws.da);
+    float* part = e->wsp<float>(e->ws.part);
+    bf16_t* a = e->wsp<bf16_t>(e->ws.a);
+    bf16_t* m = e->wsp<bf16_t>(e->ws.m);
+    bf16_t* qkv = e->wsp<bf16_t>(e->ws.qkv);
+    bf16_t* o = e->wsp<bf16_t>(e->ws.o);
+    bf16_t* gu = e->wsp<bf16_t>(e->ws.gu);
+    bf16_t* z = e->wsp<bf16_t>(e->ws.z);
+    bf16_t* dhb = e->wsp<bf16_t>(e->ws.dhb);
+    bf16_t* dz = e->wsp<bf16_t>(e->ws.dz);
+    bf16_t* dob = e->wsp<bf16_t>(e->ws.dob);
+    bf16_t* dqkv = e->wsp<bf16_t>(e->ws.dqkv);
+    bf16_t* kt = e->wsp<bf16_t>(e->ws.kt);
+    bf16_t* qt = e->wsp<bf16_t>(e->ws.qt);
+    bf16_t* dot = e->wsp<bf16_t>(e->ws.dot);
+    AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
+    GemmArgs g;
+
+    // recompute a, qkv, o, lse, h1, m, gu, z from the saved input
+    LayerBufs lb{x_l, h1, nullptr, lse};
+    int rc = decoder_layer_keep(e, w, lb, B, S);
+    if (rc != SP_OK) return rc;
+
+    // ---- FFN.  dh is dL/d(layer output); dhb its bf16 copy.
+    // dWd[d,f] = dh^T z       (contraction over tokens: both operands transposed on the way in)
+    g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_WD), f, nullptr, 0, nullptr, dm, f, Tp, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    // dz[T,f] = dh Wd         (Wd is [d,f]: its row index f is contiguous)
+    g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_WD), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+    // [dg | du] in place over [g | u]
+    SP_HIP(e, spk_launch_swiglu_bwd(st, dz, gu, T, f));
+    // dWgu[2f,d] = dgu^T m
+    g = GemmArgs{gu, 2 * f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_WGU), dm, nullptr, 0, nullptr, 2 * f, dm, Tp, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    // dm[T,d] = dgu Wgu  (fp32)
+    g = GemmArgs{gu, 2 * f, OP_KMAJOR, W(SP_T_WGU), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, 2 * f, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    // second norm: dh += d(rmsnorm)(h1) applied to dm; dg2
+    SP_HIP(e, spk_launch_rmsnorm_bwd(st, da, h1, W(SP_T_G2), dh, dhb, part, G(SP_T_G2), T, dm, d.norm_eps));
+
+    // ---- attention block.  dh is now dL/dh1.
+    // dWo[d,nq] = dh^T o
+    g = GemmArgs{dhb, dm, OP_RMAJOR, o, nq, OP_RMAJOR, G(SP_T_WO), nq, nullptr, 0, nullptr, dm, nq, Tp, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    // do[T,nq] = dh Wo
+    g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_WO), nq, OP_RMAJOR, dob, nq, nullptr, 0, nullptr, T, nq, dm, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+    SP_HIP(e, spk_launch_attn_delta(st, dob, o, delta, B, S, d.n_q_heads, d.head_dim));
+    SP_HIP(e, spk_launch_transpose_heads(st, qkv, nqkv, nq, d.n_kv_heads, B, S, d.head_dim, kt));
+    SP_HIP(e, spk_launch_transpose_heads(st, qkv, nqkv, 0, d.n_q_heads, B, S, d.head_dim, qt));
+    SP_HIP(e, spk_launch_transpose_heads(st, dob, nq, 0, d.n_q_heads, B, S, d.head_dim, dot));
+    AttnBwdArgs ab{qkv, dob, lse, delta, kt, qt, dot, dqkv};
+    SP_HIP(e, spk_launch_attention_bwd(st, ab, as));
+    // dWqkv[nqkv,d] = dqkv^T a
+    g = GemmArgs{dqkv, nqkv, OP_RMAJOR, a, dm, OP_RMAJOR, G(SP_T_WQKV), dm, nullptr, 0, nullptr, nqkv, dm, Tp, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    // da[T,d] = dqkv Wqkv (fp32)
+    g = GemmArgs{dqkv, nqkv, OP_KMAJOR, W(SP_T_WQKV), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, nqkv, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    // first norm: dh += d(rmsnorm)(x_l) applied to da; dg1.  dh is now dL/d(layer input).
+    SP_HIP(e, spk_launch_rmsnorm_bwd(st, da, x_l, W(SP_T_G1), dh, dhb, part, G(SP_T_G1), T, dm, d.norm_eps));
+
+    // ---- hand the gradient slot to the device-to-host stream
+    SP_HIP(e, hipEventRecord(e->grad_ready[gs], st));
+    SP_HIP(e, hipStreamWaitEvent(e->d2h, e->grad_ready[gs], 0));
+    SP_HIP(e, hipMemcpyAsync(e->grad_blobs[layer], gslot, L.grad_bytes, hipMemcpyDeviceToHost, e->d2h));
+    SP_HIP(e, hipEventRecord(e->gslot_free[gs], e->d2h));
+    e->gslot_used[gs] = 1;
+    e->stats_d2h_copies++;
+    e->stats_d2h_bytes += L.grad_bytes;
+    return SP_OK;
+}
+
+int sp_train_end(sp_engine* e, float* dx_dev, int B, int S) {
+    if (dx_dev)
+        SP_HIP(e, spk_launch_copy_f32(e->compute, e->wsp<float>(e->ws.dh), dx_dev, (size_t)B * S * e->desc.d_model));
+    return SP_OK;
+}

@@ -174,3 +174,93 @@ def test_attention_rejects_unsupported_head_dim():
     assert sp.spk_attention(stream_ptr(), ptr(z), ptr(z), ptr(z), None, 1, 8, 2, 2, 48, 1) == sp.SP_ERR_INVALID_ARG
     assert sp.spk_attention(stream_ptr(), ptr(z), ptr(z), ptr(z), None, 1, 8, 3, 2, 64, 1) == sp.SP_ERR_INVALID_ARG
     sync()
+
+
+# ------------------------------------------------------------------ backward kernels
+def test_mse_loss_and_gradient():
+    rng = np.random.default_rng(3)
+    n = 3 * 77 * 256
+    y = rng.standard_normal(n).astype(np.float32)
+    t = rng.standard_normal(n).astype(np.float32)
+    yd, td = dev_f32(y), dev_f32(t)
+    dy = torch.zeros(n, dtype=torch.float32, device=DEV)
+    dyb = torch.zeros(n, dtype=torch.int16, device=DEV)
+    scratch = torch.zeros(1024, dtype=torch.float32, device=DEV)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    assert sp.spk_mse(stream_ptr(), ptr(yd), ptr(td), ptr(dy), ptr(dyb), ptr(scratch), ptr(loss), n) == sp.SP_OK
+    sync()
+    ref = O.mse_loss(y.astype(np.float64), t.astype(np.float64))
+    assert abs(float(loss.item()) - ref) <= 1e-5 * ref
+    dref = 2.0 * (y.astype(np.float64) - t) / n
+    np.testing.assert_allclose(dy.cpu().numpy(), dref, rtol=1e-5, atol=1e-12)
+    assert np.all(np.abs(bf16_vals(host_u16(dyb)) - dref) <= BF16_EPS * np.abs(dref) + 1e-12)
+
+
+@pytest.mark.parametrize("T,f", [(33, 1024), (5, 5504)])
+def test_swiglu_backward(T, f):
+    rng = np.random.default_rng(T + f)
+    gb, gu = rand_bf16(rng, (T, 2 * f), 2.0)
+    db, dz = rand_bf16(rng, (T, f))
+    gud, dzd = dev_u16(gb), dev_u16(db)
+    assert sp.spk_swiglu_bwd(stream_ptr(), ptr(dzd), ptr(gud), T, f) == sp.SP_OK
+    sync()
+    dg, du = O._swiglu_bwd(dz, gu[:, :f], gu[:, f:])
+    got = bf16_vals(host_u16(gud))
+    ref = np.concatenate([dg, du], axis=1)
+    assert np.all(np.abs(got - ref) <= BF16_EPS * np.abs(ref) + 1e-6)
+
+
+@pytest.mark.parametrize("T,d", [(300, 256), (37, 2048), (5, 8192), (700, 512)])
+def test_rmsnorm_backward(T, d):
+    rng = np.random.default_rng(T * 3 + d)
+    da = rng.standard_normal((T, d)).astype(np.float32)
+    h = (rng.standard_normal((T, d)) * 1.5).astype(np.float32)
+    dh0 = rng.standard_normal((T, d)).astype(np.float32)
+    gb, g = rand_bf16(rng, d, 0.3)
+    dad, hd, gd, dhd = dev_f32(da), dev_f32(h), dev_u16(gb), dev_f32(dh0)
+    dhb = torch.zeros((T, d), dtype=torch.int16, device=DEV)
+    scratch = torch.zeros(256 * d, dtype=torch.float32, device=DEV)
+    dgain = torch.zeros(d, dtype=torch.float32, device=DEV)
+    rc = sp.spk_rmsnorm_bwd(stream_ptr(), ptr(dad), ptr(hd), ptr(gd), ptr(dhd), ptr(dhb), ptr(scratch), ptr(dgain),
+                            T, d, 1e-5)
+    assert rc == sp.SP_OK
+    sync()
+    dh_ref, dg_ref = O._rmsnorm_bwd(da.astype(np.float64), h.astype(np.float64), g, 1e-5)
+    dh_ref = dh_ref + dh0
+    got = dhd.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - dh_ref)) <= 1e-5 * np.max(np.abs(dh_ref))
+    assert np.max(np.abs(dgain.cpu().numpy() - dg_ref)) <= 1e-5 * np.max(np.abs(dg_ref)) * np.sqrt(T)
+    assert np.all(np.abs(bf16_vals(host_u16(dhb)) - got) <= BF16_EPS * np.abs(got) + 1e-12)
+
+
+@pytest.mark.parametrize("B,S,Hq,Hkv,hd,causal", [
+    (2, 128, 4, 4, 64, 1),
+    (1, 300, 8, 2, 128, 1),     # grouped-query heads, ragged S
+    (2, 77, 2, 2, 128, 0),
+    (2, 257, 2, 2, 80, 0),
+    (1, 33, 4, 1, 64, 1),
+])
+def test_attention_backward(B, S, Hq, Hkv, hd, causal):
+    rng = np.random.default_rng(B * 5 + S + Hq + hd + causal)
+    nq, nk = Hq * hd, Hkv * hd
+    nqkv = nq + 2 * nk
+    qb, qkv = rand_bf16(rng, (B * S, nqkv))
+    dob, dO = rand_bf16(rng, (B * S, nq))
+    sh = O.StackShape(O.DECODER, 1, nq, Hq, Hkv, hd, 64, bool(causal))
+    q, k, v = qkv[:, :nq], qkv[:, nq:nq + nk], qkv[:, nq + nk:]
+    dq, dk, dv = O._attention_bwd(dO, np.ascontiguousarray(q), np.ascontiguousarray(k), np.ascontiguousarray(v), B, S, sh)
+    qd, dod = dev_u16(qb), dev_u16(dob)
+    vt = torch.zeros(sp.spk_attention_scratch_elems(B, S, Hkv, hd), dtype=torch.int16, device=DEV)
+    o = torch.zeros((B * S, nq), dtype=torch.int16, device=DEV)
+    lse = torch.zeros((B, Hq, S), dtype=torch.float32, device=DEV)
+    assert sp.spk_attention(stream_ptr(), ptr(qd), ptr(vt), ptr(o), ptr(lse), B, S, Hq, Hkv, hd, causal) == sp.SP_OK
+    scratch = torch.zeros(sp.spk_attention_bwd_scratch_bytes(B, S, Hq, Hkv, hd), dtype=torch.uint8, device=DEV)
+    dqkv = torch.zeros((B * S, nqkv), dtype=torch.int16, device=DEV)
+    rc = sp.spk_attention_bwd(stream_ptr(), ptr(qd), ptr(o), ptr(dod), ptr(lse), ptr(scratch), ptr(dqkv),
+                              B, S, Hq, Hkv, hd, causal)
+    assert rc == sp.SP_OK
+    sync()
+    got = bf16_vals(host_u16(dqkv))
+    for name, g, r in (("dq", got[:, :nq], dq), ("dk", got[:, nq:nq + nk], dk), ("dv", got[:, nq + nk:], dv)):
+        err = np.max(np.abs(g - r)) / np.max(np.abs(r))
+        assert err <= 1.5e-2, (name, err)

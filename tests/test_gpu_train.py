@@ -1,0 +1,147 @@
+"""The training step on the GPU (forward, MSE, backward with re-streamed
+weights, fp32 gradients streamed to pinned host blobs) against the oracle's
+analytic gradients, and bit-identity of loss / dx / gradients over window
+settings (the paper's fidelity claim covers training too, Sec. 4.2.2)."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from oracle import stack_oracle as O  # noqa: E402
+from paper_2410_08791_amd import binding as sp  # noqa: E402
+from paper_2410_08791_amd import synth  # noqa: E402
+from tests.gpu_util import DEV, dev_f32, max_rel  # noqa: E402
+
+TOL = 2e-2
+
+
+class TrainCase:
+    def __init__(self, w):
+        self.w = w
+        self.desc = sp.make_desc(w)
+        self.blobs, self.views = sp.pinned_blobs(w, self.desc)
+        self.x = synth.make_input(w, "x")
+        self.t = synth.make_input(w, "target")
+        self.xd, self.td = dev_f32(self.x), dev_f32(self.t)
+        self.gbytes = sp.sp_layer_grad_bytes(C.byref(self.desc))
+
+    def run(self, k, p, calls=1, want_y=True, target=None, budget_layers=None):
+        w = self.w
+        eng = sp.Engine(self.desc, self.blobs, k, p, flags=sp.SP_FLAG_TRAINING, budget_layers=budget_layers)
+        gblobs = [torch.zeros(self.gbytes, dtype=torch.uint8, pin_memory=True) for _ in range(w.n_layers)]
+        y = torch.zeros_like(self.xd) if want_y else None
+        dx = torch.zeros_like(self.xd)
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        td = self.td if target is None else target
+        for _ in range(calls):
+            for g in gblobs:
+                g.fill_(0xFF)
+            eng.forward_backward(self.xd, td, y, loss, dx, gblobs, w.batch, w.seq)
+            eng.sync()
+        st = eng.stats()
+        grads = [{n: v.copy() for n, v in sp.grad_views(self.desc, g.numpy()).items()} for g in gblobs]
+        out = dict(loss=float(loss.item()), dx=dx.cpu().numpy().reshape(w.tokens, -1),
+                   y=y.cpu().numpy().reshape(w.tokens, -1) if want_y else None, grads=grads, stats=st)
+        assert eng.destroy() == sp.SP_OK
+        return out
+
+    def oracle(self, dtype=np.float64):
+        w = self.w
+        sh = O.StackShape(w.arch, w.n_layers, w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim, w.d_ffn,
+                          w.causal, w.norm_eps)
+        return O.stack_forward_backward(self.x, self.t, self.views, w.batch, w.seq, sh, dtype=dtype)
+
+
+def check_against_oracle(got, ref, tag):
+    y, loss, dx, grads = ref
+    if got["y"] is not None:
+        assert max_rel(got["y"], y) <= TOL
+    assert abs(got["loss"] - loss) <= TOL * loss, (got["loss"], loss)
+    e = max_rel(got["dx"], dx.reshape(got["dx"].shape))
+    worst = ("dx", e)
+    assert e <= TOL, ("dx", e)
+    for l, (gl, rl) in enumerate(zip(got["grads"], grads)):
+        for n, r in rl.items():
+            g = gl[n].reshape(r.shape)
+            assert np.all(np.isfinite(g)), (l, n)
+            e = max_rel(g, r)
+            if e > worst[1]:
+                worst = (f"layer {l} {n}", e)
+            assert e <= TOL, (tag, l, n, e)
+    print(f"{tag}: loss {got['loss']:.6f} vs {loss:.6f}; worst gradient error {worst[0]} = {worst[1]:.3e}")
+
+
+@pytest.fixture(scope="module")
+def small():
+    return TrainCase(synth.Workload("train_small", "decoder", 3, 256, 4, 4, 64, 512, True, 2, 96, training=True))
+
+
+def test_training_step_matches_oracle(small):
+    got = small.run(2, 1)
+    check_against_oracle(got, small.oracle(), "train_small")
+    st = got["stats"]
+    assert st.d2h_copies == 3 and st.d2h_bytes == 3 * small.gbytes
+    assert st.h2d_copies == 3          # 3 layers, 3 slots: each layer crosses the link once
+
+
+def test_training_bits_do_not_depend_on_the_window(small):
+    base = small.run(8, 8)             # resident
+    assert base["stats"].plan.fully_resident
+    for k, p in [(1, 1), (2, 1), (1, 2)]:
+        for bl in (None, 1):
+            got = small.run(k, p, budget_layers=bl)
+            assert got["loss"] == base["loss"], (k, p, bl)
+            assert np.array_equal(got["dx"], base["dx"]) and np.array_equal(got["y"], base["y"]), (k, p, bl)
+            for gl, bl_ in zip(got["grads"], base["grads"]):
+                for n in gl:
+                    assert np.array_equal(gl[n], bl_[n]), (k, p, n)
+
+
+def test_training_repeated_calls_and_link_traffic():
+    # 6 layers, 2 slots: forward copies 6, the turn re-uses 2, backward copies 4; the next
+    # call finds layers 0,1 resident
+    w = synth.Workload("train_l6", "decoder", 6, 256, 4, 2, 64, 512, True, 1, 128, training=True)
+    c = TrainCase(w)
+    a = c.run(1, 1, calls=1)
+    b = c.run(1, 1, calls=3)
+    assert a["loss"] == b["loss"] and np.array_equal(a["dx"], b["dx"])
+    assert a["stats"].h2d_copies == 6 + 4
+    assert b["stats"].h2d_copies == 10 + 2 * 8 and b["stats"].last_h2d_copies == 8
+    check_against_oracle(b, c.oracle(), "train_l6 (grouped-query heads)")
+
+
+def test_training_ragged_token_count_and_no_y():
+    # T = 3*77 = 231 tokens: not a multiple of the 64-token contraction tile
+    w = synth.Workload("train_ragged", "decoder", 2, 256, 2, 2, 128, 576, True, 3, 77, training=True)
+    c = TrainCase(w)
+    got = c.run(1, 1, want_y=False, calls=2)
+    check_against_oracle(got, c.oracle(), "train_ragged")
+
+
+def test_zero_loss_gives_zero_gradients(small):
+    first = small.run(2, 1)
+    y = dev_f32(first["y"].reshape(small.x.shape))
+    got = small.run(2, 1, target=y)
+    assert got["loss"] == 0.0 and not got["dx"].any()
+    assert all(not g.any() for gl in got["grads"] for g in gl.values())
+
+
+def test_forward_only_handle_refuses_training(small):
+    eng = sp.Engine(small.desc, small.blobs, 1, 1)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    with pytest.raises(sp.SuperpipeError) as ei:
+        eng.forward_backward(small.xd, small.td, None, loss, None, [], 2, 96)
+    assert ei.value.code == sp.SP_ERR_STATE
+    eng.destroy()
+
+
+def test_train1p3b_layer_shape():
+    """The training workload's layer shape (d 2048, 16 heads x 128, ffn 5504), two layers,
+    2 x 1024 tokens so that the fp32 oracle's backward finishes in seconds."""
+    w = synth.WORKLOADS["train1p3b"].with_(n_layers=2, batch=2)
+    c = TrainCase(w)
+    got = c.run(1, 1)
+    check_against_oracle(got, c.oracle(np.float32), "train1p3b x2 layers, batch 2")
