@@ -1,15 +1,18 @@
 #!/usr/bin/env python3
-"""Headline benchmark: tokens/s of the layer-streamed forward at a fixed HBM
+"""Headline benchmark: tokens/s of the layer-streamed stack at a fixed HBM
 weight budget, on one MI355X.
 
-    python bench.py --gpus 1 --steps K --warmup W
+    python bench.py --gpus 1 --steps K --warmup W            # the headline workload
+    python bench.py --workload vith|llama70b|train1p3b ...   # the other workloads
 
-Workload = benchmark configs[1]: the LLaMA-7B-shaped stack (32 layers,
-d 4096, 32 heads x 128, SwiGLU 11008, causal, batch 1 x seq 2048), bf16 weights
-in pinned host memory, HBM weight budget of 4 layer slots, window (k, p) =
-(2, 2).  A step is one sp_forward over the whole stack: every layer is copied
-host-to-device once per step and computed once.  Inputs are resident in HBM
-before the timed region.  Prints ONE JSON line.
+Default workload = the LLaMA-7B-shaped stack (32 layers, d 4096, 32 heads x
+128, SwiGLU 11008, causal, batch 1 x seq 2048), bf16 weights in pinned host
+memory, HBM weight budget of 4 layer slots, window (k, p) = (2, 2).  A step is
+one pass of the whole hot path: sp_forward over the whole stack (every layer
+copied host-to-device once and computed once), or for the training workload
+one sp_forward_backward (forward, loss, backward with re-streamed weights and
+gradients streamed device-to-host).  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -62,6 +65,8 @@ def main():
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--p", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None, help="run a prefix of the stack (debug)")
+    ap.add_argument("--distinct-blobs", type=int, default=None,
+                    help="generate only this many distinct layer blobs and cycle them (host RAM limit)")
     ap.add_argument("--no-wrap", action="store_true", help="do not prefetch the next call's first layers")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -81,31 +86,58 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.layers:
         w = w.with_(n_layers=args.layers)
+    training = w.training
     k = args.k or w.k
     p = args.p or w.p
     desc = sp.make_desc(w)
     blob_bytes = sp.sp_layer_blob_bytes(C.byref(desc))
     budget_layers = w.budget_layers or (k + p)
+    budget_bytes = None
+    if w.name == "llama70b":
+        budget_bytes = 16 * 10 ** 9              # the workload's cap: 16 GB for slots + workspace
+    distinct = args.distinct_blobs
+    if distinct is None and w.n_layers * blob_bytes > 100e9:
+        distinct = 16                            # ~27 GB pinned instead of ~137 GB; same traffic and schedule
     log(f"[bench] {torch.cuda.get_device_name(0)}; host cores {os.cpu_count()}; workload {w.name}: "
-        f"L={w.n_layers} d={w.d_model} T={w.tokens} blob={blob_bytes / 1e6:.1f} MB/layer")
+        f"L={w.n_layers} d={w.d_model} T={w.tokens} blob={blob_bytes / 1e6:.1f} MB/layer"
+        + (f"; {distinct} distinct blobs cycled" if distinct else ""))
 
     t0 = time.time()
     pool = synth.make_pool(16)
-    blobs, views = sp.pinned_blobs(w, desc, pool=pool)
+    nb = min(distinct, w.n_layers) if distinct else w.n_layers
+    blobs, views = sp.pinned_blobs(w, desc, n_layers=nb, pool=pool)
     pool.shutdown()
+    if nb < w.n_layers:
+        blobs = [blobs[l % nb] for l in range(w.n_layers)]
+        views = [views[l % nb] for l in range(w.n_layers)]
     log(f"[bench] weights generated into pinned memory in {time.time() - t0:.1f} s")
     x = synth.make_input(w)
     xd = torch.from_numpy(x).to("cuda:0")
     yd = torch.empty_like(xd)
     B, S, T = w.batch, w.seq, w.tokens
+    if training:
+        tgt = torch.from_numpy(synth.make_input(w, "target")).to("cuda:0")
+        gbytes = sp.sp_layer_grad_bytes(C.byref(desc))
+        gblobs = [torch.zeros(gbytes, dtype=torch.uint8, pin_memory=True) for _ in range(w.n_layers)]
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+        dxd = torch.empty_like(xd)
 
     ceiling = copy_ceiling_gbps(torch)
     log(f"[bench] plain pinned H2D copy ceiling: {ceiling:.1f} GB/s")
 
     def run(kk, pp, flags, steps, warmup):
-        eng = sp.Engine(desc, blobs, kk, pp, budget_layers=budget_layers, flags=flags)
+        if training:
+            flags |= sp.SP_FLAG_TRAINING
+        eng = sp.Engine(desc, blobs, kk, pp, budget_layers=budget_layers, budget_bytes=budget_bytes, flags=flags)
+
+        def step():
+            if training:
+                eng.forward_backward(xd, tgt, None, loss, dxd, gblobs, B, S)
+            else:
+                eng.forward(xd, yd, B, S)
+
         for _ in range(warmup):
-            eng.forward(xd, yd, B, S)
+            step()
         eng.sync()
         eng.stats()                                  # clears the kernel-timing window
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -113,19 +145,20 @@ def main():
         tw = time.perf_counter()
         e0.record(eng.compute)
         for _ in range(steps):
-            eng.forward(xd, yd, B, S)
+            step()
         e1.record(eng.compute)
         eng.sync()
         torch.cuda.synchronize()
         wall = time.perf_counter() - tw
         ms = e0.elapsed_time(e1)
         st = eng.stats()
-        y = yd.cpu().numpy().copy()
+        y = (dxd if training else yd).cpu().numpy().copy()
         eng.destroy()
         return dict(ms_per_step=ms / steps, wall_ms_per_step=wall * 1e3 / steps, stats=st, y=y,
                     budget=eng.budget_bytes)
 
-    flags = sp.SP_FLAG_TIMING | (0 if args.no_wrap else sp.SP_FLAG_WRAP_PREFETCH)
+    wrap = not args.no_wrap and not training
+    flags = sp.SP_FLAG_TIMING | (sp.SP_FLAG_WRAP_PREFETCH if wrap else 0)
     main_run = run(k, p, flags, args.steps, args.warmup)
     st = main_run["stats"]
     ms = max(main_run["ms_per_step"], main_run["wall_ms_per_step"])   # host wall covers all streams
@@ -135,12 +168,15 @@ def main():
     log(f"[bench] k={k} p={p} slots={st.plan.n_slots}: {ms:.2f} ms/step, {tokens_s:.0f} tokens/s, "
         f"H2D {h2d_gbps_wall:.1f} GB/s over wall")
 
-    # dominant kernel: the gate/up GEMM with the SwiGLU epilogue
+    # dominant kernel: the layer's largest GEMM (gate/up projection, or the first MLP GEMM)
     gm, gn, gk = st.big_gemm_m, st.big_gemm_n, st.big_gemm_k
     gemm_ms = st.big_gemm_ms_sum / max(st.big_gemm_launches, 1)
     gemm_flops = 2.0 * gm * gn * gk
     achieved_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
-    roofline = {"bound": "mfma", "kernel": "gemm_kernel<EPI_SWIGLU_BF16> (gate/up projection)",
+    kname = ("gemm_kernel<EPI_BF16> (gate/up projection)" if training else
+             "gemm_kernel<EPI_SWIGLU_BF16> (gate/up projection)" if w.arch == "decoder" else
+             "gemm_kernel<EPI_GELU_BF16> (first MLP projection)")
+    roofline = {"bound": "mfma", "kernel": kname,
                 "achieved": round(achieved_tf, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved_tf / PEAK_BF16_TFLOPS, 4), "traffic": None,
                 "flops_per_launch": gemm_flops, "avg_launch_ms": round(gemm_ms, 4),
@@ -160,18 +196,22 @@ def main():
         "event_ms_per_step": round(main_run["ms_per_step"], 3),
         "host_wall_ms_per_step": round(main_run["wall_ms_per_step"], 3),
     }
+    if training:
+        extra["d2h_gbps_over_wall"] = round(w.n_layers * gbytes / (ms * 1e-3) / 1e9, 2)
+    if w.arch == "encoder":
+        extra["images_per_s"] = round(B / (ms * 1e-3), 1)
 
-    # window sweep at the same budget (+ resident and naive comparators), bits must not change
-    sweep = []
+    # window sweep at the same budget (+ the naive comparator); bits must not change
     if not args.no_sweep:
+        sweep = []
         base = main_run["y"]
-        for kk in (1, 2, 4):
-            for pp in (1, 2):
-                r = run(kk, pp, flags & ~sp.SP_FLAG_TIMING, 3, 1)
-                m = max(r["ms_per_step"], r["wall_ms_per_step"])
-                sweep.append({"k": kk, "p": pp, "slots": int(r["stats"].plan.n_slots),
-                              "tokens_per_s": round(T / (m * 1e-3), 1),
-                              "bit_identical": bool(np.array_equal(r["y"], base))})
+        grid = [(1, 1), (1, 2), (2, 1), (2, 2), (4, 1), (4, 2)] if w.name == "llama7b" else [(1, 1), (k, p)]
+        for kk, pp in grid:
+            r = run(kk, pp, flags & ~sp.SP_FLAG_TIMING, 3, 1)
+            m = max(r["ms_per_step"], r["wall_ms_per_step"])
+            sweep.append({"k": kk, "p": pp, "slots": int(r["stats"].plan.n_slots),
+                          "tokens_per_s": round(T / (m * 1e-3), 1),
+                          "bit_identical": bool(np.array_equal(r["y"], base))})
         r = run(1, 1, sp.SP_FLAG_NO_OVERLAP, 3, 1)
         m = max(r["ms_per_step"], r["wall_ms_per_step"])
         sweep.append({"mode": "naive(2 slots, no overlap)", "tokens_per_s": round(T / (m * 1e-3), 1),
@@ -184,26 +224,36 @@ def main():
         from threadpoolctl import threadpool_info
         from oracle import stack_oracle as O
         n = min(args.cpu_layers, w.n_layers)
-        shape = O.StackShape(w.arch, w.n_layers, w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim,
+        cb = 1 if (training or w.name in ("vith", "llama70b")) else B    # bounded sample: fewer batch items
+        cb = min(B, 8) if w.name == "vith" else cb
+        shape = O.StackShape(w.arch, n, w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim,
                              w.d_ffn, w.causal, w.norm_eps)
+        xs = x[:cb]
         t0 = time.perf_counter()
-        ref = O.stack_forward(x, views, B, S, shape, dtype=np.float32, n_layers=n)
+        if training:
+            ts = synth.make_input(w, "target")[:cb]
+            ref = O.stack_forward_backward(xs, ts, views[:n], cb, S, shape, dtype=np.float32)[0]
+        else:
+            ref = O.stack_forward(xs, views, cb, S, shape, dtype=np.float32, n_layers=n)
         dt = time.perf_counter() - t0
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
-        cpu = {"value": round(T / (dt * w.n_layers / n), 2), "unit": "tokens/s", "cores": int(cores),
-               "kind": "oracle",
-               "sample": f"fp32 numpy oracle on {n} of {w.n_layers} layers at the full {T} tokens "
-                         f"({dt:.1f} s), scaled by {w.n_layers}/{n}"}
-        # parity of the same prefix on the GPU, at the bench's launch configuration
+        scale = (w.n_layers / n) * (B / cb)
+        cpu = {"value": round(T / (dt * scale), 3), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"fp32 numpy oracle ({'forward+backward' if training else 'forward'}) on {n} of "
+                         f"{w.n_layers} layers, {cb} of {B} batch items x {S} tokens ({dt:.1f} s), "
+                         f"time scaled by {scale:g}"}
+        # parity of the same sample on the GPU (forward output), same kernels and tile choices
         sub = sp.make_desc(w, n_layers=n)
         eng = sp.Engine(sub, blobs[:n], 1, 1)
-        eng.forward(xd, yd, B, S)
+        xsd = torch.from_numpy(np.ascontiguousarray(xs)).to("cuda:0")
+        ysd = torch.empty_like(xsd)
+        eng.forward(xsd, ysd, cb, S)
         eng.sync()
-        got = yd.cpu().numpy().reshape(T, -1).astype(np.float64)
+        got = ysd.cpu().numpy().reshape(cb * S, -1).astype(np.float64)
         eng.destroy()
-        extra["parity_prefix_layers"] = n
+        extra["parity_sample"] = f"{n} layers, {cb} batch items"
         extra["parity_max_rel_err"] = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
-        log(f"[bench] oracle {n} layers: {dt:.1f} s on {cores} threads; GPU vs oracle max rel err "
+        log(f"[bench] oracle sample: {dt:.1f} s on {cores} threads; GPU vs oracle max rel err "
             f"{extra['parity_max_rel_err']:.3e}")
 
     out = {
@@ -211,9 +261,11 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n_layers} layers d={w.d_model} heads={w.n_q_heads}/{w.n_kv_heads}"
-                               f"x{w.head_dim} ffn={w.d_ffn} causal={w.causal} batch {B} x seq {S}, forward",
+                               f"x{w.head_dim} ffn={w.d_ffn} causal={w.causal} batch {B} x seq {S}, "
+                               + ("forward+backward (MSE)" if training else "forward"),
                    "k": k, "p": p, "n_slots": int(st.plan.n_slots), "budget_layers": budget_layers,
-                   "wrap_prefetch": not args.no_wrap, "layer_blob_bytes": int(blob_bytes), "seed": w.seed},
+                   "wrap_prefetch": wrap, "layer_blob_bytes": int(blob_bytes),
+                   "distinct_blobs": nb, "seed": w.seed},
         "roofline": roofline, "cpu_baseline": cpu, **extra,
     }
     print(json.dumps(out), flush=True)

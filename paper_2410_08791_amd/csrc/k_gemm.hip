@@ -46,6 +46,7 @@ __device__ __forceinline__ float gelu_erf(float x) {
 template <int ROWS>
 struct LoaderK {
     static constexpr int ITERS = ROWS * 8 / 256;
+    static constexpr int N_LOADS = ITERS, N_STORES = ITERS;   // per thread and tile
     const bf16_t* src[ITERS];
     int dst[ITERS];
     u32x4_t regs[ITERS];
@@ -78,6 +79,7 @@ template <int ROWS>
 struct LoaderR {
     static constexpr int ITERS = ROWS / 256 > 0 ? ROWS / 256 : 1;
     static constexpr bool PARTIAL = ROWS < 256;
+    static constexpr int N_LOADS = ITERS * 8, N_STORES = ITERS * 8;
     const bf16_t* src[ITERS];
     int ld_;
     int rc_[ITERS], kb_;
@@ -197,32 +199,63 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
     lw.store(smem + A_BYTES);
     __syncthreads();
 
+    // Main loop, one barrier per 64-deep tile.  The body is branch-free (the last
+    // iteration re-fetches the last tile into the idle buffer) so that it is one
+    // scheduling region; fragments are double buffered in registers and the
+    // scheduling hints interleave the LDS reads of step s+1 with the MFMAs of step
+    // s, and the LDS stores of the next tile with the MFMAs of the last step.
+    constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
+    typedef typename LoaderSel<BM, AFORM>::type LA;
+    typedef typename LoaderSel<BN, WFORM>::type LW;
+    constexpr int LA_LOADS = LA::N_LOADS, LW_LOADS = LW::N_LOADS, LA_STORES = LA::N_STORES, LW_STORES = LW::N_STORES;
+    constexpr int M_MFMA = 0x008, M_VMEM_RD = 0x020, M_DS_RD = 0x100, M_DS_WR = 0x200;
     for (int kt = 0; kt < KT; ++kt) {
         unsigned char* cur = smem + (kt & 1) * STAGE;
         unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
-        const bool more = kt + 1 < KT;
-        if (more) {
-            la.fetch((kt + 1) * BK);
-            lw.fetch((kt + 1) * BK);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8_t af[TM], wf[TN];
+        const int knext = min(kt + 1, KT - 1) * BK;
+        bf16x8_t af[2][TM], wf[2][TN];
+        auto load_frags = [&](int ks, int buf) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8_t*>(cur + a_base + i * 32 * ROW_BYTES + foff[ks]);
+                af[buf][i] = *reinterpret_cast<const bf16x8_t*>(cur + a_base + i * 32 * ROW_BYTES + foff[ks]);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                wf[j] = *reinterpret_cast<const bf16x8_t*>(cur + w_base + j * 32 * ROW_BYTES + foff[ks]);
+                wf[buf][j] = *reinterpret_cast<const bf16x8_t*>(cur + w_base + j * 32 * ROW_BYTES + foff[ks]);
+        };
+        load_frags(0, 0);
+        la.fetch(knext);
+        lw.fetch(knext);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < 3) {
+                load_frags(ks + 1, (ks + 1) & 1);
+            } else {
+                la.store(nxt);
+                lw.store(nxt + A_BYTES);
+            }
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[j][i], 0, 0, 0);
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][j], af[ks & 1][i], acc[j][i], 0, 0, 0);
         }
-        if (more) {
-            la.store(nxt);
-            lw.store(nxt + A_BYTES);
+        // One pipeline description for the whole body, in issue order: the step-0
+        // fragments; then per step 2 MFMAs per fragment read of the next step (the
+        // tile's global loads ride along in step 0); in the last step one LDS store
+        // of the next tile per MFMA.
+        __builtin_amdgcn_sched_group_barrier(M_DS_RD, NFRAG, 0);
+#pragma unroll
+        for (int ks = 0; ks < 3; ++ks)
+#pragma unroll
+            for (int i = 0; i < NFRAG; ++i) {
+                __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA / NFRAG, 0);
+                __builtin_amdgcn_sched_group_barrier(M_DS_RD, 1, 0);
+                if (ks == 0) __builtin_amdgcn_sched_group_barrier(M_VMEM_RD, (LA_LOADS + LW_LOADS + NFRAG - 1) / NFRAG, 0);
+            }
+#pragma unroll
+        for (int i = 0; i < NMFMA; ++i) {
+            __builtin_amdgcn_sched_group_barrier(M_MFMA, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(M_DS_WR, (LA_STORES + LW_STORES + NMFMA - 1) / NMFMA, 0);
         }
         __syncthreads();
     }

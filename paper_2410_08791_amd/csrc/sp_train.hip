@@ -46,7 +46,14 @@ int decoder_layer_keep(sp_engine* e, const unsigned char* w, const LayerBufs& b,
     SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_G2), nullptr, m, T, dm, d.norm_eps));
     g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, gu, 2 * f, nullptr, 0, nullptr, T, 2 * f, dm, e->gemm_tile};
+    const bool kt = (e->flags & SP_FLAG_TIMING) && !e->kt_begin.empty();
+    const size_t kti = kt ? e->kt_count % e->kt_begin.size() : 0;
+    if (kt) {
+        SP_HIP(e, hipEventRecord(e->kt_begin[kti], st));
+        e->kt_m = T; e->kt_n = 2 * f; e->kt_k = dm;
+    }
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+    if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
     SP_HIP(e, spk_launch_swiglu(st, gu, z, T, f));
     if (b.h_out) {
         g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_WD), f, OP_KMAJOR, b.h_out, dm, b.h_mid, dm, nullptr, T, dm, f, e->gemm_tile};
