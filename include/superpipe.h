@@ -68,7 +68,7 @@ typedef struct {
     int32_t d_model;
     int32_t n_q_heads;
     int32_t n_kv_heads;     /* divides n_q_heads; query head j uses kv head j / (n_q/n_kv) */
-    int32_t head_dim;       /* multiple of 16, <= 128 */
+    int32_t head_dim;       /* 64, 80 or 128 */
     int32_t d_ffn;
     int32_t arch;           /* SP_DECODER_SWIGLU_RMS | SP_ENCODER_GELU_LN */
     int32_t causal;         /* 1: query i attends keys j <= i */
@@ -83,9 +83,11 @@ enum {
     SP_FLAG_POISON = 1u << 2,      /* debug: fill a slot with NaN patterns before reuse    */
     SP_FLAG_NO_OVERLAP = 1u << 3,  /* "Naive" comparator (Sec. 4.2): copies wait for all
                                       enqueued compute, compute waits for the copies       */
-    SP_FLAG_WRAP_PREFETCH = 1u << 4 /* forward-only: when the tail of a pass frees slots,
+    SP_FLAG_WRAP_PREFETCH = 1u << 4, /* forward-only: when the tail of a pass frees slots,
                                       start loading layers 0.. for the next call (the
                                       consecutive-forward stall of Sec. 5)                 */
+    SP_FLAG_KERNEL_TIMING = 1u << 5 /* bracket the layer's largest GEMM with timed events on
+                                      the compute stream only (big_gemm_* in sp_stats)     */
 };
 
 typedef struct {
@@ -131,7 +133,7 @@ typedef struct {
     float copy_hidden_ms;       /* part of it that lies under some layer's compute      */
     float compute_busy_ms;      /* sum of layer compute durations                       */
     float wall_ms;              /* first op begin -> last op end                        */
-    /* SP_FLAG_TIMING: the layer's largest GEMM (decoder: gate/up with the SwiGLU
+    /* SP_FLAG_KERNEL_TIMING (or SP_FLAG_TIMING): the layer's largest GEMM (decoder: gate/up with the SwiGLU
      * epilogue; encoder: the first MLP GEMM), bracketed by events on the compute
      * stream at every launch since the previous sp_get_stats.                         */
     uint32_t big_gemm_launches;

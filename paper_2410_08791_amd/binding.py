@@ -27,6 +27,7 @@ lib = C.CDLL(LIB_PATH)
 SP_OK, SP_ERR_INVALID_ARG, SP_ERR_BUDGET, SP_ERR_NOT_PINNED, SP_ERR_HIP, SP_ERR_STATE, SP_ERR_SHAPE = 0, -1, -2, -3, -4, -5, -6
 SP_DECODER_SWIGLU_RMS, SP_ENCODER_GELU_LN = 0, 1
 SP_FLAG_TRAINING, SP_FLAG_TIMING, SP_FLAG_POISON, SP_FLAG_NO_OVERLAP, SP_FLAG_WRAP_PREFETCH = 1, 2, 4, 8, 16
+SP_FLAG_KERNEL_TIMING = 32
 SP_MAX_TRACE_LAYERS = 256
 EPI_BF16, EPI_RESID_F32, EPI_GELU_BF16, EPI_SWIGLU_BF16, EPI_F32 = 0, 1, 2, 3, 4
 

@@ -33,7 +33,7 @@ struct AttnCfg {
 };
 
 template <int HD>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
                                                        const bf16_t* __restrict__ vt,
                                                        bf16_t* __restrict__ o, float* __restrict__ lse,
                                                        int S, int S_pad, int Hq, int Hkv, int ld_qkv,
@@ -93,7 +93,8 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
             d[1] = u32x2_t{v[2], v[3]};
         }
         __syncthreads();
-        if (causal && key0 > wq_last) continue;  // wave-uniform: nothing visible to this wave
+        // wave-uniform skips: nothing visible to this wave / no valid query in this wave
+        if ((causal && key0 > wq_last) || wq0 >= S) continue;
 
         // ---- S^T = K Q^T for two 32-key tiles
         f32x16_t sacc[2];
@@ -108,24 +109,27 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
                 sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[t], 0, 0, 0);
             }
         }
-        // ---- scale, mask, online softmax (base 2)
+        // ---- mask, online softmax in base 2 on the raw scores (the scale is positive,
+        //      so it commutes with max and is folded into the exponent's fma)
         const bool need_mask = (causal && key0 + KB - 1 > wq0) || (key0 + KB > S);
         float mx = -INFINITY;
+        if (need_mask) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int key = key0 + t * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+                    if (key >= S || (causal && key > qi)) sacc[t][e] = -INFINITY;
+                }
+        }
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float s = sacc[t][e] * scale_log2e;
-                if (need_mask) {
-                    const int key = key0 + t * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
-                    if (key >= S || (causal && key > qi)) s = -INFINITY;
-                }
-                sacc[t][e] = s;
-                mx = fmaxf(mx, s);
-            }
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[t][e]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m_run, mx);   // finite: key 0 is visible to every query
-        const float alpha = exp2f(m_run - m_new);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
+        const float m_scaled = m_new * scale_log2e;
         m_run = m_new;
         float psum = 0.f;
         bf16x8_t pf[2][2];
@@ -135,15 +139,17 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float pv = exp2f(sacc[t][j * 8 + e] - m_new);
+                    const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[t][j * 8 + e], scale_log2e, -m_scaled));
                     psum += pv;
                     pf[t][j][e] = (__bf16)pv;
                 }
         l_run = l_run * alpha + psum;
+        if (__any(alpha != 1.0f)) {   // the running maximum moved for some query of the wave
 #pragma unroll
-        for (int t = 0; t < C::NMT; ++t)
+            for (int t = 0; t < C::NMT; ++t)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+                for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+        }
         // ---- O^T += V^T P^T.  Step (t, j) contracts keys
         //      t*32 + 16j + {half*4 + 0..3, 8 + half*4 + 0..3}.
 #pragma unroll
@@ -177,7 +183,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
                                    pack_bf2(oacc[mt][g * 4 + 2] * inv, oacc[mt][g * 4 + 3] * inv));
             }
         if (lse && half == 0)
-            lse[((size_t)b * Hq + h) * S + qi] = m_run * 0.69314718055994530942f + logf(l_run);
+            lse[((size_t)b * Hq + h) * S + qi] = m_run * scale_log2e * 0.69314718055994530942f + logf(l_run);
     }
 }
 

@@ -37,15 +37,22 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {
     return row * ROW_BYTES + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
+// Exact-erf GELU, 0.5 x (1 + erf(x / sqrt 2)), with erf from the five-term rational
+// approximation of Abramowitz & Stegun 7.1.26 (absolute error < 1.5e-7, far below the
+// bf16 rounding of the result): branch-free, one exp and one reciprocal.
 __device__ __forceinline__ float gelu_erf(float x) {
-    return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+    const float z = fabsf(x) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float erf_abs = 1.0f - poly * __expf(-z * z);
+    return 0.5f * x * (1.0f + copysignf(erf_abs, x));
 }
 
 // ---- tile loaders -----------------------------------------------------------
 // K-major source: rows of 64 contiguous k. ROWS*8 16-byte chunks over 256 threads.
-template <int ROWS>
+template <int ROWS, int NT>
 struct LoaderK {
-    static constexpr int ITERS = ROWS * 8 / 256;
+    static constexpr int ITERS = ROWS * 8 / NT;
     static constexpr int N_LOADS = ITERS, N_STORES = ITERS;   // per thread and tile
     const bf16_t* src[ITERS];
     int dst[ITERS];
@@ -55,7 +62,7 @@ struct LoaderK {
     __device__ __forceinline__ void init(const bf16_t* base, int ld, RowMap row_of) {
 #pragma unroll
         for (int i = 0; i < ITERS; ++i) {
-            const int q = threadIdx.x + i * 256;
+            const int q = threadIdx.x + i * NT;
             const int row = q >> 3, c = q & 7;
             src[i] = base + (size_t)row_of(row) * ld + c * 8;
             dst[i] = lds_off(row, c);
@@ -75,10 +82,10 @@ struct LoaderK {
 // block per 256 tile rows.  Lane -> (k block = t & 7, row chunk = t >> 3): a
 // global row k gets 128 contiguous bytes from 8 lanes, and the 16-byte LDS
 // stores of 8 lanes fill one 128-byte tile row.
-template <int ROWS>
+template <int ROWS, int NT>
 struct LoaderR {
-    static constexpr int ITERS = ROWS / 256 > 0 ? ROWS / 256 : 1;
-    static constexpr bool PARTIAL = ROWS < 256;
+    static constexpr int ITERS = ROWS / NT > 0 ? ROWS / NT : 1;
+    static constexpr bool PARTIAL = ROWS < NT;
     static constexpr int N_LOADS = ITERS * 8, N_STORES = ITERS * 8;
     const bf16_t* src[ITERS];
     int ld_;
@@ -90,7 +97,7 @@ struct LoaderR {
         kb_ = threadIdx.x & 7;
 #pragma unroll
         for (int i = 0; i < ITERS; ++i) {
-            rc_[i] = (threadIdx.x >> 3) + i * 32;  // 8-row chunk index inside the tile
+            rc_[i] = (threadIdx.x >> 3) + i * (NT / 8);  // 8-row chunk index inside the tile
             src[i] = base + (size_t)(kb_ * 8) * ld + col_of(rc_[i] * 8);
         }
     }
@@ -123,16 +130,19 @@ struct LoaderR {
     }
 };
 
-template <int ROWS, int FORM>
-struct LoaderSel { typedef LoaderK<ROWS> type; };
-template <int ROWS>
-struct LoaderSel<ROWS, OP_RMAJOR> { typedef LoaderR<ROWS> type; };
+template <int ROWS, int NT, int FORM>
+struct LoaderSel { typedef LoaderK<ROWS, NT> type; };
+template <int ROWS, int NT>
+struct LoaderSel<ROWS, NT, OP_RMAJOR> { typedef LoaderR<ROWS, NT> type; };
 
 // ---- the kernel ---------------------------------------------------------------
-template <int BM, int BN, int EPI, int AFORM, int WFORM>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
+template <int BM, int BN, int EPI, int AFORM, int WFORM, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_kernel(GemmDev p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 tiles per wave
+    constexpr int NT = WAVES * 64;
+    constexpr int WNC = WAVES / 2;               // wave grid: 2 (m) x WNC (n)
+    constexpr int WN = BN / WNC;                 // tile rows of W per wave column
+    constexpr int TM = BM / 64, TN = WN / 32;    // 32x32 tiles per wave
     constexpr int A_BYTES = BM * ROW_BYTES, W_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + W_BYTES;
     constexpr bool SWIGLU = (EPI == EPI_SWIGLU_BF16);
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;  // output columns per block
@@ -152,8 +162,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
     const int tn = (pid % group) / gm;
     const int m0 = tm * BM, n0 = tn * BN_OUT;
 
-    typename LoaderSel<BM, AFORM>::type la;
-    typename LoaderSel<BN, WFORM>::type lw;
+    typename LoaderSel<BM, NT, AFORM>::type la;
+    typename LoaderSel<BN, NT, WFORM>::type lw;
     {
         const int M = p.M, N = p.N;
         if (AFORM == OP_KMAJOR)
@@ -164,9 +174,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
             // tile row r -> wave column wr, 32-row tile j; first half of a wave's
             // tiles are gate rows, second half the matching up rows (offset N).
             lw.init(p.W, p.ldw, [=](int r) {
-                const int wr = r / (BN / 2), j = (r % (BN / 2)) >> 5, rr = r & 31;
+                const int wr = r / WN, j = (r % WN) >> 5, rr = r & 31;
                 const int isup = j >= TN / 2;
-                const int col = n0 + wr * (BN / 4) + (isup ? j - TN / 2 : j) * 32 + rr;
+                const int col = n0 + wr * (WN / 2) + (isup ? j - TN / 2 : j) * 32 + rr;
                 return min(col, N - 1) + (isup ? N : 0);
             });
         } else if (WFORM == OP_KMAJOR) {
@@ -190,7 +200,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) foff[ks] = l32 * ROW_BYTES + (((2 * ks + half) ^ sw) << 4);
     const int a_base = wm * (BM / 2) * ROW_BYTES;
-    const int w_base = A_BYTES + wn * (BN / 2) * ROW_BYTES;
+    const int w_base = A_BYTES + wn * WN * ROW_BYTES;
 
     const int KT = p.K / BK;
     la.fetch(0);
@@ -205,8 +215,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
     // scheduling hints interleave the LDS reads of step s+1 with the MFMAs of step
     // s, and the LDS stores of the next tile with the MFMAs of the last step.
     constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
-    typedef typename LoaderSel<BM, AFORM>::type LA;
-    typedef typename LoaderSel<BN, WFORM>::type LW;
+    typedef typename LoaderSel<BM, NT, AFORM>::type LA;
+    typedef typename LoaderSel<BN, NT, WFORM>::type LW;
     constexpr int LA_LOADS = LA::N_LOADS, LW_LOADS = LW::N_LOADS, LA_STORES = LA::N_STORES, LW_STORES = LW::N_STORES;
     constexpr int M_MFMA = 0x008, M_VMEM_RD = 0x020, M_DS_RD = 0x100, M_DS_WR = 0x200;
     for (int kt = 0; kt < KT; ++kt) {
@@ -245,13 +255,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
         // of the next tile per MFMA.
         __builtin_amdgcn_sched_group_barrier(M_DS_RD, NFRAG, 0);
 #pragma unroll
-        for (int ks = 0; ks < 3; ++ks)
+        for (int ks = 0; ks < 3; ++ks) {
 #pragma unroll
             for (int i = 0; i < NFRAG; ++i) {
                 __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA / NFRAG, 0);
                 __builtin_amdgcn_sched_group_barrier(M_DS_RD, 1, 0);
                 if (ks == 0) __builtin_amdgcn_sched_group_barrier(M_VMEM_RD, (LA_LOADS + LW_LOADS + NFRAG - 1) / NFRAG, 0);
             }
+            if (NMFMA % NFRAG) __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA % NFRAG, 0);
+        }
 #pragma unroll
         for (int i = 0; i < NMFMA; ++i) {
             __builtin_amdgcn_sched_group_barrier(M_MFMA, 1, 0);
@@ -271,13 +283,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
             for (int j = 0; j < TN / 2; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * (BN / 4) + j * 32 + g * 8 + half * 4;
+                    const int n = n0 + wn * (WN / 2) + j * 32 + g * 8 + half * 4;
                     if (n >= p.N) continue;
                     float z[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float gv = acc[j][i][g * 4 + e], uv = acc[j + TN / 2][i][g * 4 + e];
-                        z[e] = gv / (1.0f + __expf(-gv)) * uv;
+                        z[e] = gv * __builtin_amdgcn_rcpf(1.0f + __expf(-gv)) * uv;
                     }
                     *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n) =
                         make_uint2(pack_bf2(z[0], z[1]), pack_bf2(z[2], z[3]));
@@ -287,7 +299,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * (BN / 2) + j * 32 + g * 8 + half * 4;
+                    const int n = n0 + wn * WN + j * 32 + g * 8 + half * 4;
                     if (n >= p.N) continue;
                     float v[4];
 #pragma unroll
@@ -316,12 +328,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmDev p) {
     }
 }
 
-template <int BM, int BN, int EPI, int AFORM, int WFORM>
+template <int BM, int BN, int EPI, int AFORM, int WFORM, int WAVES>
 hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
     constexpr int LDS = 2 * (BM + BN) * ROW_BYTES;
     constexpr int BN_OUT = (EPI == EPI_SWIGLU_BF16) ? BN / 2 : BN;
     static bool attr_set = false;  // per instantiation; a benign race sets it twice at worst
-    auto kern = gemm_kernel<BM, BN, EPI, AFORM, WFORM>;
+    auto kern = gemm_kernel<BM, BN, EPI, AFORM, WFORM, WAVES>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -335,29 +347,30 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
     d.tilesM = (g.M + BM - 1) / BM;
     d.tilesN = (g.N + BN_OUT - 1) / BN_OUT;
     const int nblocks = d.tilesM * d.tilesN;
-    gemm_kernel<BM, BN, EPI, AFORM, WFORM><<<nblocks, 256, LDS, st>>>(d);
+    gemm_kernel<BM, BN, EPI, AFORM, WFORM, WAVES><<<nblocks, WAVES * 64, LDS, st>>>(d);
     return hipGetLastError();
 }
 
-// Tile shapes: 1 = 128x128, 2 = 128x256 (BM x BN), 3 = 256x256.
-// The heuristic wants at least ~2 work-groups per CU's worth of tiles before it
-// moves to a larger tile (256 CUs; the 256x256 tile runs one group per CU).
-int pick_tile(int M, int N, int epi) {
+// Tile shapes: 1 = 128x128, 2 = 128x256 (BM x BN), 3 = 256x256, 4 = 256x256 with 8 waves.
+// Measured on MI355X over the workloads' shapes: the 256x256 tile wins once it yields
+// about 150 work-groups (256 CUs), else 128x128 (two groups per CU).  With both
+// operands' contraction index contiguous the 8-wave form is used (two waves per SIMD hide
+// each other's stalls); the transposing loaders need more registers and stay at 4 waves.
+int pick_tile(int M, int N, int epi, bool kmajor_operands) {
     const int n_out_256 = (epi == EPI_SWIGLU_BF16) ? 128 : 256;
     const long t256 = (long)((M + 255) / 256) * ((N + n_out_256 - 1) / n_out_256);
-    const long t128x256 = (long)((M + 127) / 128) * ((N + n_out_256 - 1) / n_out_256);
-    if (t256 >= 480) return 3;
-    if (t128x256 >= 480) return 2;
+    if (t256 >= 150) return kmajor_operands ? 4 : 3;
     return 1;
 }
 
 template <int EPI, int AFORM, int WFORM>
 hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
-    int tile = g.tile ? g.tile : pick_tile(g.M, g.N, EPI);
+    int tile = g.tile ? g.tile : pick_tile(g.M, g.N, EPI, AFORM == OP_KMAJOR && WFORM == OP_KMAJOR);
     switch (tile) {
-        case 1: return launch_one<128, 128, EPI, AFORM, WFORM>(st, g);
-        case 2: return launch_one<128, 256, EPI, AFORM, WFORM>(st, g);
-        case 3: return launch_one<256, 256, EPI, AFORM, WFORM>(st, g);
+        case 1: return launch_one<128, 128, EPI, AFORM, WFORM, 4>(st, g);
+        case 2: return launch_one<128, 256, EPI, AFORM, WFORM, 4>(st, g);
+        case 3: return launch_one<256, 256, EPI, AFORM, WFORM, 4>(st, g);
+        case 4: return launch_one<256, 256, EPI, AFORM, WFORM, 8>(st, g);
     }
     return hipErrorInvalidValue;
 }

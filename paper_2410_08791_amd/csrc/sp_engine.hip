@@ -156,7 +156,7 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
     SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     // b5: a = norm(h)
     SP_HIP(e, spk_launch_norm(st, h, W(dec ? SP_T_G2 : SP_T_LN2_G), dec ? nullptr : W(SP_T_LN2_B), a, T, dm, d.norm_eps));
-    const bool kt = (e->flags & SP_FLAG_TIMING) && !e->kt_begin.empty();
+    const bool kt = !e->kt_begin.empty();
     const size_t kti = kt ? e->kt_count % e->kt_begin.size() : 0;
     if (kt) {
         SP_HIP(e, hipEventRecord(e->kt_begin[kti], st));
@@ -262,8 +262,8 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
         he = mk(&e->grad_ready[i], hipEventDisableTiming);
         if (he == hipSuccess) he = mk(&e->gslot_free[i], hipEventDisableTiming);
     }
-    if (he == hipSuccess && timing) {
-        he = mk(&e->t0, hipEventDefault);
+    if (he == hipSuccess && timing) he = mk(&e->t0, hipEventDefault);
+    if (he == hipSuccess && (cfg->flags & (SP_FLAG_TIMING | SP_FLAG_KERNEL_TIMING))) {
         e->kt_begin.assign(2048, nullptr);
         e->kt_end.assign(2048, nullptr);
         for (size_t i = 0; i < e->kt_begin.size() && he == hipSuccess; ++i) {
@@ -374,7 +374,7 @@ extern "C" int sp_get_stats(sp_handle e, sp_stats* out) {
     out->d2h_bytes = e->stats_d2h_bytes;
     out->last_h2d_copies = e->call_h2d_copies;
     out->last_h2d_bytes = e->call_h2d_bytes;
-    if (!(e->flags & SP_FLAG_TIMING) || e->calls == 0) return SP_OK;
+    if (!(e->flags & (SP_FLAG_TIMING | SP_FLAG_KERNEL_TIMING)) || e->calls == 0) return SP_OK;
     SP_HIP(e, hipStreamSynchronize(e->h2d));
     SP_HIP(e, hipStreamSynchronize(e->compute));
     if (e->d2h) SP_HIP(e, hipStreamSynchronize(e->d2h));
@@ -389,6 +389,7 @@ extern "C" int sp_get_stats(sp_handle e, sp_stats* out) {
         out->big_gemm_m = e->kt_m; out->big_gemm_n = e->kt_n; out->big_gemm_k = e->kt_k;
         e->kt_count = 0;
     }
+    if (!(e->flags & SP_FLAG_TIMING)) return SP_OK;
     // Per-op trace of the most recent call from the fence events' timestamps.  An op
     // begins when its stream's previous op has ended and its dependency is met.
     const int nc = e->ci, nm = e->mi;

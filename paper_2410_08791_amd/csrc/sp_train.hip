@@ -46,7 +46,7 @@ int decoder_layer_keep(sp_engine* e, const unsigned char* w, const LayerBufs& b,
     SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_G2), nullptr, m, T, dm, d.norm_eps));
     g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, gu, 2 * f, nullptr, 0, nullptr, T, 2 * f, dm, e->gemm_tile};
-    const bool kt = (e->flags & SP_FLAG_TIMING) && !e->kt_begin.empty();
+    const bool kt = !e->kt_begin.empty();
     const size_t kti = kt ? e->kt_count % e->kt_begin.size() : 0;
     if (kt) {
         SP_HIP(e, hipEventRecord(e->kt_begin[kti], st));
