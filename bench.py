@@ -189,6 +189,16 @@ def main():
                 "flops_per_launch": gemm_flops, "avg_launch_ms": round(gemm_ms, 4),
                 "launches_timed": int(kst.big_gemm_launches), "shape_mnk": [gm, gn, gk]}
 
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}_gate_up_gemm.json")
+    if os.path.exists(tpath) and not training:
+        # HBM-side bytes per launch of this kernel from two rocprofv3 --pmc runs of this same
+        # command (FETCH_SIZE, WRITE_SIZE), scaled by a copy kernel of known size; a stored
+        # measurement, since counters cannot be read from inside this process
+        tj = json.load(open(tpath))
+        roofline["traffic"] = tj["traffic_bytes_per_launch"]
+        roofline["traffic_source"] = os.path.relpath(tpath, ROOT)
+        roofline["algorithmic_bytes"] = tj["algorithmic_bytes_per_launch"]
+
     extra = {
         "peak_hbm_bytes": int(st.plan.arena_bytes_used), "budget_bytes": int(main_run["budget"]),
         "h2d_gbps_over_wall": round(h2d_gbps_wall, 2),

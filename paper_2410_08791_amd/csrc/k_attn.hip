@@ -39,14 +39,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
                                                        int S, int S_pad, int Hq, int Hkv, int ld_qkv,
                                                        int causal, float scale_log2e) {
     typedef AttnCfg<HD> C;
-    __shared__ __attribute__((aligned(16))) unsigned char sK[C::K_BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char sV[C::V_BYTES];
+    // two K tiles then two V^T tiles (double buffered)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    // heavy (late) query blocks first when causal
+    // Causal: late query blocks carry more key tiles.  Work-groups are dealt to the CUs in
+    // id order, two resident per CU, so every other batch of 256 ids walks the query blocks
+    // in the opposite direction: a CU then holds one heavy and one light block.
     const int nqb = gridDim.x;
-    const int qb = causal ? nqb - 1 - blockIdx.x : blockIdx.x;
+    const int lin = blockIdx.x + nqb * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int qb = !causal ? blockIdx.x : (((lin >> 8) & 1) ? blockIdx.x : nqb - 1 - blockIdx.x);
     const int h = blockIdx.y, b = blockIdx.z;
     const int kvh = h / (Hq / Hkv);
     const int q0 = qb * QB;
@@ -76,25 +79,62 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
     const int ntiles = (k_end + KB - 1) / KB;
     const int wq_last = wq0 + 31;
 
+    // Tile staging: global -> registers (issued one tile ahead) -> LDS buffer (kt+1)&1
+    // while buffer kt&1 is being consumed; one barrier per tile.
+    constexpr int NK = (C::CHUNKS_K + 255) / 256, NV = (C::CHUNKS_V + 255) / 256;
+    u32x4_t rk[NK], rv[NV];
+    auto fetch = [&](int key0) {
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            const int c = threadIdx.x + i * 256;
+            if (c < C::CHUNKS_K) {
+                const int r = c / (HD / 8), cc = c % (HD / 8);
+                rk[i] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)min(key0 + r, S - 1) * ld_qkv + cc * 8);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = threadIdx.x + i * 256;
+            if (c < C::CHUNKS_V) {
+                const int r = c / (KB / 8), cc = c % (KB / 8);
+                rv[i] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)r * S_pad + key0 + cc * 8);
+            }
+        }
+    };
+    auto stash = [&](int buf) {
+        unsigned char* dK = smem_attn + buf * C::K_BYTES;
+        unsigned char* dV = smem_attn + 2 * C::K_BYTES + buf * C::V_BYTES;
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            const int c = threadIdx.x + i * 256;
+            if (c < C::CHUNKS_K) {
+                const int r = c / (HD / 8), cc = c % (HD / 8);
+                *reinterpret_cast<u32x4_t*>(dK + r * C::K_STRIDE + cc * 16) = rk[i];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = threadIdx.x + i * 256;
+            if (c < C::CHUNKS_V) {
+                const int r = c / (KB / 8), cc = c % (KB / 8);
+                u32x2_t* d = reinterpret_cast<u32x2_t*>(dV + r * C::V_STRIDE + cc * 16);
+                d[0] = u32x2_t{rv[i][0], rv[i][1]};
+                d[1] = u32x2_t{rv[i][2], rv[i][3]};
+            }
+        }
+    };
+    fetch(0);
+    stash(0);
+    __syncthreads();
+
     for (int kt = 0; kt < ntiles; ++kt) {
         const int key0 = kt * KB;
-        __syncthreads();  // previous tile fully consumed
-        for (int c = threadIdx.x; c < C::CHUNKS_K; c += 256) {
-            const int r = c / (HD / 8), cc = c % (HD / 8);
-            const int kr = min(key0 + r, S - 1);
-            *reinterpret_cast<u32x4_t*>(sK + r * C::K_STRIDE + cc * 16) =
-                *reinterpret_cast<const u32x4_t*>(kbase + (size_t)kr * ld_qkv + cc * 8);
-        }
-        for (int c = threadIdx.x; c < C::CHUNKS_V; c += 256) {
-            const int r = c / (KB / 8), cc = c % (KB / 8);
-            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)r * S_pad + key0 + cc * 8);
-            u32x2_t* d = reinterpret_cast<u32x2_t*>(sV + r * C::V_STRIDE + cc * 16);
-            d[0] = u32x2_t{v[0], v[1]};
-            d[1] = u32x2_t{v[2], v[3]};
-        }
-        __syncthreads();
+        const bool more = kt + 1 < ntiles;
+        if (more) fetch(key0 + KB);
+        const unsigned char* sK = smem_attn + (kt & 1) * C::K_BYTES;
+        const unsigned char* sV = smem_attn + 2 * C::K_BYTES + (kt & 1) * C::V_BYTES;
         // wave-uniform skips: nothing visible to this wave / no valid query in this wave
-        if ((causal && key0 > wq_last) || wq0 >= S) continue;
+        if (!((causal && key0 > wq_last) || wq0 >= S)) {
 
         // ---- S^T = K Q^T for two 32-key tiles
         f32x16_t sacc[2];
@@ -165,6 +205,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
                     oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, both),
                                                                        pf[t][j], oacc[mt], 0, 0, 0);
                 }
+        }
+        if (more) stash((kt + 1) & 1);
+        __syncthreads();
     }
 
     // ---- finish: denominators, write o (and the log-sum-exp for the backward)
@@ -208,6 +251,22 @@ __global__ __launch_bounds__(256) void transpose_heads_kernel(const bf16_t* __re
     }
 }
 
+template <int HD>
+hipError_t launch_fwd(hipStream_t st, dim3 grid, const bf16_t* qkv, const bf16_t* vt, bf16_t* o, float* lse,
+                      const AttnShape& a, int sp, float sl2) {
+    typedef AttnCfg<HD> C;
+    constexpr int LDS = 2 * (C::K_BYTES + C::V_BYTES);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_kernel<HD>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    attn_fwd_kernel<HD><<<grid, 256, LDS, st>>>(qkv, vt, o, lse, a.S, sp, a.Hq, a.Hkv, a.ld_qkv, a.causal, sl2);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t spk_launch_transpose_heads(hipStream_t st, const bf16_t* src, int ld, int col0, int nheads, int B, int S,
@@ -233,17 +292,10 @@ hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, const bf16_t*
     dim3 grid((a.S + QB - 1) / QB, a.Hq, a.B);
     const int sp = attn_s_pad(a.S);
     switch (a.hd) {
-        case 64:
-            attn_fwd_kernel<64><<<grid, 256, 0, st>>>(qkv, vt, o, lse, a.S, sp, a.Hq, a.Hkv, a.ld_qkv, a.causal, sl2);
-            break;
-        case 80:
-            attn_fwd_kernel<80><<<grid, 256, 0, st>>>(qkv, vt, o, lse, a.S, sp, a.Hq, a.Hkv, a.ld_qkv, a.causal, sl2);
-            break;
-        case 128:
-            attn_fwd_kernel<128><<<grid, 256, 0, st>>>(qkv, vt, o, lse, a.S, sp, a.Hq, a.Hkv, a.ld_qkv, a.causal, sl2);
-            break;
-        default:
-            return hipErrorInvalidValue;
+        case 64: return launch_fwd<64>(st, grid, qkv, vt, o, lse, a, sp, sl2);
+        case 80: return launch_fwd<80>(st, grid, qkv, vt, o, lse, a, sp, sl2);
+        case 128: return launch_fwd<128>(st, grid, qkv, vt, o, lse, a, sp, sl2);
+        default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
