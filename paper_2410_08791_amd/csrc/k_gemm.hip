@@ -135,6 +135,68 @@ struct LoaderSel { typedef LoaderK<ROWS, NT> type; };
 template <int ROWS, int NT>
 struct LoaderSel<ROWS, NT, OP_RMAJOR> { typedef LoaderR<ROWS, NT> type; };
 
+// Epilogue shared by the GEMM kernels.  acc[j][i] is the 32x32 tile (n tile j, m tile i) of
+// a wave whose first row is m_base and first output column n_base; a lane holds row l32 of
+// the m tile and, in register e, column j*32 + (e/4)*8 + half*4 + e%4.
+template <int EPI, int TM, int TN>
+__device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[TN][TM], int m_base, int n_base,
+                                              int l32, int half) {
+    constexpr bool SWIGLU = (EPI == EPI_SWIGLU_BF16);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m_base + i * 32 + l32;
+        if (m >= p.M) continue;
+        if (SWIGLU) {
+#pragma unroll
+            for (int j = 0; j < TN / 2; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n_base + j * 32 + g * 8 + half * 4;
+                    if (n >= p.N) continue;
+                    float z[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float gv = acc[j][i][g * 4 + e], uv = acc[j + TN / 2][i][g * 4 + e];
+                        z[e] = gv * __builtin_amdgcn_rcpf(1.0f + __expf(-gv)) * uv;
+                    }
+                    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n) =
+                        make_uint2(pack_bf2(z[0], z[1]), pack_bf2(z[2], z[3]));
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n_base + j * 32 + g * 8 + half * 4;
+                    if (n >= p.N) continue;
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = acc[j][i][g * 4 + e];
+                    if (p.bias) {
+                        const uint2 b = *reinterpret_cast<const uint2*>(p.bias + n);
+                        v[0] += bf_lo(b.x); v[1] += bf_hi(b.x); v[2] += bf_lo(b.y); v[3] += bf_hi(b.y);
+                    }
+                    if (EPI == EPI_RESID_F32) {
+                        const float4 r = *reinterpret_cast<const float4*>(p.R + (size_t)m * p.ldr + n);
+                        *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (size_t)m * p.ldc + n) =
+                            make_float4(r.x + v[0], r.y + v[1], r.z + v[2], r.w + v[3]);
+                    } else if (EPI == EPI_F32) {
+                        *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (size_t)m * p.ldc + n) =
+                            make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+                        if (EPI == EPI_GELU_BF16) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
+                        }
+                        *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n) =
+                            make_uint2(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]));
+                    }
+                }
+        }
+    }
+}
+
+
 // ---- the kernel ---------------------------------------------------------------
 template <int BM, int BN, int EPI, int AFORM, int WFORM, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void gemm_kernel(GemmDev p) {
@@ -272,60 +334,170 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_kernel(GemmDev p) {
         __syncthreads();
     }
 
-    // ---- epilogue: lane holds row m (l32), register e of tile j = column
-    //      j*32 + (e/4)*8 + half*4 + e%4 of the wave's n range.
+    gemm_epilogue<EPI, TM, TN>(p, acc, m0 + wm * (BM / 2), SWIGLU ? n0 + wn * (WN / 2) : n0 + wn * WN, l32, half);
+}
+
+// ---- LDS-DMA variant: 256x256 tile, 32-deep stages, 4-stage ring ---------------------
+// Global loads write LDS directly (global_load_lds_dwordx4): no staging registers, no LDS
+// store instructions, and three tiles in flight instead of one.  A wave instruction lands
+// 64 lanes x 16 bytes = 16 tile rows of 64 bytes contiguously, so the XOR swizzle of the
+// 16-byte chunks is applied on the global side (which chunk a lane fetches).  The compiler
+// does not track these loads against later LDS reads, so the kernel counts them itself:
+// every iteration issues the same number of loads per thread (the tail re-fetches the last
+// tile into an idle stage) and waits with an explicit vmcnt before the barrier.
+constexpr int DBK = 32, DROW = 64, DSTAGES = 4;
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+template <int EPI, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int BM = 256, BN = 256;
+    constexpr int WNC = WAVES / 2, WN = BN / WNC;
+    constexpr int TM = BM / 64, TN = WN / 32;
+    constexpr int A_BYTES = BM * DROW, STAGE = (BM + BN) * DROW;
+    constexpr bool SWIGLU = (EPI == EPI_SWIGLU_BF16);
+    constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    constexpr int NI = 32 / WAVES;             // 1 KiB load instructions per wave and stage
+    static_assert(!SWIGLU || (TN % 2 == 0), "gate and up tiles pair up inside a wave");
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    int pid = xcd_remap(blockIdx.x, gridDim.x);
+    constexpr int GM = 8;
+    const int group = GM * p.tilesN;
+    const int first_m = (pid / group) * GM;
+    const int gm = min(p.tilesM - first_m, GM);
+    const int tm = first_m + (pid % group) % gm;
+    const int tn = (pid % group) / gm;
+    const int m0 = tm * BM, n0 = tn * BN_OUT;
+
+    // load assignment: block b of 16 tile rows, b < 16 -> A rows, else W rows
+    const bf16_t* src[NI];
+    int dst[NI];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm * (BM / 2) + i * 32 + l32;
-        if (m >= p.M) continue;
-        if (SWIGLU) {
-#pragma unroll
-            for (int j = 0; j < TN / 2; ++j)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * (WN / 2) + j * 32 + g * 8 + half * 4;
-                    if (n >= p.N) continue;
-                    float z[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float gv = acc[j][i][g * 4 + e], uv = acc[j + TN / 2][i][g * 4 + e];
-                        z[e] = gv * __builtin_amdgcn_rcpf(1.0f + __expf(-gv)) * uv;
-                    }
-                    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n) =
-                        make_uint2(pack_bf2(z[0], z[1]), pack_bf2(z[2], z[3]));
-                }
+    for (int i = 0; i < NI; ++i) {
+        const int blk = wave * NI + i;
+        const bool is_w = blk >= 16;
+        const int row = (blk & 15) * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+        if (is_w) {
+            int grow;
+            if (SWIGLU) {
+                const int wr = row / WN, j = (row % WN) >> 5, rr = row & 31;
+                const int isup = j >= TN / 2;
+                const int col = n0 + wr * (WN / 2) + (isup ? j - TN / 2 : j) * 32 + rr;
+                grow = min(col, p.N - 1) + (isup ? p.N : 0);
+            } else {
+                grow = min(n0 + row, p.N - 1);
+            }
+            src[i] = p.W + (size_t)grow * p.ldw + chunk * 8;
         } else {
+            src[i] = p.A + (size_t)min(m0 + row, p.M - 1) * p.lda + chunk * 8;
+        }
+        dst[i] = (is_w ? A_BYTES : 0) + (blk & 15) * 16 * DROW;
+    }
+    const int KT = p.K / DBK;
+    // (The builtin's address-space-qualified parameters do not type-check in the host pass
+    // of a template, which would silently drop the kernel's host stub: device pass only.)
+#if defined(__HIP_DEVICE_COMPILE__)
+#define SP_DMA_ISSUE(tile, stage)                                                                              \
+    do {                                                                                                       \
+        const int k0_ = min((tile), KT - 1) * DBK;                                                             \
+        _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_)                                                      \
+            __builtin_amdgcn_global_load_lds(src[i_] + k0_, (lds_void_ptr)(smem + (stage) * STAGE + dst[i_]), \
+                                             16, 0, 0);                                                        \
+    } while (0)
+#else
+#define SP_DMA_ISSUE(tile, stage) ((void)src, (void)dst)
+#endif
+
+    f32x16_t acc[TN][TM];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+
+    const int sw = (l32 >> 2) & 3;
+    int foff[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) foff[ks] = l32 * DROW + (((2 * ks + half) ^ sw) << 4);
+    const int a_base = wm * (BM / 2) * DROW;
+    const int w_base = A_BYTES + wn * WN * DROW;
+
+    SP_DMA_ISSUE(0, 0);
+    SP_DMA_ISSUE(1, 1);
+    SP_DMA_ISSUE(2, 2);
+    constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
+    constexpr int M_MFMA = 0x008, M_DS_RD = 0x100;
+    // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt 7<<4 | lgkmcnt 15<<8 | vmcnt[5:4]<<14)
+    constexpr int VM_KEEP = 2 * NI;
+    constexpr int WAIT_IMM = (VM_KEEP & 15) | (7 << 4) | (15 << 8) | ((VM_KEEP >> 4) << 14);
+    for (int kt = 0; kt < KT; ++kt) {
+        // This thread's loads of tile kt have landed; after the barrier everyone's have, and
+        // stage (kt+3)&3 is idle.  A bare s_barrier: the fence of __syncthreads() would wait
+        // for ALL outstanding LDS-DMA loads and empty the pipeline.  The empty asm statements
+        // keep the compiler from moving LDS accesses across it.
+        __builtin_amdgcn_s_waitcnt(WAIT_IMM);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        SP_DMA_ISSUE(kt + 3, (kt + 3) & 3);
+        const unsigned char* cur = smem + (kt & 3) * STAGE;
+        bf16x8_t af[2][TM], wf[2][TN];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[ks][i] = *reinterpret_cast<const bf16x8_t*>(cur + a_base + i * 32 * DROW + foff[ks]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                wf[ks][j] = *reinterpret_cast<const bf16x8_t*>(cur + w_base + j * 32 * DROW + foff[ks]);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * WN + j * 32 + g * 8 + half * 4;
-                    if (n >= p.N) continue;
-                    float v[4];
+                for (int i = 0; i < TM; ++i)
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks][j], af[ks][i], acc[j][i], 0, 0, 0);
+        // first step's fragments up front, the second step's reads under the first step's MFMAs
+        __builtin_amdgcn_sched_group_barrier(M_DS_RD, NFRAG, 0);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = acc[j][i][g * 4 + e];
-                    if (p.bias) {
-                        const uint2 b = *reinterpret_cast<const uint2*>(p.bias + n);
-                        v[0] += bf_lo(b.x); v[1] += bf_hi(b.x); v[2] += bf_lo(b.y); v[3] += bf_hi(b.y);
-                    }
-                    if (EPI == EPI_RESID_F32) {
-                        const float4 r = *reinterpret_cast<const float4*>(p.R + (size_t)m * p.ldr + n);
-                        *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (size_t)m * p.ldc + n) =
-                            make_float4(r.x + v[0], r.y + v[1], r.z + v[2], r.w + v[3]);
-                    } else if (EPI == EPI_F32) {
-                        *reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (size_t)m * p.ldc + n) =
-                            make_float4(v[0], v[1], v[2], v[3]);
-                    } else {
-                        if (EPI == EPI_GELU_BF16) {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
-                        }
-                        *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n) =
-                            make_uint2(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]));
-                    }
-                }
+        for (int i = 0; i < NFRAG; ++i) {
+            __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA / NFRAG, 0);
+            __builtin_amdgcn_sched_group_barrier(M_DS_RD, 1, 0);
         }
     }
+    __builtin_amdgcn_s_waitcnt((0 & 15) | (7 << 4) | (15 << 8));   // drain the tail's idle loads
+    gemm_epilogue<EPI, TM, TN>(p, acc, m0 + wm * (BM / 2), SWIGLU ? n0 + wn * (WN / 2) : n0 + wn * WN, l32, half);
+#undef SP_DMA_ISSUE
+}
+
+template <int EPI, int WAVES>
+hipError_t launch_dma(hipStream_t st, const GemmArgs& g) {
+    constexpr int LDS = DSTAGES * 512 * DROW;
+    constexpr int BN_OUT = (EPI == EPI_SWIGLU_BF16) ? 128 : 256;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<EPI, WAVES>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    GemmDev d;
+    d.A = g.A; d.W = g.W; d.C = g.C; d.R = g.R; d.bias = g.bias;
+    d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc; d.ldr = g.ldr;
+    d.M = g.M; d.N = g.N; d.K = g.K;
+    d.tilesM = (g.M + 255) / 256;
+    d.tilesN = (g.N + BN_OUT - 1) / BN_OUT;
+    gemm_dma_kernel<EPI, WAVES><<<d.tilesM * d.tilesN, WAVES * 64, LDS, st>>>(d);
+    return hipGetLastError();
 }
 
 template <int BM, int BN, int EPI, int AFORM, int WFORM, int WAVES>
@@ -371,6 +543,8 @@ hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
         case 2: return launch_one<128, 256, EPI, AFORM, WFORM, 4>(st, g);
         case 3: return launch_one<256, 256, EPI, AFORM, WFORM, 4>(st, g);
         case 4: return launch_one<256, 256, EPI, AFORM, WFORM, 8>(st, g);
+        case 5: if (AFORM == OP_KMAJOR && WFORM == OP_KMAJOR) return launch_dma<EPI, 8>(st, g); break;
+        case 6: if (AFORM == OP_KMAJOR && WFORM == OP_KMAJOR) return launch_dma<EPI, 4>(st, g); break;
     }
     return hipErrorInvalidValue;
 }

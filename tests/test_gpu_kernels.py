@@ -52,7 +52,7 @@ def gemm_ref(A, W, epi, R=None, bias=None, N=None):
     return acc
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 0])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 0])
 @pytest.mark.parametrize("M,N,K", [(200, 328, 128), (257, 296, 64), (300, 520, 256), (64, 128, 1024)])
 @pytest.mark.parametrize("epi", [sp.EPI_BF16, sp.EPI_RESID_F32, sp.EPI_GELU_BF16, sp.EPI_SWIGLU_BF16, sp.EPI_F32])
 def test_gemm_kmajor(epi, M, N, K, tile):
