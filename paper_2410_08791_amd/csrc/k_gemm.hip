@@ -16,9 +16,9 @@
 // pieces of a row instead of single elements.
 //
 // An operand whose contraction index is NOT contiguous in memory (the backward
-// GEMMs) is transposed on the way in: a thread loads an 8x8 bf16 block with
-// eight 16-byte loads, transposes it in registers with byte permutes and
-// stores eight 16-byte chunks.
+// GEMMs) is staged as it lies in memory (LDS row = contraction index) and read
+// with the transposing LDS load of gfx950 (ds_read_b64_tr_b16), which hands each
+// lane four consecutive contraction elements of one operand row.
 #include "sp_kernels.h"
 
 namespace {
@@ -78,57 +78,64 @@ struct LoaderK {
     }
 };
 
-// Row-major source (element (r,k) at base[k*ld + r]): per thread one 8(k) x 8(r)
-// block per 256 tile rows.  Lane -> (k block = t & 7, row chunk = t >> 3): a
-// global row k gets 128 contiguous bytes from 8 lanes, and the 16-byte LDS
-// stores of 8 lanes fill one 128-byte tile row.
+// Row-major source (element (r,k) at base[k*ld + r]): the tile is copied as it lies in
+// memory -- LDS row = contraction index k (64 rows), ROWS contiguous r values per row, rows
+// padded by 64 bytes -- with the same coalesced 16-byte chunks as above.  The transposition
+// happens in the fragment read (ds_read_b64_tr_b16, see tr_frag below).
+template <int ROWS>
+struct TLayout {
+    static constexpr int STRIDE = ROWS * 2 + 64;   // bytes per k row
+    static constexpr int BYTES = BK * STRIDE;
+};
+
 template <int ROWS, int NT>
 struct LoaderR {
-    static constexpr int ITERS = ROWS / NT > 0 ? ROWS / NT : 1;
-    static constexpr bool PARTIAL = ROWS < NT;
-    static constexpr int N_LOADS = ITERS * 8, N_STORES = ITERS * 8;
+    static constexpr int CPR = ROWS / 8;           // 16-byte chunks per k row
+    static constexpr int ITERS = BK * CPR / NT;
+    static constexpr int N_LOADS = ITERS, N_STORES = ITERS;
     const bf16_t* src[ITERS];
+    int dst[ITERS];
     int ld_;
-    int rc_[ITERS], kb_;
-    u32x4_t regs[ITERS][8];
+    u32x4_t regs[ITERS];
+    // col_of(r) maps the tile's first r of a chunk to a (clamped) global r.
     template <class ColMap>
     __device__ __forceinline__ void init(const bf16_t* base, int ld, ColMap col_of) {
         ld_ = ld;
-        kb_ = threadIdx.x & 7;
 #pragma unroll
         for (int i = 0; i < ITERS; ++i) {
-            rc_[i] = (threadIdx.x >> 3) + i * (NT / 8);  // 8-row chunk index inside the tile
-            src[i] = base + (size_t)(kb_ * 8) * ld + col_of(rc_[i] * 8);
+            const int q = threadIdx.x + i * NT;
+            const int k = q / CPR, c = q % CPR;
+            src[i] = base + (size_t)k * ld + col_of(c * 8);
+            dst[i] = k * TLayout<ROWS>::STRIDE + c * 16;
         }
     }
-    __device__ __forceinline__ bool active(int i) const { return !PARTIAL || rc_[i] * 8 < ROWS; }
     __device__ __forceinline__ void fetch(int k0) {
 #pragma unroll
-        for (int i = 0; i < ITERS; ++i)
-            if (active(i)) {
-                const bf16_t* p = src[i] + (size_t)k0 * ld_;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) regs[i][e] = *reinterpret_cast<const u32x4_t*>(p + (size_t)e * ld_);
-            }
+        for (int i = 0; i < ITERS; ++i) regs[i] = *reinterpret_cast<const u32x4_t*>(src[i] + (size_t)k0 * ld_);
     }
     __device__ __forceinline__ void store(unsigned char* lds) {
 #pragma unroll
-        for (int i = 0; i < ITERS; ++i)
-            if (active(i)) {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    u32x4_t o;
-#pragma unroll
-                    for (int ee = 0; ee < 4; ++ee) {
-                        const uint32_t lo = regs[i][2 * ee][j >> 1], hi = regs[i][2 * ee + 1][j >> 1];
-                        o[ee] = (j & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
-                                        : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-                    }
-                    *reinterpret_cast<u32x4_t*>(lds + lds_off(rc_[i] * 8 + j, kb_)) = o;
-                }
-            }
+        for (int i = 0; i < ITERS; ++i) *reinterpret_cast<u32x4_t*>(lds + dst[i]) = regs[i];
     }
 };
+
+// Fragment of a 32-row MFMA operand out of a k-row tile.  ds_read_b64_tr_b16 works on
+// groups of 16 lanes: lane s of a group supplies the address of an 8-byte block (4 values of
+// one k row), and lane i receives element i%4 of the blocks supplied by lanes i/4, i/4+4,
+// i/4+8, i/4+12 (layout checked on the device with an index pattern).  With lane s pointing at
+// k row (s>>2) and r block 4*(s&3), lane i ends up with r = 4*(i>>2) + (i&3) = i and four
+// consecutive k: two reads give the eight k of a lane's operand, in the same order as the
+// 16-byte read of a k-contiguous tile, so both operand forms can be mixed.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+
+__device__ __forceinline__ bf16x8_t tr_frag(const unsigned char* p, int stride) {
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * stride));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    const s16x8_t both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8_t, both);
+}
 
 template <int ROWS, int NT, int FORM>
 struct LoaderSel { typedef LoaderK<ROWS, NT> type; };
@@ -205,7 +212,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_kernel(GemmDev p) {
     constexpr int WNC = WAVES / 2;               // wave grid: 2 (m) x WNC (n)
     constexpr int WN = BN / WNC;                 // tile rows of W per wave column
     constexpr int TM = BM / 64, TN = WN / 32;    // 32x32 tiles per wave
-    constexpr int A_BYTES = BM * ROW_BYTES, W_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + W_BYTES;
+    constexpr int A_BYTES = AFORM == OP_KMAJOR ? BM * ROW_BYTES : TLayout<BM>::BYTES;
+    constexpr int W_BYTES = WFORM == OP_KMAJOR ? BN * ROW_BYTES : TLayout<BN>::BYTES;
+    constexpr int STAGE = A_BYTES + W_BYTES;
     constexpr bool SWIGLU = (EPI == EPI_SWIGLU_BF16);
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;  // output columns per block
     static_assert(!SWIGLU || (TN % 2 == 0), "gate and up tiles pair up inside a wave");
@@ -261,8 +270,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_kernel(GemmDev p) {
     int foff[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) foff[ks] = l32 * ROW_BYTES + (((2 * ks + half) ^ sw) << 4);
-    const int a_base = wm * (BM / 2) * ROW_BYTES;
-    const int w_base = A_BYTES + wn * WN * ROW_BYTES;
+    // k-row tiles: lane -> k row 8*half + (s>>2), r block 16*((lane>>4)&1) + 4*(s&3), s = lane&15
+    const int s16 = lane & 15;
+    const int tro_a = (8 * half + (s16 >> 2)) * TLayout<BM>::STRIDE + (16 * ((lane >> 4) & 1) + 4 * (s16 & 3)) * 2;
+    const int tro_w = (8 * half + (s16 >> 2)) * TLayout<BN>::STRIDE + (16 * ((lane >> 4) & 1) + 4 * (s16 & 3)) * 2;
+    const int a_base = AFORM == OP_KMAJOR ? wm * (BM / 2) * ROW_BYTES : wm * (BM / 2) * 2 + tro_a;
+    const int w_base = A_BYTES + (WFORM == OP_KMAJOR ? wn * WN * ROW_BYTES : wn * WN * 2 + tro_w);
 
     const int KT = p.K / BK;
     la.fetch(0);
@@ -289,10 +302,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_kernel(GemmDev p) {
         auto load_frags = [&](int ks, int buf) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                af[buf][i] = *reinterpret_cast<const bf16x8_t*>(cur + a_base + i * 32 * ROW_BYTES + foff[ks]);
+                af[buf][i] = AFORM == OP_KMAJOR
+                                 ? *reinterpret_cast<const bf16x8_t*>(cur + a_base + i * 32 * ROW_BYTES + foff[ks])
+                                 : tr_frag(cur + a_base + i * 64 + ks * 16 * TLayout<BM>::STRIDE, TLayout<BM>::STRIDE);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                wf[buf][j] = *reinterpret_cast<const bf16x8_t*>(cur + w_base + j * 32 * ROW_BYTES + foff[ks]);
+                wf[buf][j] = WFORM == OP_KMAJOR
+                                 ? *reinterpret_cast<const bf16x8_t*>(cur + w_base + j * 32 * ROW_BYTES + foff[ks])
+                                 : tr_frag(cur + w_base + j * 64 + ks * 16 * TLayout<BN>::STRIDE, TLayout<BN>::STRIDE);
         };
         load_frags(0, 0);
         la.fetch(knext);
@@ -315,13 +332,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_kernel(GemmDev p) {
         // fragments; then per step 2 MFMAs per fragment read of the next step (the
         // tile's global loads ride along in step 0); in the last step one LDS store
         // of the next tile per MFMA.
-        __builtin_amdgcn_sched_group_barrier(M_DS_RD, NFRAG, 0);
+        constexpr int AR = AFORM == OP_KMAJOR ? 1 : 2, WR = WFORM == OP_KMAJOR ? 1 : 2;   // LDS reads per fragment
+        __builtin_amdgcn_sched_group_barrier(M_DS_RD, TM * AR + TN * WR, 0);
 #pragma unroll
         for (int ks = 0; ks < 3; ++ks) {
 #pragma unroll
             for (int i = 0; i < NFRAG; ++i) {
                 __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA / NFRAG, 0);
-                __builtin_amdgcn_sched_group_barrier(M_DS_RD, 1, 0);
+                if (i < TM) __builtin_amdgcn_sched_group_barrier(M_DS_RD, AR, 0);
+                else __builtin_amdgcn_sched_group_barrier(M_DS_RD, WR, 0);
                 if (ks == 0) __builtin_amdgcn_sched_group_barrier(M_VMEM_RD, (LA_LOADS + LW_LOADS + NFRAG - 1) / NFRAG, 0);
             }
             if (NMFMA % NFRAG) __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA % NFRAG, 0);
@@ -502,7 +521,8 @@ hipError_t launch_dma(hipStream_t st, const GemmArgs& g) {
 
 template <int BM, int BN, int EPI, int AFORM, int WFORM, int WAVES>
 hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
-    constexpr int LDS = 2 * (BM + BN) * ROW_BYTES;
+    constexpr int LDS = 2 * ((AFORM == OP_KMAJOR ? BM * ROW_BYTES : TLayout<BM>::BYTES) +
+                             (WFORM == OP_KMAJOR ? BN * ROW_BYTES : TLayout<BN>::BYTES));
     constexpr int BN_OUT = (EPI == EPI_SWIGLU_BF16) ? BN / 2 : BN;
     static bool attr_set = false;  // per instantiation; a benign race sets it twice at worst
     auto kern = gemm_kernel<BM, BN, EPI, AFORM, WFORM, WAVES>;
@@ -523,21 +543,20 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
     return hipGetLastError();
 }
 
-// Tile shapes: 1 = 128x128, 2 = 128x256 (BM x BN), 3 = 256x256, 4 = 256x256 with 8 waves.
-// Measured on MI355X over the workloads' shapes: the 256x256 tile wins once it yields
-// about 150 work-groups (256 CUs), else 128x128 (two groups per CU).  With both
-// operands' contraction index contiguous the 8-wave form is used (two waves per SIMD hide
-// each other's stalls); the transposing loaders need more registers and stay at 4 waves.
-int pick_tile(int M, int N, int epi, bool kmajor_operands) {
+// Tile shapes: 1 = 128x128, 2 = 128x256 (BM x BN), 3 = 256x256, 4 = 256x256 with 8 waves,
+// 5/6 = the LDS-DMA kernel with 8/4 waves (contraction-contiguous operands only).
+// Measured on MI355X over the workloads' shapes: the 8-wave 256x256 tile (two waves per SIMD
+// hide each other's stalls) wins once it yields about 150 work-groups (256 CUs), else
+// 128x128 (two groups per CU).
+int pick_tile(int M, int N, int epi) {
     const int n_out_256 = (epi == EPI_SWIGLU_BF16) ? 128 : 256;
     const long t256 = (long)((M + 255) / 256) * ((N + n_out_256 - 1) / n_out_256);
-    if (t256 >= 150) return kmajor_operands ? 4 : 3;
-    return 1;
+    return t256 >= 150 ? 4 : 1;
 }
 
 template <int EPI, int AFORM, int WFORM>
 hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
-    int tile = g.tile ? g.tile : pick_tile(g.M, g.N, EPI, AFORM == OP_KMAJOR && WFORM == OP_KMAJOR);
+    int tile = g.tile ? g.tile : pick_tile(g.M, g.N, EPI);
     switch (tile) {
         case 1: return launch_one<128, 128, EPI, AFORM, WFORM, 4>(st, g);
         case 2: return launch_one<128, 256, EPI, AFORM, WFORM, 4>(st, g);

@@ -77,7 +77,7 @@ def test_gemm_kmajor(epi, M, N, K, tile):
     assert np.all(np.abs(got - ref) <= tol + 1e-6), float(np.max(np.abs(got - ref)))
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
 @pytest.mark.parametrize("M,N,K", [(200, 328, 128), (264, 520, 192)])
 def test_gemm_transposed_operands(M, N, K, tile):
     """The backward forms: dX = dY W (weight read with its row index contiguous) and
