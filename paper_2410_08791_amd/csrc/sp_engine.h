@@ -30,8 +30,8 @@ struct sp_engine {
     int ci = 0, mi = 0;                                  // ops issued by the current call
     std::vector<int> tr_copy_layer, tr_copy_dep, tr_comp_layer, tr_comp_dep;
     hipEvent_t ev_sync_c = nullptr, ev_sync_h = nullptr;
-    hipEvent_t grad_ready[2] = {nullptr, nullptr}, gslot_free[2] = {nullptr, nullptr};
-    char gslot_used[2] = {0, 0};
+    hipEvent_t grad_ready[sp::kGradSlots] = {}, gslot_free[sp::kGradSlots] = {};
+    char gslot_used[sp::kGradSlots] = {};
     int gslot_next = 0;
     hipEvent_t t0 = nullptr;
     std::vector<hipEvent_t> kt_begin, kt_end;   // ring of event pairs around the largest GEMM

@@ -258,7 +258,7 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     for (size_t i = 0; i < e->comp_ev.size() && he == hipSuccess; ++i) he = mk(&e->comp_ev[i], evflags);
     if (he == hipSuccess) he = mk(&e->ev_sync_c, hipEventDisableTiming);
     if (he == hipSuccess) he = mk(&e->ev_sync_h, hipEventDisableTiming);
-    for (int i = 0; i < 2 && he == hipSuccess; ++i) {
+    for (int i = 0; i < kGradSlots && he == hipSuccess; ++i) {
         he = mk(&e->grad_ready[i], hipEventDisableTiming);
         if (he == hipSuccess) he = mk(&e->gslot_free[i], hipEventDisableTiming);
     }
@@ -462,7 +462,7 @@ static int destroy_engine(sp_engine* e) {
     kill(e->ev_sync_c);
     kill(e->ev_sync_h);
     kill(e->t0);
-    for (int i = 0; i < 2; ++i) { kill(e->grad_ready[i]); kill(e->gslot_free[i]); }
+    for (int i = 0; i < kGradSlots; ++i) { kill(e->grad_ready[i]); kill(e->gslot_free[i]); }
     (void)hipGetLastError();
     delete e;
     return SP_OK;

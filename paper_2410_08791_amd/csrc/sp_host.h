@@ -14,6 +14,7 @@ namespace sp {
 constexpr size_t kTensorAlign = 256;
 constexpr size_t kSlotAlign = 4096;
 constexpr int kMaxTensors = 12;
+constexpr int kGradSlots = 4;   // fp32 gradient slots cycled by the backward pass
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -47,7 +48,7 @@ struct Workspace {
     size_t dqkv, dob, dz;                  // bf16 gradients of qkv, attention output, SwiGLU output
     size_t kt, qt, dot;                    // K, Q, dO transposed per head: bf16 [B][H][hd_pad][S_pad]
     size_t part;                           // fp32 [kNormBwdBlocks, d] gain-gradient partials (+ loss partials)
-    size_t gslot[2];                       // fp32 gradient slots
+    size_t gslot[kGradSlots];              // fp32 gradient slots
     size_t total;
     int t_pad;                             // token rows padded to 64 (training)
 };

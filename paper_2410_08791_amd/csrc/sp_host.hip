@@ -98,8 +98,7 @@ void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Wor
         ws->dot = take((size_t)d->max_batch * d->n_q_heads * hdp * sp * 2);
         ws->part = take(((size_t)kNormBwdBlocks * dm + 1024) * 4);
         off = align_up(off, kSlotAlign);
-        ws->gslot[0] = take(align_up(lay.grad_bytes, kSlotAlign));
-        ws->gslot[1] = take(align_up(lay.grad_bytes, kSlotAlign));
+        for (int i = 0; i < kGradSlots; ++i) ws->gslot[i] = take(align_up(lay.grad_bytes, kSlotAlign));
     }
     ws->total = align_up(off, kSlotAlign);
 }

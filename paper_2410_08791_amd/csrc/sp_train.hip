@@ -2,9 +2,9 @@
 // pass).  Forward keeps every layer's fp32 input; the backward walks the layers
 // in reverse, and when layer l's weights are back in a slot it recomputes the
 // layer's internals from the saved input and runs the backward of every op.
-// fp32 weight gradients are written into one of two device gradient slots (same
+// fp32 weight gradients are written into one of a few device gradient slots (same
 // tensor order as the weight blob, offsets doubled) and streamed to the caller's
-// pinned host blob on the device-to-host stream, fenced by two event pairs:
+// pinned host blob on the device-to-host stream, fenced by one event pair per slot:
 //   grad_ready[g]  compute -> d2h   (gradients of a layer complete)
 //   gslot_free[g]  d2h -> compute   (slot g has been copied out, may be rewritten)
 #include "sp_engine.h"
@@ -115,7 +115,7 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, nqkv = nq + 2 * nkv;
     auto W = [&](int t) { return reinterpret_cast<const bf16_t*>(w + L.t[t].offset); };
     const int gs = e->gslot_next;
-    e->gslot_next ^= 1;
+    e->gslot_next = (gs + 1) % sp::kGradSlots;
     unsigned char* gslot = e->arena + e->ws.gslot[gs];
     auto G = [&](int t) { return reinterpret_cast<float*>(gslot + 2 * L.t[t].offset); };
     if (e->gslot_used[gs]) SP_HIP(e, hipStreamWaitEvent(st, e->gslot_free[gs], 0));

@@ -193,3 +193,14 @@ def test_vith_layer_shape():
     err = max_rel(y, c.ref(np.float32).astype(np.float64))
     print(f"vith x2 layers, batch 8: max rel err vs fp32 oracle {err:.3e}")
     assert err <= TOL
+
+
+def test_llama70b_layer_shape():
+    """Grouped-query 64/8 heads, d 8192, ffn 28672: one layer of the 70B-shaped workload on
+    512 tokens (the oracle's fp32 pass over 856 M parameters takes ~10 s)."""
+    w = synth.WORKLOADS["llama70b"].with_(n_layers=1, batch=1, seq=512)
+    c = Case(w)
+    (y,), st = c.run(1, 1)
+    err = max_rel(y, c.ref(np.float32).astype(np.float64))
+    print(f"llama70b x1 layer, 512 tokens: max rel err vs fp32 oracle {err:.3e}")
+    assert err <= TOL
