@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--distinct-blobs", type=int, default=None,
                     help="generate only this many distinct layer blobs and cycle them (host RAM limit)")
     ap.add_argument("--no-wrap", action="store_true", help="do not prefetch the next call's first layers")
+    ap.add_argument("--keep-activations", action="store_true",
+                    help="training: keep every layer's activations instead of recomputing them")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true", help="experiment: no event brackets in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -128,7 +130,7 @@ def main():
 
     def run(kk, pp, flags, steps, warmup):
         if training:
-            flags |= sp.SP_FLAG_TRAINING
+            flags |= sp.SP_FLAG_TRAINING | (sp.SP_FLAG_KEEP_ACTIVATIONS if args.keep_activations else 0)
         eng = sp.Engine(desc, blobs, kk, pp, budget_layers=budget_layers, budget_bytes=budget_bytes, flags=flags)
 
         def step():
@@ -282,7 +284,8 @@ def main():
                                f"x{w.head_dim} ffn={w.d_ffn} causal={w.causal} batch {B} x seq {S}, "
                                + ("forward+backward (MSE)" if training else "forward"),
                    "k": k, "p": p, "n_slots": int(st.plan.n_slots), "budget_layers": budget_layers,
-                   "wrap_prefetch": wrap, "layer_blob_bytes": int(blob_bytes),
+                   "wrap_prefetch": wrap, "keep_activations": bool(training and args.keep_activations),
+                   "layer_blob_bytes": int(blob_bytes),
                    "distinct_blobs": nb, "seed": w.seed},
         "roofline": roofline, "cpu_baseline": cpu, **extra,
     }

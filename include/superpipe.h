@@ -86,6 +86,10 @@ enum {
     SP_FLAG_WRAP_PREFETCH = 1u << 4, /* forward-only: when the tail of a pass frees slots,
                                       start loading layers 0.. for the next call (the
                                       consecutive-forward stall of Sec. 5)                 */
+    SP_FLAG_KEEP_ACTIVATIONS = 1u << 6, /* training: keep every layer's activations in the
+                                      workspace instead of recomputing them in the backward
+                                      (the paper's "without gradient checkpointing" column,
+                                      Table 2): more HBM, about a quarter less compute      */
     SP_FLAG_KERNEL_TIMING = 1u << 5 /* bracket the layer's largest GEMM with timed events on
                                       the compute stream only (big_gemm_* in sp_stats)     */
 };
@@ -153,8 +157,9 @@ size_t sp_tensor_elems(const sp_stack_desc* desc, int tensor_id);
 size_t sp_layer_blob_bytes(const sp_stack_desc* desc);
 /* Bytes of one layer's fp32 gradient blob: same tensor order, offsets doubled. */
 size_t sp_layer_grad_bytes(const sp_stack_desc* desc);
-/* Device workspace for max_batch*max_seq tokens (activations, saved layer inputs
- * and gradient slots when training != 0). */
+/* Device workspace for max_batch*max_seq tokens.  training: 0 = forward only; 1 = training
+ * (saved layer inputs, backward scratch, gradient slots); 2 = training with
+ * SP_FLAG_KEEP_ACTIVATIONS (one activation set per layer). */
 size_t sp_workspace_bytes(const sp_stack_desc* desc, int training);
 /* The slot-count policy above as a pure function. */
 int sp_make_plan(const sp_stack_desc* desc, int k, int p, uint64_t budget_bytes, int training,

@@ -28,6 +28,7 @@ SP_OK, SP_ERR_INVALID_ARG, SP_ERR_BUDGET, SP_ERR_NOT_PINNED, SP_ERR_HIP, SP_ERR_
 SP_DECODER_SWIGLU_RMS, SP_ENCODER_GELU_LN = 0, 1
 SP_FLAG_TRAINING, SP_FLAG_TIMING, SP_FLAG_POISON, SP_FLAG_NO_OVERLAP, SP_FLAG_WRAP_PREFETCH = 1, 2, 4, 8, 16
 SP_FLAG_KERNEL_TIMING = 32
+SP_FLAG_KEEP_ACTIVATIONS = 64
 SP_MAX_TRACE_LAYERS = 256
 EPI_BF16, EPI_RESID_F32, EPI_GELU_BF16, EPI_SWIGLU_BF16, EPI_F32 = 0, 1, 2, 3, 4
 
@@ -188,7 +189,7 @@ class Engine:
         self.desc = desc
         self.blobs = blobs                      # keep the pinned tensors alive
         training = bool(flags & SP_FLAG_TRAINING)
-        ws = sp_workspace_bytes(C.byref(desc), int(training))
+        ws = sp_workspace_bytes(C.byref(desc), (2 if flags & SP_FLAG_KEEP_ACTIVATIONS else 1) if training else 0)
         slot = (sp_layer_blob_bytes(C.byref(desc)) + 4095) // 4096 * 4096
         if budget_bytes is None:
             nl = budget_layers if budget_layers else min(k + p, desc.n_layers)

@@ -202,6 +202,9 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     if (!cfg->device_arena || ((uintptr_t)cfg->device_arena & (kSlotAlign - 1)))
         return fail(nullptr, SP_ERR_INVALID_ARG, "device_arena must be non-NULL and 4 KiB aligned");
     const bool training = cfg->flags & SP_FLAG_TRAINING;
+    const int mode = training ? ((cfg->flags & SP_FLAG_KEEP_ACTIVATIONS) ? 2 : 1) : 0;
+    if (!training && (cfg->flags & SP_FLAG_KEEP_ACTIVATIONS))
+        return fail(nullptr, SP_ERR_INVALID_ARG, "SP_FLAG_KEEP_ACTIVATIONS needs SP_FLAG_TRAINING");
     if (cfg->h2d_stream == cfg->compute_stream) return fail(nullptr, SP_ERR_INVALID_ARG, "h2d_stream must differ from compute_stream");
     if (training && (!cfg->d2h_stream || cfg->d2h_stream == cfg->compute_stream || cfg->d2h_stream == cfg->h2d_stream))
         return fail(nullptr, SP_ERR_INVALID_ARG, "training needs a d2h_stream distinct from the other two");
@@ -209,7 +212,7 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
         return fail(nullptr, SP_ERR_INVALID_ARG, "training is implemented for decoder stacks only");
     if (desc->n_layers > 4096) return fail(nullptr, SP_ERR_INVALID_ARG, "n_layers > 4096");
     sp_plan plan;
-    int rc = make_plan(desc, cfg->resident_window_k, cfg->prefetch_depth_p, cfg->gpu_budget_bytes, training, &plan);
+    int rc = make_plan(desc, cfg->resident_window_k, cfg->prefetch_depth_p, cfg->gpu_budget_bytes, mode, &plan);
     if (rc == SP_ERR_BUDGET) {
         return fail(nullptr, rc, "gpu_budget_bytes=%llu cannot hold the workspace (%llu) plus one layer slot (%llu)",
                     (unsigned long long)cfg->gpu_budget_bytes, (unsigned long long)plan.workspace_bytes,
@@ -231,7 +234,7 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     e->flags = cfg->flags;
     e->plan = plan;
     make_layout(desc, &e->lay);
-    make_workspace(desc, e->lay, training, &e->ws);
+    make_workspace(desc, e->lay, mode, &e->ws);
     e->arena = static_cast<unsigned char*>(cfg->device_arena);
     e->slots = e->arena + e->ws.total;
     e->compute = static_cast<hipStream_t>(cfg->compute_stream);

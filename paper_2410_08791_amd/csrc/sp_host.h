@@ -38,6 +38,7 @@ int make_layout(const sp_stack_desc* d, Layout* out);
 // Device workspace, as byte offsets from its base (all 256-byte aligned).
 struct Workspace {
     size_t a, qkv, vt, o, gu, z;           // forward activations (bf16)
+    size_t set_stride;                     // > 0: layer l's copy of {a,qkv,o,gu,z,m,h1,lse} lies l*set_stride further
     // training only
     size_t xs;                             // layer inputs fp32 [L][T, d], kept for the backward
     size_t m;                              // second normed activation bf16 [Tp, d]
@@ -52,6 +53,8 @@ struct Workspace {
     size_t total;
     int t_pad;                             // token rows padded to 64 (training)
 };
+// training: 0 = forward only, 1 = training with per-layer recompute, 2 = training keeping every
+// layer's activations (no recompute)
 void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Workspace* ws);
 
 int make_plan(const sp_stack_desc* d, int k, int p, uint64_t budget, int training, sp_plan* out);

@@ -75,17 +75,25 @@ void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Wor
     const size_t hdp = (d->head_dim + 31) / 32 * 32, sp = align_up(d->max_seq, 64);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, kTensorAlign); return o; };
+    // per-layer activation set (one shared set, or one per layer when activations are kept)
     ws->a = take(Tp * dm * 2);
     ws->qkv = take(Tp * nqkv * 2);
-    ws->vt = take((size_t)d->max_batch * d->n_kv_heads * hdp * sp * 2);
     ws->o = take(Tp * nq * 2);
     ws->gu = take(Tp * (d->arch == SP_DECODER_SWIGLU_RMS ? 2 * f : f) * 2);
     ws->z = take(Tp * f * 2);
     if (training) {
-        ws->xs = take((size_t)d->n_layers * T * dm * 4);
         ws->m = take(Tp * dm * 2);
         ws->h1 = take(T * dm * 4);
         ws->lse = take((size_t)d->max_batch * d->n_q_heads * d->max_seq * 4);
+    }
+    ws->set_stride = 0;
+    if (training == 2) {
+        ws->set_stride = off;                       // sets of layers 1..L-1 follow set 0
+        off += ws->set_stride * (size_t)(d->n_layers - 1);
+    }
+    ws->vt = take((size_t)d->max_batch * d->n_kv_heads * hdp * sp * 2);
+    if (training) {
+        ws->xs = take((size_t)d->n_layers * T * dm * 4);
         ws->delta = take((size_t)d->max_batch * d->n_q_heads * d->max_seq * 4);
         ws->dh = take(T * dm * 4);
         ws->da = take(T * dm * 4);

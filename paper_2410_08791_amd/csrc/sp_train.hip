@@ -20,21 +20,28 @@ struct LayerBufs {
     float* lse;          // nullptr: not needed
 };
 
-// Decoder layer with every intermediate kept in the workspace (a, qkv, o, m, gu, z).
-int decoder_layer_keep(sp_engine* e, const unsigned char* w, const LayerBufs& b, int B, int S) {
+// The activation set of a layer: the shared one, or the layer's own when activations are kept.
+struct ActSet {
+    bf16_t *a, *m, *qkv, *o, *gu, *z;
+    float *h1, *lse;
+};
+ActSet act_set(sp_engine* e, int layer) {
+    unsigned char* base = e->arena + (size_t)layer * e->ws.set_stride;
+    auto P = [&](size_t off) { return base + off; };
+    return ActSet{(bf16_t*)P(e->ws.a), (bf16_t*)P(e->ws.m), (bf16_t*)P(e->ws.qkv), (bf16_t*)P(e->ws.o),
+                  (bf16_t*)P(e->ws.gu), (bf16_t*)P(e->ws.z), (float*)P(e->ws.h1), (float*)P(e->ws.lse)};
+}
+
+// Decoder layer with every intermediate kept in the activation set (a, qkv, o, m, gu, z).
+int decoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, const LayerBufs& b, int B, int S) {
     const sp_stack_desc& d = e->desc;
     const Layout& L = e->lay;
     hipStream_t st = e->compute;
     const int T = B * S, dm = d.d_model, f = d.d_ffn;
     const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, nqkv = nq + 2 * nkv;
     auto W = [&](int t) { return reinterpret_cast<const bf16_t*>(w + L.t[t].offset); };
-    bf16_t* a = e->wsp<bf16_t>(e->ws.a);
-    bf16_t* m = e->wsp<bf16_t>(e->ws.m);
-    bf16_t* qkv = e->wsp<bf16_t>(e->ws.qkv);
+    bf16_t *a = as_.a, *m = as_.m, *qkv = as_.qkv, *o = as_.o, *gu = as_.gu, *z = as_.z;
     bf16_t* vt = e->wsp<bf16_t>(e->ws.vt);
-    bf16_t* o = e->wsp<bf16_t>(e->ws.o);
-    bf16_t* gu = e->wsp<bf16_t>(e->ws.gu);
-    bf16_t* z = e->wsp<bf16_t>(e->ws.z);
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
     GemmArgs g;
     SP_HIP(e, spk_launch_norm(st, b.h_in, W(SP_T_G1), nullptr, a, T, dm, d.norm_eps));
@@ -77,13 +84,17 @@ int sp_train_begin(sp_engine* e, const float* x_dev, int B, int S) {
         // token rows [T, Tp) of the buffers that feed the weight-gradient GEMMs (contraction
         // over tokens, padded to a multiple of 64) must read as zero
         const int nq = d.n_q_heads * d.head_dim, nqkv = nq + 2 * d.n_kv_heads * d.head_dim;
-        struct { size_t off; int cols; } bufs[] = {{e->ws.a, d.d_model}, {e->ws.m, d.d_model}, {e->ws.o, nq},
-                                                   {e->ws.gu, 2 * d.d_ffn}, {e->ws.z, d.d_ffn},
-                                                   {e->ws.dhb, d.d_model}, {e->ws.dqkv, nqkv}};
-        for (auto& bf : bufs) {
-            uint32_t* p = reinterpret_cast<uint32_t*>(e->arena + bf.off + (size_t)T * bf.cols * 2);
-            SP_HIP(e, spk_launch_fill_u32(st, p, 0u, (size_t)(Tp - T) * bf.cols / 2));
-        }
+        struct { size_t off; int cols; bool per_set; } bufs[] = {
+            {e->ws.a, d.d_model, true}, {e->ws.m, d.d_model, true}, {e->ws.o, nq, true},
+            {e->ws.gu, 2 * d.d_ffn, true}, {e->ws.z, d.d_ffn, true},
+            {e->ws.dhb, d.d_model, false}, {e->ws.dqkv, nqkv, false}};
+        const int n_sets = e->ws.set_stride ? d.n_layers : 1;
+        for (auto& bf : bufs)
+            for (int set = 0; set < (bf.per_set ? n_sets : 1); ++set) {
+                uint32_t* p = reinterpret_cast<uint32_t*>(e->arena + (size_t)set * e->ws.set_stride + bf.off +
+                                                          (size_t)T * bf.cols * 2);
+                SP_HIP(e, spk_launch_fill_u32(st, p, 0u, (size_t)(Tp - T) * bf.cols / 2));
+            }
     }
     SP_HIP(e, spk_launch_copy_f32(st, x_dev, saved_input(e, 0, T), (size_t)T * d.d_model));
     return SP_OK;
@@ -94,8 +105,10 @@ int sp_layer_forward_train(sp_engine* e, int layer, const unsigned char* w, int 
     // the last layer writes y (the caller's buffer, or the stream-gradient buffer that the
     // loss kernel then turns into dy in place)
     float* out = layer + 1 < L ? saved_input(e, layer + 1, T) : (e->y_out ? e->y_out : e->wsp<float>(e->ws.dh));
-    LayerBufs b{saved_input(e, layer, T), e->wsp<float>(e->ws.h1), out, nullptr};
-    return decoder_layer_keep(e, w, b, B, S);
+    const ActSet as_ = act_set(e, layer);
+    // with kept activations the forward also produces what the backward needs (log-sum-exp)
+    LayerBufs b{saved_input(e, layer, T), as_.h1, out, e->ws.set_stride ? as_.lse : nullptr};
+    return decoder_layer_keep(e, w, as_, b, B, S);
 }
 
 int sp_train_loss(sp_engine* e, const float* target_dev, float* loss_dev, int B, int S) {
@@ -120,19 +133,15 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     auto G = [&](int t) { return reinterpret_cast<float*>(gslot + 2 * L.t[t].offset); };
     if (e->gslot_used[gs]) SP_HIP(e, hipStreamWaitEvent(st, e->gslot_free[gs], 0));
 
+    const ActSet as_ = act_set(e, layer);
     float* x_l = saved_input(e, layer, T);
-    float* h1 = e->wsp<float>(e->ws.h1);
-    float* lse = e->wsp<float>(e->ws.lse);
+    float* h1 = as_.h1;
+    float* lse = as_.lse;
     float* delta = e->wsp<float>(e->ws.delta);
     float* dh = e->wsp<float>(e->ws.dh);
     float* da = e->wsp<float>(e->ws.da);
     float* part = e->wsp<float>(e->ws.part);
-    bf16_t* a = e->wsp<bf16_t>(e->ws.a);
-    bf16_t* m = e->wsp<bf16_t>(e->ws.m);
-    bf16_t* qkv = e->wsp<bf16_t>(e->ws.qkv);
-    bf16_t* o = e->wsp<bf16_t>(e->ws.o);
-    bf16_t* gu = e->wsp<bf16_t>(e->ws.gu);
-    bf16_t* z = e->wsp<bf16_t>(e->ws.z);
+    bf16_t *a = as_.a, *m = as_.m, *qkv = as_.qkv, *o = as_.o, *gu = as_.gu, *z = as_.z;
     bf16_t* dhb = e->wsp<bf16_t>(e->ws.dhb);
     bf16_t* dz = e->wsp<bf16_t>(e->ws.dz);
     bf16_t* dob = e->wsp<bf16_t>(e->ws.dob);
@@ -143,10 +152,12 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
     GemmArgs g;
 
-    // recompute a, qkv, o, lse, h1, m, gu, z from the saved input
-    LayerBufs lb{x_l, h1, nullptr, lse};
-    int rc = decoder_layer_keep(e, w, lb, B, S);
-    if (rc != SP_OK) return rc;
+    // recompute a, qkv, o, lse, h1, m, gu, z from the saved input -- unless the forward kept them
+    if (!e->ws.set_stride) {
+        LayerBufs lb{x_l, h1, nullptr, lse};
+        int rc = decoder_layer_keep(e, w, as_, lb, B, S);
+        if (rc != SP_OK) return rc;
+    }
 
     // ---- FFN.  dh is dL/d(layer output); dhb its bf16 copy.
     // dWd[d,f] = dh^T z       (contraction over tokens: both operands transposed on the way in)

@@ -28,9 +28,9 @@ class TrainCase:
         self.xd, self.td = dev_f32(self.x), dev_f32(self.t)
         self.gbytes = sp.sp_layer_grad_bytes(C.byref(self.desc))
 
-    def run(self, k, p, calls=1, want_y=True, target=None, budget_layers=None):
+    def run(self, k, p, calls=1, want_y=True, target=None, budget_layers=None, flags=0):
         w = self.w
-        eng = sp.Engine(self.desc, self.blobs, k, p, flags=sp.SP_FLAG_TRAINING, budget_layers=budget_layers)
+        eng = sp.Engine(self.desc, self.blobs, k, p, flags=sp.SP_FLAG_TRAINING | flags, budget_layers=budget_layers)
         gblobs = [torch.zeros(self.gbytes, dtype=torch.uint8, pin_memory=True) for _ in range(w.n_layers)]
         y = torch.zeros_like(self.xd) if want_y else None
         dx = torch.zeros_like(self.xd)
@@ -119,6 +119,23 @@ def test_training_ragged_token_count_and_no_y():
     c = TrainCase(w)
     got = c.run(1, 1, want_y=False, calls=2)
     check_against_oracle(got, c.oracle(), "train_ragged")
+
+
+def test_kept_activations_give_the_same_bits_as_recompute(small):
+    """Without recompute (every layer's activations kept in HBM, the paper's 'without gradient
+    checkpointing' column) the backward sees exactly the tensors the recompute would rebuild."""
+    base = small.run(2, 1, calls=2)
+    kept = small.run(2, 1, calls=2, flags=sp.SP_FLAG_KEEP_ACTIVATIONS)
+    assert kept["loss"] == base["loss"] and np.array_equal(kept["dx"], base["dx"])
+    for gl, bl in zip(kept["grads"], base["grads"]):
+        for n in gl:
+            assert np.array_equal(gl[n], bl[n]), n
+    assert kept["stats"].plan.workspace_bytes > base["stats"].plan.workspace_bytes
+    # ragged token count: the padded rows of every layer's set must read as zero
+    w = synth.Workload("train_ragged_keep", "decoder", 3, 256, 2, 2, 128, 576, True, 3, 77, training=True)
+    c = TrainCase(w)
+    got = c.run(1, 1, flags=sp.SP_FLAG_KEEP_ACTIVATIONS, calls=2)
+    check_against_oracle(got, c.oracle(), "train_ragged_keep")
 
 
 def test_zero_loss_gives_zero_gradients(small):
