@@ -198,7 +198,11 @@ int sp_forward(sp_handle h, const float* x_dev, float* y_dev, int B, int S);
  * mean((y - target)^2), backward with each layer's weights re-streamed in
  * reverse order, fp32 weight gradients written (overwrite, not accumulate) to
  * grad_host_blobs[l] (host, pinned, sp_layer_grad_bytes each) over d2h_stream.
- * loss_dev: dev, 1 fp32.  dx_dev: dev fp32 [B,S,d] or NULL.  y_dev may be NULL. */
+ * loss_dev: dev, 1 fp32.  dx_dev: dev fp32 [B,S,d] or NULL.  y_dev may be NULL.
+ * The call returns once the step is enqueued.  At most one training step is in
+ * flight per handle: a call first blocks the host until the previous step's
+ * last gradient has landed (the point its consumer, the host-side optimizer,
+ * has to wait for anyway before the weights of the next step exist). */
 int sp_forward_backward(sp_handle h, const float* x_dev, const float* target_dev, float* y_dev,
                         float* loss_dev, float* dx_dev, void* const* grad_host_blobs, int B, int S);
 

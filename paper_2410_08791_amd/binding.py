@@ -180,6 +180,21 @@ def pinned_blobs(w, desc, n_layers=None, pool=None):
     return blobs, views
 
 
+_STREAMS = {}
+
+
+def _device_streams(torch, device):
+    """One (compute, h2d, d2h) stream trio per device, shared by every Engine of the
+    process.  HIP multiplexes a process's streams onto a few hardware queues (4 by
+    default); once there are more streams than queues a copy stream lands on the queue
+    of another stream and its copies serialise behind that stream's kernels (measured:
+    +23 % on the training step).  Three streams plus the default one stay within that."""
+    key = (device.type, device.index if device.index is not None else torch.cuda.current_device())
+    if key not in _STREAMS:
+        _STREAMS[key] = tuple(torch.cuda.Stream(device=device) for _ in range(3))
+    return _STREAMS[key]
+
+
 class Engine:
     """Owns an sp_handle plus the torch-allocated arena and streams it runs on."""
 
@@ -201,9 +216,8 @@ class Engine:
             self._arena_raw = torch.empty(self.budget_bytes + 4096, dtype=torch.uint8, device=self.device)
             skew = (-self._arena_raw.data_ptr()) % 4096
             self.arena = self._arena_raw[skew:skew + self.budget_bytes]
-            self.compute = torch.cuda.Stream(device=self.device)
-            self.h2d = torch.cuda.Stream(device=self.device)
-            self.d2h = torch.cuda.Stream(device=self.device) if training else None
+            self.compute, self.h2d, d2h = _device_streams(torch, self.device)
+            self.d2h = d2h if training else None
         assert self.arena.data_ptr() % 4096 == 0
         ptrs = (C.c_void_p * len(blobs))(*[b.data_ptr() for b in blobs])
         cfg = sp_config(C.sizeof(sp_config), k, p, self.budget_bytes, self.arena.data_ptr(),

@@ -30,6 +30,8 @@ struct sp_engine {
     int ci = 0, mi = 0;                                  // ops issued by the current call
     std::vector<int> tr_copy_layer, tr_copy_dep, tr_comp_layer, tr_comp_dep;
     hipEvent_t ev_sync_c = nullptr, ev_sync_h = nullptr;
+    hipEvent_t pass_end_c = nullptr, pass_end_d = nullptr;   // end of the latest training pass on compute / d2h
+    bool pass_pending = false;
     hipEvent_t grad_ready[sp::kGradSlots] = {}, gslot_free[sp::kGradSlots] = {};
     char gslot_used[sp::kGradSlots] = {};
     int gslot_next = 0;

@@ -261,6 +261,8 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     for (size_t i = 0; i < e->comp_ev.size() && he == hipSuccess; ++i) he = mk(&e->comp_ev[i], evflags);
     if (he == hipSuccess) he = mk(&e->ev_sync_c, hipEventDisableTiming);
     if (he == hipSuccess) he = mk(&e->ev_sync_h, hipEventDisableTiming);
+    if (he == hipSuccess && training) he = mk(&e->pass_end_c, hipEventDisableTiming);
+    if (he == hipSuccess && training) he = mk(&e->pass_end_d, hipEventDisableTiming);
     for (int i = 0; i < kGradSlots && he == hipSuccess; ++i) {
         he = mk(&e->grad_ready[i], hipEventDisableTiming);
         if (he == hipSuccess) he = mk(&e->gslot_free[i], hipEventDisableTiming);
@@ -347,6 +349,15 @@ extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float*
         return fail(e, SP_ERR_INVALID_ARG, "device tensors must be 16-byte aligned");
     for (int l = 0; l < e->desc.n_layers; ++l)
         if (!grad_host_blobs[l]) return fail(e, SP_ERR_INVALID_ARG, "grad_host_blobs[%d] is NULL", l);
+    // One training pass in flight: the host waits here until the previous pass has
+    // delivered its last gradient.  Its consumer (the host-side optimizer) needs that
+    // point anyway, and copies enqueued more than a pass ahead were measured to drop
+    // the device-to-host engine to a fraction of the link rate.
+    if (e->pass_pending) {
+        SP_HIP(e, hipEventSynchronize(e->pass_end_d));
+        SP_HIP(e, hipEventSynchronize(e->pass_end_c));
+        e->pass_pending = false;
+    }
     if ((rc = begin_call(e)) != SP_OK) return rc;
     e->grad_blobs = grad_host_blobs;
     e->y_out = y_dev;
@@ -360,6 +371,9 @@ extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float*
     sink.training_fwd = false;
     if ((rc = e->sched.run_pass(-1, false, sink)) != SP_OK) return rc;
     if ((rc = sp_train_end(e, dx_dev, B, S)) != SP_OK) return rc;
+    SP_HIP(e, hipEventRecord(e->pass_end_c, e->compute));
+    SP_HIP(e, hipEventRecord(e->pass_end_d, e->d2h));
+    e->pass_pending = true;
     e->calls++;
     return SP_OK;
 }
@@ -464,6 +478,8 @@ static int destroy_engine(sp_engine* e) {
     for (auto ev : e->kt_end) kill(ev);
     kill(e->ev_sync_c);
     kill(e->ev_sync_h);
+    kill(e->pass_end_c);
+    kill(e->pass_end_d);
     kill(e->t0);
     for (int i = 0; i < kGradSlots; ++i) { kill(e->grad_ready[i]); kill(e->gslot_free[i]); }
     (void)hipGetLastError();
