@@ -217,6 +217,17 @@ def main():
         "event_ms_per_step": round(main_run["ms_per_step"], 3),
         "host_wall_ms_per_step": round(main_run["wall_ms_per_step"], 3),
     }
+    # window the cost-model tuner would pick at this budget from the measured per-layer times
+    grad_ms = gbytes / (ceiling * 1e6) if training else 0.0
+    cost = sp.layer_costs(st, w.n_layers, training=training, grad_ms=grad_ms)
+    try:
+        tk, tp, tms = sp.autotune(desc, int(main_run["budget"]), cost, wrap=wrap,
+                                  training=(2 if args.keep_activations else 1) if training else 0)
+        extra["autotune"] = {"k": tk, "p": tp, "modelled_ms_per_step": round(tms, 3),
+                             "layer_cost_ms": {"copy": round(cost[0], 3), "fwd": round(cost[1], 3),
+                                               "bwd": round(cost[2], 3), "grad": round(cost[3], 3)}}
+    except sp.SuperpipeError as ex:
+        extra["autotune"] = {"error": str(ex)}
     if training:
         extra["d2h_gbps_over_wall"] = round(w.n_layers * gbytes / (ms * 1e-3) / 1e9, 2)
     if w.arch == "encoder":

@@ -181,6 +181,31 @@ typedef struct {
 int sp_trace_schedule(int n_layers, int n_slots, int p_eff, int training, int wrap_prefetch,
                       int passes, sp_sched_op* ops, int cap);
 
+/* Cost model of the schedule (host only).  Plays what sp_trace_schedule lists on
+ * three in-order streams -- layer copies, layer computes, gradient copies --
+ * with one duration per kind, and returns the duration in ms of the last of
+ * `calls` consecutive calls (forward passes, or training steps when training != 0;
+ * a training step starts when the previous one has delivered its gradients).
+ * Durations come from a measurement (sp_stats' per-layer trace) or from
+ * bytes / link rate and FLOP / rate.  Returns < 0 on invalid arguments. */
+typedef struct {
+    double copy_ms;   /* one layer blob, host to device             */
+    double fwd_ms;    /* one layer forward (training: incl. what the forward pass does) */
+    double bwd_ms;    /* one layer backward incl. recompute (training only)             */
+    double grad_ms;   /* one layer's gradient copy, device to host (training only)      */
+} sp_layer_cost;
+double sp_simulate_call_ms(int n_layers, int n_slots, int p_eff, int training, int wrap_prefetch,
+                           int calls, const sp_layer_cost* cost);
+
+/* Window choice under a byte budget (the paper finds k and k' by grid search,
+ * Sec. 4.2, and names adaptive selection as future work, Sec. 5): every (k, p)
+ * whose plan fits budget_bytes is run through the cost model; of those within
+ * (1 + tolerance) of the best modelled time the one with the fewest slots, then
+ * the smallest p, is returned (fewest bytes of HBM for the same speed).
+ * training: 0, 1 or 2 as for sp_workspace_bytes.  SP_ERR_BUDGET if nothing fits. */
+int sp_autotune(const sp_stack_desc* desc, uint64_t budget_bytes, int training, int wrap_prefetch,
+                const sp_layer_cost* cost, double tolerance, int* k_out, int* p_out, double* ms_out);
+
 /* ---- the four calls ------------------------------------------------------ */
 
 /* Create an executor.  layer_host_blobs[n_layers]: host, pinned, each

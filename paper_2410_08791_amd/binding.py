@@ -75,8 +75,15 @@ class sp_sched_op(C.Structure):
                 ("pass_", C.c_int32)]
 
 
+class sp_layer_cost(C.Structure):
+    _fields_ = [("copy_ms", C.c_double), ("fwd_ms", C.c_double), ("bwd_ms", C.c_double), ("grad_ms", C.c_double)]
+
+
 _P = C.POINTER
 _sig = {
+    "sp_simulate_call_ms": (C.c_double, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P(sp_layer_cost)]),
+    "sp_autotune": (C.c_int, [_P(sp_stack_desc), C.c_uint64, C.c_int, C.c_int, _P(sp_layer_cost), C.c_double,
+                              _P(C.c_int), _P(C.c_int), _P(C.c_double)]),
     "sp_num_tensors": (C.c_int, [_P(sp_stack_desc)]),
     "sp_tensor_offset": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
     "sp_tensor_elems": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
@@ -161,6 +168,34 @@ def trace_schedule(n_layers, n_slots, p_eff, training=False, wrap=False, passes=
     ops = (sp_sched_op * n)()
     sp_trace_schedule(n_layers, n_slots, p_eff, int(training), int(wrap), passes, ops, n)
     return [(o.kind, o.layer, o.slot, o.wait_layer, o.pass_) for o in ops]
+
+
+def simulate_call_ms(n_layers, n_slots, p_eff, cost, training=False, wrap=False, calls=3):
+    """Modelled duration of the last of `calls` calls; cost = (copy, fwd, bwd, grad) in ms."""
+    c = sp_layer_cost(*cost)
+    return sp_simulate_call_ms(n_layers, n_slots, p_eff, int(training), int(wrap), calls, C.byref(c))
+
+
+def autotune(desc, budget_bytes, cost, training=0, wrap=False, tolerance=0.02):
+    """(k, p, modelled ms) for the smallest window within `tolerance` of the best modelled time."""
+    c = sp_layer_cost(*cost)
+    k, p, ms = C.c_int(), C.c_int(), C.c_double()
+    rc = sp_autotune(C.byref(desc), budget_bytes, int(training), int(wrap), C.byref(c), tolerance,
+                     C.byref(k), C.byref(p), C.byref(ms))
+    if rc != SP_OK:
+        raise SuperpipeError(rc, "sp_autotune")
+    return k.value, p.value, ms.value
+
+
+def layer_costs(st, n_layers, training=False, grad_ms=0.0):
+    """(copy, fwd, bwd, grad) per-layer medians in ms from a SP_FLAG_TIMING sp_stats."""
+    n = st.n_timed
+    comp = [st.comp_end_ms[j] - st.comp_begin_ms[j] for j in range(n)]
+    copy = [st.copy_end_ms[j] - st.copy_begin_ms[j] for j in range(n) if st.copy_begin_ms[j] >= 0]
+    med = lambda v: float(np.median(v)) if len(v) else 0.0
+    fwd = comp[:n_layers] if training else comp
+    bwd = comp[n_layers:2 * n_layers] if training else []
+    return med(copy), med(fwd), med(bwd), float(grad_ms)
 
 
 def pinned_blobs(w, desc, n_layers=None, pool=None):

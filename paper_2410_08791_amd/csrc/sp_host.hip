@@ -283,3 +283,103 @@ extern "C" int sp_trace_schedule(int n_layers, int n_slots, int p_eff, int train
     }
     return sink.n;
 }
+
+// ---- schedule cost model and window tuner ----------------------------------
+namespace {
+// Plays the scheduler's decisions on three in-order streams (copy, compute, gradient
+// copy) with fixed per-layer durations; the same dependencies the engine expresses as
+// events become max() of end times here.
+struct SimSink : SchedSink {
+    const sp_layer_cost& c;
+    std::vector<double> loaded, done;
+    double t_copy = 0, t_comp = 0, t_grad = 0, t_floor = 0;
+    double gslot_free[kGradSlots] = {};
+    int gs = 0;
+    bool training = false;
+    SimSink(const sp_layer_cost& cost, int L) : c(cost), loaded(L, 0.0), done(L, 0.0) {}
+    int copy(int layer, int, int wait_layer) override {
+        double b = std::max(t_copy, t_floor);
+        if (wait_layer >= 0) b = std::max(b, done[wait_layer]);
+        t_copy = b + c.copy_ms;
+        loaded[layer] = t_copy;
+        return SP_OK;
+    }
+    int compute(int layer, int, int dir, bool fresh) override {
+        double b = std::max(t_comp, t_floor);
+        if (fresh) b = std::max(b, loaded[layer]);
+        if (dir > 0) {
+            t_comp = b + c.fwd_ms;
+        } else {
+            b = std::max(b, gslot_free[gs]);            // its gradient slot must have drained
+            t_comp = b + c.bwd_ms;
+            t_grad = std::max(t_grad, t_comp) + c.grad_ms;
+            gslot_free[gs] = t_grad;
+            gs = (gs + 1) % kGradSlots;
+        }
+        done[layer] = t_comp;
+        return SP_OK;
+    }
+    double now() const { return std::max(std::max(t_copy, t_comp), t_grad); }
+};
+
+double simulate(int L, int n_slots, int p_eff, int training, int wrap, int calls, const sp_layer_cost& c) {
+    Scheduler sch;
+    sch.reset(L, n_slots, p_eff);
+    SimSink sink(c, L);
+    double begin = 0, end = 0;
+    for (int i = 0; i < calls; ++i) {
+        // forward-only calls follow each other on the streams; a training step starts
+        // when the previous one has delivered its last gradient
+        begin = training ? sink.now() : sink.t_comp;
+        if (training) sink.t_floor = begin;
+        sch.run_pass(+1, !training && wrap, sink);
+        if (training) sch.run_pass(-1, false, sink);
+        end = training ? sink.now() : sink.t_comp;
+    }
+    return end - begin;
+}
+}  // namespace
+
+extern "C" double sp_simulate_call_ms(int n_layers, int n_slots, int p_eff, int training, int wrap_prefetch,
+                                      int calls, const sp_layer_cost* cost) {
+    if (n_layers < 1 || n_slots < 1 || n_slots > n_layers || p_eff < 1 || calls < 1 || !cost ||
+        !(cost->copy_ms >= 0) || !(cost->fwd_ms >= 0) || !(cost->bwd_ms >= 0) || !(cost->grad_ms >= 0))
+        return -1.0;
+    return simulate(n_layers, n_slots, p_eff, training, wrap_prefetch, calls, *cost);
+}
+
+extern "C" int sp_autotune(const sp_stack_desc* desc, uint64_t budget_bytes, int training, int wrap_prefetch,
+                           const sp_layer_cost* cost, double tolerance, int* k_out, int* p_out, double* ms_out) {
+    const char* why = nullptr;
+    if (!desc || !cost || !k_out || !p_out || validate_desc(desc, &why) != SP_OK || !(tolerance >= 0))
+        return SP_ERR_INVALID_ARG;
+    const int L = desc->n_layers;
+    struct Cand { int n, p; double ms; };
+    std::vector<Cand> cands;
+    int rc_first = SP_OK;
+    for (int p = 1; p <= L; ++p) {
+        for (int k = 1; k + p <= L + 1; ++k) {
+            sp_plan pl;
+            int rc = make_plan(desc, k, p, budget_bytes, training, &pl);
+            if (rc != SP_OK) { if (rc_first == SP_OK) rc_first = rc; continue; }
+            bool seen = false;
+            for (const Cand& c : cands) seen = seen || (c.n == pl.n_slots && c.p == pl.p_eff);
+            if (seen) continue;
+            const double ms = sp_simulate_call_ms(L, pl.n_slots, pl.p_eff, training ? 1 : 0, wrap_prefetch, 3, cost);
+            if (ms < 0) return SP_ERR_INVALID_ARG;
+            cands.push_back(Cand{pl.n_slots, pl.p_eff, ms});
+        }
+    }
+    if (cands.empty()) return rc_first != SP_OK ? rc_first : SP_ERR_BUDGET;
+    double best = cands[0].ms;
+    for (const Cand& c : cands) best = std::min(best, c.ms);
+    const Cand* pick = nullptr;
+    for (const Cand& c : cands) {
+        if (c.ms > best * (1.0 + tolerance)) continue;
+        if (!pick || c.n < pick->n || (c.n == pick->n && c.p < pick->p)) pick = &c;
+    }
+    *p_out = pick->p;
+    *k_out = std::max(pick->n - pick->p, 1);
+    if (ms_out) *ms_out = pick->ms;
+    return SP_OK;
+}

@@ -204,3 +204,54 @@ def test_llama70b_layer_shape():
     err = max_rel(y, c.ref(np.float32).astype(np.float64))
     print(f"llama70b x1 layer, 512 tokens: max rel err vs fp32 oracle {err:.3e}")
     assert err <= TOL
+
+
+def _timed_passes(desc, blobs, xd, w, k, p, budget_bytes, flags, calls=4):
+    """ms per steady-state pass (events on the compute stream) and the last call's stats."""
+    eng = sp.Engine(desc, blobs, k, p, budget_bytes=budget_bytes, flags=flags)
+    y = torch.empty_like(xd)
+    eng.forward(xd, y, w.batch, w.seq)
+    eng.sync()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(eng.compute)
+    for _ in range(calls):
+        eng.forward(xd, y, w.batch, w.seq)
+    e1.record(eng.compute)
+    eng.sync()
+    st = eng.stats()
+    assert eng.destroy() == sp.SP_OK
+    return e0.elapsed_time(e1) / calls, st, y.cpu().numpy()
+
+
+@pytest.mark.parametrize("name,over", [
+    ("train1p3b", dict(n_layers=12, batch=2, seq=1024)),     # copy-bound: 101 MB per layer, 2048 tokens
+    ("vith", dict(n_layers=12, batch=64)),                   # compute-bound
+])
+def test_cost_model_and_tuner_against_measurement(name, over):
+    """The cost model fed with the measured per-layer copy and compute times predicts the
+    measured pass; the window the tuner picks is as fast as the best of a measured grid
+    (the paper's grid search over k and k', Sec. 4.2) and gives the same bits."""
+    w = synth.WORKLOADS[name].with_(**over)
+    desc = sp.make_desc(w)
+    pool = synth.make_pool(8)
+    one, _ = sp.pinned_blobs(w, desc, n_layers=2, pool=pool)
+    pool.shutdown()
+    blobs = [one[l % 2] for l in range(w.n_layers)]
+    xd = dev_f32(synth.make_input(w))
+    slot = (sp.sp_layer_blob_bytes(C.byref(desc)) + 4095) // 4096 * 4096
+    budget = sp.sp_workspace_bytes(C.byref(desc), 0) + 6 * slot
+    wrap = sp.SP_FLAG_WRAP_PREFETCH
+    ms_traced, st, y_ref = _timed_passes(desc, blobs, xd, w, 2, 1, budget, wrap | sp.SP_FLAG_TIMING)
+    cost = sp.layer_costs(st, w.n_layers)
+    model = sp.simulate_call_ms(w.n_layers, 3, 1, cost, wrap=True)
+    print(f"{name}: copy {cost[0]:.3f} ms, forward {cost[1]:.3f} ms per layer; pass measured {ms_traced:.2f} ms, "
+          f"modelled {model:.2f} ms")
+    assert abs(model - ms_traced) <= 0.2 * ms_traced
+    k, p, _ = sp.autotune(desc, budget, cost, wrap=True)
+    grid = {(1, 1), (2, 1), (2, 2), (4, 2), (k, p)}
+    ms = {}
+    for kk, pp in sorted(grid):
+        ms[(kk, pp)], _, y = _timed_passes(desc, blobs, xd, w, kk, pp, budget, wrap)
+        assert np.array_equal(y, y_ref)
+    print(f"{name}: tuner picked (k,p)=({k},{p}); measured ms per pass: {ms}")
+    assert ms[(k, p)] <= 1.1 * min(ms.values())
