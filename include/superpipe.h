@@ -90,8 +90,8 @@ enum {
                                       workspace instead of recomputing them in the backward
                                       (the paper's "without gradient checkpointing" column,
                                       Table 2): more HBM, about a quarter less compute      */
-    SP_FLAG_KERNEL_TIMING = 1u << 5 /* bracket the layer's largest GEMM with timed events on
-                                      the compute stream only (big_gemm_* in sp_stats)     */
+    SP_FLAG_KERNEL_TIMING = 1u << 5 /* bracket every 4th launch of the layer's largest GEMM with
+                                      timed events on the compute stream (big_gemm_* in sp_stats) */
 };
 
 typedef struct {
@@ -104,20 +104,33 @@ typedef struct {
     void* h2d_stream;           /* hipStream_t, must differ from compute_stream  */
     void* d2h_stream;           /* hipStream_t, needed only with SP_FLAG_TRAINING */
     uint32_t flags;
+    int32_t pinned_layers;      /* layers 0..n-1 that stay in HBM for the handle's life and are
+                                   never re-copied; SP_PIN_AUTO = as many as the budget leaves
+                                   after the k + p window; 0 = none (every layer streams)      */
 } sp_config;
+#define SP_PIN_AUTO (-1)
 
-/* Slot-count policy (one function decides it).  The requested number of HBM
- * layer slots is k + p -- the paper's "k partitions on the GPU" with its k' = p
+/* Slot-count policy (one function decides it).  The streaming window asks for
+ * k + p HBM layer slots -- the paper's "k partitions on the GPU" with its k' = p
  * of them being refilled (Fig. 1: k=4, k'=2 is (k,p) = (2,2)) -- clamped by the
- * layer count and by what the arena holds after the workspace:
- *   n_slots = min(k + p, L, (budget - workspace) / slot_bytes);  0 -> SP_ERR_BUDGET
- *   p_eff   = min(p, max(n_slots - 1, 1)),  k_eff = max(n_slots - p_eff, 1).      */
+ * layer count and by what the arena holds after the workspace; pinned layers
+ * take what the budget leaves after the window:
+ *   cap      = min(L, (budget - workspace) / slot_bytes);   0 -> SP_ERR_BUDGET
+ *   window   = min(k + p, cap)
+ *   n_pinned = min(pinned_layers, cap - window)   (SP_PIN_AUTO: cap - window)
+ *   n_slots  = window + n_pinned;  if that reaches L: fully resident, n_pinned = 0
+ *   p_eff    = min(p, max(window - 1, 1)),  k_eff = max(window - p_eff, 1).
+ * With n_pinned layers held, a steady-state pass copies L - n_pinned blobs
+ * instead of L: on a link-bound stack that is the only way to go faster at a
+ * fixed budget once the link is saturated. */
 typedef struct {
     int32_t n_slots, k_eff, p_eff;
     int32_t fully_resident;     /* n_slots == n_layers */
     uint64_t slot_bytes;        /* blob bytes rounded up to 4 KiB */
     uint64_t workspace_bytes;
     uint64_t arena_bytes_used;  /* workspace + n_slots * slot_bytes (+ gradient slots) */
+    int32_t n_pinned;           /* of the n_slots, those holding layers 0..n_pinned-1 for good */
+    int32_t reserved_;
 } sp_plan;
 
 #define SP_MAX_TRACE_LAYERS 256
@@ -139,7 +152,8 @@ typedef struct {
     float wall_ms;              /* first op begin -> last op end                        */
     /* SP_FLAG_KERNEL_TIMING (or SP_FLAG_TIMING): the layer's largest GEMM (decoder: gate/up with the SwiGLU
      * epilogue; encoder: the first MLP GEMM), bracketed by events on the compute
-     * stream at every launch since the previous sp_get_stats.                         */
+     * stream at every 4th launch since the previous sp_get_stats (a sample: each pair
+     * of event records leaves a gap on the stream).                                   */
     uint32_t big_gemm_launches;
     float big_gemm_ms_sum;
     int32_t big_gemm_m, big_gemm_n, big_gemm_k;   /* its shape: C[m,n] over k (n counts gate and up) */
@@ -162,14 +176,15 @@ size_t sp_layer_grad_bytes(const sp_stack_desc* desc);
  * SP_FLAG_KEEP_ACTIVATIONS (one activation set per layer). */
 size_t sp_workspace_bytes(const sp_stack_desc* desc, int training);
 /* The slot-count policy above as a pure function. */
-int sp_make_plan(const sp_stack_desc* desc, int k, int p, uint64_t budget_bytes, int training,
-                 sp_plan* out);
+int sp_make_plan(const sp_stack_desc* desc, int k, int p, int pinned_layers, uint64_t budget_bytes,
+                 int training, sp_plan* out);
 
 /* One step of the host-side schedule, for inspection and host-only tests.
  * sp_trace_schedule writes the ordered op list that `passes` consecutive calls
  * would enqueue (dir +1 = forward pass over layers 0..L-1, the pattern
  * forward,backward repeats when training != 0).  Returns the number of ops
- * (may exceed cap; only cap are written) or a negative sp_status. */
+ * (may exceed cap; only cap are written) or a negative sp_status.  n_slots
+ * counts every slot, the n_pinned < n_slots pinned ones included. */
 typedef struct {
     int32_t kind;    /* 0 = COPY layer->slot (copy stream), 1 = COMPUTE layer (compute stream),
                         2 = BACKWARD layer (compute stream) */
@@ -178,8 +193,8 @@ typedef struct {
                             COMPUTE/BACKWARD: 1 if it waits for a copy issued earlier, else 0 */
     int32_t pass;
 } sp_sched_op;
-int sp_trace_schedule(int n_layers, int n_slots, int p_eff, int training, int wrap_prefetch,
-                      int passes, sp_sched_op* ops, int cap);
+int sp_trace_schedule(int n_layers, int n_slots, int n_pinned, int p_eff, int training,
+                      int wrap_prefetch, int passes, sp_sched_op* ops, int cap);
 
 /* Cost model of the schedule (host only).  Plays what sp_trace_schedule lists on
  * three in-order streams -- layer copies, layer computes, gradient copies --
@@ -194,17 +209,19 @@ typedef struct {
     double bwd_ms;    /* one layer backward incl. recompute (training only)             */
     double grad_ms;   /* one layer's gradient copy, device to host (training only)      */
 } sp_layer_cost;
-double sp_simulate_call_ms(int n_layers, int n_slots, int p_eff, int training, int wrap_prefetch,
-                           int calls, const sp_layer_cost* cost);
+double sp_simulate_call_ms(int n_layers, int n_slots, int n_pinned, int p_eff, int training,
+                           int wrap_prefetch, int calls, const sp_layer_cost* cost);
 
 /* Window choice under a byte budget (the paper finds k and k' by grid search,
  * Sec. 4.2, and names adaptive selection as future work, Sec. 5): every (k, p)
- * whose plan fits budget_bytes is run through the cost model; of those within
+ * whose plan fits budget_bytes, once with no pinned layers and once with the
+ * rest of the budget pinned, is run through the cost model; of those within
  * (1 + tolerance) of the best modelled time the one with the fewest slots, then
  * the smallest p, is returned (fewest bytes of HBM for the same speed).
  * training: 0, 1 or 2 as for sp_workspace_bytes.  SP_ERR_BUDGET if nothing fits. */
 int sp_autotune(const sp_stack_desc* desc, uint64_t budget_bytes, int training, int wrap_prefetch,
-                const sp_layer_cost* cost, double tolerance, int* k_out, int* p_out, double* ms_out);
+                const sp_layer_cost* cost, double tolerance, int* k_out, int* p_out, int* pinned_out,
+                double* ms_out);
 
 /* ---- the four calls ------------------------------------------------------ */
 

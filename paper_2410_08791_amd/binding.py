@@ -29,6 +29,7 @@ SP_DECODER_SWIGLU_RMS, SP_ENCODER_GELU_LN = 0, 1
 SP_FLAG_TRAINING, SP_FLAG_TIMING, SP_FLAG_POISON, SP_FLAG_NO_OVERLAP, SP_FLAG_WRAP_PREFETCH = 1, 2, 4, 8, 16
 SP_FLAG_KERNEL_TIMING = 32
 SP_FLAG_KEEP_ACTIVATIONS = 64
+SP_PIN_AUTO = -1
 SP_MAX_TRACE_LAYERS = 256
 EPI_BF16, EPI_RESID_F32, EPI_GELU_BF16, EPI_SWIGLU_BF16, EPI_F32 = 0, 1, 2, 3, 4
 
@@ -48,12 +49,14 @@ class sp_stack_desc(C.Structure):
 class sp_config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("resident_window_k", C.c_int32), ("prefetch_depth_p", C.c_int32),
                 ("gpu_budget_bytes", C.c_uint64), ("device_arena", C.c_void_p), ("compute_stream", C.c_void_p),
-                ("h2d_stream", C.c_void_p), ("d2h_stream", C.c_void_p), ("flags", C.c_uint32)]
+                ("h2d_stream", C.c_void_p), ("d2h_stream", C.c_void_p), ("flags", C.c_uint32),
+                ("pinned_layers", C.c_int32)]
 
 
 class sp_plan(C.Structure):
     _fields_ = [("n_slots", C.c_int32), ("k_eff", C.c_int32), ("p_eff", C.c_int32), ("fully_resident", C.c_int32),
-                ("slot_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("arena_bytes_used", C.c_uint64)]
+                ("slot_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("arena_bytes_used", C.c_uint64),
+                ("n_pinned", C.c_int32), ("reserved_", C.c_int32)]
 
 
 _F = C.c_float * SP_MAX_TRACE_LAYERS
@@ -81,17 +84,17 @@ class sp_layer_cost(C.Structure):
 
 _P = C.POINTER
 _sig = {
-    "sp_simulate_call_ms": (C.c_double, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P(sp_layer_cost)]),
+    "sp_simulate_call_ms": (C.c_double, [C.c_int] * 7 + [_P(sp_layer_cost)]),
     "sp_autotune": (C.c_int, [_P(sp_stack_desc), C.c_uint64, C.c_int, C.c_int, _P(sp_layer_cost), C.c_double,
-                              _P(C.c_int), _P(C.c_int), _P(C.c_double)]),
+                              _P(C.c_int), _P(C.c_int), _P(C.c_int), _P(C.c_double)]),
     "sp_num_tensors": (C.c_int, [_P(sp_stack_desc)]),
     "sp_tensor_offset": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
     "sp_tensor_elems": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
     "sp_layer_blob_bytes": (C.c_size_t, [_P(sp_stack_desc)]),
     "sp_layer_grad_bytes": (C.c_size_t, [_P(sp_stack_desc)]),
     "sp_workspace_bytes": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
-    "sp_make_plan": (C.c_int, [_P(sp_stack_desc), C.c_int, C.c_int, C.c_uint64, C.c_int, _P(sp_plan)]),
-    "sp_trace_schedule": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P(sp_sched_op), C.c_int]),
+    "sp_make_plan": (C.c_int, [_P(sp_stack_desc), C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_int, _P(sp_plan)]),
+    "sp_trace_schedule": (C.c_int, [C.c_int] * 7 + [_P(sp_sched_op), C.c_int]),
     "sp_create": (C.c_int, [_P(C.c_void_p), _P(sp_stack_desc), _P(C.c_void_p), _P(sp_config)]),
     "sp_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
     "sp_forward_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -155,36 +158,37 @@ def grad_views(desc, gblob_u8: np.ndarray):
     return out
 
 
-def plan(desc, k, p, budget, training=False):
+def plan(desc, k, p, budget, training=False, pinned=0):
     pl = sp_plan()
-    rc = sp_make_plan(C.byref(desc), k, p, budget, int(training), C.byref(pl))
+    rc = sp_make_plan(C.byref(desc), k, p, pinned, budget, int(training), C.byref(pl))
     return rc, pl
 
 
-def trace_schedule(n_layers, n_slots, p_eff, training=False, wrap=False, passes=1):
-    n = sp_trace_schedule(n_layers, n_slots, p_eff, int(training), int(wrap), passes, None, 0)
+def trace_schedule(n_layers, n_slots, p_eff, training=False, wrap=False, passes=1, pinned=0):
+    n = sp_trace_schedule(n_layers, n_slots, pinned, p_eff, int(training), int(wrap), passes, None, 0)
     if n < 0:
         raise SuperpipeError(n, "sp_trace_schedule")
     ops = (sp_sched_op * n)()
-    sp_trace_schedule(n_layers, n_slots, p_eff, int(training), int(wrap), passes, ops, n)
+    sp_trace_schedule(n_layers, n_slots, pinned, p_eff, int(training), int(wrap), passes, ops, n)
     return [(o.kind, o.layer, o.slot, o.wait_layer, o.pass_) for o in ops]
 
 
-def simulate_call_ms(n_layers, n_slots, p_eff, cost, training=False, wrap=False, calls=3):
+def simulate_call_ms(n_layers, n_slots, p_eff, cost, training=False, wrap=False, calls=3, pinned=0):
     """Modelled duration of the last of `calls` calls; cost = (copy, fwd, bwd, grad) in ms."""
     c = sp_layer_cost(*cost)
-    return sp_simulate_call_ms(n_layers, n_slots, p_eff, int(training), int(wrap), calls, C.byref(c))
+    return sp_simulate_call_ms(n_layers, n_slots, pinned, p_eff, int(training), int(wrap), calls, C.byref(c))
 
 
 def autotune(desc, budget_bytes, cost, training=0, wrap=False, tolerance=0.02):
-    """(k, p, modelled ms) for the smallest window within `tolerance` of the best modelled time."""
+    """(k, p, pinned layers, modelled ms) for the smallest window within `tolerance` of the best
+    modelled time."""
     c = sp_layer_cost(*cost)
-    k, p, ms = C.c_int(), C.c_int(), C.c_double()
+    k, p, r, ms = C.c_int(), C.c_int(), C.c_int(), C.c_double()
     rc = sp_autotune(C.byref(desc), budget_bytes, int(training), int(wrap), C.byref(c), tolerance,
-                     C.byref(k), C.byref(p), C.byref(ms))
+                     C.byref(k), C.byref(p), C.byref(r), C.byref(ms))
     if rc != SP_OK:
         raise SuperpipeError(rc, "sp_autotune")
-    return k.value, p.value, ms.value
+    return k.value, p.value, r.value, ms.value
 
 
 def layer_costs(st, n_layers, training=False, grad_ms=0.0):
@@ -233,7 +237,8 @@ def _device_streams(torch, device):
 class Engine:
     """Owns an sp_handle plus the torch-allocated arena and streams it runs on."""
 
-    def __init__(self, desc, blobs, k, p, budget_bytes=None, budget_layers=None, flags=0, device="cuda:0"):
+    def __init__(self, desc, blobs, k, p, budget_bytes=None, budget_layers=None, flags=0, device="cuda:0",
+                 pinned=0):
         import torch
         self.torch = torch
         self.desc = desc
@@ -242,7 +247,7 @@ class Engine:
         ws = sp_workspace_bytes(C.byref(desc), (2 if flags & SP_FLAG_KEEP_ACTIVATIONS else 1) if training else 0)
         slot = (sp_layer_blob_bytes(C.byref(desc)) + 4095) // 4096 * 4096
         if budget_bytes is None:
-            nl = budget_layers if budget_layers else min(k + p, desc.n_layers)
+            nl = budget_layers if budget_layers else min(k + p + max(pinned, 0), desc.n_layers)
             budget_bytes = ws + nl * slot
         self.budget_bytes = int(budget_bytes)
         self.device = torch.device(device)
@@ -257,7 +262,7 @@ class Engine:
         ptrs = (C.c_void_p * len(blobs))(*[b.data_ptr() for b in blobs])
         cfg = sp_config(C.sizeof(sp_config), k, p, self.budget_bytes, self.arena.data_ptr(),
                         self.compute.cuda_stream, self.h2d.cuda_stream,
-                        self.d2h.cuda_stream if training else None, flags)
+                        self.d2h.cuda_stream if training else None, flags, pinned)
         self.handle = C.c_void_p()
         rc = sp_create(C.byref(self.handle), C.byref(desc), ptrs, C.byref(cfg))
         if rc != SP_OK:

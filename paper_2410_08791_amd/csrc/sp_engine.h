@@ -30,6 +30,11 @@ struct sp_engine {
     int ci = 0, mi = 0;                                  // ops issued by the current call
     std::vector<int> tr_copy_layer, tr_copy_dep, tr_comp_layer, tr_comp_dep;
     hipEvent_t ev_sync_c = nullptr, ev_sync_h = nullptr;
+    // Host run-ahead bound: ring of events, one per enqueued layer op, with the running count
+    // of compute-stream packets at each; see throttle() in sp_engine.hip.
+    std::vector<hipEvent_t> thr_ev;
+    std::vector<uint64_t> thr_at;
+    uint64_t thr_head = 0, thr_tail = 0, thr_packets = 0;
     hipEvent_t pass_end_c = nullptr, pass_end_d = nullptr;   // end of the latest training pass on compute / d2h
     bool pass_pending = false;
     hipEvent_t grad_ready[sp::kGradSlots] = {}, gslot_free[sp::kGradSlots] = {};
@@ -38,6 +43,7 @@ struct sp_engine {
     hipEvent_t t0 = nullptr;
     std::vector<hipEvent_t> kt_begin, kt_end;   // ring of event pairs around the largest GEMM
     uint32_t kt_count = 0;                      // pairs recorded since the last sp_get_stats
+    uint32_t kt_seen = 0;                       // launches of that GEMM seen (every 4th is timed)
     int kt_m = 0, kt_n = 0, kt_k = 0;
     // counters
     uint64_t calls = 0, stats_h2d_copies = 0, stats_h2d_bytes = 0, stats_d2h_copies = 0, stats_d2h_bytes = 0;

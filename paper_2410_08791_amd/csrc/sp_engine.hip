@@ -51,6 +51,39 @@ int sp_fail(sp_engine* e, int code, const char* fmt, ...) {
 }
 #define fail sp_fail
 
+// ---- host run-ahead bound -----------------------------------------------------------
+// The host enqueues a whole call in a few milliseconds.  Measured on this runtime: once
+// more than roughly 1500 packets (kernels and event records) wait on the compute stream,
+// passes take 30-60 % longer in bursts and device-to-host copies drop to a fraction of the
+// link rate; below that every pass runs at its steady time.  A host-side wait is not free
+// either (the copies of the next layers are enqueued late, 3-5 ms per wait on a step whose
+// link is busy), so waits are made rare: when more than kMaxQueuedPackets are unfinished
+// the host sleeps until kResumePackets are left, then runs ahead again.  Per-op packet
+// counts are rounded-up estimates; the ring is longer than any window they allow.
+constexpr uint64_t kMaxQueuedPackets = 1024;
+constexpr uint64_t kResumePackets = 256;
+constexpr size_t kThrottleRing = 256;
+
+static int throttle_before(sp_engine* e) {
+    auto left_after = [&](uint64_t i) { return e->thr_packets - e->thr_at[i % kThrottleRing]; };
+    if (e->thr_tail < e->thr_head &&
+        (left_after(e->thr_tail) > kMaxQueuedPackets || e->thr_head - e->thr_tail >= kThrottleRing)) {
+        while (e->thr_tail + 1 < e->thr_head && left_after(e->thr_tail + 1) > kResumePackets) e->thr_tail++;
+        SP_HIP(e, hipEventSynchronize(e->thr_ev[e->thr_tail % kThrottleRing]));
+        e->thr_tail++;
+    }
+    return SP_OK;
+}
+
+static int throttle_after(sp_engine* e, unsigned packets) {
+    e->thr_packets += packets;
+    const size_t i = e->thr_head % kThrottleRing;
+    SP_HIP(e, hipEventRecord(e->thr_ev[i], e->compute));
+    e->thr_at[i] = e->thr_packets;
+    e->thr_head++;
+    return SP_OK;
+}
+
 // ---- the sink that enqueues real stream work -------------------------------------
 struct HipSink : SchedSink {
     sp_engine* e;
@@ -95,6 +128,8 @@ struct HipSink : SchedSink {
     int compute(int layer, int slot, int dir, bool /*fresh*/) override {
         hipStream_t st = e->compute;
         if (e->mi >= (int)e->comp_ev.size()) return sp_fail(e, SP_ERR_STATE, "compute event pool exhausted");
+        int rc = throttle_before(e);
+        if (rc != SP_OK) return rc;
         int dep = -1;
         if (e->flags & SP_FLAG_NO_OVERLAP) {
             // Naive comparator: compute starts only after every copy enqueued so far.
@@ -106,7 +141,6 @@ struct HipSink : SchedSink {
             dep = e->layer_loaded_idx[layer];
         }
         const unsigned char* w = e->slots + (size_t)slot * e->plan.slot_bytes;
-        int rc;
         if (dir > 0)
             rc = training_fwd ? sp_layer_forward_train(e, layer, w, B, S) : sp_layer_forward(e, w, hbuf, B, S);
         else
@@ -119,7 +153,8 @@ struct HipSink : SchedSink {
         e->tr_comp_layer[e->mi] = layer;
         e->tr_comp_dep[e->mi] = dep;
         e->mi++;
-        return SP_OK;
+        // packets per op, counted generously: forward ~9 kernels + events, backward ~40
+        return throttle_after(e, dir > 0 ? 16 : 56);
     }
 };
 
@@ -156,7 +191,9 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
     SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     // b5: a = norm(h)
     SP_HIP(e, spk_launch_norm(st, h, W(dec ? SP_T_G2 : SP_T_LN2_G), dec ? nullptr : W(SP_T_LN2_B), a, T, dm, d.norm_eps));
-    const bool kt = !e->kt_begin.empty();
+    // every 4th launch of the largest GEMM is bracketed: the two event records cost a gap
+    // on the stream, which on a compute-bound stack would show in the step time
+    const bool kt = !e->kt_begin.empty() && (e->kt_seen++ % 4 == 0);
     const size_t kti = kt ? e->kt_count % e->kt_begin.size() : 0;
     if (kt) {
         SP_HIP(e, hipEventRecord(e->kt_begin[kti], st));
@@ -212,7 +249,8 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
         return fail(nullptr, SP_ERR_INVALID_ARG, "training is implemented for decoder stacks only");
     if (desc->n_layers > 4096) return fail(nullptr, SP_ERR_INVALID_ARG, "n_layers > 4096");
     sp_plan plan;
-    int rc = make_plan(desc, cfg->resident_window_k, cfg->prefetch_depth_p, cfg->gpu_budget_bytes, mode, &plan);
+    int rc = make_plan(desc, cfg->resident_window_k, cfg->prefetch_depth_p, cfg->pinned_layers, cfg->gpu_budget_bytes, mode,
+                       &plan);
     if (rc == SP_ERR_BUDGET) {
         return fail(nullptr, rc, "gpu_budget_bytes=%llu cannot hold the workspace (%llu) plus one layer slot (%llu)",
                     (unsigned long long)cfg->gpu_budget_bytes, (unsigned long long)plan.workspace_bytes,
@@ -261,6 +299,9 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     for (size_t i = 0; i < e->comp_ev.size() && he == hipSuccess; ++i) he = mk(&e->comp_ev[i], evflags);
     if (he == hipSuccess) he = mk(&e->ev_sync_c, hipEventDisableTiming);
     if (he == hipSuccess) he = mk(&e->ev_sync_h, hipEventDisableTiming);
+    e->thr_ev.assign(kThrottleRing, nullptr);
+    e->thr_at.assign(kThrottleRing, 0);
+    for (size_t i = 0; i < kThrottleRing && he == hipSuccess; ++i) he = mk(&e->thr_ev[i], hipEventDisableTiming);
     if (he == hipSuccess && training) he = mk(&e->pass_end_c, hipEventDisableTiming);
     if (he == hipSuccess && training) he = mk(&e->pass_end_d, hipEventDisableTiming);
     for (int i = 0; i < kGradSlots && he == hipSuccess; ++i) {
@@ -282,7 +323,7 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
         return SP_ERR_HIP;
     }
     const bool naive = cfg->flags & SP_FLAG_NO_OVERLAP;
-    e->sched.reset(L, plan.n_slots, naive ? plan.n_slots : plan.p_eff);
+    e->sched.reset(L, plan.n_slots, naive ? plan.n_slots - plan.n_pinned : plan.p_eff, plan.n_pinned);
     e->fuse_swiglu = true;
     e->gemm_tile = 0;
     if (const char* t = getenv("SP_GEMM_TILE")) e->gemm_tile = atoi(t);
@@ -478,6 +519,7 @@ static int destroy_engine(sp_engine* e) {
     for (auto ev : e->kt_end) kill(ev);
     kill(e->ev_sync_c);
     kill(e->ev_sync_h);
+    for (auto ev : e->thr_ev) kill(ev);
     kill(e->pass_end_c);
     kill(e->pass_end_d);
     kill(e->t0);

@@ -57,7 +57,7 @@ struct Workspace {
 // layer's activations (no recompute)
 void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Workspace* ws);
 
-int make_plan(const sp_stack_desc* d, int k, int p, uint64_t budget, int training, sp_plan* out);
+int make_plan(const sp_stack_desc* d, int k, int p, int pinned, uint64_t budget, int training, sp_plan* out);
 
 // ---- window scheduler --------------------------------------------------------
 // Decides, in host order, which layer is copied into which slot and when a
@@ -73,15 +73,17 @@ struct SchedSink {
 
 class Scheduler {
 public:
-    void reset(int n_layers, int n_slots, int group);
+    // n_pinned: layers 0..n_pinned-1 keep a slot each for good; the others stream through the rest
+    void reset(int n_layers, int n_slots, int group, int n_pinned = 0);
     // One pass over all layers: dir +1 = 0..L-1, dir -1 = L-1..0.  With wrap
     // (forward-only use) slots freed at the tail are refilled with the first layers.
     int run_pass(int dir, bool wrap, SchedSink& sink);
     int n_slots() const { return n_slots_; }
+    int n_pinned() const { return n_pinned_; }
     const std::vector<int>& layer_slot() const { return layer_slot_; }
 
 private:
-    int n_layers_ = 0, n_slots_ = 0, group_ = 1;
+    int n_layers_ = 0, n_slots_ = 0, group_ = 1, n_pinned_ = 0;
     std::vector<int> slot_layer_;   // layer occupying (or being copied into) a slot, -1 = empty
     std::vector<int> slot_last_;    // last layer computed out of a slot, -1 = none
     std::vector<int> layer_slot_;   // slot of a resident layer, -1 = not on the device

@@ -111,35 +111,42 @@ void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Wor
     ws->total = align_up(off, kSlotAlign);
 }
 
-int make_plan(const sp_stack_desc* d, int k, int p, uint64_t budget, int training, sp_plan* out) {
+int make_plan(const sp_stack_desc* d, int k, int p, int pinned, uint64_t budget, int training, sp_plan* out) {
     if (!out) return SP_ERR_INVALID_ARG;
     memset(out, 0, sizeof(*out));
     Layout lay;
     int rc = make_layout(d, &lay);
     if (rc != SP_OK) return rc;
-    if (k < 1 || p < 1) return SP_ERR_INVALID_ARG;
+    if (k < 1 || p < 1 || pinned < SP_PIN_AUTO) return SP_ERR_INVALID_ARG;
     Workspace ws;
     make_workspace(d, lay, training, &ws);
     out->slot_bytes = align_up(lay.blob_bytes, kSlotAlign);
     out->workspace_bytes = ws.total;
     if (budget < ws.total + out->slot_bytes) return SP_ERR_BUDGET;
-    const uint64_t fit = (budget - ws.total) / out->slot_bytes;
-    int64_t want = (int64_t)k + p;
-    int64_t n = std::min<int64_t>(want, d->n_layers);
-    n = std::min<int64_t>(n, (int64_t)std::min<uint64_t>(fit, 1u << 30));
+    const int64_t L = d->n_layers;
+    const int64_t cap = std::min<int64_t>(L, (int64_t)std::min<uint64_t>((budget - ws.total) / out->slot_bytes, 1u << 30));
+    // the streaming window comes first; pinned layers take what the budget leaves
+    const int64_t window = std::min<int64_t>((int64_t)k + p, cap);
+    int64_t r = pinned == SP_PIN_AUTO ? cap - window : std::min<int64_t>(pinned, cap - window);
+    int64_t n = window + r;
+    if (n >= L) { n = L; r = 0; }       // everything fits: nothing streams, nothing to pin
     out->n_slots = (int)n;
-    out->p_eff = (int)std::min<int64_t>(p, std::max<int64_t>(n - 1, 1));
-    out->k_eff = (int)std::max<int64_t>(n - out->p_eff, 1);
-    out->fully_resident = n == d->n_layers;
+    out->n_pinned = (int)r;
+    const int64_t ring = n - r;
+    out->p_eff = (int)std::min<int64_t>(p, std::max<int64_t>(ring - 1, 1));
+    out->k_eff = (int)std::max<int64_t>(ring - out->p_eff, 1);
+    out->fully_resident = n == L;
     out->arena_bytes_used = ws.total + (uint64_t)n * out->slot_bytes;
     return SP_OK;
 }
 
 // ---- scheduler ---------------------------------------------------------------
-void Scheduler::reset(int n_layers, int n_slots, int group) {
+void Scheduler::reset(int n_layers, int n_slots, int group, int n_pinned) {
     n_layers_ = n_layers;
     n_slots_ = n_slots;
     group_ = std::max(1, group);
+    // pinned layers only make sense next to a streaming ring of at least one slot
+    n_pinned_ = (n_slots >= n_layers) ? 0 : std::max(0, std::min(n_pinned, n_slots - 1));
     slot_layer_.assign(n_slots, -1);
     slot_last_.assign(n_slots, -1);
     layer_slot_.assign(n_layers, -1);
@@ -147,51 +154,71 @@ void Scheduler::reset(int n_layers, int n_slots, int group) {
 }
 
 int Scheduler::run_pass(int dir, bool wrap, SchedSink& sink) {
-    const int L = n_layers_, N = n_slots_;
-    auto at = [&](int i) { return dir > 0 ? i : L - 1 - i; };  // i-th layer of this pass
+    const int L = n_layers_, N = n_slots_, R = n_pinned_;
     int rc;
-    // Initial load (Sec. 1: "load k units into GPU memory initially"): the first
-    // N layers of the pass, except those still resident from the previous pass.
-    const int first = std::min(N, L);
-    std::vector<char> keep(N, 0);
-    for (int i = 0; i < first; ++i)
-        if (layer_slot_[at(i)] >= 0) keep[layer_slot_[at(i)]] = 1;
-    int scan = 0;
-    for (int i = 0; i < first; ++i) {
-        const int l = at(i);
-        if (layer_slot_[l] >= 0) continue;
-        while (scan < N && keep[scan]) ++scan;
-        if (scan >= N) return SP_ERR_STATE;  // cannot happen: first <= N
-        const int s = scan;
-        keep[s] = 1;
+    // Layers 0..R-1 are pinned: slot l holds layer l from its first use on and is never
+    // refilled.  The other layers stream through the ring of slots R..N-1.
+    std::vector<int> order;            // streamed layers in the order this pass needs them
+    order.reserve(L - R);
+    for (int i = 0; i < L; ++i) {
+        const int l = dir > 0 ? i : L - 1 - i;
+        if (l >= R) order.push_back(l);
+    }
+    const int M = (int)order.size(), ring = N - R;
+    auto load = [&](int l, int s) {
         if (slot_layer_[s] >= 0) layer_slot_[slot_layer_[s]] = -1;
         slot_layer_[s] = l;
         layer_slot_[l] = s;
         fresh_[l] = 1;
-        if ((rc = sink.copy(l, s, slot_last_[s])) != SP_OK) return rc;
+        return sink.copy(l, s, slot_last_[s]);
+    };
+    if (dir > 0)
+        for (int l = 0; l < R; ++l)
+            if (layer_slot_[l] < 0 && (rc = load(l, l)) != SP_OK) return rc;
+    // Initial load (Sec. 3.3: k partitions are on the device before the first compute):
+    // the first `ring` streamed layers of the pass, except those still resident from the
+    // previous pass.
+    const int first = std::min(ring, M);
+    std::vector<char> keep(N, 0);
+    for (int i = 0; i < first; ++i)
+        if (layer_slot_[order[i]] >= 0) keep[layer_slot_[order[i]]] = 1;
+    int scan = R;
+    for (int i = 0; i < first; ++i) {
+        const int l = order[i];
+        if (layer_slot_[l] >= 0) continue;
+        while (scan < N && keep[scan]) ++scan;
+        if (scan >= N) return SP_ERR_STATE;  // cannot happen: first <= ring
+        keep[scan] = 1;
+        if ((rc = load(l, scan)) != SP_OK) return rc;
     }
-    // Steady state (Sec. 3.3, Fig. 1): after each group of `group_` executed
-    // layers, their slots are refilled with the next layers of the pass.
-    int next = first;          // position in the pass of the next layer to fetch
-    int wrapped = 0;           // layers of the NEXT pass already fetched (wrap)
-    int gbegin = 0;
+    if (dir < 0)
+        for (int l = R - 1; l >= 0; --l)
+            if (layer_slot_[l] < 0 && (rc = load(l, l)) != SP_OK) return rc;
+    // Steady state (Sec. 3.3, Fig. 1): after each group of `group_` executed streamed
+    // layers, their slots are refilled with the next streamed layers of the pass.
+    int next = first;          // position in `order` of the next layer to fetch
+    int wrapped = 0;           // streamed layers of the NEXT pass already fetched (wrap)
+    int gbegin = 0;            // first position in `order` of the current group
+    int mi = 0;                // streamed layers computed so far
     for (int i = 0; i < L; ++i) {
-        const int l = at(i);
+        const int l = dir > 0 ? i : L - 1 - i;
         const int s = layer_slot_[l];
         if (s < 0) return SP_ERR_STATE;
         if ((rc = sink.compute(l, s, dir, fresh_[l] != 0)) != SP_OK) return rc;
         fresh_[l] = 0;
         slot_last_[s] = l;
-        if (i + 1 - gbegin == group_ || i == L - 1) {
-            for (int j = gbegin; j <= i; ++j) {
-                const int done = at(j);
+        if (l < R) continue;
+        ++mi;
+        if (mi - gbegin == group_ || mi == M) {
+            for (int j = gbegin; j < mi; ++j) {
+                const int done = order[j];
                 int t = -1;
-                while (next < L && layer_slot_[at(next)] >= 0) ++next;  // already on the device
-                if (next < L) {
-                    t = at(next++);
-                } else if (wrap && N < L) {
-                    while (wrapped < N && layer_slot_[at(wrapped)] >= 0) ++wrapped;
-                    if (wrapped < N) t = at(wrapped++);
+                while (next < M && layer_slot_[order[next]] >= 0) ++next;  // already on the device
+                if (next < M) {
+                    t = order[next++];
+                } else if (wrap && ring < M) {
+                    while (wrapped < ring && layer_slot_[order[wrapped]] >= 0) ++wrapped;
+                    if (wrapped < ring) t = order[wrapped++];
                 }
                 if (t < 0) break;
                 const int sl = layer_slot_[done];
@@ -201,7 +228,7 @@ int Scheduler::run_pass(int dir, bool wrap, SchedSink& sink) {
                 fresh_[t] = 1;
                 if ((rc = sink.copy(t, sl, done)) != SP_OK) return rc;
             }
-            gbegin = i + 1;
+            gbegin = mi;
         }
     }
     return SP_OK;
@@ -248,9 +275,9 @@ extern "C" size_t sp_workspace_bytes(const sp_stack_desc* desc, int training) {
     return ws.total;
 }
 
-extern "C" int sp_make_plan(const sp_stack_desc* desc, int k, int p, uint64_t budget_bytes, int training,
-                            sp_plan* out) {
-    return make_plan(desc, k, p, budget_bytes, training, out);
+extern "C" int sp_make_plan(const sp_stack_desc* desc, int k, int p, int pinned_layers, uint64_t budget_bytes,
+                            int training, sp_plan* out) {
+    return make_plan(desc, k, p, pinned_layers, budget_bytes, training, out);
 }
 
 namespace {
@@ -266,12 +293,13 @@ struct TraceSink : SchedSink {
 };
 }  // namespace
 
-extern "C" int sp_trace_schedule(int n_layers, int n_slots, int p_eff, int training, int wrap_prefetch, int passes,
-                                 sp_sched_op* ops, int cap) {
-    if (n_layers < 1 || n_slots < 1 || n_slots > n_layers || p_eff < 1 || passes < 1 || cap < 0 || (cap && !ops))
+extern "C" int sp_trace_schedule(int n_layers, int n_slots, int n_pinned, int p_eff, int training,
+                                 int wrap_prefetch, int passes, sp_sched_op* ops, int cap) {
+    if (n_layers < 1 || n_slots < 1 || n_slots > n_layers || n_pinned < 0 || n_pinned >= n_slots || p_eff < 1 ||
+        passes < 1 || cap < 0 || (cap && !ops))
         return SP_ERR_INVALID_ARG;
     Scheduler sch;
-    sch.reset(n_layers, n_slots, p_eff);
+    sch.reset(n_layers, n_slots, p_eff, n_pinned);
     TraceSink sink;
     sink.ops = ops;
     sink.cap = cap;
@@ -322,9 +350,10 @@ struct SimSink : SchedSink {
     double now() const { return std::max(std::max(t_copy, t_comp), t_grad); }
 };
 
-double simulate(int L, int n_slots, int p_eff, int training, int wrap, int calls, const sp_layer_cost& c) {
+double simulate(int L, int n_slots, int n_pinned, int p_eff, int training, int wrap, int calls,
+                const sp_layer_cost& c) {
     Scheduler sch;
-    sch.reset(L, n_slots, p_eff);
+    sch.reset(L, n_slots, p_eff, n_pinned);
     SimSink sink(c, L);
     double begin = 0, end = 0;
     for (int i = 0; i < calls; ++i) {
@@ -340,34 +369,40 @@ double simulate(int L, int n_slots, int p_eff, int training, int wrap, int calls
 }
 }  // namespace
 
-extern "C" double sp_simulate_call_ms(int n_layers, int n_slots, int p_eff, int training, int wrap_prefetch,
-                                      int calls, const sp_layer_cost* cost) {
-    if (n_layers < 1 || n_slots < 1 || n_slots > n_layers || p_eff < 1 || calls < 1 || !cost ||
+extern "C" double sp_simulate_call_ms(int n_layers, int n_slots, int n_pinned, int p_eff, int training,
+                                      int wrap_prefetch, int calls, const sp_layer_cost* cost) {
+    if (n_layers < 1 || n_slots < 1 || n_slots > n_layers || n_pinned < 0 || n_pinned >= n_slots || p_eff < 1 ||
+        calls < 1 || !cost ||
         !(cost->copy_ms >= 0) || !(cost->fwd_ms >= 0) || !(cost->bwd_ms >= 0) || !(cost->grad_ms >= 0))
         return -1.0;
-    return simulate(n_layers, n_slots, p_eff, training, wrap_prefetch, calls, *cost);
+    return simulate(n_layers, n_slots, n_pinned, p_eff, training, wrap_prefetch, calls, *cost);
 }
 
 extern "C" int sp_autotune(const sp_stack_desc* desc, uint64_t budget_bytes, int training, int wrap_prefetch,
-                           const sp_layer_cost* cost, double tolerance, int* k_out, int* p_out, double* ms_out) {
+                           const sp_layer_cost* cost, double tolerance, int* k_out, int* p_out, int* pinned_out,
+                           double* ms_out) {
     const char* why = nullptr;
-    if (!desc || !cost || !k_out || !p_out || validate_desc(desc, &why) != SP_OK || !(tolerance >= 0))
+    if (!desc || !cost || !k_out || !p_out || !pinned_out || validate_desc(desc, &why) != SP_OK || !(tolerance >= 0))
         return SP_ERR_INVALID_ARG;
     const int L = desc->n_layers;
-    struct Cand { int n, p; double ms; };
+    struct Cand { int n, r, p; double ms; };
     std::vector<Cand> cands;
     int rc_first = SP_OK;
-    for (int p = 1; p <= L; ++p) {
-        for (int k = 1; k + p <= L + 1; ++k) {
-            sp_plan pl;
-            int rc = make_plan(desc, k, p, budget_bytes, training, &pl);
-            if (rc != SP_OK) { if (rc_first == SP_OK) rc_first = rc; continue; }
-            bool seen = false;
-            for (const Cand& c : cands) seen = seen || (c.n == pl.n_slots && c.p == pl.p_eff);
-            if (seen) continue;
-            const double ms = sp_simulate_call_ms(L, pl.n_slots, pl.p_eff, training ? 1 : 0, wrap_prefetch, 3, cost);
-            if (ms < 0) return SP_ERR_INVALID_ARG;
-            cands.push_back(Cand{pl.n_slots, pl.p_eff, ms});
+    // windows without pinned layers, and the same windows with the rest of the budget pinned
+    for (int pin = 0; pin < 2; ++pin) {
+        for (int p = 1; p <= L; ++p) {
+            for (int k = 1; k + p <= L + 1; ++k) {
+                sp_plan pl;
+                int rc = make_plan(desc, k, p, pin ? SP_PIN_AUTO : 0, budget_bytes, training, &pl);
+                if (rc != SP_OK) { if (rc_first == SP_OK) rc_first = rc; continue; }
+                bool seen = false;
+                for (const Cand& c : cands) seen = seen || (c.n == pl.n_slots && c.r == pl.n_pinned && c.p == pl.p_eff);
+                if (seen) continue;
+                const double ms = sp_simulate_call_ms(L, pl.n_slots, pl.n_pinned, pl.p_eff, training ? 1 : 0,
+                                                      wrap_prefetch, 3, cost);
+                if (ms < 0) return SP_ERR_INVALID_ARG;
+                cands.push_back(Cand{pl.n_slots, pl.n_pinned, pl.p_eff, ms});
+            }
         }
     }
     if (cands.empty()) return rc_first != SP_OK ? rc_first : SP_ERR_BUDGET;
@@ -379,7 +414,8 @@ extern "C" int sp_autotune(const sp_stack_desc* desc, uint64_t budget_bytes, int
         if (!pick || c.n < pick->n || (c.n == pick->n && c.p < pick->p)) pick = &c;
     }
     *p_out = pick->p;
-    *k_out = std::max(pick->n - pick->p, 1);
+    *k_out = std::max(pick->n - pick->r - pick->p, 1);
+    *pinned_out = pick->r;
     if (ms_out) *ms_out = pick->ms;
     return SP_OK;
 }

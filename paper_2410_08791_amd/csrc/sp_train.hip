@@ -53,7 +53,9 @@ int decoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
     SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_G2), nullptr, m, T, dm, d.norm_eps));
     g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, gu, 2 * f, nullptr, 0, nullptr, T, 2 * f, dm, e->gemm_tile};
-    const bool kt = !e->kt_begin.empty();
+    // every 4th launch of the largest GEMM is bracketed: the two event records cost a gap
+    // on the stream, which on a compute-bound stack would show in the step time
+    const bool kt = !e->kt_begin.empty() && (e->kt_seen++ % 4 == 0);
     const size_t kti = kt ? e->kt_count % e->kt_begin.size() : 0;
     if (kt) {
         SP_HIP(e, hipEventRecord(e->kt_begin[kti], st));

@@ -106,6 +106,20 @@ def test_slot_count_policy():
     assert rc == sp.SP_OK and pl.n_slots == 32 and pl.fully_resident
     for k, p in [(0, 1), (1, 0), (-1, 1)]:
         assert sp.plan(d, k, p, budget)[0] == sp.SP_ERR_INVALID_ARG
+    # pinned layers take what the budget leaves after the window
+    got = {}
+    for (k, p, pin) in [(1, 1, sp.SP_PIN_AUTO), (2, 1, sp.SP_PIN_AUTO), (2, 2, sp.SP_PIN_AUTO), (1, 1, 1), (1, 1, 5),
+                        (2, 2, 3)]:
+        rc, pl = sp.plan(d, k, p, budget, pinned=pin)
+        assert rc == sp.SP_OK and pl.arena_bytes_used == ws + pl.n_slots * slot <= budget
+        got[(k, p, pin)] = (pl.n_slots, pl.n_pinned, pl.k_eff, pl.p_eff)
+    assert got == {(1, 1, -1): (4, 2, 1, 1), (2, 1, -1): (4, 1, 2, 1), (2, 2, -1): (4, 0, 2, 2),
+                   (1, 1, 1): (3, 1, 1, 1), (1, 1, 5): (4, 2, 1, 1), (2, 2, 3): (4, 0, 2, 2)}
+    rc, pl = sp.plan(d, 2, 2, ws + 40 * slot, pinned=sp.SP_PIN_AUTO)      # everything fits
+    assert rc == sp.SP_OK and pl.fully_resident and pl.n_slots == 32 and pl.n_pinned == 0
+    rc, pl = sp.plan(d, 2, 2, ws + 31 * slot, pinned=sp.SP_PIN_AUTO)      # one layer short of resident
+    assert rc == sp.SP_OK and not pl.fully_resident and (pl.n_slots, pl.n_pinned) == (31, 27)
+    assert sp.plan(d, 1, 1, budget, pinned=-2)[0] == sp.SP_ERR_INVALID_ARG
     # training workspace is larger (saved inputs, gradient slots)
     wt = synth.WORKLOADS["train1p3b"]
     dt = sp.make_desc(wt)

@@ -55,14 +55,16 @@ def test_model_equals_replay_of_the_traced_schedule(training):
     for _ in range(200):
         L = rnd.randint(1, 24)
         n = rnd.randint(1, L)
-        p = rnd.randint(1, max(n - 1, 1))
         wrap = (not training) and rnd.random() < 0.5
+        R = rnd.randint(0, n - 1) if n < L else 0
+        p = rnd.randint(1, max(n - R - 1, 1))
         calls = rnd.randint(1, 4)
         cost = (rnd.uniform(0, 5), rnd.uniform(0.1, 5), rnd.uniform(0.1, 9), rnd.uniform(0, 6))
-        ops = sp.trace_schedule(L, n, p, training=training, wrap=wrap, passes=calls * (2 if training else 1))
+        ops = sp.trace_schedule(L, n, p, training=training, wrap=wrap, passes=calls * (2 if training else 1),
+                                pinned=R)
         want = replay(ops, cost, training, calls)[-1]
-        got = sp.simulate_call_ms(L, n, p, cost, training=training, wrap=wrap, calls=calls)
-        assert got == pytest.approx(want, rel=1e-12, abs=1e-12), (L, n, p, wrap, calls, cost)
+        got = sp.simulate_call_ms(L, n, p, cost, training=training, wrap=wrap, calls=calls, pinned=R)
+        assert got == pytest.approx(want, rel=1e-12, abs=1e-12), (L, n, R, p, wrap, calls, cost)
 
 
 def test_closed_forms_forward():
@@ -79,6 +81,8 @@ def test_closed_forms_forward():
     assert sp.simulate_call_ms(L, L, 1, (7.0, 1.0, 0, 0), calls=2) == pytest.approx(L * 1.0)
     # one slot: copy and compute strictly alternate
     assert sp.simulate_call_ms(L, 1, 1, (2.0, 3.0, 0, 0), calls=1) == pytest.approx(L * 5.0)
+    # copy-bound with R pinned layers: only L - R blobs cross the link per call
+    assert sp.simulate_call_ms(L, 4, 1, (7.0, 1.0, 0, 0), wrap=True, calls=3, pinned=2) == pytest.approx((L - 2) * 7.0)
 
 
 def test_closed_forms_training():
@@ -97,7 +101,8 @@ def test_model_argument_errors():
     assert sp.simulate_call_ms(4, 2, 0, (1, 1, 1, 1)) < 0
     assert sp.simulate_call_ms(4, 2, 1, (-1, 1, 1, 1)) < 0
     assert sp.simulate_call_ms(4, 2, 1, (float("nan"), 1, 1, 1)) < 0
-    assert sp.sp_simulate_call_ms(4, 2, 1, 0, 0, 1, None) < 0
+    assert sp.sp_simulate_call_ms(4, 2, 0, 1, 0, 0, 1, None) < 0
+    assert sp.simulate_call_ms(4, 2, 1, (1, 1, 1, 1), pinned=2) < 0
 
 
 def _desc_and_sizes(name="llama7b"):
@@ -111,18 +116,22 @@ def _desc_and_sizes(name="llama7b"):
 def test_tuner_picks_the_smallest_window_that_saturates_the_link():
     w, desc, slot, ws = _desc_and_sizes()
     budget = ws + 6 * slot
-    # copy-bound (the paper's LLM case, Sec. 4.2): two slots already keep the link busy
-    k, p, ms = sp.autotune(desc, budget, (7.1, 1.1, 0, 0), wrap=True)
-    assert (k, p) == (1, 1) and ms == pytest.approx(w.n_layers * 7.1)
+    # copy-bound (the paper's LLM case, Sec. 4.2): two slots already keep the link busy, and
+    # the other four hold pinned layers, which saves 4 of 32 copies per call
+    k, p, r, ms = sp.autotune(desc, budget, (7.1, 1.1, 0, 0), wrap=True)
+    assert (k, p, r) == (1, 1, 4) and ms == pytest.approx((w.n_layers - 4) * 7.1)
     # whatever it returns is a plan that fits
-    rc, pl = sp.plan(desc, k, p, budget)
-    assert rc == sp.SP_OK and pl.arena_bytes_used <= budget
+    rc, pl = sp.plan(desc, k, p, budget, pinned=r)
+    assert rc == sp.SP_OK and pl.arena_bytes_used <= budget and pl.n_pinned == r
+    # compute-bound: pinning gains nothing, the smallest window wins
+    k, p, r, ms = sp.autotune(desc, budget, (1.0, 4.0, 0, 0), wrap=True)
+    assert (k, p, r) == (1, 1, 0) and ms == pytest.approx(w.n_layers * 4.0)
 
 
 def test_tuner_goes_resident_when_the_budget_allows():
     w, desc, slot, ws = _desc_and_sizes()
-    k, p, ms = sp.autotune(desc, ws + w.n_layers * slot, (7.1, 1.1, 0, 0), wrap=True)
-    assert k + p >= w.n_layers and ms == pytest.approx(w.n_layers * 1.1)
+    k, p, r, ms = sp.autotune(desc, ws + w.n_layers * slot, (7.1, 1.1, 0, 0), wrap=True)
+    assert k + p >= w.n_layers and r == 0 and ms == pytest.approx(w.n_layers * 1.1)
 
 
 def test_tuner_needs_depth_when_copies_are_slower_only_sometimes():
@@ -131,14 +140,16 @@ def test_tuner_needs_depth_when_copies_are_slower_only_sometimes():
     w, desc, slot, ws = _desc_and_sizes()
     budget = ws + 8 * slot
     cost = (3.0, 4.0, 0, 0)
-    k0, p0, best = sp.autotune(desc, budget, cost, wrap=False, tolerance=0.0)
+    k0, p0, r0, best = sp.autotune(desc, budget, cost, wrap=False, tolerance=0.0)
     for kk in range(1, 8):
         for pp in range(1, 8):
-            rc, pl = sp.plan(desc, kk, pp, budget)
-            if rc == sp.SP_OK:
-                assert sp.simulate_call_ms(w.n_layers, pl.n_slots, pl.p_eff, cost, calls=3) >= best - 1e-9
-    k1, p1, ms1 = sp.autotune(desc, budget, cost, wrap=False, tolerance=0.05)
-    assert k1 + p1 <= k0 + p0 and ms1 <= best * 1.05 + 1e-9
+            for pin in (0, sp.SP_PIN_AUTO):
+                rc, pl = sp.plan(desc, kk, pp, budget, pinned=pin)
+                if rc == sp.SP_OK:
+                    assert sp.simulate_call_ms(w.n_layers, pl.n_slots, pl.p_eff, cost, calls=3,
+                                               pinned=pl.n_pinned) >= best - 1e-9
+    k1, p1, r1, ms1 = sp.autotune(desc, budget, cost, wrap=False, tolerance=0.05)
+    assert k1 + p1 + r1 <= k0 + p0 + r0 and ms1 <= best * 1.05 + 1e-9
 
 
 def test_tuner_budget_and_argument_errors():
@@ -148,5 +159,5 @@ def test_tuner_budget_and_argument_errors():
     assert e.value.code == sp.SP_ERR_BUDGET
     with pytest.raises(sp.SuperpipeError):
         sp.autotune(desc, ws + 4 * slot, (1, 1, 0, 0), tolerance=-1.0)
-    k, p = C.c_int(), C.c_int()
-    assert sp.sp_autotune(None, 1 << 40, 0, 0, None, 0.0, C.byref(k), C.byref(p), None) == sp.SP_ERR_INVALID_ARG
+    k, p, r = C.c_int(), C.c_int(), C.c_int()
+    assert sp.sp_autotune(None, 1 << 40, 0, 0, None, 0.0, C.byref(k), C.byref(p), C.byref(r), None) == sp.SP_ERR_INVALID_ARG

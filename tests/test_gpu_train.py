@@ -28,9 +28,10 @@ class TrainCase:
         self.xd, self.td = dev_f32(self.x), dev_f32(self.t)
         self.gbytes = sp.sp_layer_grad_bytes(C.byref(self.desc))
 
-    def run(self, k, p, calls=1, want_y=True, target=None, budget_layers=None, flags=0):
+    def run(self, k, p, calls=1, want_y=True, target=None, budget_layers=None, flags=0, pinned=0):
         w = self.w
-        eng = sp.Engine(self.desc, self.blobs, k, p, flags=sp.SP_FLAG_TRAINING | flags, budget_layers=budget_layers)
+        eng = sp.Engine(self.desc, self.blobs, k, p, flags=sp.SP_FLAG_TRAINING | flags, budget_layers=budget_layers,
+                        pinned=pinned)
         gblobs = [torch.zeros(self.gbytes, dtype=torch.uint8, pin_memory=True) for _ in range(w.n_layers)]
         y = torch.zeros_like(self.xd) if want_y else None
         dx = torch.zeros_like(self.xd)
@@ -111,6 +112,15 @@ def test_training_repeated_calls_and_link_traffic():
     assert a["stats"].h2d_copies == 6 + 4
     assert b["stats"].h2d_copies == 10 + 2 * 8 and b["stats"].last_h2d_copies == 8
     check_against_oracle(b, c.oracle(), "train_l6 (grouped-query heads)")
+    # two pinned layers next to the 2-slot ring: they are copied once in the handle's life, the
+    # other four stream: 4 in the first forward, 2 in each backward and each later forward
+    d = c.run(1, 1, calls=3, pinned=2)
+    assert d["stats"].plan.n_pinned == 2 and d["stats"].plan.n_slots == 4
+    assert d["stats"].h2d_copies == 2 + 4 + 2 + 2 * 4 and d["stats"].last_h2d_copies == 4
+    assert d["loss"] == b["loss"] and np.array_equal(d["dx"], b["dx"])
+    for gl, bl in zip(d["grads"], b["grads"]):
+        for n in gl:
+            assert np.array_equal(gl[n], bl[n]), n
 
 
 def test_training_ragged_token_count_and_no_y():

@@ -98,6 +98,41 @@ def test_schedule_invariants_over_a_grid(training):
                         assert sorted(l for ps, l in copies if ps == 0) == list(range(L))
 
 
+@pytest.mark.parametrize("training", [False, True])
+def test_pinned_layers_are_copied_once_and_the_rest_stream(training):
+    """Layers 0..R-1 sit in slots 0..R-1 from their first use on and are never copied
+    again; the other layers use only the slots R..N-1; compute order and slot contents
+    stay right (same replay as above)."""
+    for L in range(2, 10):
+        for N in range(2, L):
+            for R in range(1, N):
+                for p in range(1, max(N - R, 2)):
+                    for wrap in ([False, True] if not training else [False]):
+                        passes = 4
+                        ops = sp.trace_schedule(L, N, p, training=training, wrap=wrap, passes=passes, pinned=R)
+                        computes = simulate(ops, L, N, seed=L * 1000 + N * 100 + R * 10 + p)
+                        for ps in range(passes):
+                            seq = [l for q, k, l in computes if q == ps]
+                            bwd = training and ps % 2 == 1
+                            assert seq == (list(range(L - 1, -1, -1)) if bwd else list(range(L)))
+                        copies = [(ps, l, s) for k, l, s, w, ps in ops if k == COPY]
+                        for l in range(R):
+                            assert [(ps, s) for ps, ll, s in copies if ll == l] == [(0, l)]
+                        assert all(s >= R for ps, l, s in copies if l >= R)
+                        assert all((s >= R) == (l >= R) for k, l, s, w, ps in ops if k != COPY)
+                        per_pass = [sum(1 for ps, l, s in copies if ps == q and l >= R) for q in range(passes)]
+                        ring = N - R
+                        if training:    # the turn re-uses what the ring still holds
+                            assert per_pass[0] == L - R and all(c == L - R - ring for c in per_pass[1:])
+                        elif wrap:      # steady state: every streamed layer once per call
+                            assert per_pass[0] == L - R + ring and all(c == L - R for c in per_pass[1:])
+
+
+def test_pinned_zero_is_the_plain_schedule():
+    for L, N, p in [(8, 4, 2), (12, 5, 3), (7, 7, 1)]:
+        assert sp.trace_schedule(L, N, p, passes=3, wrap=True) == sp.trace_schedule(L, N, p, passes=3, wrap=True, pinned=0)
+
+
 def test_refill_happens_in_groups_of_p():
     ops = sp.trace_schedule(12, 5, 3)
     kinds = "".join("L" if k == COPY else "X" for k, *_ in ops)
@@ -112,3 +147,6 @@ def test_trace_argument_errors():
     for args in [(0, 1, 1), (4, 0, 1), (4, 5, 1), (4, 2, 0)]:
         with pytest.raises(sp.SuperpipeError):
             sp.trace_schedule(*args)
+    for pinned in (-1, 2, 3):
+        with pytest.raises(sp.SuperpipeError):
+            sp.trace_schedule(4, 2, 1, pinned=pinned)
