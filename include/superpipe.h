@@ -236,6 +236,27 @@ int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* const* laye
  * buffer.  1 <= B <= max_batch, 1 <= S <= max_seq. */
 int sp_forward(sp_handle h, const float* x_dev, float* y_dev, int B, int S);
 
+/* Autoregressive generation (the paper quotes its LLM results in ms per token,
+ * Sec. 4.2, Table 1): every generated token is one pass over the streamed stack.
+ * Causal decoder stacks with head_dim 64 or 128 only (SP_ERR_STATE otherwise).
+ *
+ * kv_cache_dev: dev, caller-owned, sp_kv_cache_bytes(desc, B, max_len) bytes, 16-byte
+ * aligned, used with the same B and max_len in every call of one generation.  Per
+ * layer it holds the keys transposed, bf16 [B][Hkv][head_dim][max_len], then the
+ * values, bf16 [B][Hkv][max_len][head_dim].  max_len: multiple of 8, <= 32768.
+ *
+ * sp_prefill: y = stack(x) over S prompt positions per sequence (x_dev, y_dev: dev,
+ * fp32 [B, S, d_model], as sp_forward) and stores their keys and values at cache
+ * positions 0..S-1.
+ * sp_decode: one new position per sequence.  x_dev, y_dev: dev, fp32 [B, d_model];
+ * the token sits at position pos (the same for every sequence: pos positions are
+ * already cached), its keys/values are stored at pos and its query attends to
+ * positions 0..pos.  pos < max_len.
+ * Both return once the pass is enqueued, like sp_forward. */
+size_t sp_kv_cache_bytes(const sp_stack_desc* desc, int batch, int max_len);
+int sp_prefill(sp_handle h, const float* x_dev, float* y_dev, void* kv_cache_dev, int B, int S, int max_len);
+int sp_decode(sp_handle h, const float* x_dev, float* y_dev, void* kv_cache_dev, int B, int pos, int max_len);
+
 /* One training step's device work (Sec. 3.3): forward, loss =
  * mean((y - target)^2), backward with each layer's weights re-streamed in
  * reverse order, fp32 weight gradients written (overwrite, not accumulate) to

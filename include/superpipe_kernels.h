@@ -50,6 +50,21 @@ size_t spk_attention_scratch_elems(int B, int S, int Hkv, int hd);
 int spk_attention(void* stream, const uint16_t* qkv, uint16_t* vt_scratch, uint16_t* o, float* lse,
                   int B, int S, int Hq, int Hkv, int hd, int causal);
 
+/* ---- decode steps (one new token per sequence against a key/value cache) ---- */
+
+/* One layer's cache: kt bf16 [B][Hkv][hd][max_len] (keys, position contiguous) and
+ * v bf16 [B][Hkv][max_len][hd].  Copies the key and value parts of the fused
+ * activation qkv bf16 [B*S, (Hq+2Hkv)*hd] into positions pos0 .. pos0+S-1.
+ * pos0 + S <= max_len, hd <= 128. */
+int spk_kv_append(void* stream, const uint16_t* qkv, uint16_t* kt, uint16_t* v, int B, int S, int pos0,
+                  int Hq, int Hkv, int hd, int max_len);
+
+/* o bf16 [B, Hq*hd]: row b = softmax(q_b K^T / sqrt(hd)) V over the first n cached
+ * positions of sequence b, q_b = the query part of row b of qkv bf16 [B, (Hq+2Hkv)*hd].
+ * hd 64 or 128; max_len even, <= 32768; 1 <= n <= max_len. */
+int spk_decode_attention(void* stream, const uint16_t* qkv, const uint16_t* kt, const uint16_t* v, uint16_t* o,
+                         int B, int n, int max_len, int Hq, int Hkv, int hd);
+
 /* ---- backward steps (training, Sec. 3.3) ---- */
 
 /* loss[0] = mean((y-t)^2) over n fp32 elements; dy fp32 [n] = 2 (y-t)/n; dy_bf16 the same rounded.

@@ -97,6 +97,11 @@ _sig = {
     "sp_trace_schedule": (C.c_int, [C.c_int] * 7 + [_P(sp_sched_op), C.c_int]),
     "sp_create": (C.c_int, [_P(C.c_void_p), _P(sp_stack_desc), _P(C.c_void_p), _P(sp_config)]),
     "sp_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
+    "sp_kv_cache_bytes": (C.c_size_t, [_P(sp_stack_desc), C.c_int, C.c_int]),
+    "sp_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int]),
+    "sp_decode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int]),
+    "spk_kv_append": (C.c_int, [C.c_void_p] * 4 + [C.c_int] * 7),
+    "spk_decode_attention": (C.c_int, [C.c_void_p] * 5 + [C.c_int] * 6),
     "sp_forward_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       _P(C.c_void_p), C.c_int, C.c_int]),
     "sp_get_stats": (C.c_int, [C.c_void_p, _P(sp_stats)]),
@@ -277,6 +282,16 @@ class Engine:
         torch's current stream has enqueued so far, e.g. the producer of x)."""
         self.compute.wait_stream(self.torch.cuda.current_stream(self.device))
         self._check(sp_forward(self.handle, x.data_ptr(), y.data_ptr(), B, S))
+
+    def prefill(self, x, y, kv_cache, B, S, max_len):
+        """x, y: fp32 cuda [B,S,d]; kv_cache: cuda uint8 tensor of sp_kv_cache_bytes."""
+        self.compute.wait_stream(self.torch.cuda.current_stream(self.device))
+        self._check(sp_prefill(self.handle, x.data_ptr(), y.data_ptr(), kv_cache.data_ptr(), B, S, max_len))
+
+    def decode(self, x, y, kv_cache, B, pos, max_len):
+        """x, y: fp32 cuda [B,d]: one new token per sequence at position pos."""
+        self.compute.wait_stream(self.torch.cuda.current_stream(self.device))
+        self._check(sp_decode(self.handle, x.data_ptr(), y.data_ptr(), kv_cache.data_ptr(), B, pos, max_len))
 
     def forward_backward(self, x, target, y, loss, dx, grad_blobs, B, S):
         ptrs = (C.c_void_p * len(grad_blobs))(*[g.data_ptr() for g in grad_blobs])

@@ -61,7 +61,14 @@ struct sp_engine {
 };
 
 // One layer forward, residual stream h (fp32 [B*S, d]) updated in place.
-int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int S);
+// Key/value cache of the layer being run (decode): nullptr fields = plain forward.
+struct KvLayer {
+    bf16_t* kt = nullptr;   // [B][Hkv][hd][max_len]
+    bf16_t* v = nullptr;    // [B][Hkv][max_len][hd]
+    int max_len = 0;
+    int pos = -1;           // >= 0: one new token per sequence at this position (S == 1)
+};
+int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int S, const KvLayer* kv = nullptr);
 // Training forward of layer l: reads its saved input, writes the next layer's.
 int sp_layer_forward_train(sp_engine* e, int layer, const unsigned char* w, int B, int S);
 // Recompute + backward of layer l; leaves dL/d(input) in the stream-gradient buffer

@@ -90,6 +90,9 @@ struct HipSink : SchedSink {
     float* hbuf;        // forward: the residual stream (fp32 [T, d]) being updated in place
     int B, S;
     bool training_fwd = false;
+    unsigned char* kv_cache = nullptr;   // decode: the caller's cache, one layer after another
+    size_t kv_layer_bytes = 0;
+    int kv_max_len = 0, kv_pos = -1;
     explicit HipSink(sp_engine* eng) : e(eng), hbuf(nullptr), B(0), S(0) {}
 
     int copy(int layer, int slot, int wait_layer) override {
@@ -141,7 +144,14 @@ struct HipSink : SchedSink {
             dep = e->layer_loaded_idx[layer];
         }
         const unsigned char* w = e->slots + (size_t)slot * e->plan.slot_bytes;
-        if (dir > 0)
+        if (dir > 0 && kv_cache) {
+            KvLayer kv;
+            kv.kt = reinterpret_cast<bf16_t*>(kv_cache + (size_t)layer * kv_layer_bytes);
+            kv.v = reinterpret_cast<bf16_t*>(kv_cache + (size_t)layer * kv_layer_bytes + kv_layer_bytes / 2);
+            kv.max_len = kv_max_len;
+            kv.pos = kv_pos;
+            rc = sp_layer_forward(e, w, hbuf, B, S, &kv);
+        } else if (dir > 0)
             rc = training_fwd ? sp_layer_forward_train(e, layer, w, B, S) : sp_layer_forward(e, w, hbuf, B, S);
         else
             rc = sp_layer_backward(e, layer, w, B, S);
@@ -159,7 +169,7 @@ struct HipSink : SchedSink {
 };
 
 // ---- one decoder / encoder layer, forward, residual stream updated in place -------
-int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int S) {
+int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int S, const KvLayer* kv) {
     const sp_stack_desc& d = e->desc;
     const Layout& L = e->lay;
     hipStream_t st = e->compute;
@@ -182,9 +192,18 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
     g = GemmArgs{a, dm, OP_KMAJOR, W(dec ? SP_T_WQKV : SP_T_E_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0,
                  dec ? nullptr : W(SP_T_BQKV), T, nqkv, dm, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
-    // b3: attention
-    SP_HIP(e, spk_launch_transpose_v(st, qkv, vt, as));
-    SP_HIP(e, spk_launch_attention(st, qkv, vt, o, nullptr, as));
+    // b3: attention.  With a cache the new keys/values are stored first; a decode step then
+    // attends its single query per sequence to the cached positions 0..pos.
+    if (kv)
+        SP_HIP(e, spk_launch_kv_append(st, qkv, nqkv, kv->kt, kv->v, B, S, kv->pos >= 0 ? kv->pos : 0, d.n_q_heads,
+                                       d.n_kv_heads, d.head_dim, kv->max_len));
+    if (kv && kv->pos >= 0) {
+        SP_HIP(e, spk_launch_decode_attention(st, qkv, nqkv, kv->kt, kv->v, o, nq, B, kv->pos + 1, kv->max_len,
+                                              d.n_q_heads, d.n_kv_heads, d.head_dim));
+    } else {
+        SP_HIP(e, spk_launch_transpose_v(st, qkv, vt, as));
+        SP_HIP(e, spk_launch_attention(st, qkv, vt, o, nullptr, as));
+    }
     // b4: h += o Wo^T (+ b)
     g = GemmArgs{o, nq, OP_KMAJOR, W(dec ? SP_T_WO : SP_T_E_WO), nq, OP_KMAJOR, h, dm, h, dm,
                  dec ? nullptr : W(SP_T_BO), T, dm, nq, e->gemm_tile};
@@ -378,6 +397,64 @@ extern "C" int sp_forward(sp_handle e, const float* x_dev, float* y_dev, int B, 
     if (rc != SP_OK) return rc;
     e->calls++;
     return SP_OK;
+}
+
+// bytes of one layer's cache: keys and values, bf16
+static size_t kv_layer_bytes(const sp_stack_desc& d, int batch, int max_len) {
+    return (size_t)2 * batch * d.n_kv_heads * d.head_dim * max_len * sizeof(bf16_t);
+}
+
+extern "C" size_t sp_kv_cache_bytes(const sp_stack_desc* desc, int batch, int max_len) {
+    const char* why = nullptr;
+    if (!desc || validate_desc(desc, &why) != SP_OK || batch < 1 || max_len < 2 || (max_len & 7) ||
+        max_len > kDecodeMaxLen)
+        return 0;
+    return (size_t)desc->n_layers * kv_layer_bytes(*desc, batch, max_len);
+}
+
+static int cached_forward(sp_engine* e, const float* x_dev, float* y_dev, void* kv_cache_dev, int B, int S, int pos,
+                          int max_len) {
+    const sp_stack_desc& d = e->desc;
+    if (d.arch != SP_DECODER_SWIGLU_RMS || !d.causal || (d.head_dim != 64 && d.head_dim != 128))
+        return fail(e, SP_ERR_STATE, "the key/value cache needs a causal decoder stack with head_dim 64 or 128");
+    if (e->flags & SP_FLAG_TRAINING) return fail(e, SP_ERR_STATE, "handle was created for training");
+    if (!x_dev || !y_dev || !kv_cache_dev) return fail(e, SP_ERR_INVALID_ARG, "NULL argument");
+    if (((uintptr_t)x_dev | (uintptr_t)y_dev | (uintptr_t)kv_cache_dev) & 15)
+        return fail(e, SP_ERR_INVALID_ARG, "x_dev / y_dev / kv_cache_dev must be 16-byte aligned");
+    if (max_len < 2 || (max_len & 7) || max_len > kDecodeMaxLen)
+        return fail(e, SP_ERR_SHAPE, "max_len=%d must be a multiple of 8 in 8..%d", max_len, kDecodeMaxLen);
+    const int first = pos >= 0 ? pos : 0;
+    if (first + S > max_len) return fail(e, SP_ERR_SHAPE, "positions %d..%d exceed max_len=%d", first, first + S - 1, max_len);
+    int rc;
+    if ((rc = begin_call(e)) != SP_OK) return rc;
+    SP_HIP(e, spk_launch_copy_f32(e->compute, x_dev, y_dev, (size_t)B * S * d.d_model));
+    HipSink sink(e);
+    sink.hbuf = y_dev;
+    sink.B = B;
+    sink.S = S;
+    sink.kv_cache = static_cast<unsigned char*>(kv_cache_dev);
+    sink.kv_layer_bytes = kv_layer_bytes(d, B, max_len);
+    sink.kv_max_len = max_len;
+    sink.kv_pos = pos;
+    rc = e->sched.run_pass(+1, (e->flags & SP_FLAG_WRAP_PREFETCH) != 0, sink);
+    if (rc != SP_OK) return rc;
+    e->calls++;
+    return SP_OK;
+}
+
+extern "C" int sp_prefill(sp_handle e, const float* x_dev, float* y_dev, void* kv_cache_dev, int B, int S,
+                          int max_len) {
+    int rc = check_call(e, B, S);
+    if (rc != SP_OK) return rc;
+    return cached_forward(e, x_dev, y_dev, kv_cache_dev, B, S, -1, max_len);
+}
+
+extern "C" int sp_decode(sp_handle e, const float* x_dev, float* y_dev, void* kv_cache_dev, int B, int pos,
+                         int max_len) {
+    int rc = check_call(e, B, 1);
+    if (rc != SP_OK) return rc;
+    if (pos < 0) return fail(e, SP_ERR_SHAPE, "pos=%d is negative", pos);
+    return cached_forward(e, x_dev, y_dev, kv_cache_dev, B, 1, pos, max_len);
 }
 
 extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float* target_dev, float* y_dev,

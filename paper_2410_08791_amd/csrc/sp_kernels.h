@@ -60,6 +60,17 @@ hipError_t spk_launch_transpose_v(hipStream_t st, const bf16_t* qkv, bf16_t* vt,
 hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, const bf16_t* vt, bf16_t* o,
                                 float* lse, const AttnShape& a);
 
+// ---- decode (key/value cache) ---------------------------------------------------------
+// One layer's cache: kt bf16 [B][Hkv][hd][max_len], v bf16 [B][Hkv][max_len][hd].
+// Copies the k and v parts of qkv [B*S, ld_qkv] into positions pos0 .. pos0+S-1.
+hipError_t spk_launch_kv_append(hipStream_t st, const bf16_t* qkv, int ld_qkv, bf16_t* kt, bf16_t* v, int B, int S,
+                                int pos0, int Hq, int Hkv, int hd, int max_len);
+// o bf16 [B, ld_o] = softmax(q K^T / sqrt(hd)) V for one query per sequence (row b of qkv)
+// over the first n cached positions.  hd 64 or 128, max_len even and <= kDecodeMaxLen.
+hipError_t spk_launch_decode_attention(hipStream_t st, const bf16_t* qkv, int ld_qkv, const bf16_t* kt,
+                                       const bf16_t* v, bf16_t* o, int ld_o, int B, int n, int max_len, int Hq,
+                                       int Hkv, int hd);
+
 hipError_t spk_launch_copy_f32(hipStream_t st, const float* src, float* dst, size_t n);
 hipError_t spk_launch_fill_u32(hipStream_t st, uint32_t* dst, uint32_t v, size_t n);
 

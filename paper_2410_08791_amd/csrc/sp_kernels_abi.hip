@@ -42,6 +42,20 @@ extern "C" int spk_attention(void* stream, const uint16_t* qkv, uint16_t* vt, ui
     return st(spk_launch_attention((hipStream_t)stream, qkv, vt, o, lse, a));
 }
 
+extern "C" int spk_kv_append(void* stream, const uint16_t* qkv, uint16_t* kt, uint16_t* v, int B, int S, int pos0,
+                             int Hq, int Hkv, int hd, int max_len) {
+    if (!qkv || !kt || !v || Hq < 1 || Hkv < 1 || hd < 1) return SP_ERR_INVALID_ARG;
+    return st(spk_launch_kv_append((hipStream_t)stream, qkv, (Hq + 2 * Hkv) * hd, kt, v, B, S, pos0, Hq, Hkv, hd,
+                                   max_len));
+}
+
+extern "C" int spk_decode_attention(void* stream, const uint16_t* qkv, const uint16_t* kt, const uint16_t* v,
+                                    uint16_t* o, int B, int n, int max_len, int Hq, int Hkv, int hd) {
+    if (!qkv || !kt || !v || !o || Hq < 1 || Hkv < 1) return SP_ERR_INVALID_ARG;
+    return st(spk_launch_decode_attention((hipStream_t)stream, qkv, (Hq + 2 * Hkv) * hd, kt, v, o, Hq * hd, B, n,
+                                          max_len, Hq, Hkv, hd));
+}
+
 extern "C" int spk_mse(void* stream, const float* y, const float* t, float* dy, uint16_t* dyb, float* scratch,
                        float* loss, size_t n) {
     if (!y || !t || !dy || !dyb || !scratch || !loss || n == 0) return SP_ERR_INVALID_ARG;
