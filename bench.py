@@ -122,6 +122,13 @@ def main():
     xd = torch.from_numpy(x).to("cuda:0")
     yd = torch.empty_like(xd)
     B, S, T = w.batch, w.seq, w.tokens
+    decoding = w.gen > 0
+    if decoding:
+        T = B                                        # tokens per step: one per sequence
+        max_len = (S + args.warmup + max(args.steps, 3) + 8 + 7) // 8 * 8
+        cache = torch.empty(sp.sp_kv_cache_bytes(C.byref(desc), B, max_len), dtype=torch.uint8, device="cuda:0")
+        x1 = torch.from_numpy(np.ascontiguousarray(x[:, 0])).to("cuda:0")     # the token fed at every step
+        y1 = torch.empty_like(x1)
     if training:
         tgt = torch.from_numpy(synth.make_input(w, "target")).to("cuda:0")
         gbytes = sp.sp_layer_grad_bytes(C.byref(desc))
@@ -138,11 +145,19 @@ def main():
         eng = sp.Engine(desc, blobs, kk, pp, budget_layers=budget_layers, budget_bytes=budget_bytes, flags=flags,
                         pinned=pinned)
 
+        pos = [S]
+
         def step():
             if training:
                 eng.forward_backward(xd, tgt, None, loss, dxd, gblobs, B, S)
+            elif decoding:
+                eng.decode(x1, y1, cache, B, pos[0], max_len)
+                pos[0] += 1
             else:
                 eng.forward(xd, yd, B, S)
+
+        if decoding:
+            eng.prefill(xd, yd, cache, B, S, max_len)        # the prompt; not part of the timed steps
 
         for _ in range(warmup):
             step()
@@ -160,7 +175,7 @@ def main():
         wall = time.perf_counter() - tw
         ms = e0.elapsed_time(e1)
         st = eng.stats()
-        y = (dxd if training else yd).cpu().numpy().copy()
+        y = (dxd if training else y1 if decoding else yd).cpu().numpy().copy()
         eng.destroy()
         return dict(ms_per_step=ms / steps, wall_ms_per_step=wall * 1e3 / steps, stats=st, y=y,
                     budget=eng.budget_bytes)
@@ -218,6 +233,16 @@ def main():
                 "flops_per_launch": gemm_flops, "avg_launch_ms": round(gemm_ms, 4),
                 "launches_timed": int(kst.big_gemm_launches), "shape_mnk": [gm, gn, gk]}
 
+    if decoding:
+        # with one row per sequence the same kernel streams the weight matrix once and does
+        # almost no arithmetic: bound by HBM, bytes = weights + the few activation rows
+        gbytes_launch = 2.0 * (gn * gk + gm * gk + gm * gn / 2)
+        achieved_gbs = gbytes_launch / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
+        roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved_gbs, 1), "peak": 8000.0,
+                    "unit": "GB/s", "frac": round(achieved_gbs / 8000.0, 4), "traffic": None,
+                    "bytes_per_launch": gbytes_launch, "avg_launch_ms": round(gemm_ms, 4),
+                    "launches_timed": int(kst.big_gemm_launches), "shape_mnk": [gm, gn, gk]}
+
     tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}_gate_up_gemm.json")
     if os.path.exists(tpath) and not training:
         # HBM-side bytes per launch of this kernel from two rocprofv3 --pmc runs of this same
@@ -253,13 +278,16 @@ def main():
     # window sweep at the same budget (+ the naive comparator); bits must not change
     if not args.no_sweep:
         sweep = []
-        base = main_run["y"]
+        # decode runs are compared at the same position: against the sweep's first entry
+        base = None if decoding else main_run["y"]
         A = sp.SP_PIN_AUTO
         grid = ([(1, 1, 0), (1, 2, 0), (2, 1, 0), (2, 2, 0), (4, 1, 0), (4, 2, 0), (1, 1, A), (1, 2, A), (2, 1, A)]
                 if w.name == "llama7b" else sorted({(1, 1, 0), (w.k, w.p, 0), (1, 1, A), (k, p, pinned)}))
         for kk, pp, rr in grid:
             r = run(kk, pp, flags & ~sp.SP_FLAG_TIMING, 3, 1, pinned=rr)
             m = max(r["ms_per_step"], r["wall_ms_per_step"])
+            if base is None:
+                base = r["y"]
             sweep.append({"k": kk, "p": pp, "pinned": int(r["stats"].plan.n_pinned),
                           "slots": int(r["stats"].plan.n_slots),
                           "tokens_per_s": round(T / (m * 1e-3), 1),
@@ -272,7 +300,10 @@ def main():
         log("[bench] sweep: " + json.dumps(sweep))
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if decoding:
+        extra["ms_per_token"] = round(ms, 3)             # per sequence: one step yields one token each
+        extra["prompt_positions"] = S
+    if not args.no_cpu_baseline and not decoding:
         from threadpoolctl import threadpool_info
         from oracle import stack_oracle as O
         n = min(args.cpu_layers, w.n_layers)
@@ -314,7 +345,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n_layers} layers d={w.d_model} heads={w.n_q_heads}/{w.n_kv_heads}"
                                f"x{w.head_dim} ffn={w.d_ffn} causal={w.causal} batch {B} x seq {S}, "
-                               + ("forward+backward (MSE)" if training else "forward"),
+                               + ("forward+backward (MSE)" if training else
+                                  f"prompt, then decode of one token per sequence per step" if decoding else "forward"),
                    "k": k, "p": p, "pinned_layers": int(st.plan.n_pinned), "n_slots": int(st.plan.n_slots),
                    "budget_layers": budget_layers,
                    "wrap_prefetch": wrap, "keep_activations": bool(training and args.keep_activations),

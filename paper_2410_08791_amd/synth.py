@@ -42,6 +42,7 @@ class Workload:
     p: int = 1                 # prefetch depth
     budget_layers: int = 0     # HBM weight budget in layer slots (0 = k + p)
     training: bool = False
+    gen: int = 0               # > 0: decode workload, `seq` prompt positions then this many new tokens
     norm_eps: float = 1e-5
     seed: int = 0
 
@@ -64,6 +65,9 @@ WORKLOADS = {
     # LLaMA-70B shape with grouped-query heads
     "llama70b": Workload("llama70b", DECODER, 80, 8192, 64, 8, 128, 28672, True, 4, 1024,
                          k=2, p=2),
+    # the same stack generating tokens: 8 sequences, 512-position prompt, one token per step
+    "llama7b_decode": Workload("llama7b_decode", DECODER, 32, 4096, 32, 32, 128, 11008, True, 8, 512,
+                               k=2, p=2, budget_layers=4, gen=32),
     # 1.3B-shaped training step
     "train1p3b": Workload("train1p3b", DECODER, 24, 2048, 16, 16, 128, 5504, True, 8, 1024,
                           k=2, p=1, training=True),
