@@ -74,6 +74,9 @@ def main():
     ap.add_argument("--no-wrap", action="store_true", help="do not prefetch the next call's first layers")
     ap.add_argument("--keep-activations", action="store_true",
                     help="training: keep every layer's activations instead of recomputing them")
+    ap.add_argument("--frozen", type=int, default=0,
+                    help="training: this many lowest layers get no weight gradients; no input gradient is "
+                         "asked for, so the backward stops above them")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true", help="experiment: no event brackets in the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -143,13 +146,13 @@ def main():
         if training:
             flags |= sp.SP_FLAG_TRAINING | (sp.SP_FLAG_KEEP_ACTIVATIONS if args.keep_activations else 0)
         eng = sp.Engine(desc, blobs, kk, pp, budget_layers=budget_layers, budget_bytes=budget_bytes, flags=flags,
-                        pinned=pinned)
+                        pinned=pinned, frozen=args.frozen if training else 0)
 
         pos = [S]
 
         def step():
             if training:
-                eng.forward_backward(xd, tgt, None, loss, dxd, gblobs, B, S)
+                eng.forward_backward(xd, tgt, None, loss, None if args.frozen else dxd, gblobs, B, S)
             elif decoding:
                 eng.decode(x1, y1, cache, B, pos[0], max_len)
                 pos[0] += 1
@@ -175,7 +178,7 @@ def main():
         wall = time.perf_counter() - tw
         ms = e0.elapsed_time(e1)
         st = eng.stats()
-        y = (dxd if training else y1 if decoding else yd).cpu().numpy().copy()
+        y = ((loss if args.frozen else dxd) if training else y1 if decoding else yd).cpu().numpy().copy()
         eng.destroy()
         return dict(ms_per_step=ms / steps, wall_ms_per_step=wall * 1e3 / steps, stats=st, y=y,
                     budget=eng.budget_bytes)
@@ -350,6 +353,7 @@ def main():
                    "k": k, "p": p, "pinned_layers": int(st.plan.n_pinned), "n_slots": int(st.plan.n_slots),
                    "budget_layers": budget_layers,
                    "wrap_prefetch": wrap, "keep_activations": bool(training and args.keep_activations),
+                   "frozen_layers": args.frozen if training else 0,
                    "layer_blob_bytes": int(blob_bytes),
                    "distinct_blobs": nb, "seed": w.seed},
         "roofline": roofline, "cpu_baseline": cpu, **extra,

@@ -104,6 +104,11 @@ typedef struct {
     void* h2d_stream;           /* hipStream_t, must differ from compute_stream  */
     void* d2h_stream;           /* hipStream_t, needed only with SP_FLAG_TRAINING */
     uint32_t flags;
+    int32_t frozen_layers;      /* training: layers 0..n-1 receive no weight gradients (the paper's
+                                   "half of layers frozen" rows, Table 2).  Their gradient blobs
+                                   are not written; when sp_forward_backward is called with
+                                   dx_dev == NULL the backward pass stops above them, so they
+                                   are neither re-streamed nor recomputed.                     */
     int32_t pinned_layers;      /* layers 0..n-1 that stay in HBM for the handle's life and are
                                    never re-copied; SP_PIN_AUTO = as many as the budget leaves
                                    after the k + p window; 0 = none (every layer streams)      */
@@ -184,7 +189,8 @@ int sp_make_plan(const sp_stack_desc* desc, int k, int p, int pinned_layers, uin
  * would enqueue (dir +1 = forward pass over layers 0..L-1, the pattern
  * forward,backward repeats when training != 0).  Returns the number of ops
  * (may exceed cap; only cap are written) or a negative sp_status.  n_slots
- * counts every slot, the n_pinned < n_slots pinned ones included. */
+ * counts every slot, the n_pinned < n_slots pinned ones included.  training = 1 + F
+ * traces backward passes that stop above F frozen layers (layers F..L-1 only). */
 typedef struct {
     int32_t kind;    /* 0 = COPY layer->slot (copy stream), 1 = COMPUTE layer (compute stream),
                         2 = BACKWARD layer (compute stream) */

@@ -50,7 +50,7 @@ class sp_config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("resident_window_k", C.c_int32), ("prefetch_depth_p", C.c_int32),
                 ("gpu_budget_bytes", C.c_uint64), ("device_arena", C.c_void_p), ("compute_stream", C.c_void_p),
                 ("h2d_stream", C.c_void_p), ("d2h_stream", C.c_void_p), ("flags", C.c_uint32),
-                ("pinned_layers", C.c_int32)]
+                ("frozen_layers", C.c_int32), ("pinned_layers", C.c_int32)]
 
 
 class sp_plan(C.Structure):
@@ -169,7 +169,8 @@ def plan(desc, k, p, budget, training=False, pinned=0):
     return rc, pl
 
 
-def trace_schedule(n_layers, n_slots, p_eff, training=False, wrap=False, passes=1, pinned=0):
+def trace_schedule(n_layers, n_slots, p_eff, training=False, wrap=False, passes=1, pinned=0, frozen=0):
+    training = int(bool(training)) + (frozen if training else 0)
     n = sp_trace_schedule(n_layers, n_slots, pinned, p_eff, int(training), int(wrap), passes, None, 0)
     if n < 0:
         raise SuperpipeError(n, "sp_trace_schedule")
@@ -243,7 +244,7 @@ class Engine:
     """Owns an sp_handle plus the torch-allocated arena and streams it runs on."""
 
     def __init__(self, desc, blobs, k, p, budget_bytes=None, budget_layers=None, flags=0, device="cuda:0",
-                 pinned=0):
+                 pinned=0, frozen=0):
         import torch
         self.torch = torch
         self.desc = desc
@@ -267,7 +268,7 @@ class Engine:
         ptrs = (C.c_void_p * len(blobs))(*[b.data_ptr() for b in blobs])
         cfg = sp_config(C.sizeof(sp_config), k, p, self.budget_bytes, self.arena.data_ptr(),
                         self.compute.cuda_stream, self.h2d.cuda_stream,
-                        self.d2h.cuda_stream if training else None, flags, pinned)
+                        self.d2h.cuda_stream if training else None, flags, frozen, pinned)
         self.handle = C.c_void_p()
         rc = sp_create(C.byref(self.handle), C.byref(desc), ptrs, C.byref(cfg))
         if rc != SP_OK:

@@ -37,6 +37,7 @@ struct sp_engine {
     uint64_t thr_head = 0, thr_tail = 0, thr_packets = 0;
     hipEvent_t pass_end_c = nullptr, pass_end_d = nullptr;   // end of the latest training pass on compute / d2h
     bool pass_pending = false;
+    int frozen = 0;                             // training: layers below this get no weight gradients
     hipEvent_t grad_ready[sp::kGradSlots] = {}, gslot_free[sp::kGradSlots] = {};
     char gslot_used[sp::kGradSlots] = {};
     int gslot_next = 0;

@@ -267,6 +267,8 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     if (training && desc->arch != SP_DECODER_SWIGLU_RMS)
         return fail(nullptr, SP_ERR_INVALID_ARG, "training is implemented for decoder stacks only");
     if (desc->n_layers > 4096) return fail(nullptr, SP_ERR_INVALID_ARG, "n_layers > 4096");
+    if (cfg->frozen_layers < 0 || cfg->frozen_layers > desc->n_layers || (cfg->frozen_layers && !training))
+        return fail(nullptr, SP_ERR_INVALID_ARG, "frozen_layers must be in 0..n_layers and needs SP_FLAG_TRAINING");
     sp_plan plan;
     int rc = make_plan(desc, cfg->resident_window_k, cfg->prefetch_depth_p, cfg->pinned_layers, cfg->gpu_budget_bytes, mode,
                        &plan);
@@ -289,6 +291,7 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     if (!e) return fail(nullptr, SP_ERR_INVALID_ARG, "out of host memory");
     e->desc = *desc;
     e->flags = cfg->flags;
+    e->frozen = training ? cfg->frozen_layers : 0;
     e->plan = plan;
     make_layout(desc, &e->lay);
     make_workspace(desc, e->lay, mode, &e->ws);
@@ -487,7 +490,8 @@ extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float*
     if ((rc = e->sched.run_pass(+1, false, sink)) != SP_OK) return rc;
     if ((rc = sp_train_loss(e, target_dev, loss_dev, B, S)) != SP_OK) return rc;
     sink.training_fwd = false;
-    if ((rc = e->sched.run_pass(-1, false, sink)) != SP_OK) return rc;
+    // without dx nothing below the frozen layers needs a gradient: the backward stops above them
+    if ((rc = e->sched.run_pass(-1, false, sink, dx_dev ? 0 : e->frozen)) != SP_OK) return rc;
     if ((rc = sp_train_end(e, dx_dev, B, S)) != SP_OK) return rc;
     SP_HIP(e, hipEventRecord(e->pass_end_c, e->compute));
     SP_HIP(e, hipEventRecord(e->pass_end_d, e->d2h));

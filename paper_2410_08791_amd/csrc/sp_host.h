@@ -77,7 +77,8 @@ public:
     void reset(int n_layers, int n_slots, int group, int n_pinned = 0);
     // One pass over all layers: dir +1 = 0..L-1, dir -1 = L-1..0.  With wrap
     // (forward-only use) slots freed at the tail are refilled with the first layers.
-    int run_pass(int dir, bool wrap, SchedSink& sink);
+    // lo: the pass covers layers lo..L-1 only (a backward pass that stops above frozen layers).
+    int run_pass(int dir, bool wrap, SchedSink& sink, int lo = 0);
     int n_slots() const { return n_slots_; }
     int n_pinned() const { return n_pinned_; }
     const std::vector<int>& layer_slot() const { return layer_slot_; }

@@ -153,8 +153,9 @@ void Scheduler::reset(int n_layers, int n_slots, int group, int n_pinned) {
     fresh_.assign(n_layers, 0);
 }
 
-int Scheduler::run_pass(int dir, bool wrap, SchedSink& sink) {
+int Scheduler::run_pass(int dir, bool wrap, SchedSink& sink, int lo) {
     const int L = n_layers_, N = n_slots_, R = n_pinned_;
+    if (lo < 0 || lo > L) return SP_ERR_INVALID_ARG;
     int rc;
     // Layers 0..R-1 are pinned: slot l holds layer l from its first use on and is never
     // refilled.  The other layers stream through the ring of slots R..N-1.
@@ -162,7 +163,7 @@ int Scheduler::run_pass(int dir, bool wrap, SchedSink& sink) {
     order.reserve(L - R);
     for (int i = 0; i < L; ++i) {
         const int l = dir > 0 ? i : L - 1 - i;
-        if (l >= R) order.push_back(l);
+        if (l >= R && l >= lo) order.push_back(l);
     }
     const int M = (int)order.size(), ring = N - R;
     auto load = [&](int l, int s) {
@@ -173,7 +174,7 @@ int Scheduler::run_pass(int dir, bool wrap, SchedSink& sink) {
         return sink.copy(l, s, slot_last_[s]);
     };
     if (dir > 0)
-        for (int l = 0; l < R; ++l)
+        for (int l = lo; l < R; ++l)
             if (layer_slot_[l] < 0 && (rc = load(l, l)) != SP_OK) return rc;
     // Initial load (Sec. 3.3: k partitions are on the device before the first compute):
     // the first `ring` streamed layers of the pass, except those still resident from the
@@ -192,7 +193,7 @@ int Scheduler::run_pass(int dir, bool wrap, SchedSink& sink) {
         if ((rc = load(l, scan)) != SP_OK) return rc;
     }
     if (dir < 0)
-        for (int l = R - 1; l >= 0; --l)
+        for (int l = R - 1; l >= lo; --l)
             if (layer_slot_[l] < 0 && (rc = load(l, l)) != SP_OK) return rc;
     // Steady state (Sec. 3.3, Fig. 1): after each group of `group_` executed streamed
     // layers, their slots are refilled with the next streamed layers of the pass.
@@ -202,6 +203,7 @@ int Scheduler::run_pass(int dir, bool wrap, SchedSink& sink) {
     int mi = 0;                // streamed layers computed so far
     for (int i = 0; i < L; ++i) {
         const int l = dir > 0 ? i : L - 1 - i;
+        if (l < lo) continue;
         const int s = layer_slot_[l];
         if (s < 0) return SP_ERR_STATE;
         if ((rc = sink.compute(l, s, dir, fresh_[l] != 0)) != SP_OK) return rc;
@@ -295,8 +297,10 @@ struct TraceSink : SchedSink {
 
 extern "C" int sp_trace_schedule(int n_layers, int n_slots, int n_pinned, int p_eff, int training,
                                  int wrap_prefetch, int passes, sp_sched_op* ops, int cap) {
+    // training > 1: backward passes stop after layer training - 1 (layers below are frozen)
+    const int bwd_lo = training > 1 ? training - 1 : 0;
     if (n_layers < 1 || n_slots < 1 || n_slots > n_layers || n_pinned < 0 || n_pinned >= n_slots || p_eff < 1 ||
-        passes < 1 || cap < 0 || (cap && !ops))
+        passes < 1 || cap < 0 || (cap && !ops) || training < 0 || bwd_lo > n_layers)
         return SP_ERR_INVALID_ARG;
     Scheduler sch;
     sch.reset(n_layers, n_slots, p_eff, n_pinned);
@@ -306,7 +310,7 @@ extern "C" int sp_trace_schedule(int n_layers, int n_slots, int n_pinned, int p_
     for (int ps = 0; ps < passes; ++ps) {
         sink.pass = ps;
         const int dir = (training && (ps & 1)) ? -1 : +1;
-        int rc = sch.run_pass(dir, !training && wrap_prefetch, sink);
+        int rc = sch.run_pass(dir, !training && wrap_prefetch, sink, dir < 0 ? bwd_lo : 0);
         if (rc != SP_OK) return rc;
     }
     return sink.n;

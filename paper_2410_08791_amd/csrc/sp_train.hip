@@ -129,6 +129,9 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     const int T = B * S, Tp = (T + 63) / 64 * 64, dm = d.d_model, f = d.d_ffn;
     const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, nqkv = nq + 2 * nkv;
     auto W = [&](int t) { return reinterpret_cast<const bf16_t*>(w + L.t[t].offset); };
+    // a frozen layer only passes the gradient on to its input: no weight-gradient GEMMs, no
+    // copy to the host (its gain gradients land in the slot and are dropped)
+    const bool frozen = layer < e->frozen;
     const int gs = e->gslot_next;
     e->gslot_next = (gs + 1) % sp::kGradSlots;
     unsigned char* gslot = e->arena + e->ws.gslot[gs];
@@ -164,7 +167,7 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     // ---- FFN.  dh is dL/d(layer output); dhb its bf16 copy.
     // dWd[d,f] = dh^T z       (contraction over tokens: both operands transposed on the way in)
     g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_WD), f, nullptr, 0, nullptr, dm, f, Tp, e->gemm_tile};
-    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
     // dz[T,f] = dh Wd         (Wd is [d,f]: its row index f is contiguous)
     g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_WD), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
@@ -172,7 +175,7 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     SP_HIP(e, spk_launch_swiglu_bwd(st, dz, gu, T, f));
     // dWgu[2f,d] = dgu^T m
     g = GemmArgs{gu, 2 * f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_WGU), dm, nullptr, 0, nullptr, 2 * f, dm, Tp, e->gemm_tile};
-    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
     // dm[T,d] = dgu Wgu  (fp32)
     g = GemmArgs{gu, 2 * f, OP_KMAJOR, W(SP_T_WGU), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, 2 * f, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
@@ -182,7 +185,7 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     // ---- attention block.  dh is now dL/dh1.
     // dWo[d,nq] = dh^T o
     g = GemmArgs{dhb, dm, OP_RMAJOR, o, nq, OP_RMAJOR, G(SP_T_WO), nq, nullptr, 0, nullptr, dm, nq, Tp, e->gemm_tile};
-    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
     // do[T,nq] = dh Wo
     g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_WO), nq, OP_RMAJOR, dob, nq, nullptr, 0, nullptr, T, nq, dm, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
@@ -194,13 +197,14 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     SP_HIP(e, spk_launch_attention_bwd(st, ab, as));
     // dWqkv[nqkv,d] = dqkv^T a
     g = GemmArgs{dqkv, nqkv, OP_RMAJOR, a, dm, OP_RMAJOR, G(SP_T_WQKV), dm, nullptr, 0, nullptr, nqkv, dm, Tp, e->gemm_tile};
-    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
     // da[T,d] = dqkv Wqkv (fp32)
     g = GemmArgs{dqkv, nqkv, OP_KMAJOR, W(SP_T_WQKV), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, nqkv, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
     // first norm: dh += d(rmsnorm)(x_l) applied to da; dg1.  dh is now dL/d(layer input).
     SP_HIP(e, spk_launch_rmsnorm_bwd(st, da, x_l, W(SP_T_G1), dh, dhb, part, G(SP_T_G1), T, dm, d.norm_eps));
 
+    if (frozen) return SP_OK;
     // ---- hand the gradient slot to the device-to-host stream
     SP_HIP(e, hipEventRecord(e->grad_ready[gs], st));
     SP_HIP(e, hipStreamWaitEvent(e->d2h, e->grad_ready[gs], 0));

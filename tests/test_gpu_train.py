@@ -28,10 +28,11 @@ class TrainCase:
         self.xd, self.td = dev_f32(self.x), dev_f32(self.t)
         self.gbytes = sp.sp_layer_grad_bytes(C.byref(self.desc))
 
-    def run(self, k, p, calls=1, want_y=True, target=None, budget_layers=None, flags=0, pinned=0):
+    def run(self, k, p, calls=1, want_y=True, target=None, budget_layers=None, flags=0, pinned=0, frozen=0,
+            want_dx=True):
         w = self.w
         eng = sp.Engine(self.desc, self.blobs, k, p, flags=sp.SP_FLAG_TRAINING | flags, budget_layers=budget_layers,
-                        pinned=pinned)
+                        pinned=pinned, frozen=frozen)
         gblobs = [torch.zeros(self.gbytes, dtype=torch.uint8, pin_memory=True) for _ in range(w.n_layers)]
         y = torch.zeros_like(self.xd) if want_y else None
         dx = torch.zeros_like(self.xd)
@@ -40,7 +41,7 @@ class TrainCase:
         for _ in range(calls):
             for g in gblobs:
                 g.fill_(0xFF)
-            eng.forward_backward(self.xd, td, y, loss, dx, gblobs, w.batch, w.seq)
+            eng.forward_backward(self.xd, td, y, loss, dx if want_dx else None, gblobs, w.batch, w.seq)
             eng.sync()
         st = eng.stats()
         grads = [{n: v.copy() for n, v in sp.grad_views(self.desc, g.numpy()).items()} for g in gblobs]
@@ -121,6 +122,39 @@ def test_training_repeated_calls_and_link_traffic():
     for gl, bl in zip(d["grads"], b["grads"]):
         for n in gl:
             assert np.array_equal(gl[n], bl[n]), n
+
+
+def test_frozen_lower_layers():
+    """The paper's 'half of layers frozen' rows (Table 2): the trainable layers' gradients
+    are bit for bit those of the fully trainable run, frozen layers' gradient blobs are
+    not written, and without an input gradient the backward stops above the frozen
+    layers (fewer layer copies, fewer gradient copies)."""
+    w = synth.Workload("train_l6", "decoder", 6, 256, 4, 2, 64, 512, True, 1, 128, training=True)
+    c = TrainCase(w)
+    full = c.run(1, 1, calls=2)
+    for flags in (0, sp.SP_FLAG_KEEP_ACTIVATIONS):
+        with_dx = c.run(1, 1, calls=2, frozen=3, flags=flags)
+        no_dx = c.run(1, 1, calls=2, frozen=3, want_dx=False, flags=flags)
+        for got in (with_dx, no_dx):
+            assert got["loss"] == full["loss"] and np.array_equal(got["y"], full["y"])
+            for l in range(6):
+                for n, g in got["grads"][l].items():
+                    if l >= 3:
+                        assert np.array_equal(g, full["grads"][l][n]), (l, n)
+                    else:
+                        assert np.all(g.view(np.uint32) == 0xFFFFFFFF), (l, n)     # untouched fill
+            assert got["stats"].d2h_copies == 2 * 3
+        assert np.array_equal(with_dx["dx"], full["dx"])
+        # forward 6 copies; the backward re-uses the 2 resident layers and stops at layer 3
+        assert no_dx["stats"].h2d_copies < with_dx["stats"].h2d_copies
+        ops = sp.trace_schedule(6, 2, 1, training=True, passes=4, frozen=3)
+        assert no_dx["stats"].h2d_copies == sum(1 for o in ops if o[0] == 0)
+    # everything frozen, no dx: forward and loss only
+    none = c.run(1, 1, frozen=6, want_dx=False)
+    assert none["loss"] == full["loss"] and none["stats"].d2h_copies == 0
+    for bad in (-1, 7):
+        with pytest.raises(sp.SuperpipeError):
+            c.run(1, 1, frozen=bad)
 
 
 def test_training_ragged_token_count_and_no_y():

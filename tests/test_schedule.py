@@ -128,6 +128,21 @@ def test_pinned_layers_are_copied_once_and_the_rest_stream(training):
                             assert per_pass[0] == L - R + ring and all(c == L - R for c in per_pass[1:])
 
 
+def test_backward_stops_above_frozen_layers():
+    """Training with F frozen layers and no input gradient: the backward pass covers layers
+    L-1..F only, never copies a layer below F, and the next forward starts at layer 0 again."""
+    for L in range(2, 9):
+        for N in range(1, L + 1):
+            for F in range(0, L + 1):
+                for R in ([0] if N < 2 or N == L else [0, 1]):
+                    ops = sp.trace_schedule(L, N, 1, training=True, passes=4, pinned=R, frozen=F)
+                    computes = simulate(ops, L, N, seed=L * 100 + N * 10 + F)
+                    for ps in range(4):
+                        seq = [l for q, k, l in computes if q == ps]
+                        assert seq == (list(range(L - 1, F - 1, -1)) if ps % 2 else list(range(L))), (L, N, F, ps)
+                    assert all(l >= F for k, l, s, w, ps in ops if k == COPY and ps % 2 == 1)
+
+
 def test_pinned_zero_is_the_plain_schedule():
     for L, N, p in [(8, 4, 2), (12, 5, 3), (7, 7, 1)]:
         assert sp.trace_schedule(L, N, p, passes=3, wrap=True) == sp.trace_schedule(L, N, p, passes=3, wrap=True, pinned=0)
