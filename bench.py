@@ -266,6 +266,11 @@ def main():
         "copy_hidden_frac": round(st.copy_hidden_ms / st.copy_busy_ms, 4) if st.copy_busy_ms > 0 else None,
         "copy_busy_ms": round(st.copy_busy_ms, 3), "compute_busy_ms": round(st.compute_busy_ms, 3),
         "last_step_wall_ms": round(st.wall_ms, 3),
+        # (T_copy_only + T_compute_only - T_pipelined) / min(T_copy_only, T_compute_only): 1 = everything
+        # that could be hidden was hidden (copy_hidden_frac is capped by compute/copy when link-bound)
+        "overlap_efficiency": round((st.copy_busy_ms + st.compute_busy_ms - trace_run["ms_per_step"]) /
+                                    min(st.copy_busy_ms, st.compute_busy_ms), 4)
+        if min(st.copy_busy_ms, st.compute_busy_ms) > 0 else None,
         "copy_stream_idle_frac": round(max(0.0, 1 - st.copy_busy_ms / st.wall_ms), 4) if st.wall_ms > 0 else None,
         "trace_run_ms_per_step": round(max(trace_run["ms_per_step"], trace_run["wall_ms_per_step"]), 3),
         "event_ms_per_step": round(main_run["ms_per_step"], 3),
