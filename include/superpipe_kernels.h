@@ -87,6 +87,24 @@ size_t spk_attention_bwd_scratch_bytes(int B, int S, int Hq, int Hkv, int hd);
 int spk_attention_bwd(void* stream, const uint16_t* qkv, const uint16_t* o, const uint16_t* dO, const float* lse,
                       void* scratch, uint16_t* dqkv, int B, int S, int Hq, int Hkv, int hd, int causal);
 
+/* ---- backward steps of the encoder layer ---- */
+
+/* LayerNorm backward (biased variance, as in spk_norm with bias != NULL): given da fp32 [T,d],
+ * the norm's input h fp32 [T,d] and gain bf16 [d]:  dh_io fp32 [T,d] += dL/dh;
+ * dh_bf16 = the updated dh_io rounded; dgain fp32 [d] = sum_t da*xhat; dbias fp32 [d] = sum_t da.
+ * scratch: 256 * 2d floats.  d % 4 == 0, d <= 8192. */
+int spk_layernorm_bwd(void* stream, const float* da, const float* h, const uint16_t* gain, float* dh_io,
+                      uint16_t* dh_bf16, float* scratch, float* dgain, float* dbias, int T, int d, float eps);
+
+/* z bf16 [n] = gelu(u) (0.5 u (1 + erf(u / sqrt 2))); and the backward in place:
+ * u <- dz * gelu'(u).  n % 8 == 0. */
+int spk_gelu(void* stream, const uint16_t* u, uint16_t* z, size_t n);
+int spk_gelu_bwd(void* stream, const uint16_t* dz, uint16_t* u, size_t n);
+
+/* out fp32 [n] = sum over the T rows of src bf16 [T, ld] (bias gradient of a linear map).
+ * scratch: 256 * n floats.  n and ld even. */
+int spk_colsum_bf16(void* stream, const uint16_t* src, int ld, int T, int n, float* scratch, float* out);
+
 #ifdef __cplusplus
 }
 #endif

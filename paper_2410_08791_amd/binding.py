@@ -102,6 +102,10 @@ _sig = {
     "sp_decode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int]),
     "spk_kv_append": (C.c_int, [C.c_void_p] * 4 + [C.c_int] * 7),
     "spk_decode_attention": (C.c_int, [C.c_void_p] * 5 + [C.c_int] * 6),
+    "spk_layernorm_bwd": (C.c_int, [C.c_void_p] * 9 + [C.c_int, C.c_int, C.c_float]),
+    "spk_gelu": (C.c_int, [C.c_void_p] * 3 + [C.c_size_t]),
+    "spk_gelu_bwd": (C.c_int, [C.c_void_p] * 3 + [C.c_size_t]),
+    "spk_colsum_bf16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "sp_forward_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       _P(C.c_void_p), C.c_int, C.c_int]),
     "sp_get_stats": (C.c_int, [C.c_void_p, _P(sp_stats)]),

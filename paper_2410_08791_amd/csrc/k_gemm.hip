@@ -37,17 +37,6 @@ __device__ __forceinline__ int lds_off(int row, int chunk) {
     return row * ROW_BYTES + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
-// Exact-erf GELU, 0.5 x (1 + erf(x / sqrt 2)), with erf from the five-term rational
-// approximation of Abramowitz & Stegun 7.1.26 (absolute error < 1.5e-7, far below the
-// bf16 rounding of the result): branch-free, one exp and one reciprocal.
-__device__ __forceinline__ float gelu_erf(float x) {
-    const float z = fabsf(x) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);
-    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-    const float erf_abs = 1.0f - poly * __expf(-z * z);
-    return 0.5f * x * (1.0f + copysignf(erf_abs, x));
-}
-
 // ---- tile loaders -----------------------------------------------------------
 // K-major source: rows of 64 contiguous k. ROWS*8 16-byte chunks over 256 threads.
 template <int ROWS, int NT>

@@ -28,6 +28,29 @@ __device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
+// erf by the five-term rational approximation of Abramowitz & Stegun 7.1.26 (absolute
+// error < 1.5e-7, far below the bf16 rounding of what it feeds): branch-free, one exp and
+// one reciprocal.  Returns erf(|x| / sqrt 2) and exp(-x^2 / 2).
+__device__ __forceinline__ float erf_abs_half(float x, float* gauss) {
+    const float z = fabsf(x) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    *gauss = __expf(-z * z);
+    return 1.0f - poly * *gauss;
+}
+// Exact-erf GELU, 0.5 x (1 + erf(x / sqrt 2)).
+__device__ __forceinline__ float gelu_erf(float x) {
+    float gs;
+    const float e = erf_abs_half(x, &gs);
+    return 0.5f * x * (1.0f + copysignf(e, x));
+}
+// Its derivative: 0.5 (1 + erf(x / sqrt 2)) + x exp(-x^2 / 2) / sqrt(2 pi).
+__device__ __forceinline__ float gelu_erf_grad(float x) {
+    float gs;
+    const float e = erf_abs_half(x, &gs);
+    return 0.5f * (1.0f + copysignf(e, x)) + x * gs * 0.39894228040143267794f;
+}
+
 // Sum / max over the 64 lanes of a wave; every lane gets the result.
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

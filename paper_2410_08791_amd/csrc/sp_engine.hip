@@ -264,8 +264,6 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     if (cfg->h2d_stream == cfg->compute_stream) return fail(nullptr, SP_ERR_INVALID_ARG, "h2d_stream must differ from compute_stream");
     if (training && (!cfg->d2h_stream || cfg->d2h_stream == cfg->compute_stream || cfg->d2h_stream == cfg->h2d_stream))
         return fail(nullptr, SP_ERR_INVALID_ARG, "training needs a d2h_stream distinct from the other two");
-    if (training && desc->arch != SP_DECODER_SWIGLU_RMS)
-        return fail(nullptr, SP_ERR_INVALID_ARG, "training is implemented for decoder stacks only");
     if (desc->n_layers > 4096) return fail(nullptr, SP_ERR_INVALID_ARG, "n_layers > 4096");
     if (cfg->frozen_layers < 0 || cfg->frozen_layers > desc->n_layers || (cfg->frozen_layers && !training))
         return fail(nullptr, SP_ERR_INVALID_ARG, "frozen_layers must be in 0..n_layers and needs SP_FLAG_TRAINING");

@@ -104,7 +104,10 @@ void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Wor
         ws->kt = take((size_t)d->max_batch * d->n_kv_heads * hdp * sp * 2);
         ws->qt = take((size_t)d->max_batch * d->n_q_heads * hdp * sp * 2);
         ws->dot = take((size_t)d->max_batch * d->n_q_heads * hdp * sp * 2);
-        ws->part = take(((size_t)kNormBwdBlocks * dm + 1024) * 4);
+        // partial rows of the two-stage column reductions: gain gradients (d columns), and
+        // for the encoder gain + bias (2d) and the linear maps' bias gradients (up to nqkv or f)
+        const size_t pcols = d->arch == SP_DECODER_SWIGLU_RMS ? dm : std::max(std::max(2 * dm, nqkv), f);
+        ws->part = take(((size_t)kNormBwdBlocks * pcols + 1024) * 4);
         off = align_up(off, kSlotAlign);
         for (int i = 0; i < kGradSlots; ++i) ws->gslot[i] = take(align_up(lay.grad_bytes, kSlotAlign));
     }

@@ -84,6 +84,16 @@ hipError_t spk_launch_swiglu_bwd(hipStream_t st, const bf16_t* dz, bf16_t* gu, i
 // dgain fp32 [d] = sum_t da*h*r.  part: SPK_NORM_BWD_BLOCKS * d floats.
 hipError_t spk_launch_rmsnorm_bwd(hipStream_t st, const float* da, const float* h, const bf16_t* gain, float* dh_io,
                                   bf16_t* dhb, float* part, float* dgain, int T, int d, float eps);
+// LayerNorm backward (biased variance): dh_io += d(norm)/dh applied to da; dhb = bf16(dh_io);
+// dgain = sum_t da*xhat, dbias = sum_t da.  part: SPK_NORM_BWD_BLOCKS * 2d floats.
+hipError_t spk_launch_layernorm_bwd(hipStream_t st, const float* da, const float* h, const bf16_t* gain, float* dh_io,
+                                    bf16_t* dhb, float* part, float* dgain, float* dbias, int T, int d, float eps);
+// z = gelu(u) (exact-erf form) over n bf16 elements; and u <- dz * gelu'(u) in place.
+hipError_t spk_launch_gelu(hipStream_t st, const bf16_t* u, bf16_t* z, size_t n);
+hipError_t spk_launch_gelu_bwd(hipStream_t st, const bf16_t* dz, bf16_t* u, size_t n);
+// out fp32 [n] = column sums over the T rows of src bf16 [T, ld] (bias gradients).
+// part: SPK_NORM_BWD_BLOCKS * n floats.
+hipError_t spk_launch_colsum_bf16(hipStream_t st, const bf16_t* src, int ld, int T, int n, float* part, float* out);
 hipError_t spk_launch_f32_to_bf16(hipStream_t st, const float* src, bf16_t* dst, size_t n);
 // delta fp32 [B,Hq,S] = rowsum(dO * O), both bf16 [B*S, Hq*hd].
 hipError_t spk_launch_attn_delta(hipStream_t st, const bf16_t* dO, const bf16_t* O, float* delta, int B, int S,

@@ -106,3 +106,24 @@ extern "C" int spk_attention_bwd(void* stream, const uint16_t* qkv, const uint16
     AttnBwdArgs g{qkv, dO, lse, delta, kt, qt, dot, dqkv};
     return st(spk_launch_attention_bwd(s, g, a));
 }
+
+extern "C" int spk_layernorm_bwd(void* stream, const float* da, const float* h, const uint16_t* gain, float* dh_io,
+                                 uint16_t* dhb, float* scratch, float* dgain, float* dbias, int T, int d, float eps) {
+    if (!da || !h || !gain || !dh_io || !dhb || !scratch || !dgain || !dbias) return SP_ERR_INVALID_ARG;
+    return st(spk_launch_layernorm_bwd((hipStream_t)stream, da, h, gain, dh_io, dhb, scratch, dgain, dbias, T, d, eps));
+}
+
+extern "C" int spk_gelu(void* stream, const uint16_t* u, uint16_t* z, size_t n) {
+    if (!u || !z) return SP_ERR_INVALID_ARG;
+    return st(spk_launch_gelu((hipStream_t)stream, u, z, n));
+}
+
+extern "C" int spk_gelu_bwd(void* stream, const uint16_t* dz, uint16_t* u, size_t n) {
+    if (!dz || !u) return SP_ERR_INVALID_ARG;
+    return st(spk_launch_gelu_bwd((hipStream_t)stream, dz, u, n));
+}
+
+extern "C" int spk_colsum_bf16(void* stream, const uint16_t* src, int ld, int T, int n, float* scratch, float* out) {
+    if (!src || !scratch || !out) return SP_ERR_INVALID_ARG;
+    return st(spk_launch_colsum_bf16((hipStream_t)stream, src, ld, T, n, scratch, out));
+}

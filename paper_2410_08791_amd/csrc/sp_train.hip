@@ -71,6 +71,50 @@ int decoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
     return SP_OK;
 }
 
+// Encoder layer (pre-LayerNorm, biased linears, GELU) with every intermediate kept; the
+// pre-activation u of the MLP goes where the decoder keeps [g | u], z = gelu(u) is a pass of
+// its own because the backward needs both.
+int encoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, const LayerBufs& b, int B, int S) {
+    const sp_stack_desc& d = e->desc;
+    const Layout& L = e->lay;
+    hipStream_t st = e->compute;
+    const int T = B * S, dm = d.d_model, f = d.d_ffn;
+    const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, nqkv = nq + 2 * nkv;
+    auto W = [&](int t) { return reinterpret_cast<const bf16_t*>(w + L.t[t].offset); };
+    bf16_t *a = as_.a, *m = as_.m, *qkv = as_.qkv, *o = as_.o, *u = as_.gu, *z = as_.z;
+    bf16_t* vt = e->wsp<bf16_t>(e->ws.vt);
+    AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
+    GemmArgs g;
+    SP_HIP(e, spk_launch_norm(st, b.h_in, W(SP_T_LN1_G), W(SP_T_LN1_B), a, T, dm, d.norm_eps));
+    g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_E_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0, W(SP_T_BQKV), T, nqkv, dm, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+    SP_HIP(e, spk_launch_transpose_v(st, qkv, vt, as));
+    SP_HIP(e, spk_launch_attention(st, qkv, vt, o, b.lse, as));
+    g = GemmArgs{o, nq, OP_KMAJOR, W(SP_T_E_WO), nq, OP_KMAJOR, b.h_mid, dm, b.h_in, dm, W(SP_T_BO), T, dm, nq, e->gemm_tile};
+    SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+    SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_LN2_G), W(SP_T_LN2_B), m, T, dm, d.norm_eps));
+    g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_W1), dm, OP_KMAJOR, u, f, nullptr, 0, W(SP_T_B1), T, f, dm, e->gemm_tile};
+    const bool kt = !e->kt_begin.empty() && (e->kt_seen++ % 4 == 0);
+    const size_t kti = kt ? e->kt_count % e->kt_begin.size() : 0;
+    if (kt) {
+        SP_HIP(e, hipEventRecord(e->kt_begin[kti], st));
+        e->kt_m = T; e->kt_n = f; e->kt_k = dm;
+    }
+    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+    if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
+    SP_HIP(e, spk_launch_gelu(st, u, z, (size_t)T * f));
+    if (b.h_out) {
+        g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_W2), f, OP_KMAJOR, b.h_out, dm, b.h_mid, dm, W(SP_T_B2), T, dm, f, e->gemm_tile};
+        SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+    }
+    return SP_OK;
+}
+
+int layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, const LayerBufs& b, int B, int S) {
+    return e->desc.arch == SP_DECODER_SWIGLU_RMS ? decoder_layer_keep(e, w, as_, b, B, S)
+                                                 : encoder_layer_keep(e, w, as_, b, B, S);
+}
+
 float* saved_input(sp_engine* e, int layer, int T) {
     return e->wsp<float>(e->ws.xs) + (size_t)layer * T * e->desc.d_model;
 }
@@ -88,7 +132,7 @@ int sp_train_begin(sp_engine* e, const float* x_dev, int B, int S) {
         const int nq = d.n_q_heads * d.head_dim, nqkv = nq + 2 * d.n_kv_heads * d.head_dim;
         struct { size_t off; int cols; bool per_set; } bufs[] = {
             {e->ws.a, d.d_model, true}, {e->ws.m, d.d_model, true}, {e->ws.o, nq, true},
-            {e->ws.gu, 2 * d.d_ffn, true}, {e->ws.z, d.d_ffn, true},
+            {e->ws.gu, (d.arch == SP_DECODER_SWIGLU_RMS ? 2 : 1) * d.d_ffn, true}, {e->ws.z, d.d_ffn, true},
             {e->ws.dhb, d.d_model, false}, {e->ws.dqkv, nqkv, false}};
         const int n_sets = e->ws.set_stride ? d.n_layers : 1;
         for (auto& bf : bufs)
@@ -110,7 +154,7 @@ int sp_layer_forward_train(sp_engine* e, int layer, const unsigned char* w, int 
     const ActSet as_ = act_set(e, layer);
     // with kept activations the forward also produces what the backward needs (log-sum-exp)
     LayerBufs b{saved_input(e, layer, T), as_.h1, out, e->ws.set_stride ? as_.lse : nullptr};
-    return decoder_layer_keep(e, w, as_, b, B, S);
+    return layer_keep(e, w, as_, b, B, S);
 }
 
 int sp_train_loss(sp_engine* e, const float* target_dev, float* loss_dev, int B, int S) {
@@ -160,34 +204,68 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     // recompute a, qkv, o, lse, h1, m, gu, z from the saved input -- unless the forward kept them
     if (!e->ws.set_stride) {
         LayerBufs lb{x_l, h1, nullptr, lse};
-        int rc = decoder_layer_keep(e, w, as_, lb, B, S);
+        int rc = layer_keep(e, w, as_, lb, B, S);
         if (rc != SP_OK) return rc;
     }
 
+    const bool dec = d.arch == SP_DECODER_SWIGLU_RMS;
+    const int t_wo = dec ? SP_T_WO : SP_T_E_WO, t_wqkv = dec ? SP_T_WQKV : SP_T_E_WQKV;
+    // bias gradient of a linear map = column sums of its output gradient over the tokens
+    auto bias_grad = [&](const bf16_t* dy, int n, int t) -> int {
+        if (frozen) return SP_OK;
+        SP_HIP(e, spk_launch_colsum_bf16(st, dy, n, T, n, part, G(t)));
+        return SP_OK;
+    };
+    int rc;
+
     // ---- FFN.  dh is dL/d(layer output); dhb its bf16 copy.
-    // dWd[d,f] = dh^T z       (contraction over tokens: both operands transposed on the way in)
-    g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_WD), f, nullptr, 0, nullptr, dm, f, Tp, e->gemm_tile};
-    if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
-    // dz[T,f] = dh Wd         (Wd is [d,f]: its row index f is contiguous)
-    g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_WD), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, e->gemm_tile};
-    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
-    // [dg | du] in place over [g | u]
-    SP_HIP(e, spk_launch_swiglu_bwd(st, dz, gu, T, f));
-    // dWgu[2f,d] = dgu^T m
-    g = GemmArgs{gu, 2 * f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_WGU), dm, nullptr, 0, nullptr, 2 * f, dm, Tp, e->gemm_tile};
-    if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
-    // dm[T,d] = dgu Wgu  (fp32)
-    g = GemmArgs{gu, 2 * f, OP_KMAJOR, W(SP_T_WGU), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, 2 * f, e->gemm_tile};
-    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
-    // second norm: dh += d(rmsnorm)(h1) applied to dm; dg2
-    SP_HIP(e, spk_launch_rmsnorm_bwd(st, da, h1, W(SP_T_G2), dh, dhb, part, G(SP_T_G2), T, dm, d.norm_eps));
+    if (dec) {
+        // dWd[d,f] = dh^T z       (contraction over tokens: both operands transposed on the way in)
+        g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_WD), f, nullptr, 0, nullptr, dm, f, Tp, e->gemm_tile};
+        if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        // dz[T,f] = dh Wd         (Wd is [d,f]: its row index f is contiguous)
+        g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_WD), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, e->gemm_tile};
+        SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+        // [dg | du] in place over [g | u]
+        SP_HIP(e, spk_launch_swiglu_bwd(st, dz, gu, T, f));
+        // dWgu[2f,d] = dgu^T m
+        g = GemmArgs{gu, 2 * f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_WGU), dm, nullptr, 0, nullptr, 2 * f, dm, Tp, e->gemm_tile};
+        if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        // dm[T,d] = dgu Wgu  (fp32)
+        g = GemmArgs{gu, 2 * f, OP_KMAJOR, W(SP_T_WGU), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, 2 * f, e->gemm_tile};
+        SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        // second norm: dh += d(rmsnorm)(h1) applied to dm; dg2
+        SP_HIP(e, spk_launch_rmsnorm_bwd(st, da, h1, W(SP_T_G2), dh, dhb, part, G(SP_T_G2), T, dm, d.norm_eps));
+    } else {
+        bf16_t* u = gu;                     // pre-activation of the MLP, [T, f]
+        if ((rc = bias_grad(dhb, dm, SP_T_B2)) != SP_OK) return rc;
+        // dW2[d,f] = dh^T z
+        g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_W2), f, nullptr, 0, nullptr, dm, f, Tp, e->gemm_tile};
+        if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        // dz[T,f] = dh W2
+        g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_W2), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, e->gemm_tile};
+        SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+        // du = dz gelu'(u), in place over u
+        SP_HIP(e, spk_launch_gelu_bwd(st, dz, u, (size_t)T * f));
+        if ((rc = bias_grad(u, f, SP_T_B1)) != SP_OK) return rc;
+        // dW1[f,d] = du^T m
+        g = GemmArgs{u, f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_W1), dm, nullptr, 0, nullptr, f, dm, Tp, e->gemm_tile};
+        if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        // dm[T,d] = du W1  (fp32)
+        g = GemmArgs{u, f, OP_KMAJOR, W(SP_T_W1), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, f, e->gemm_tile};
+        SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        // second norm: dh += d(layernorm)(h1) applied to dm; its gain and bias gradients
+        SP_HIP(e, spk_launch_layernorm_bwd(st, da, h1, W(SP_T_LN2_G), dh, dhb, part, G(SP_T_LN2_G), G(SP_T_LN2_B), T,
+                                           dm, d.norm_eps));
+    }
 
     // ---- attention block.  dh is now dL/dh1.
+    if (!dec && (rc = bias_grad(dhb, dm, SP_T_BO)) != SP_OK) return rc;
     // dWo[d,nq] = dh^T o
-    g = GemmArgs{dhb, dm, OP_RMAJOR, o, nq, OP_RMAJOR, G(SP_T_WO), nq, nullptr, 0, nullptr, dm, nq, Tp, e->gemm_tile};
+    g = GemmArgs{dhb, dm, OP_RMAJOR, o, nq, OP_RMAJOR, G(t_wo), nq, nullptr, 0, nullptr, dm, nq, Tp, e->gemm_tile};
     if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
     // do[T,nq] = dh Wo
-    g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_WO), nq, OP_RMAJOR, dob, nq, nullptr, 0, nullptr, T, nq, dm, e->gemm_tile};
+    g = GemmArgs{dhb, dm, OP_KMAJOR, W(t_wo), nq, OP_RMAJOR, dob, nq, nullptr, 0, nullptr, T, nq, dm, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
     SP_HIP(e, spk_launch_attn_delta(st, dob, o, delta, B, S, d.n_q_heads, d.head_dim));
     SP_HIP(e, spk_launch_transpose_heads(st, qkv, nqkv, nq, d.n_kv_heads, B, S, d.head_dim, kt));
@@ -195,14 +273,20 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     SP_HIP(e, spk_launch_transpose_heads(st, dob, nq, 0, d.n_q_heads, B, S, d.head_dim, dot));
     AttnBwdArgs ab{qkv, dob, lse, delta, kt, qt, dot, dqkv};
     SP_HIP(e, spk_launch_attention_bwd(st, ab, as));
+    if (!dec && (rc = bias_grad(dqkv, nqkv, SP_T_BQKV)) != SP_OK) return rc;
     // dWqkv[nqkv,d] = dqkv^T a
-    g = GemmArgs{dqkv, nqkv, OP_RMAJOR, a, dm, OP_RMAJOR, G(SP_T_WQKV), dm, nullptr, 0, nullptr, nqkv, dm, Tp, e->gemm_tile};
+    g = GemmArgs{dqkv, nqkv, OP_RMAJOR, a, dm, OP_RMAJOR, G(t_wqkv), dm, nullptr, 0, nullptr, nqkv, dm, Tp, e->gemm_tile};
     if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
     // da[T,d] = dqkv Wqkv (fp32)
-    g = GemmArgs{dqkv, nqkv, OP_KMAJOR, W(SP_T_WQKV), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, nqkv, e->gemm_tile};
+    g = GemmArgs{dqkv, nqkv, OP_KMAJOR, W(t_wqkv), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, nqkv, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
-    // first norm: dh += d(rmsnorm)(x_l) applied to da; dg1.  dh is now dL/d(layer input).
-    SP_HIP(e, spk_launch_rmsnorm_bwd(st, da, x_l, W(SP_T_G1), dh, dhb, part, G(SP_T_G1), T, dm, d.norm_eps));
+    // first norm: dh += d(norm)(x_l) applied to da; its parameter gradients.  dh is now
+    // dL/d(layer input).
+    if (dec)
+        SP_HIP(e, spk_launch_rmsnorm_bwd(st, da, x_l, W(SP_T_G1), dh, dhb, part, G(SP_T_G1), T, dm, d.norm_eps));
+    else
+        SP_HIP(e, spk_launch_layernorm_bwd(st, da, x_l, W(SP_T_LN1_G), dh, dhb, part, G(SP_T_LN1_G), G(SP_T_LN1_B), T,
+                                           dm, d.norm_eps));
 
     if (frozen) return SP_OK;
     // ---- hand the gradient slot to the device-to-host stream

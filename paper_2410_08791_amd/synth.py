@@ -71,6 +71,9 @@ WORKLOADS = {
     # 1.3B-shaped training step
     "train1p3b": Workload("train1p3b", DECODER, 24, 2048, 16, 16, 128, 5504, True, 8, 1024,
                           k=2, p=1, training=True),
+    # ViT-H-shaped training step (the paper's ViT rows of Table 2), 32 images per step
+    "trainvith": Workload("trainvith", ENCODER, 32, 1280, 16, 16, 80, 5120, False, 32, 257,
+                          k=2, p=1, training=True),
 }
 
 

@@ -264,3 +264,62 @@ def test_attention_backward(B, S, Hq, Hkv, hd, causal):
     for name, g, r in (("dq", got[:, :nq], dq), ("dk", got[:, nq:nq + nk], dk), ("dv", got[:, nq + nk:], dv)):
         err = np.max(np.abs(g - r)) / np.max(np.abs(r))
         assert err <= 1.5e-2, (name, err)
+
+
+@pytest.mark.parametrize("T,d", [(300, 256), (37, 1280), (5, 8192), (700, 320)])
+def test_layernorm_backward(T, d):
+    rng = np.random.default_rng(T * 5 + d)
+    da = rng.standard_normal((T, d)).astype(np.float32)
+    h = (rng.standard_normal((T, d)) * 1.5 + 0.7).astype(np.float32)
+    dh0 = rng.standard_normal((T, d)).astype(np.float32)
+    gb, g = rand_bf16(rng, d, 0.3)
+    dad, hd, gd, dhd = dev_f32(da), dev_f32(h), dev_u16(gb), dev_f32(dh0)
+    dhb = torch.zeros((T, d), dtype=torch.int16, device=DEV)
+    scratch = torch.zeros(256 * 2 * d, dtype=torch.float32, device=DEV)
+    dgain = torch.zeros(d, dtype=torch.float32, device=DEV)
+    dbias = torch.zeros(d, dtype=torch.float32, device=DEV)
+    rc = sp.spk_layernorm_bwd(stream_ptr(), ptr(dad), ptr(hd), ptr(gd), ptr(dhd), ptr(dhb), ptr(scratch), ptr(dgain),
+                              ptr(dbias), T, d, 1e-5)
+    assert rc == sp.SP_OK
+    sync()
+    dh_ref, dg_ref, db_ref = O._layernorm_bwd(da.astype(np.float64), h.astype(np.float64), g, 1e-5)
+    dh_ref = dh_ref + dh0
+    got = dhd.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - dh_ref)) <= 1e-5 * np.max(np.abs(dh_ref))
+    assert np.max(np.abs(dgain.cpu().numpy() - dg_ref)) <= 1e-5 * np.max(np.abs(dg_ref)) * np.sqrt(T)
+    assert np.max(np.abs(dbias.cpu().numpy() - db_ref)) <= 1e-5 * np.max(np.abs(db_ref)) * np.sqrt(T)
+    assert np.all(np.abs(bf16_vals(host_u16(dhb)) - got) <= BF16_EPS * np.abs(got) + 1e-12)
+
+
+@pytest.mark.parametrize("n", [8, 4096 * 33, 5120 * 7])
+def test_gelu_and_its_backward(n):
+    rng = np.random.default_rng(n)
+    ub, u = rand_bf16(rng, n, 2.0)
+    dzb, dz = rand_bf16(rng, n)
+    ud, dzd = dev_u16(ub), dev_u16(dzb)
+    z = torch.zeros(n, dtype=torch.int16, device=DEV)
+    assert sp.spk_gelu(stream_ptr(), ptr(ud), ptr(z), n) == sp.SP_OK
+    assert sp.spk_gelu_bwd(stream_ptr(), ptr(dzd), ptr(ud), n) == sp.SP_OK
+    sync()
+    zr = O.gelu(u)
+    assert np.all(np.abs(bf16_vals(host_u16(z)) - zr) <= BF16_EPS * np.abs(zr) + 2e-7)
+    # the derivative by central differences of the oracle's gelu in fp64
+    e = 1e-6
+    dref = dz * (O.gelu(u + e) - O.gelu(u - e)) / (2 * e)
+    got = bf16_vals(host_u16(ud))
+    assert np.all(np.abs(got - dref) <= BF16_EPS * np.abs(dref) + 1e-6 * np.abs(dz) + 1e-9)
+    assert sp.spk_gelu(stream_ptr(), ptr(ud), ptr(z), 12) == sp.SP_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("T,n,ld", [(300, 256, 256), (1000, 3840, 3840), (37, 1280, 2560), (5, 2, 8)])
+def test_column_sums(T, n, ld):
+    rng = np.random.default_rng(T + n)
+    sb, s = rand_bf16(rng, (T, ld))
+    sd = dev_u16(sb)
+    scratch = torch.zeros(256 * n, dtype=torch.float32, device=DEV)
+    out = torch.zeros(n, dtype=torch.float32, device=DEV)
+    assert sp.spk_colsum_bf16(stream_ptr(), ptr(sd), ld, T, n, ptr(scratch), ptr(out)) == sp.SP_OK
+    sync()
+    ref = s[:, :n].sum(axis=0)
+    assert np.max(np.abs(out.cpu().numpy() - ref)) <= 1e-5 * np.sqrt(T) * max(np.max(np.abs(ref)), 1.0)
+    assert sp.spk_colsum_bf16(stream_ptr(), ptr(sd), ld, T, 3, ptr(scratch), ptr(out)) == sp.SP_ERR_INVALID_ARG

@@ -206,3 +206,35 @@ def test_train1p3b_layer_shape():
     c = TrainCase(w)
     got = c.run(1, 1)
     check_against_oracle(got, c.oracle(np.float32), "train1p3b x2 layers, batch 2")
+
+
+@pytest.mark.parametrize("hd,seq", [(64, 50), (80, 33)])
+def test_encoder_training_matches_oracle(hd, seq):
+    """The encoder layer kind (LayerNorm, biased linears, GELU, bidirectional attention) through
+    the same training path: loss, dx and all twelve tensors' gradients per layer against the
+    oracle; same bits for every window and with kept activations; frozen lower layer."""
+    d = 4 * hd
+    w = synth.Workload(f"train_enc{hd}", "encoder", 3, d, 4, 4, hd, 4 * d, False, 2, seq, training=True)
+    c = TrainCase(w)
+    base = c.run(1, 1, calls=2)
+    check_against_oracle(base, c.oracle(), w.name)
+    for kwargs in (dict(k=4, p=4), dict(k=1, p=1, flags=sp.SP_FLAG_KEEP_ACTIVATIONS), dict(k=1, p=1, pinned=1)):
+        k, p = kwargs.pop("k"), kwargs.pop("p")
+        got = c.run(k, p, calls=2, **kwargs)
+        assert got["loss"] == base["loss"] and np.array_equal(got["dx"], base["dx"])
+        for gl, bl in zip(got["grads"], base["grads"]):
+            for n in gl:
+                assert np.array_equal(gl[n], bl[n]), (kwargs, n)
+    fr = c.run(1, 1, frozen=1)
+    assert np.array_equal(fr["dx"], base["dx"])
+    for n, g in fr["grads"][2].items():
+        assert np.array_equal(g, base["grads"][2][n]), n
+    assert all(np.all(g.view(np.uint32) == 0xFFFFFFFF) for g in fr["grads"][0].values())
+
+
+def test_vith_layer_shape_training():
+    """ViT-H layer shape (d 1280, 16 heads of 80, ffn 5120), two layers, 4 images of 257 tokens."""
+    w = synth.WORKLOADS["vith"].with_(n_layers=2, batch=4, training=True)
+    c = TrainCase(w)
+    got = c.run(1, 1)
+    check_against_oracle(got, c.oracle(np.float32), "vith x2 layers, batch 4 (fp32 oracle)")
