@@ -141,11 +141,8 @@ __global__ __launch_bounds__(TH) void rmsnorm_bwd_kernel(const float* __restrict
 
 __global__ __launch_bounds__(TH) void colsum_final_kernel(const float* __restrict__ part, int nparts, int d,
                                                           float* __restrict__ out) {
-    const int c = blockIdx.x * TH + threadIdx.x;
-    if (c >= d) return;
-    float s = 0.f;
-    for (int p = 0; p < nparts; ++p) s += part[(size_t)p * d + c];
-    out[c] = s;
+    __shared__ float lds[256];
+    colsum_rows_body(part, nparts, d, d, out, lds);
 }
 
 __global__ __launch_bounds__(TH) void f32_to_bf16_kernel(const float4* __restrict__ src, uint2* __restrict__ dst, size_t n4) {
@@ -212,7 +209,7 @@ hipError_t spk_launch_rmsnorm_bwd(hipStream_t st, const float* da, const float* 
     rmsnorm_bwd_kernel<<<nb, TH, 0, st>>>(da, h, gain, dh_io, dhb, part, T, d, eps);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    colsum_final_kernel<<<(d + TH - 1) / TH, TH, 0, st>>>(part, nb, d, dgain);
+    colsum_final_kernel<<<(d + 63) / 64, TH, 0, st>>>(part, nb, d, dgain);
     return hipGetLastError();
 }
 

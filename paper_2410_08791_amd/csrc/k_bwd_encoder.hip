@@ -98,14 +98,10 @@ __global__ __launch_bounds__(TH) void layernorm_bwd_kernel(const float* __restri
     }
 }
 
-// out[c] = sum over partial rows p of part[p * ld + c]
 __global__ __launch_bounds__(TH) void colsum_rows_kernel(const float* __restrict__ part, int nparts, int ld, int n,
                                                          float* __restrict__ out) {
-    const int c = blockIdx.x * TH + threadIdx.x;
-    if (c >= n) return;
-    float s = 0.f;
-    for (int p = 0; p < nparts; ++p) s += part[(size_t)p * ld + c];
-    out[c] = s;
+    __shared__ float lds[256];
+    colsum_rows_body(part, nparts, ld, n, out, lds);
 }
 
 // z = gelu(u), 8 elements per thread
@@ -163,8 +159,8 @@ hipError_t spk_launch_layernorm_bwd(hipStream_t st, const float* da, const float
     layernorm_bwd_kernel<<<nb, TH, 0, st>>>(da, h, gain, dh_io, dhb, part, T, d, eps);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    colsum_rows_kernel<<<(d + TH - 1) / TH, TH, 0, st>>>(part, nb, 2 * d, d, dgain);
-    colsum_rows_kernel<<<(d + TH - 1) / TH, TH, 0, st>>>(part + d, nb, 2 * d, d, dbias);
+    colsum_rows_kernel<<<(d + 63) / 64, TH, 0, st>>>(part, nb, 2 * d, d, dgain);
+    colsum_rows_kernel<<<(d + 63) / 64, TH, 0, st>>>(part + d, nb, 2 * d, d, dbias);
     return hipGetLastError();
 }
 
@@ -189,6 +185,6 @@ hipError_t spk_launch_colsum_bf16(hipStream_t st, const bf16_t* src, int ld, int
     colsum_bf16_kernel<<<nb, TH, 0, st>>>(src, ld, T, n, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    colsum_rows_kernel<<<(n + TH - 1) / TH, TH, 0, st>>>(part, nb, n, n, out);
+    colsum_rows_kernel<<<(n + 63) / 64, TH, 0, st>>>(part, nb, n, n, out);
     return hipGetLastError();
 }

@@ -81,3 +81,27 @@ __device__ __forceinline__ int xcd_remap(int pid, int nblocks) {
     const int per = nblocks >> 3, rem = nblocks & 7;
     return xcd * per + (xcd < rem ? xcd : rem) + q;
 }
+
+// Second stage of the deterministic column reductions: out[c] = sum over partial rows p of
+// part[p * ld + c].  A work-group covers 64 columns; its four waves each add every fourth
+// row with four independent accumulators (loads in flight instead of one dependent chain),
+// then the 16 partial sums of a column are added in a fixed order.
+__device__ __forceinline__ void colsum_rows_body(const float* __restrict__ part, int nparts, int ld, int n,
+                                                 float* __restrict__ out, float* lds /* [4][64] */) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    if (c < n) {
+        int p = w;
+        for (; p + 12 < nparts; p += 16) {
+            a0 += part[(size_t)p * ld + c];
+            a1 += part[(size_t)(p + 4) * ld + c];
+            a2 += part[(size_t)(p + 8) * ld + c];
+            a3 += part[(size_t)(p + 12) * ld + c];
+        }
+        for (; p < nparts; p += 4) a0 += part[(size_t)p * ld + c];
+    }
+    lds[w * 64 + lane] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (w == 0 && c < n) out[c] = (lds[lane] + lds[64 + lane]) + (lds[128 + lane] + lds[192 + lane]);
+}
