@@ -78,7 +78,8 @@ def main():
                     help="training: this many lowest layers get no weight gradients; no input gradient is "
                          "asked for, so the backward stops above them")
     ap.add_argument("--no-sweep", action="store_true")
-    ap.add_argument("--no-kernel-timing", action="store_true", help="experiment: no event brackets in the timed region")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="no event brackets around the dominant GEMM in the timed region (roofline fields read 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=2, help="oracle sample: layers at full token count")
     args = ap.parse_args()

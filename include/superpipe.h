@@ -88,8 +88,8 @@ enum {
                                       consecutive-forward stall of Sec. 5)                 */
     SP_FLAG_KEEP_ACTIVATIONS = 1u << 6, /* training: keep every layer's activations in the
                                       workspace instead of recomputing them in the backward
-                                      (the paper's "without gradient checkpointing" column,
-                                      Table 2): more HBM, about a quarter less compute      */
+                                      (the columns of Table 2 that train without gradient
+                                      checkpointing): more HBM, about a quarter less compute */
     SP_FLAG_KERNEL_TIMING = 1u << 5 /* bracket every 4th launch of the layer's largest GEMM with
                                       timed events on the compute stream (big_gemm_* in sp_stats) */
 };
@@ -104,9 +104,9 @@ typedef struct {
     void* h2d_stream;           /* hipStream_t, must differ from compute_stream  */
     void* d2h_stream;           /* hipStream_t, needed only with SP_FLAG_TRAINING */
     uint32_t flags;
-    int32_t frozen_layers;      /* training: layers 0..n-1 receive no weight gradients (the paper's
-                                   "half of layers frozen" rows, Table 2).  Their gradient blobs
-                                   are not written; when sp_forward_backward is called with
+    int32_t frozen_layers;      /* training: layers 0..n-1 receive no weight gradients (the rows
+                                   of Table 2 with half of the layers frozen).  Their gradient
+                                   blobs are not written; when sp_forward_backward is called with
                                    dx_dev == NULL the backward pass stops above them, so they
                                    are neither re-streamed nor recomputed.                     */
     int32_t pinned_layers;      /* layers 0..n-1 that stay in HBM for the handle's life and are
@@ -116,7 +116,7 @@ typedef struct {
 #define SP_PIN_AUTO (-1)
 
 /* Slot-count policy (one function decides it).  The streaming window asks for
- * k + p HBM layer slots -- the paper's "k partitions on the GPU" with its k' = p
+ * k + p HBM layer slots -- the paper's k (partitions held on the GPU) with its k' = p
  * of them being refilled (Fig. 1: k=4, k'=2 is (k,p) = (2,2)) -- clamped by the
  * layer count and by what the arena holds after the workspace; pinned layers
  * take what the budget leaves after the window:
@@ -233,7 +233,7 @@ int sp_autotune(const sp_stack_desc* desc, uint64_t budget_bytes, int training, 
 
 /* Create an executor.  layer_host_blobs[n_layers]: host, pinned, each
  * sp_layer_blob_bytes long, caller-owned, must stay valid and UNMODIFIED until
- * sp_destroy (the library never writes them: "no parameter modification",
+ * sp_destroy (the library never writes them: the method leaves parameters untouched,
  * Sec. 1).  Entries may alias.  On failure *out is NULL. */
 int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* const* layer_host_blobs,
               const sp_config* cfg);

@@ -7,8 +7,8 @@ constants are common to the two, and neither imports the other.
 
 What it computes.  The paper's method (Sec. 3.2-3.3) moves layers between host
 and device but leaves the model's arithmetic untouched: its result is that of
-the un-offloaded model (Sec. 4.2, "identical to those of the standard mode";
-Sec. 4.2.2; Sec. 6).  The oracle is therefore the plain definition of the
+the un-offloaded model (Sec. 4.2, Sec. 4.2.2 and Sec. 6 all state that outputs
+equal those of the standard mode).  The oracle is therefore the plain definition of the
 layer stack, with every weight "resident": no window, no slots, no streams.
 A partition is one repeated transformer layer (Sec. 3.2.1); training repeats
 the process for the backward pass (Sec. 3.3), here the analytic gradient of a
