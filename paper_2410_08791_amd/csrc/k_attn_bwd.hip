@@ -142,19 +142,48 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restri
     }
 }
 
+// Transposed MFMA operand out of a token-row tile (rows = tokens, head dimension contiguous):
+// the lane ends up with head-dimension row (lane & 31) of the 32-row block the pointer selects
+// and the eight tokens 4*half + {0..3} and 8 + 4*half + {0..3} of a 16-token step -- the token
+// order in which the score tiles hold their bf16 operands.  ds_read_b64_tr_b16 works on groups
+// of 16 lanes: lane s supplies the address of four values of one token row, lane i receives
+// element i%4 of the blocks supplied by lanes i/4, i/4+4, i/4+8, i/4+12.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+__device__ __forceinline__ int tr_lane_off(int lane, int stride) {
+    const int s16 = lane & 15, half = lane >> 5;
+    return (4 * half + (s16 >> 2)) * stride + (16 * ((lane >> 4) & 1) + 4 * (s16 & 3)) * 2;
+}
+__device__ __forceinline__ bf16x8_t tr_frag_tok(const unsigned char* p, int stride) {
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 8 * stride));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    const s16x8_t both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8_t, both);
+}
+
+// Row stride (bytes) of a token-row tile: 16 * odd keeps the 16-byte row reads of the score
+// products conflict-free, and the residue spreads the four token rows of a transposed read.
+template <int HD> struct TokTile { static constexpr int RS = ((HD + 31) / 32 * 32) * 2 + 48; };
+template <> struct TokTile<80> { static constexpr int RS = 96 * 2 + 16; };
+template <> struct TokTile<64> { static constexpr int RS = 64 * 2 + 16; };
+
 // ---------------------------------------------------------------------- dk, dv
+// A work-group owns 128 keys of one kv head (a wave 32 of them, one key per lane as the B
+// operand of S = Q K^T and dP = dO V^T) and walks 64-query tiles of every query head of the
+// group.  Q and dO tiles sit in LDS once, as token rows: the score products read them
+// straight, dV^T += dO^T P and dK^T += Q^T dS read them through the transposing LDS read.
+// The next tile's rows are fetched into registers before the current tile is computed.
 template <int HD>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           const bf16_t* __restrict__ qt, const bf16_t* __restrict__ dot,
-                                                           bf16_t* __restrict__ dqkv, int S, int S_pad, int Hq, int Hkv,
+                                                           bf16_t* __restrict__ dqkv, int S, int Hq, int Hkv,
                                                            int ld_qkv, int causal, float scale, float scale_log2e) {
     typedef BwdCfg<HD> C;
-    constexpr int QT = 32, T_STRIDE = QT * 2 + 8;
-    __shared__ __attribute__((aligned(16))) unsigned char sQ[QT * C::R_STRIDE];
-    __shared__ __attribute__((aligned(16))) unsigned char sdO[QT * C::R_STRIDE];
-    __shared__ __attribute__((aligned(16))) unsigned char sQt[C::HDP * T_STRIDE];
-    __shared__ __attribute__((aligned(16))) unsigned char sdOt[C::HDP * T_STRIDE];
+    constexpr int QT = 64, RS = TokTile<HD>::RS;
+    constexpr int CHUNKS = QT * (HD / 8), ITERS = (CHUNKS + 255) / 256;
+    __shared__ __attribute__((aligned(16))) unsigned char sQ[QT * RS];
+    __shared__ __attribute__((aligned(16))) unsigned char sdO[QT * RS];
     __shared__ float s_lse[QT], s_delta[QT];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -163,8 +192,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
     const int grp = Hq / Hkv;
     const int k0 = blockIdx.x * 128, wk0 = k0 + wave * 32, kj = wk0 + l32;
     const size_t tok0 = (size_t)b * S;
+    const int ld_do = Hq * HD;
 
-    // this lane's key and value rows: B operands (column = key)
     bf16x8_t kf[C::NKS], vf[C::NKS];
     {
         const bf16_t* kp = qkv + (tok0 + min(kj, S - 1)) * ld_qkv + (size_t)Hq * HD + (size_t)kvh * HD + half * 8;
@@ -181,48 +210,66 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
 #pragma unroll
         for (int e = 0; e < 16; ++e) { dk[t][e] = 0.f; dv[t][e] = 0.f; }
 
+    // the tiles of this work-group in walking order: (query head of the group, 64-query tile)
     const int q_begin = causal ? (k0 / QT) * QT : 0;
-    for (int g = 0; g < grp; ++g) {
-        const int h = kvh * grp + g;
+    const int tiles_per_head = (S - q_begin + QT - 1) / QT;
+    const int n_tiles = grp * tiles_per_head;
+    const int tro = tr_lane_off(lane, RS);
+
+    u32x4_t rq[ITERS], rdo[ITERS];
+    float r_lse = 0.f, r_delta = 0.f;
+    auto fetch = [&](int tile) {
+        const int h = kvh * grp + tile / tiles_per_head;
+        const int q0 = q_begin + (tile % tiles_per_head) * QT;
         const bf16_t* qbase = qkv + tok0 * ld_qkv + h * HD;
-        const bf16_t* dobase = dO + tok0 * (size_t)(Hq * HD) + h * HD;
-        const bf16_t* qtbase = qt + ((size_t)b * Hq + h) * C::HDP * S_pad;
-        const bf16_t* dotbase = dot + ((size_t)b * Hq + h) * C::HDP * S_pad;
-        const float* lbase = lse + ((size_t)b * Hq + h) * S;
-        const float* dbase = delta + ((size_t)b * Hq + h) * S;
-        for (int q0 = q_begin; q0 < S; q0 += QT) {
-            __syncthreads();
-            for (int c = threadIdx.x; c < QT * (HD / 8); c += 256) {
+        const bf16_t* dobase = dO + tok0 * (size_t)ld_do + h * HD;
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            const int c = threadIdx.x + i * 256;
+            if (CHUNKS % 256 == 0 || c < CHUNKS) {
                 const int r = c / (HD / 8), cc = c % (HD / 8);
                 const int row = min(q0 + r, S - 1);
-                *reinterpret_cast<u32x4_t*>(sQ + r * C::R_STRIDE + cc * 16) =
-                    *reinterpret_cast<const u32x4_t*>(qbase + (size_t)row * ld_qkv + cc * 8);
-                *reinterpret_cast<u32x4_t*>(sdO + r * C::R_STRIDE + cc * 16) =
-                    *reinterpret_cast<const u32x4_t*>(dobase + (size_t)row * (Hq * HD) + cc * 8);
+                rq[i] = *reinterpret_cast<const u32x4_t*>(qbase + (size_t)row * ld_qkv + cc * 8);
+                rdo[i] = *reinterpret_cast<const u32x4_t*>(dobase + (size_t)row * ld_do + cc * 8);
             }
-            for (int c = threadIdx.x; c < C::HDP * (QT / 8); c += 256) {
-                const int r = c / (QT / 8), cc = c % (QT / 8);
-                const u32x4_t a = *reinterpret_cast<const u32x4_t*>(qtbase + (size_t)r * S_pad + q0 + cc * 8);
-                const u32x4_t d = *reinterpret_cast<const u32x4_t*>(dotbase + (size_t)r * S_pad + q0 + cc * 8);
-                u32x2_t* pa = reinterpret_cast<u32x2_t*>(sQt + r * T_STRIDE + cc * 16);
-                u32x2_t* pd = reinterpret_cast<u32x2_t*>(sdOt + r * T_STRIDE + cc * 16);
-                pa[0] = u32x2_t{a[0], a[1]}; pa[1] = u32x2_t{a[2], a[3]};
-                pd[0] = u32x2_t{d[0], d[1]}; pd[1] = u32x2_t{d[2], d[3]};
+        }
+        if (threadIdx.x < QT) {
+            const int row = min(q0 + (int)threadIdx.x, S - 1);
+            r_lse = lse[((size_t)b * Hq + h) * S + row] * 1.4426950408889634f;
+            r_delta = delta[((size_t)b * Hq + h) * S + row];
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            const int c = threadIdx.x + i * 256;
+            if (CHUNKS % 256 == 0 || c < CHUNKS) {
+                const int r = c / (HD / 8), cc = c % (HD / 8);
+                *reinterpret_cast<u32x4_t*>(sQ + r * RS + cc * 16) = rq[i];
+                *reinterpret_cast<u32x4_t*>(sdO + r * RS + cc * 16) = rdo[i];
             }
-            if (threadIdx.x < QT) {
-                const int row = min(q0 + (int)threadIdx.x, S - 1);
-                s_lse[threadIdx.x] = lbase[row] * 1.4426950408889634f;
-                s_delta[threadIdx.x] = dbase[row];
-            }
-            __syncthreads();
-            if (causal && q0 + QT - 1 < wk0) continue;   // every query of the tile precedes this wave's keys
+        }
+        if (threadIdx.x < QT) { s_lse[threadIdx.x] = r_lse; s_delta[threadIdx.x] = r_delta; }
+    };
 
+    if (n_tiles > 0) fetch(0);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        __syncthreads();                      // everyone is done reading the previous tile
+        stash();
+        __syncthreads();
+        if (tile + 1 < n_tiles) fetch(tile + 1);
+        const int q0 = q_begin + (tile % tiles_per_head) * QT;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int qs = q0 + sub * 32;
+            if (qs >= S) continue;
+            if (causal && qs + 31 < wk0) continue;   // every query of the sub-tile precedes this wave's keys
             f32x16_t s, dp;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
             for (int ks = 0; ks < C::NKS; ++ks) {
-                const int off = l32 * C::R_STRIDE + (ks * 2 + half) * 16;
+                const int off = (sub * 32 + l32) * RS + (ks * 2 + half) * 16;
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(sQ + off), kf[ks], s, 0, 0, 0);
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(sdO + off), vf[ks], dp, 0, 0, 0);
             }
@@ -230,19 +277,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int r = (e >> 2) * 8 + half * 4 + (e & 3);
-                const int q = q0 + r;
+                const int q = qs + r;
                 const bool ok = q < S && (!causal || kj <= q);
-                const float p = ok ? exp2f(s[e] * scale_log2e - s_lse[r]) : 0.f;
+                const float p = ok ? exp2f(s[e] * scale_log2e - s_lse[sub * 32 + r]) : 0.f;
                 pf[e >> 3][e & 7] = (__bf16)p;
-                dsf[e >> 3][e & 7] = (__bf16)(p * (dp[e] - s_delta[r]));
+                dsf[e >> 3][e & 7] = (__bf16)(p * (dp[e] - s_delta[sub * 32 + r]));
             }
 #pragma unroll
             for (int mt = 0; mt < C::NMT; ++mt)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const int off = (mt * 32 + l32) * T_STRIDE + (16 * j + half * 4) * 2;
-                    dv[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_tr(sdOt + off), pf[j], dv[mt], 0, 0, 0);
-                    dk[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_tr(sQt + off), dsf[j], dk[mt], 0, 0, 0);
+                    const int off = (sub * 32 + 16 * j) * RS + mt * 64 + tro;
+                    dv[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag_tok(sdO + off, RS), pf[j], dv[mt], 0, 0, 0);
+                    dk[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag_tok(sQ + off, RS), dsf[j], dk[mt], 0, 0, 0);
                 }
         }
     }
@@ -275,8 +322,8 @@ hipError_t launch_bwd(hipStream_t st, const AttnBwdArgs& g, const AttnShape& a) 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     dim3 gk((a.S + 127) / 128, a.Hkv, a.B);
-    attn_bwd_dkv_kernel<HD><<<gk, 256, 0, st>>>(g.qkv, g.dO, g.lse, g.delta, g.qt, g.dot, g.dqkv, a.S, sp, a.Hq, a.Hkv,
-                                                a.ld_qkv, a.causal, scale, sl2);
+    attn_bwd_dkv_kernel<HD><<<gk, 256, 0, st>>>(g.qkv, g.dO, g.lse, g.delta, g.dqkv, a.S, a.Hq, a.Hkv, a.ld_qkv,
+                                                a.causal, scale, sl2);
     return hipGetLastError();
 }
 

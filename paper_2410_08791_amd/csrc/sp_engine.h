@@ -41,6 +41,7 @@ struct sp_engine {
     hipEvent_t grad_ready[sp::kGradSlots] = {}, gslot_free[sp::kGradSlots] = {};
     char gslot_used[sp::kGradSlots] = {};
     int gslot_next = 0;
+    hipEvent_t last_grad_copy = nullptr;        // gslot_free event of the most recently submitted gradient copy
     hipEvent_t t0 = nullptr;
     std::vector<hipEvent_t> kt_begin, kt_end;   // ring of event pairs around the largest GEMM
     uint32_t kt_count = 0;                      // pairs recorded since the last sp_get_stats

@@ -54,15 +54,24 @@ int sp_fail(sp_engine* e, int code, const char* fmt, ...) {
 // ---- host run-ahead bound -----------------------------------------------------------
 // The host enqueues a whole call in a few milliseconds.  Measured on this runtime: once
 // more than roughly 1500 packets (kernels and event records) wait on the compute stream,
-// passes take 30-60 % longer in bursts and device-to-host copies drop to a fraction of the
-// link rate; below that every pass runs at its steady time.  A host-side wait is not free
-// either (the copies of the next layers are enqueued late, 3-5 ms per wait on a step whose
-// link is busy), so waits are made rare: when more than kMaxQueuedPackets are unfinished
-// the host sleeps until kResumePackets are left, then runs ahead again.  Per-op packet
-// counts are rounded-up estimates; the ring is longer than any window they allow.
-constexpr uint64_t kMaxQueuedPackets = 1024;
-constexpr uint64_t kResumePackets = 256;
+// passes take 30-60 % longer in bursts; below that every pass runs at its steady time.  A
+// host-side wait is not free either (the copies of the next layers are enqueued late), so
+// waits are made rare: when more than kMaxQueuedPackets are unfinished the host sleeps
+// until kResumePackets are left, then runs ahead again.
+//
+// Gradient copies add a second rule, also measured: a device-to-host copy that is
+// submitted while an earlier one of the same stream is executing runs at a quarter of
+// the link rate (15.8 ms instead of 3.9 ms for 202 MB), and so do all copies submitted
+// after it until the host next finds the stream idle; copies submitted while the earlier
+// ones are still waiting for their gradients are not affected.  A training step that fits
+// the packet bound is therefore enqueued in one go (all its gradient copies are
+// submitted before the first one starts), and when a wait inside a backward pass cannot
+// be avoided the host also lets the gradient stream drain before it goes on.
+// Per-op packet counts are estimates; the ring is longer than any window they allow.
+constexpr uint64_t kMaxQueuedPackets = 1400;
+constexpr uint64_t kResumePackets = 350;
 constexpr size_t kThrottleRing = 256;
+constexpr unsigned kPacketsForward = 16, kPacketsForwardTrain = 14, kPacketsBackward = 44;
 
 static int throttle_before(sp_engine* e) {
     auto left_after = [&](uint64_t i) { return e->thr_packets - e->thr_at[i % kThrottleRing]; };
@@ -71,6 +80,7 @@ static int throttle_before(sp_engine* e) {
         while (e->thr_tail + 1 < e->thr_head && left_after(e->thr_tail + 1) > kResumePackets) e->thr_tail++;
         SP_HIP(e, hipEventSynchronize(e->thr_ev[e->thr_tail % kThrottleRing]));
         e->thr_tail++;
+        if (e->last_grad_copy) SP_HIP(e, hipEventSynchronize(e->last_grad_copy));
     }
     return SP_OK;
 }
@@ -163,8 +173,7 @@ struct HipSink : SchedSink {
         e->tr_comp_layer[e->mi] = layer;
         e->tr_comp_dep[e->mi] = dep;
         e->mi++;
-        // packets per op, counted generously: forward ~9 kernels + events, backward ~40
-        return throttle_after(e, dir > 0 ? 16 : 56);
+        return throttle_after(e, dir < 0 ? kPacketsBackward : training_fwd ? kPacketsForwardTrain : kPacketsForward);
     }
 };
 
