@@ -82,7 +82,8 @@ int spk_rmsnorm_bwd(void* stream, const float* da, const float* h, const uint16_
                     uint16_t* dh_bf16, float* scratch, float* dgain, int T, int d, float eps);
 
 /* Attention backward.  qkv as in spk_attention, o and lse its outputs, dO bf16 [B*S, Hq*hd].
- * dqkv bf16 (layout of qkv) receives dq, dk, dv.  scratch: spk_attention_bwd_scratch_bytes bytes. */
+ * dqkv bf16 (layout of qkv) receives dq, dk, dv.  scratch: spk_attention_bwd_scratch_bytes bytes
+ * (the fp32 row sums of dO * O). */
 size_t spk_attention_bwd_scratch_bytes(int B, int S, int Hq, int Hkv, int hd);
 int spk_attention_bwd(void* stream, const uint16_t* qkv, const uint16_t* o, const uint16_t* dO, const float* lse,
                       void* scratch, uint16_t* dqkv, int B, int S, int Hq, int Hkv, int hd, int causal);

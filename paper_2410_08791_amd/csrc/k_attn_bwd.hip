@@ -11,7 +11,8 @@
 // bf16 is already the B operand of dQ^T = K^T dS^T.  In the dk/dv kernel scores
 // are formed straight (S = Q K^T, dP = dO V^T): a lane holds one key, and P, dS
 // in bf16 are the B operands of dV^T = dO^T P and dK^T = Q^T dS.  The A operands
-// K^T, dO^T, Q^T come from per-head transposed copies made once per layer.
+// K^T, dO^T, Q^T are read out of the same token-row LDS tiles the score products use,
+// through the transposing LDS read: no transposed copies exist in memory.
 #include "sp_kernels.h"
 
 namespace {
@@ -20,127 +21,7 @@ template <int HD>
 struct BwdCfg {
     static constexpr int NKS = HD / 16;
     static constexpr int NMT = (HD + 31) / 32;
-    static constexpr int HDP = NMT * 32;
-    static constexpr int R_STRIDE = HD * 2 + 16;   // row-major tile: bytes per token row
 };
-
-__device__ __forceinline__ bf16x8_t ld_frag_tr(const unsigned char* p) {
-    // two 8-byte pieces 16 bytes apart -> one 8-element operand
-    const u32x2_t lo = *reinterpret_cast<const u32x2_t*>(p);
-    const u32x2_t hi = *reinterpret_cast<const u32x2_t*>(p + 16);
-    const u32x4_t both = u32x4_t{lo[0], lo[1], hi[0], hi[1]};
-    return __builtin_bit_cast(bf16x8_t, both);
-}
-
-// ------------------------------------------------------------------------- dq
-template <int HD>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
-                                                          const float* __restrict__ lse, const float* __restrict__ delta,
-                                                          const bf16_t* __restrict__ kt, bf16_t* __restrict__ dqkv,
-                                                          int S, int S_pad, int Hq, int Hkv, int ld_qkv, int causal,
-                                                          float scale, float scale_log2e) {
-    typedef BwdCfg<HD> C;
-    constexpr int KB = 64, T_STRIDE = KB * 2 + 8;
-    __shared__ __attribute__((aligned(16))) unsigned char sK[KB * C::R_STRIDE];
-    __shared__ __attribute__((aligned(16))) unsigned char sV[KB * C::R_STRIDE];
-    __shared__ __attribute__((aligned(16))) unsigned char sKt[C::HDP * T_STRIDE];
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int l32 = lane & 31, half = lane >> 5;
-    const int qb = causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
-    const int h = blockIdx.y, b = blockIdx.z;
-    const int kvh = h / (Hq / Hkv);
-    const int q0 = qb * 128, wq0 = q0 + wave * 32, qi = wq0 + l32;
-    const size_t tok0 = (size_t)b * S;
-    const int qr = min(qi, S - 1);
-
-    bf16x8_t qf[C::NKS], dof[C::NKS];
-    {
-        const bf16_t* qp = qkv + (tok0 + qr) * ld_qkv + h * HD + half * 8;
-        const bf16_t* dp = dO + (tok0 + qr) * (size_t)(Hq * HD) + h * HD + half * 8;
-#pragma unroll
-        for (int ks = 0; ks < C::NKS; ++ks) {
-            qf[ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16);
-            dof[ks] = *reinterpret_cast<const bf16x8_t*>(dp + ks * 16);
-        }
-    }
-    const float lse_q = lse[((size_t)b * Hq + h) * S + qr] * 1.4426950408889634f;
-    const float delta_q = delta[((size_t)b * Hq + h) * S + qr];
-    const bf16_t* kbase = qkv + tok0 * ld_qkv + (size_t)Hq * HD + (size_t)kvh * HD;
-    const bf16_t* vbase = kbase + (size_t)Hkv * HD;
-    const bf16_t* ktbase = kt + ((size_t)b * Hkv + kvh) * C::HDP * S_pad;
-
-    f32x16_t acc[C::NMT];
-#pragma unroll
-    for (int t = 0; t < C::NMT; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
-
-    const int k_end = causal ? min(S, q0 + 128) : S;
-    const int ntiles = (k_end + KB - 1) / KB;
-    for (int tile = 0; tile < ntiles; ++tile) {
-        const int key0 = tile * KB;
-        __syncthreads();
-        for (int c = threadIdx.x; c < KB * (HD / 8); c += 256) {
-            const int r = c / (HD / 8), cc = c % (HD / 8);
-            const size_t row = (size_t)min(key0 + r, S - 1) * ld_qkv + cc * 8;
-            *reinterpret_cast<u32x4_t*>(sK + r * C::R_STRIDE + cc * 16) = *reinterpret_cast<const u32x4_t*>(kbase + row);
-            *reinterpret_cast<u32x4_t*>(sV + r * C::R_STRIDE + cc * 16) = *reinterpret_cast<const u32x4_t*>(vbase + row);
-        }
-        for (int c = threadIdx.x; c < C::HDP * (KB / 8); c += 256) {
-            const int r = c / (KB / 8), cc = c % (KB / 8);
-            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(ktbase + (size_t)r * S_pad + key0 + cc * 8);
-            u32x2_t* d = reinterpret_cast<u32x2_t*>(sKt + r * T_STRIDE + cc * 16);
-            d[0] = u32x2_t{v[0], v[1]};
-            d[1] = u32x2_t{v[2], v[3]};
-        }
-        __syncthreads();
-        if (causal && key0 > wq0 + 31) continue;
-
-        bf16x8_t dsf[2][2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            f32x16_t s, dp;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
-#pragma unroll
-            for (int ks = 0; ks < C::NKS; ++ks) {
-                const int off = (t * 32 + l32) * C::R_STRIDE + (ks * 2 + half) * 16;
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(sK + off), qf[ks], s, 0, 0, 0);
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(sV + off), dof[ks], dp, 0, 0, 0);
-            }
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = key0 + t * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
-                const bool ok = key < S && (!causal || key <= qi);
-                const float p = ok ? exp2f(s[e] * scale_log2e - lse_q) : 0.f;
-                dsf[t][e >> 3][e & 7] = (__bf16)(p * (dp[e] - delta_q));
-            }
-        }
-#pragma unroll
-        for (int mt = 0; mt < C::NMT; ++mt)
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        ld_frag_tr(sKt + (mt * 32 + l32) * T_STRIDE + (t * 32 + 16 * j + half * 4) * 2), dsf[t][j],
-                        acc[mt], 0, 0, 0);
-    }
-    if (qi < S) {
-        bf16_t* op = dqkv + (tok0 + qi) * ld_qkv + h * HD;
-#pragma unroll
-        for (int mt = 0; mt < C::NMT; ++mt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int e0 = mt * 32 + g * 8 + half * 4;
-                if (e0 < HD)
-                    *reinterpret_cast<uint2*>(op + e0) =
-                        make_uint2(pack_bf2(acc[mt][g * 4] * scale, acc[mt][g * 4 + 1] * scale),
-                                   pack_bf2(acc[mt][g * 4 + 2] * scale, acc[mt][g * 4 + 3] * scale));
-            }
-    }
-}
 
 // Transposed MFMA operand out of a token-row tile (rows = tokens, head dimension contiguous):
 // the lane ends up with head-dimension row (lane & 31) of the 32-row block the pointer selects
@@ -167,6 +48,134 @@ __device__ __forceinline__ bf16x8_t tr_frag_tok(const unsigned char* p, int stri
 template <int HD> struct TokTile { static constexpr int RS = ((HD + 31) / 32 * 32) * 2 + 48; };
 template <> struct TokTile<80> { static constexpr int RS = 96 * 2 + 16; };
 template <> struct TokTile<64> { static constexpr int RS = 64 * 2 + 16; };
+
+// ------------------------------------------------------------------------- dq
+// A work-group owns 128 queries of one head (a wave 32 of them, one query per lane as the B
+// operand) and walks 64-key tiles.  K and V tiles sit in LDS as token rows: S^T = K Q^T and
+// dP^T = V dO^T read them straight, dQ^T += K^T dS^T reads K through the transposing LDS
+// read.  The next tile's rows are fetched into registers before the current one is computed.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
+                                                          const float* __restrict__ lse, const float* __restrict__ delta,
+                                                          bf16_t* __restrict__ dqkv, int S, int Hq, int Hkv, int ld_qkv,
+                                                          int causal, float scale, float scale_log2e) {
+    typedef BwdCfg<HD> C;
+    constexpr int KB = 64, RS = TokTile<HD>::RS;
+    constexpr int CHUNKS = KB * (HD / 8), ITERS = (CHUNKS + 255) / 256;
+    __shared__ __attribute__((aligned(16))) unsigned char sK[KB * RS];
+    __shared__ __attribute__((aligned(16))) unsigned char sV[KB * RS];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int qb = causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int kvh = h / (Hq / Hkv);
+    const int q0 = qb * 128, wq0 = q0 + wave * 32, qi = wq0 + l32;
+    const size_t tok0 = (size_t)b * S;
+    const int qr = min(qi, S - 1);
+
+    bf16x8_t qf[C::NKS], dof[C::NKS];
+    {
+        const bf16_t* qp = qkv + (tok0 + qr) * ld_qkv + h * HD + half * 8;
+        const bf16_t* dp = dO + (tok0 + qr) * (size_t)(Hq * HD) + h * HD + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < C::NKS; ++ks) {
+            qf[ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16);
+            dof[ks] = *reinterpret_cast<const bf16x8_t*>(dp + ks * 16);
+        }
+    }
+    const float lse_q = lse[((size_t)b * Hq + h) * S + qr] * 1.4426950408889634f;
+    const float delta_q = delta[((size_t)b * Hq + h) * S + qr];
+    const bf16_t* kbase = qkv + tok0 * ld_qkv + (size_t)Hq * HD + (size_t)kvh * HD;
+    const bf16_t* vbase = kbase + (size_t)Hkv * HD;
+    const int tro = tr_lane_off(lane, RS);
+
+    f32x16_t acc[C::NMT];
+#pragma unroll
+    for (int t = 0; t < C::NMT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+
+    u32x4_t rk[ITERS], rv[ITERS];
+    auto fetch = [&](int tile) {
+        const int key0 = tile * KB;
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            const int c = threadIdx.x + i * 256;
+            if (CHUNKS % 256 == 0 || c < CHUNKS) {
+                const int r = c / (HD / 8), cc = c % (HD / 8);
+                const size_t row = (size_t)min(key0 + r, S - 1) * ld_qkv + cc * 8;
+                rk[i] = *reinterpret_cast<const u32x4_t*>(kbase + row);
+                rv[i] = *reinterpret_cast<const u32x4_t*>(vbase + row);
+            }
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) {
+            const int c = threadIdx.x + i * 256;
+            if (CHUNKS % 256 == 0 || c < CHUNKS) {
+                const int r = c / (HD / 8), cc = c % (HD / 8);
+                *reinterpret_cast<u32x4_t*>(sK + r * RS + cc * 16) = rk[i];
+                *reinterpret_cast<u32x4_t*>(sV + r * RS + cc * 16) = rv[i];
+            }
+        }
+    };
+
+    const int k_end = causal ? min(S, q0 + 128) : S;
+    const int ntiles = (k_end + KB - 1) / KB;
+    fetch(0);
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const int key0 = tile * KB;
+        __syncthreads();
+        stash();
+        __syncthreads();
+        if (tile + 1 < ntiles) fetch(tile + 1);
+        if (causal && key0 > wq0 + 31) continue;
+
+        bf16x8_t dsf[2][2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            f32x16_t s, dp;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < C::NKS; ++ks) {
+                const int off = (t * 32 + l32) * RS + (ks * 2 + half) * 16;
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(sK + off), qf[ks], s, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(sV + off), dof[ks], dp, 0, 0, 0);
+            }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = key0 + t * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+                const bool ok = key < S && (!causal || key <= qi);
+                const float p = ok ? exp2f(s[e] * scale_log2e - lse_q) : 0.f;
+                dsf[t][e >> 3][e & 7] = (__bf16)(p * (dp[e] - delta_q));
+            }
+        }
+#pragma unroll
+        for (int mt = 0; mt < C::NMT; ++mt)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        tr_frag_tok(sK + (t * 32 + 16 * j) * RS + mt * 64 + tro, RS), dsf[t][j], acc[mt], 0, 0, 0);
+    }
+    if (qi < S) {
+        bf16_t* op = dqkv + (tok0 + qi) * ld_qkv + h * HD;
+#pragma unroll
+        for (int mt = 0; mt < C::NMT; ++mt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int e0 = mt * 32 + g * 8 + half * 4;
+                if (e0 < HD)
+                    *reinterpret_cast<uint2*>(op + e0) =
+                        make_uint2(pack_bf2(acc[mt][g * 4] * scale, acc[mt][g * 4 + 1] * scale),
+                                   pack_bf2(acc[mt][g * 4 + 2] * scale, acc[mt][g * 4 + 3] * scale));
+            }
+    }
+}
 
 // ---------------------------------------------------------------------- dk, dv
 // A work-group owns 128 keys of one kv head (a wave 32 of them, one key per lane as the B
@@ -315,10 +324,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
 template <int HD>
 hipError_t launch_bwd(hipStream_t st, const AttnBwdArgs& g, const AttnShape& a) {
     const float scale = 1.0f / sqrtf((float)a.hd), sl2 = scale * 1.4426950408889634f;
-    const int sp = attn_s_pad(a.S);
     dim3 gq((a.S + 127) / 128, a.Hq, a.B);
-    attn_bwd_dq_kernel<HD><<<gq, 256, 0, st>>>(g.qkv, g.dO, g.lse, g.delta, g.kt, g.dqkv, a.S, sp, a.Hq, a.Hkv, a.ld_qkv,
-                                               a.causal, scale, sl2);
+    attn_bwd_dq_kernel<HD><<<gq, 256, 0, st>>>(g.qkv, g.dO, g.lse, g.delta, g.dqkv, a.S, a.Hq, a.Hkv, a.ld_qkv, a.causal,
+                                               scale, sl2);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     dim3 gk((a.S + 127) / 128, a.Hkv, a.B);
@@ -332,7 +340,7 @@ hipError_t launch_bwd(hipStream_t st, const AttnBwdArgs& g, const AttnShape& a) 
 hipError_t spk_launch_attention_bwd(hipStream_t st, const AttnBwdArgs& g, const AttnShape& a) {
     if (a.B <= 0 || a.S <= 0) return hipSuccess;
     if (a.Hkv <= 0 || a.Hq % a.Hkv || a.ld_qkv % 8 || a.B > 65535 || a.Hq > 65535) return hipErrorInvalidValue;
-    if (!g.qkv || !g.dO || !g.lse || !g.delta || !g.kt || !g.qt || !g.dot || !g.dqkv) return hipErrorInvalidValue;
+    if (!g.qkv || !g.dO || !g.lse || !g.delta || !g.dqkv) return hipErrorInvalidValue;
     switch (a.hd) {
         case 64: return launch_bwd<64>(st, g, a);
         case 80: return launch_bwd<80>(st, g, a);

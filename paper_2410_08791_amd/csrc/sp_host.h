@@ -47,7 +47,6 @@ struct Workspace {
     size_t dh, da;                         // fp32 [T, d]: stream gradient, norm-output gradient
     size_t dhb;                            // bf16 [Tp, d] copy of dh (GEMM operand)
     size_t dqkv, dob, dz;                  // bf16 gradients of qkv, attention output, SwiGLU output
-    size_t kt, qt, dot;                    // K, Q, dO transposed per head: bf16 [B][H][hd_pad][S_pad]
     size_t part;                           // fp32 [kNormBwdBlocks, d] gain-gradient partials (+ loss partials)
     size_t gslot[kGradSlots];              // fp32 gradient slots
     size_t total;

@@ -101,9 +101,6 @@ void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Wor
         ws->dqkv = take(Tp * nqkv * 2);
         ws->dob = take(Tp * nq * 2);
         ws->dz = take(Tp * f * 2);
-        ws->kt = take((size_t)d->max_batch * d->n_kv_heads * hdp * sp * 2);
-        ws->qt = take((size_t)d->max_batch * d->n_q_heads * hdp * sp * 2);
-        ws->dot = take((size_t)d->max_batch * d->n_q_heads * hdp * sp * 2);
         // partial rows of the two-stage column reductions: gain gradients (d columns), and
         // for the encoder gain + bias (2d) and the linear maps' bias gradients (up to nqkv or f)
         const size_t pcols = d->arch == SP_DECODER_SWIGLU_RMS ? dm : std::max(std::max(2 * dm, nqkv), f);

@@ -99,11 +99,10 @@ hipError_t spk_launch_f32_to_bf16(hipStream_t st, const float* src, bf16_t* dst,
 hipError_t spk_launch_attn_delta(hipStream_t st, const bf16_t* dO, const bf16_t* O, float* delta, int B, int S,
                                  int Hq, int hd);
 // Attention backward.  qkv, dO, lse, delta as produced by the forward / the launchers above;
-// kt, qt, dot: K, Q and dO transposed per head (spk_launch_transpose_heads).  Writes dq, dk, dv
+// Writes dq, dk, dv
 // into dqkv (same layout as qkv, bf16).
 struct AttnBwdArgs {
     const bf16_t* qkv; const bf16_t* dO; const float* lse; const float* delta;
-    const bf16_t* kt; const bf16_t* qt; const bf16_t* dot;
     bf16_t* dqkv;
 };
 hipError_t spk_launch_attention_bwd(hipStream_t st, const AttnBwdArgs& g, const AttnShape& a);

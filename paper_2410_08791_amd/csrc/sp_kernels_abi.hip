@@ -77,8 +77,7 @@ static size_t al256(size_t v) { return (v + 255) / 256 * 256; }
 
 extern "C" size_t spk_attention_bwd_scratch_bytes(int B, int S, int Hq, int Hkv, int hd) {
     if (B < 1 || S < 1 || Hq < 1 || Hkv < 1 || hd < 1) return 0;
-    const size_t per = (size_t)attn_hd_pad(hd) * attn_s_pad(S) * 2;
-    return al256((size_t)B * Hq * S * 4) + al256(B * Hkv * per) + 2 * al256(B * Hq * per);
+    return al256((size_t)B * Hq * S * 4);     // delta = rowsum(dO * O)
 }
 
 extern "C" int spk_attention_bwd(void* stream, const uint16_t* qkv, const uint16_t* o, const uint16_t* dO,
@@ -87,23 +86,11 @@ extern "C" int spk_attention_bwd(void* stream, const uint16_t* qkv, const uint16
     if (!qkv || !o || !dO || !lse || !scratch || !dqkv || B < 1 || S < 1 || Hq < 1 || Hkv < 1) return SP_ERR_INVALID_ARG;
     if (hd != 64 && hd != 80 && hd != 128) return SP_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    const int nq = Hq * hd, nqkv = (Hq + 2 * Hkv) * hd;
-    const size_t per = (size_t)attn_hd_pad(hd) * attn_s_pad(S) * 2;
-    unsigned char* p = static_cast<unsigned char*>(scratch);
-    float* delta = reinterpret_cast<float*>(p);
-    p += al256((size_t)B * Hq * S * 4);
-    bf16_t* kt = reinterpret_cast<bf16_t*>(p);
-    p += al256(B * Hkv * per);
-    bf16_t* qt = reinterpret_cast<bf16_t*>(p);
-    p += al256(B * Hq * per);
-    bf16_t* dot = reinterpret_cast<bf16_t*>(p);
-    AttnShape a{B, S, Hq, Hkv, hd, causal, nqkv};
+    float* delta = static_cast<float*>(scratch);
+    AttnShape a{B, S, Hq, Hkv, hd, causal, (Hq + 2 * Hkv) * hd};
     hipError_t e = spk_launch_attn_delta(s, dO, o, delta, B, S, Hq, hd);
-    if (e == hipSuccess) e = spk_launch_transpose_heads(s, qkv, nqkv, nq, Hkv, B, S, hd, kt);
-    if (e == hipSuccess) e = spk_launch_transpose_heads(s, qkv, nqkv, 0, Hq, B, S, hd, qt);
-    if (e == hipSuccess) e = spk_launch_transpose_heads(s, dO, nq, 0, Hq, B, S, hd, dot);
     if (e != hipSuccess) return st(e);
-    AttnBwdArgs g{qkv, dO, lse, delta, kt, qt, dot, dqkv};
+    AttnBwdArgs g{qkv, dO, lse, delta, dqkv};
     return st(spk_launch_attention_bwd(s, g, a));
 }
 

@@ -195,9 +195,6 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     bf16_t* dz = e->wsp<bf16_t>(e->ws.dz);
     bf16_t* dob = e->wsp<bf16_t>(e->ws.dob);
     bf16_t* dqkv = e->wsp<bf16_t>(e->ws.dqkv);
-    bf16_t* kt = e->wsp<bf16_t>(e->ws.kt);
-    bf16_t* qt = e->wsp<bf16_t>(e->ws.qt);
-    bf16_t* dot = e->wsp<bf16_t>(e->ws.dot);
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
     GemmArgs g;
 
@@ -268,10 +265,7 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     g = GemmArgs{dhb, dm, OP_KMAJOR, W(t_wo), nq, OP_RMAJOR, dob, nq, nullptr, 0, nullptr, T, nq, dm, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
     SP_HIP(e, spk_launch_attn_delta(st, dob, o, delta, B, S, d.n_q_heads, d.head_dim));
-    SP_HIP(e, spk_launch_transpose_heads(st, qkv, nqkv, nq, d.n_kv_heads, B, S, d.head_dim, kt));
-    SP_HIP(e, spk_launch_transpose_heads(st, qkv, nqkv, 0, d.n_q_heads, B, S, d.head_dim, qt));
-    SP_HIP(e, spk_launch_transpose_heads(st, dob, nq, 0, d.n_q_heads, B, S, d.head_dim, dot));
-    AttnBwdArgs ab{qkv, dob, lse, delta, kt, qt, dot, dqkv};
+    AttnBwdArgs ab{qkv, dob, lse, delta, dqkv};
     SP_HIP(e, spk_launch_attention_bwd(st, ab, as));
     if (!dec && (rc = bias_grad(dqkv, nqkv, SP_T_BQKV)) != SP_OK) return rc;
     // dWqkv[nqkv,d] = dqkv^T a
