@@ -228,10 +228,10 @@ def main():
     gemm_ms = kst.big_gemm_ms_sum / max(kst.big_gemm_launches, 1)
     gemm_flops = 2.0 * gm * gn * gk
     achieved_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
-    kname = ("gemm_kernel<EPI_BF16> (first MLP projection, bias epilogue)" if training and w.arch == "encoder" else
-             "gemm_kernel<EPI_BF16> (gate/up projection)" if training else
-             "gemm_kernel<EPI_SWIGLU_BF16> (gate/up projection)" if w.arch == "decoder" else
-             "gemm_kernel<EPI_GELU_BF16> (first MLP projection)")
+    kname = ("gemm_dma_kernel<EPI_BF16> (first MLP projection, bias epilogue)" if training and w.arch == "encoder" else
+             "gemm_dma_kernel<EPI_BF16> (gate/up projection)" if training else
+             "gemm_dma_kernel<EPI_SWIGLU_BF16> (gate/up projection)" if w.arch == "decoder" else
+             "gemm_dma_kernel<EPI_GELU_BF16> (first MLP projection)")
     roofline = {"bound": "mfma", "kernel": kname,
                 "achieved": round(achieved_tf, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved_tf / PEAK_BF16_TFLOPS, 4), "traffic": None,

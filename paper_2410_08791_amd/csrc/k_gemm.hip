@@ -2,13 +2,17 @@
 // accumulate, used for every dense projection of a layer (QKV, O, gate/up,
 // down) and for the backward contractions.
 //
-// Work-group = 256 threads = 4 waves in a 2x2 grid; block tile BM x BN x 64,
-// each wave owns (BM/2) x (BN/2) as 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16).
+// Work-group = 4 or 8 waves in a 2 x (waves/2) grid; block tile BM x BN x 64,
+// each wave owns its share as 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16).
 // Both operand tiles are staged in LDS with the contraction index contiguous
 // (128-byte rows, 16-byte chunks XOR-swizzled so that both the 16-byte stores
 // and the per-lane 16-byte fragment loads spread over all banks), double
-// buffered: global loads for tile t+1 are issued before the MFMAs of tile t and
-// stored to the other buffer afterwards, one barrier per tile.
+// buffered.  Two kernels build that LDS image: gemm_dma_kernel (global loads
+// that write LDS directly; used whenever both operands have the contraction
+// index contiguous, i.e. every forward projection) and gemm_kernel (register
+// staging: global loads for tile t+1 are issued before the MFMAs of tile t and
+// stored to the other buffer afterwards, one barrier per tile; takes every
+// operand form).
 //
 // The MFMA is issued "transposed" (weights as the A operand, activations as B)
 // so that a lane's four consecutive accumulator registers are four consecutive
@@ -345,28 +349,41 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_kernel(GemmDev p) {
     gemm_epilogue<EPI, TM, TN>(p, acc, m0 + wm * (BM / 2), SWIGLU ? n0 + wn * (WN / 2) : n0 + wn * WN, l32, half);
 }
 
-// ---- LDS-DMA variant: 256x256 tile, 32-deep stages, 4-stage ring ---------------------
-// Global loads write LDS directly (global_load_lds_dwordx4): no staging registers, no LDS
-// store instructions, and three tiles in flight instead of one.  A wave instruction lands
-// 64 lanes x 16 bytes = 16 tile rows of 64 bytes contiguously, so the XOR swizzle of the
-// 16-byte chunks is applied on the global side (which chunk a lane fetches).  The compiler
-// does not track these loads against later LDS reads, so the kernel counts them itself:
-// every iteration issues the same number of loads per thread (the tail re-fetches the last
-// tile into an idle stage) and waits with an explicit vmcnt before the barrier.
-constexpr int DBK = 32, DROW = 64, DSTAGES = 4;
-
+// ---- LDS-DMA kernel (both operands contraction-contiguous) ----------------------------------
+// Global loads write LDS directly (global_load_lds_dwordx4): no staging registers and no
+// ds_write instructions.  Measured on MI355X, LDS writes issued by the waves run at about
+// 75 bytes/clk per CU and serialise with the fragment reads (215 bytes/clk), so a 256x256x64
+// tile costs ~870 + ~900 LDS cycles against 2048 MFMA cycles; the DMA writes overlap the reads.
+// A wave instruction lands 64 lanes x 16 bytes = 8 tile rows of 128 bytes contiguously, so the
+// XOR swizzle of the 16-byte chunks is applied on the global side (which chunk a lane fetches);
+// the LDS image is the one the register-staged kernel builds.
+//
+// Two 64-deep stages.  The only barrier of a tile sits before its LAST k-step: by then a wave
+// has read all its fragments of the tile (the last step's are in registers) and its loads of the
+// next tile, issued one tile earlier, have landed, so after the barrier the other stage is
+// readable and this stage is free.  The last step then runs with the first fragments of the
+// next tile being read under its MFMAs: nothing that follows the barrier waits on memory.
+// The loads of a tile are spread over three k-steps (after the barrier, then steps 0 and 1 of
+// the next tile): issued in one burst they fill the address unit's queue and stall the
+// wave's MFMAs behind them (253 -> 231 us on the gate/up shape with zero operands).
+// The compiler does not order these loads against later LDS reads; the kernel waits with
+// explicit vmcnt/lgkmcnt counts and uses a bare s_barrier (the fence of __syncthreads() is
+// what the counts replace).
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
-template <int EPI, int WAVES>
+template <int BM, int BN, int EPI, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int BM = 256, BN = 256;
     constexpr int WNC = WAVES / 2, WN = BN / WNC;
     constexpr int TM = BM / 64, TN = WN / 32;
-    constexpr int A_BYTES = BM * DROW, STAGE = (BM + BN) * DROW;
+    constexpr int A_BYTES = BM * ROW_BYTES, STAGE = (BM + BN) * ROW_BYTES;
     constexpr bool SWIGLU = (EPI == EPI_SWIGLU_BF16);
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
-    constexpr int NI = 32 / WAVES;             // 1 KiB load instructions per wave and stage
+    constexpr int NBLK_A = BM / 8, NBLK = (BM + BN) / 8;   // 1 KiB load blocks (8 tile rows each)
+    constexpr int NI = NBLK / WAVES;           // load instructions per wave and stage
+    constexpr int N_AFTER = (3 * NI + 7) / 8;  // of those: issued right after the barrier,
+    constexpr int N_STEP0 = N_AFTER < NI - N_AFTER ? N_AFTER : NI - N_AFTER;   // in step 0 (rest: step 1)
+    static_assert(NBLK % WAVES == 0, "whole load blocks per wave");
     static_assert(!SWIGLU || (TN % 2 == 0), "gate and up tiles pair up inside a wave");
 
     const int lane = threadIdx.x & 63;
@@ -383,15 +400,16 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
     const int tn = (pid % group) / gm;
     const int m0 = tm * BM, n0 = tn * BN_OUT;
 
-    // load assignment: block b of 16 tile rows, b < 16 -> A rows, else W rows
+    // load assignment: block b of 8 tile rows, b < BM/8 -> A rows, else W rows.  Lane l lands at
+    // row l>>3, 16-byte position l&7 of the block, and fetches the chunk that the swizzle puts there.
     const bf16_t* src[NI];
     int dst[NI];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int blk = wave * NI + i;
-        const bool is_w = blk >= 16;
-        const int row = (blk & 15) * 16 + (lane >> 2);
-        const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+        const bool is_w = blk >= NBLK_A;
+        const int row = (is_w ? blk - NBLK_A : blk) * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
         if (is_w) {
             int grow;
             if (SWIGLU) {
@@ -406,21 +424,23 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
         } else {
             src[i] = p.A + (size_t)min(m0 + row, p.M - 1) * p.lda + chunk * 8;
         }
-        dst[i] = (is_w ? A_BYTES : 0) + (blk & 15) * 16 * DROW;
+        dst[i] = blk * 8 * ROW_BYTES;
     }
-    const int KT = p.K / DBK;
+    const int KT = p.K / BK;
     // (The builtin's address-space-qualified parameters do not type-check in the host pass
     // of a template, which would silently drop the kernel's host stub: device pass only.)
 #if defined(__HIP_DEVICE_COMPILE__)
-#define SP_DMA_ISSUE(tile, stage)                                                                              \
+#define SP_DMA_ISSUE(tile, stage) SP_DMA_ISSUE_R(tile, stage, 0, NI)
+#define SP_DMA_ISSUE_R(tile, stage, i0, i1)                                                                   \
     do {                                                                                                       \
-        const int k0_ = min((tile), KT - 1) * DBK;                                                             \
-        _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_)                                                      \
+        const int k0_ = min((tile), KT - 1) * BK;                                                              \
+        _Pragma("unroll") for (int i_ = (i0); i_ < (i1); ++i_)                                                 \
             __builtin_amdgcn_global_load_lds(src[i_] + k0_, (lds_void_ptr)(smem + (stage) * STAGE + dst[i_]), \
                                              16, 0, 0);                                                        \
     } while (0)
 #else
 #define SP_DMA_ISSUE(tile, stage) ((void)src, (void)dst)
+#define SP_DMA_ISSUE_R(tile, stage, i0, i1) ((void)src, (void)dst)
 #endif
 
     f32x16_t acc[TN][TM];
@@ -431,69 +451,96 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
 
-    const int sw = (l32 >> 2) & 3;
-    int foff[2];
+    const int sw = (l32 >> 1) & 7;
+    int foff[4];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) foff[ks] = l32 * DROW + (((2 * ks + half) ^ sw) << 4);
-    const int a_base = wm * (BM / 2) * DROW;
-    const int w_base = A_BYTES + wn * WN * DROW;
+    for (int ks = 0; ks < 4; ++ks) foff[ks] = l32 * ROW_BYTES + (((2 * ks + half) ^ sw) << 4);
+    const int a_base = wm * (BM / 2) * ROW_BYTES;
+    const int w_base = A_BYTES + wn * WN * ROW_BYTES;
+
+    constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
+    constexpr int M_MFMA = 0x008, M_VMEM_RD = 0x020, M_DS_RD = 0x100;
+    // s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt<<4 | lgkmcnt<<8 | vmcnt[5:4]<<14)
+    constexpr int WAIT_VM0_LGKM0 = (0 & 15) | (7 << 4) | (0 << 8) | (0 << 14);
+    constexpr int WAIT_VM_AFTER = (N_AFTER & 15) | (7 << 4) | (15 << 8) | ((N_AFTER >> 4) << 14);
+
+    bf16x8_t af[2][TM], wf[2][TN];
+    auto load_frags = [&](const unsigned char* tile, int ks, int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            af[buf][i] = *reinterpret_cast<const bf16x8_t*>(tile + a_base + i * 32 * ROW_BYTES + foff[ks]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            wf[buf][j] = *reinterpret_cast<const bf16x8_t*>(tile + w_base + j * 32 * ROW_BYTES + foff[ks]);
+    };
+    auto mfmas = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], af[buf][i], acc[j][i], 0, 0, 0);
+    };
 
     SP_DMA_ISSUE(0, 0);
-    SP_DMA_ISSUE(1, 1);
-    SP_DMA_ISSUE(2, 2);
-    constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
-    constexpr int M_MFMA = 0x008, M_DS_RD = 0x100;
-    // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt 7<<4 | lgkmcnt 15<<8 | vmcnt[5:4]<<14)
-    constexpr int VM_KEEP = 2 * NI;
-    constexpr int WAIT_IMM = (VM_KEEP & 15) | (7 << 4) | (15 << 8) | ((VM_KEEP >> 4) << 14);
+    SP_DMA_ISSUE_R(1, 1, 0, N_AFTER);
+    __builtin_amdgcn_s_waitcnt(WAIT_VM_AFTER);      // this thread's loads of tile 0 have landed
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    load_frags(smem, 0, 0);
     for (int kt = 0; kt < KT; ++kt) {
-        // This thread's loads of tile kt have landed; after the barrier everyone's have, and
-        // stage (kt+3)&3 is idle.  A bare s_barrier: the fence of __syncthreads() would wait
-        // for ALL outstanding LDS-DMA loads and empty the pipeline.  The empty asm statements
-        // keep the compiler from moving LDS accesses across it.
-        __builtin_amdgcn_s_waitcnt(WAIT_IMM);
+        unsigned char* cur = smem + (kt & 1) * STAGE;
+        unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+        // the rest of tile kt+1's loads (its first N_AFTER went out after the last barrier)
+        SP_DMA_ISSUE_R(kt + 1, (kt + 1) & 1, N_AFTER, N_AFTER + N_STEP0);
+        load_frags(cur, 1, 1);
+        mfmas(0);
+        SP_DMA_ISSUE_R(kt + 1, (kt + 1) & 1, N_AFTER + N_STEP0, NI);
+        load_frags(cur, 2, 0);
+        mfmas(1);
+        load_frags(cur, 3, 1);
+        mfmas(0);
+#define SP_SCHED_STEP(NV)                                                                  \
+        _Pragma("unroll") for (int i = 0; i < NFRAG; ++i) {                                    \
+            __builtin_amdgcn_sched_group_barrier(M_DS_RD, 1, 0);                               \
+            __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA / NFRAG, 0);                    \
+            if (i < (NV)) __builtin_amdgcn_sched_group_barrier(M_VMEM_RD, 1, 0);                  \
+        }                                                                                      \
+        if (NMFMA % NFRAG) __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA % NFRAG, 0);
+        SP_SCHED_STEP(N_STEP0)
+        SP_SCHED_STEP(NI - N_AFTER - N_STEP0)
+        SP_SCHED_STEP(0)
+#undef SP_SCHED_STEP
+        // This wave's reads of tile kt are complete and its loads of tile kt+1 (issued one tile
+        // ago) have landed; after the barrier that holds for every wave, so the other stage is
+        // readable and this stage may be refilled.
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0_LGKM0);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        SP_DMA_ISSUE(kt + 3, (kt + 3) & 3);
-        const unsigned char* cur = smem + (kt & 3) * STAGE;
-        bf16x8_t af[2][TM], wf[2][TN];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                af[ks][i] = *reinterpret_cast<const bf16x8_t*>(cur + a_base + i * 32 * DROW + foff[ks]);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                wf[ks][j] = *reinterpret_cast<const bf16x8_t*>(cur + w_base + j * 32 * DROW + foff[ks]);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks][j], af[ks][i], acc[j][i], 0, 0, 0);
-        // first step's fragments up front, the second step's reads under the first step's MFMAs
-        __builtin_amdgcn_sched_group_barrier(M_DS_RD, NFRAG, 0);
+        SP_DMA_ISSUE_R(kt + 2, kt & 1, 0, N_AFTER);
+        load_frags(nxt, 0, 0);
+        mfmas(1);
 #pragma unroll
         for (int i = 0; i < NFRAG; ++i) {
             __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA / NFRAG, 0);
             __builtin_amdgcn_sched_group_barrier(M_DS_RD, 1, 0);
         }
+        if (NMFMA % NFRAG) __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA % NFRAG, 0);
     }
-    __builtin_amdgcn_s_waitcnt((0 & 15) | (7 << 4) | (15 << 8));   // drain the tail's idle loads
+    __builtin_amdgcn_s_waitcnt(WAIT_VM0_LGKM0);   // drain the tail's idle loads
     gemm_epilogue<EPI, TM, TN>(p, acc, m0 + wm * (BM / 2), SWIGLU ? n0 + wn * (WN / 2) : n0 + wn * WN, l32, half);
 #undef SP_DMA_ISSUE
+#undef SP_DMA_ISSUE_R
 }
 
-template <int EPI, int WAVES>
+template <int BM, int BN, int EPI, int WAVES>
 hipError_t launch_dma(hipStream_t st, const GemmArgs& g) {
-    constexpr int LDS = DSTAGES * 512 * DROW;
-    constexpr int BN_OUT = (EPI == EPI_SWIGLU_BF16) ? 128 : 256;
+    constexpr int LDS = 2 * (BM + BN) * ROW_BYTES;
+    constexpr int BN_OUT = (EPI == EPI_SWIGLU_BF16) ? BN / 2 : BN;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<EPI, WAVES>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<BM, BN, EPI, WAVES>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -502,9 +549,9 @@ hipError_t launch_dma(hipStream_t st, const GemmArgs& g) {
     d.A = g.A; d.W = g.W; d.C = g.C; d.R = g.R; d.bias = g.bias;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc; d.ldr = g.ldr;
     d.M = g.M; d.N = g.N; d.K = g.K;
-    d.tilesM = (g.M + 255) / 256;
+    d.tilesM = (g.M + BM - 1) / BM;
     d.tilesN = (g.N + BN_OUT - 1) / BN_OUT;
-    gemm_dma_kernel<EPI, WAVES><<<d.tilesM * d.tilesN, WAVES * 64, LDS, st>>>(d);
+    gemm_dma_kernel<BM, BN, EPI, WAVES><<<d.tilesM * d.tilesN, WAVES * 64, LDS, st>>>(d);
     return hipGetLastError();
 }
 
@@ -532,27 +579,47 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
     return hipGetLastError();
 }
 
-// Tile shapes: 1 = 128x128, 2 = 128x256 (BM x BN), 3 = 256x256, 4 = 256x256 with 8 waves,
-// 5/6 = the LDS-DMA kernel with 8/4 waves (contraction-contiguous operands only).
-// Measured on MI355X over the workloads' shapes: the 8-wave 256x256 tile (two waves per SIMD
-// hide each other's stalls) wins once it yields about 150 work-groups (256 CUs), else
-// 128x128 (two groups per CU).
-int pick_tile(int M, int N, int epi) {
-    const int n_out_256 = (epi == EPI_SWIGLU_BF16) ? 128 : 256;
-    const long t256 = (long)((M + 255) / 256) * ((N + n_out_256 - 1) / n_out_256);
-    return t256 >= 150 ? 4 : 1;
+// Tile ids: register-staged kernel 1 = 128x128, 2 = 128x256 (BM x BN), 3 = 256x256 (4 waves each),
+// 4 = 256x256 with 8 waves; LDS-DMA kernel (contraction-contiguous operands only) 5 = 256x256 and
+// 6 = 128x256 with 8 waves, 7 = 128x128 with 4 waves (two work-groups per CU).
+//
+// Choice (shapes only, so a stack's kernels never depend on the streaming window): the chip
+// runs 256 work-groups at a time (512 of tile 7), so a launch costs
+// ceil(tiles / concurrent) rounds of one tile's time; a tile's time is its area over a measured
+// relative efficiency (larger tiles move fewer operand bytes per MFMA).  Take the cheapest.
+struct TileCost { int id, bm, bn, concurrent; float eff; };
+constexpr TileCost kDmaTiles[] = {{5, 256, 256, 256, 1.00f}, {6, 128, 256, 256, 0.72f}, {7, 128, 128, 512, 0.70f}};
+constexpr TileCost kRegTiles[] = {{4, 256, 256, 256, 1.00f}, {1, 128, 128, 512, 0.66f}};
+
+template <int NC>
+int pick_tile(const TileCost (&cand)[NC], int M, int N, int epi) {
+    int best = cand[0].id;
+    float best_cost = 0.f;
+    for (int c = 0; c < NC; ++c) {
+        const TileCost& t = cand[c];
+        const int bn_out = (epi == EPI_SWIGLU_BF16) ? t.bn / 2 : t.bn;
+        const long tiles = (long)((M + t.bm - 1) / t.bm) * ((N + bn_out - 1) / bn_out);
+        const long rounds = (tiles + t.concurrent - 1) / t.concurrent;
+        // a round of the two-per-CU tile holds two tiles per CU
+        const float cost = (float)rounds * (t.concurrent / 256) * (float)(t.bm * t.bn) / t.eff;
+        if (c == 0 || cost < best_cost) { best = t.id; best_cost = cost; }
+    }
+    return best;
 }
 
 template <int EPI, int AFORM, int WFORM>
 hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
-    int tile = g.tile ? g.tile : pick_tile(g.M, g.N, EPI);
+    constexpr bool DMA_OK = (AFORM == OP_KMAJOR && WFORM == OP_KMAJOR);
+    int tile = g.tile ? g.tile : DMA_OK ? pick_tile(kDmaTiles, g.M, g.N, EPI) : pick_tile(kRegTiles, g.M, g.N, EPI);
+    if (!DMA_OK && tile >= 5 && tile <= 7) tile = tile == 5 ? 4 : tile == 6 ? 2 : 1;   // same shape, register-staged
     switch (tile) {
         case 1: return launch_one<128, 128, EPI, AFORM, WFORM, 4>(st, g);
         case 2: return launch_one<128, 256, EPI, AFORM, WFORM, 4>(st, g);
         case 3: return launch_one<256, 256, EPI, AFORM, WFORM, 4>(st, g);
         case 4: return launch_one<256, 256, EPI, AFORM, WFORM, 8>(st, g);
-        case 5: if (AFORM == OP_KMAJOR && WFORM == OP_KMAJOR) return launch_dma<EPI, 8>(st, g); break;
-        case 6: if (AFORM == OP_KMAJOR && WFORM == OP_KMAJOR) return launch_dma<EPI, 4>(st, g); break;
+        case 5: if (DMA_OK) return launch_dma<256, 256, EPI, 8>(st, g); break;
+        case 6: if (DMA_OK) return launch_dma<128, 256, EPI, 8>(st, g); break;
+        case 7: if (DMA_OK) return launch_dma<128, 128, EPI, 4>(st, g); break;
     }
     return hipErrorInvalidValue;
 }

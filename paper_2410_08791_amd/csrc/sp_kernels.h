@@ -26,7 +26,7 @@ struct GemmArgs {
     const float* R; int ldr;                // EPI_RESID_F32
     const bf16_t* bias;                     // [N] or nullptr
     int M, N, K;
-    int tile;                               // 0 = heuristic, else 1..3 = forced tile shape
+    int tile;                               // 0 = heuristic, else 1..7 = forced kernel and tile shape
 };
 
 // C[M,N] = sum_k A(m,k) W(n,k), bf16 operands, fp32 accumulate on MFMA.

@@ -52,7 +52,7 @@ def gemm_ref(A, W, epi, R=None, bias=None, N=None):
     return acc
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 0])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6, 7, 0])
 @pytest.mark.parametrize("M,N,K", [(200, 328, 128), (257, 296, 64), (300, 520, 256), (64, 128, 1024)])
 @pytest.mark.parametrize("epi", [sp.EPI_BF16, sp.EPI_RESID_F32, sp.EPI_GELU_BF16, sp.EPI_SWIGLU_BF16, sp.EPI_F32])
 def test_gemm_kmajor(epi, M, N, K, tile):
@@ -77,7 +77,7 @@ def test_gemm_kmajor(epi, M, N, K, tile):
     assert np.all(np.abs(got - ref) <= tol + 1e-6), float(np.max(np.abs(got - ref)))
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 6, 0])
 @pytest.mark.parametrize("M,N,K", [(200, 328, 128), (264, 520, 192)])
 def test_gemm_transposed_operands(M, N, K, tile):
     """The backward forms: dX = dY W (weight read with its row index contiguous) and
