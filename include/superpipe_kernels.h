@@ -47,10 +47,8 @@ int spk_gemm(void* stream, int epilogue, const uint16_t* A, int lda, int a_form,
 int spk_swiglu(void* stream, const uint16_t* gu, uint16_t* z, int T, int f);
 
 /* Attention over a fused activation qkv bf16 [B*S, (Hq+2Hkv)*hd] (query heads,
- * then key heads, then value heads).  vt_scratch: bf16, spk_attention_scratch_elems
- * elements.  o bf16 [B*S, Hq*hd].  lse fp32 [B,Hq,S] or NULL.  hd in {64,80,128}. */
-size_t spk_attention_scratch_elems(int B, int S, int Hkv, int hd);
-int spk_attention(void* stream, const uint16_t* qkv, uint16_t* vt_scratch, uint16_t* o, float* lse,
+ * then key heads, then value heads).  o bf16 [B*S, Hq*hd].  lse fp32 [B,Hq,S] or NULL.  hd in {64,80,128}. */
+int spk_attention(void* stream, const uint16_t* qkv, uint16_t* o, float* lse,
                   int B, int S, int Hq, int Hkv, int hd, int causal);
 
 /* ---- decode steps (one new token per sequence against a key/value cache) ---- */

@@ -10,8 +10,10 @@
 // bf16 in place -- already sit in the B-operand layout of the second product
 // O^T = V^T P^T.  (The contraction order over keys inside a 16-key MFMA step is
 // a fixed permutation; V^T fragments are fetched with the same permutation.)
-// V is needed with keys contiguous, so a small pass transposes it once per
-// layer into [B][Hkv][hd_pad][S_pad], zero padded.
+// V tiles are staged as they lie in memory (one row per key) and the V^T
+// fragments come out of the transposing LDS read ds_read_b64_tr_b16, which hands
+// a lane four consecutive keys of one head_dim element: no transposed copy of V
+// exists anywhere.
 #include "sp_kernels.h"
 
 namespace {
@@ -25,21 +27,26 @@ struct AttnCfg {
     static constexpr int NMT = (HD + 31) / 32;      // 32-row tiles of O^T
     static constexpr int HDP = NMT * 32;
     static constexpr int K_STRIDE = HD * 2 + 16;    // bytes per key row in LDS (padded)
-    static constexpr int V_STRIDE = KB * 2 + 8;     // bytes per V^T row in LDS (padded)
+    // bytes per value row in LDS: at least HDP elements (the fragment reads of a padded
+    // head_dim stay inside the row) and = 64 mod 128, so that the four key rows a 16-lane
+    // group touches in one transposing read fall into different 64-byte bank groups
+    static constexpr int V_STRIDE = (HDP * 2 + 63) / 128 * 128 + 64;
     static constexpr int K_BYTES = KB * K_STRIDE;
-    static constexpr int V_BYTES = HDP * V_STRIDE;
+    static constexpr int V_BYTES = KB * V_STRIDE;
     static constexpr int CHUNKS_K = KB * (HD / 8);  // 16-byte chunks of a K tile
-    static constexpr int CHUNKS_V = HDP * (KB / 8);
+    static constexpr int CHUNKS_V = CHUNKS_K;
 };
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
 
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
-                                                       const bf16_t* __restrict__ vt,
                                                        bf16_t* __restrict__ o, float* __restrict__ lse,
-                                                       int S, int S_pad, int Hq, int Hkv, int ld_qkv,
+                                                       int S, int Hq, int Hkv, int ld_qkv,
                                                        int causal, float scale_log2e) {
     typedef AttnCfg<HD> C;
-    // two K tiles then two V^T tiles (double buffered)
+    // two K tiles then two V tiles (double buffered)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -66,7 +73,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
         for (int ks = 0; ks < C::NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16);
     }
     const bf16_t* kbase = qkv + tok0 * ld_qkv + (size_t)Hq * HD + (size_t)kvh * HD;
-    const bf16_t* vbase = vt + ((size_t)b * Hkv + kvh) * C::HDP * S_pad;
+    const bf16_t* vbase = kbase + (size_t)Hkv * HD;
 
     f32x16_t oacc[C::NMT];
 #pragma unroll
@@ -74,6 +81,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[t][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
+
+    // per-lane part of the V fragment address: key row (s>>2) of a step, elements
+    // 16 * ((lane>>4)&1) + 4 * (s&3) .. +3 of a 32-element tile, s = lane & 15
+    const int v_lane_off = ((lane & 15) >> 2) * C::V_STRIDE + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 
     const int k_end = causal ? min(S, q0 + QB) : S;
     const int ntiles = (k_end + KB - 1) / KB;
@@ -96,8 +107,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
         for (int i = 0; i < NV; ++i) {
             const int c = threadIdx.x + i * 256;
             if (c < C::CHUNKS_V) {
-                const int r = c / (KB / 8), cc = c % (KB / 8);
-                rv[i] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)r * S_pad + key0 + cc * 8);
+                const int r = c / (HD / 8), cc = c % (HD / 8);
+                rv[i] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)min(key0 + r, S - 1) * ld_qkv + cc * 8);
             }
         }
     };
@@ -116,10 +127,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
         for (int i = 0; i < NV; ++i) {
             const int c = threadIdx.x + i * 256;
             if (c < C::CHUNKS_V) {
-                const int r = c / (KB / 8), cc = c % (KB / 8);
-                u32x2_t* d = reinterpret_cast<u32x2_t*>(dV + r * C::V_STRIDE + cc * 16);
-                d[0] = u32x2_t{rv[i][0], rv[i][1]};
-                d[1] = u32x2_t{rv[i][2], rv[i][3]};
+                const int r = c / (HD / 8), cc = c % (HD / 8);
+                *reinterpret_cast<u32x4_t*>(dV + r * C::V_STRIDE + cc * 16) = rv[i];
             }
         }
     };
@@ -191,17 +200,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
                 for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
         }
         // ---- O^T += V^T P^T.  Step (t, j) contracts keys
-        //      t*32 + 16j + {half*4 + 0..3, 8 + half*4 + 0..3}.
+        //      t*32 + 16j + {half*4 + 0..3, 8 + half*4 + 0..3}.  The transposing read works on
+        //      groups of 16 lanes: lane s of a group points at key row (s>>2) of the step's four
+        //      and at 4 head_dim elements, and receives four consecutive keys of ITS element
+        //      (16 * (group & 1) + s within the 32-row tile).
 #pragma unroll
         for (int mt = 0; mt < C::NMT; ++mt)
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const unsigned char* vp = sV + (mt * 32 + l32) * C::V_STRIDE + (t * 32 + 16 * j + half * 4) * 2;
-                    const u32x2_t lo = *reinterpret_cast<const u32x2_t*>(vp);
-                    const u32x2_t hi = *reinterpret_cast<const u32x2_t*>(vp + 16);
-                    const u32x4_t both = u32x4_t{lo[0], lo[1], hi[0], hi[1]};
+                    const unsigned char* vp = sV + (t * 32 + 16 * j + half * 4) * C::V_STRIDE + mt * 64 + v_lane_off;
+                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
+                    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * C::V_STRIDE));
+                    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+                    const s16x8_t both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                     oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, both),
                                                                        pf[t][j], oacc[mt], 0, 0, 0);
                 }
@@ -230,30 +243,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
     }
 }
 
-// dst[b][h][e][s] = src[(b*S+s)*ld + col0 + h*hd + e]: 64x64 tiles through LDS.
-__global__ __launch_bounds__(256) void transpose_heads_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
-                                                              int S, int S_pad, int nheads, int hd, int hdp, int ld,
-                                                              int col0) {
-    __shared__ bf16_t tile[64][66];
-    const int s0 = blockIdx.x * 64, e0 = blockIdx.y * 64;
-    const int bh = blockIdx.z, b = bh / nheads, hh = bh % nheads;
-    const bf16_t* sp = src + (size_t)b * S * ld + col0 + (size_t)hh * hd;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int r = ty; r < 64; r += 4) {
-        const int s = s0 + r, e = e0 + tx;
-        tile[r][tx] = (s < S && e < hd) ? sp[(size_t)s * ld + e] : (bf16_t)0;
-    }
-    __syncthreads();
-    bf16_t* dp = dst + (size_t)bh * hdp * S_pad;
-    for (int r = ty; r < 64; r += 4) {
-        const int e = e0 + r, s = s0 + tx;
-        if (e < hdp && s < S_pad) dp[(size_t)e * S_pad + s] = tile[tx][r];
-    }
-}
-
 template <int HD>
-hipError_t launch_fwd(hipStream_t st, dim3 grid, const bf16_t* qkv, const bf16_t* vt, bf16_t* o, float* lse,
-                      const AttnShape& a, int sp, float sl2) {
+hipError_t launch_fwd(hipStream_t st, dim3 grid, const bf16_t* qkv, bf16_t* o, float* lse,
+                      const AttnShape& a, float sl2) {
     typedef AttnCfg<HD> C;
     constexpr int LDS = 2 * (C::K_BYTES + C::V_BYTES);
     static bool attr_set = false;
@@ -263,38 +255,22 @@ hipError_t launch_fwd(hipStream_t st, dim3 grid, const bf16_t* qkv, const bf16_t
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    attn_fwd_kernel<HD><<<grid, 256, LDS, st>>>(qkv, vt, o, lse, a.S, sp, a.Hq, a.Hkv, a.ld_qkv, a.causal, sl2);
+    attn_fwd_kernel<HD><<<grid, 256, LDS, st>>>(qkv, o, lse, a.S, a.Hq, a.Hkv, a.ld_qkv, a.causal, sl2);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t spk_launch_transpose_heads(hipStream_t st, const bf16_t* src, int ld, int col0, int nheads, int B, int S,
-                                      int hd, bf16_t* dst) {
-    if (B <= 0 || S <= 0 || nheads <= 0) return hipSuccess;
-    if ((size_t)B * nheads > 65535) return hipErrorInvalidValue;
-    const int hdp = attn_hd_pad(hd), sp = attn_s_pad(S);
-    dim3 grid(sp / 64, (hdp + 63) / 64, B * nheads);
-    transpose_heads_kernel<<<grid, 256, 0, st>>>(src, dst, S, sp, nheads, hd, hdp, ld, col0);
-    return hipGetLastError();
-}
-
-hipError_t spk_launch_transpose_v(hipStream_t st, const bf16_t* qkv, bf16_t* vt, const AttnShape& a) {
-    return spk_launch_transpose_heads(st, qkv, a.ld_qkv, (a.Hq + a.Hkv) * a.hd, a.Hkv, a.B, a.S, a.hd, vt);
-}
-
-hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, const bf16_t* vt, bf16_t* o, float* lse,
-                                const AttnShape& a) {
+hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, bf16_t* o, float* lse, const AttnShape& a) {
     if (a.B <= 0 || a.S <= 0) return hipSuccess;
     if (a.Hkv <= 0 || a.Hq % a.Hkv || a.ld_qkv % 8 || a.B > 65535 || a.Hq > 65535) return hipErrorInvalidValue;
-    if (((uintptr_t)qkv | (uintptr_t)vt | (uintptr_t)o) & 15) return hipErrorInvalidValue;
+    if (((uintptr_t)qkv | (uintptr_t)o) & 15) return hipErrorInvalidValue;
     const float sl2 = 1.4426950408889634f / sqrtf((float)a.hd);
     dim3 grid((a.S + QB - 1) / QB, a.Hq, a.B);
-    const int sp = attn_s_pad(a.S);
     switch (a.hd) {
-        case 64: return launch_fwd<64>(st, grid, qkv, vt, o, lse, a, sp, sl2);
-        case 80: return launch_fwd<80>(st, grid, qkv, vt, o, lse, a, sp, sl2);
-        case 128: return launch_fwd<128>(st, grid, qkv, vt, o, lse, a, sp, sl2);
+        case 64: return launch_fwd<64>(st, grid, qkv, o, lse, a, sl2);
+        case 80: return launch_fwd<80>(st, grid, qkv, o, lse, a, sl2);
+        case 128: return launch_fwd<128>(st, grid, qkv, o, lse, a, sl2);
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -187,7 +187,6 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
     auto W = [&](int t) { return reinterpret_cast<const bf16_t*>(w + L.t[t].offset); };
     bf16_t* a = e->wsp<bf16_t>(e->ws.a);
     bf16_t* qkv = e->wsp<bf16_t>(e->ws.qkv);
-    bf16_t* vt = e->wsp<bf16_t>(e->ws.vt);
     bf16_t* o = e->wsp<bf16_t>(e->ws.o);
     bf16_t* gu = e->wsp<bf16_t>(e->ws.gu);
     bf16_t* z = e->wsp<bf16_t>(e->ws.z);
@@ -210,8 +209,7 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
         SP_HIP(e, spk_launch_decode_attention(st, qkv, nqkv, kv->kt, kv->v, o, nq, B, kv->pos + 1, kv->max_len,
                                               d.n_q_heads, d.n_kv_heads, d.head_dim));
     } else {
-        SP_HIP(e, spk_launch_transpose_v(st, qkv, vt, as));
-        SP_HIP(e, spk_launch_attention(st, qkv, vt, o, nullptr, as));
+        SP_HIP(e, spk_launch_attention(st, qkv, o, nullptr, as));
     }
     // b4: h += o Wo^T (+ b)
     g = GemmArgs{o, nq, OP_KMAJOR, W(dec ? SP_T_WO : SP_T_E_WO), nq, OP_KMAJOR, h, dm, h, dm,

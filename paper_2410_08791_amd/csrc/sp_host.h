@@ -37,7 +37,7 @@ int make_layout(const sp_stack_desc* d, Layout* out);
 
 // Device workspace, as byte offsets from its base (all 256-byte aligned).
 struct Workspace {
-    size_t a, qkv, vt, o, gu, z;           // forward activations (bf16)
+    size_t a, qkv, o, gu, z;               // forward activations (bf16)
     size_t set_stride;                     // > 0: layer l's copy of {a,qkv,o,gu,z,m,h1,lse} lies l*set_stride further
     // training only
     size_t xs;                             // layer inputs fp32 [L][T, d], kept for the backward

@@ -72,7 +72,6 @@ void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Wor
     const size_t dm = d->d_model, f = d->d_ffn;
     const size_t nq = (size_t)d->n_q_heads * d->head_dim, nkv = (size_t)d->n_kv_heads * d->head_dim;
     const size_t nqkv = nq + 2 * nkv;
-    const size_t hdp = (d->head_dim + 31) / 32 * 32, sp = align_up(d->max_seq, 64);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, kTensorAlign); return o; };
     // per-layer activation set (one shared set, or one per layer when activations are kept)
@@ -91,7 +90,6 @@ void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Wor
         ws->set_stride = off;                       // sets of layers 1..L-1 follow set 0
         off += ws->set_stride * (size_t)(d->n_layers - 1);
     }
-    ws->vt = take((size_t)d->max_batch * d->n_kv_heads * hdp * sp * 2);
     if (training) {
         ws->xs = take((size_t)d->n_layers * T * dm * 4);
         ws->delta = take((size_t)d->max_batch * d->n_q_heads * d->max_seq * 4);

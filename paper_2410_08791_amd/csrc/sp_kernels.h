@@ -44,21 +44,10 @@ struct AttnShape {
     int B, S, Hq, Hkv, hd, causal;
     int ld_qkv;      // row stride (elements) of the fused [q | k | v] activation
 };
-// Rounded-up sizes of the transposed V scratch: [B][Hkv][hd_pad][S_pad] bf16.
-static inline int attn_hd_pad(int hd) { return (hd + 31) / 32 * 32; }
-static inline int attn_s_pad(int S) { return (S + 63) / 64 * 64; }
-
-// dst[b][h][e][s] = src[(b*S+s)*ld + col0 + h*hd + e] for h < nheads; rows e >= hd (up to
-// hd_pad) and columns s >= S (up to S_pad) are written as zero.
-hipError_t spk_launch_transpose_heads(hipStream_t st, const bf16_t* src, int ld, int col0, int nheads, int B, int S,
-                                      int hd, bf16_t* dst);
-// vt[b][kvh][e][s] = v[b*S+s][kvh*hd+e]: the V part of the fused activation.
-hipError_t spk_launch_transpose_v(hipStream_t st, const bf16_t* qkv, bf16_t* vt, const AttnShape& a);
 
 // o bf16 [B*S, Hq*hd] = softmax(q k^T / sqrt(hd) + mask) v per (batch, head);
 // lse (nullable) fp32 [B, Hq, S] = log of the softmax denominator incl. the row max.
-hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, const bf16_t* vt, bf16_t* o,
-                                float* lse, const AttnShape& a);
+hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, bf16_t* o, float* lse, const AttnShape& a);
 
 // ---- decode (key/value cache) ---------------------------------------------------------
 // One layer's cache: kt bf16 [B][Hkv][hd][max_len], v bf16 [B][Hkv][max_len][hd].

@@ -28,18 +28,11 @@ extern "C" int spk_swiglu(void* stream, const uint16_t* gu, uint16_t* z, int T, 
     return st(spk_launch_swiglu((hipStream_t)stream, gu, z, T, f));
 }
 
-extern "C" size_t spk_attention_scratch_elems(int B, int S, int Hkv, int hd) {
-    if (B < 1 || S < 1 || Hkv < 1 || hd < 1) return 0;
-    return (size_t)B * Hkv * attn_hd_pad(hd) * attn_s_pad(S);
-}
-
-extern "C" int spk_attention(void* stream, const uint16_t* qkv, uint16_t* vt, uint16_t* o, float* lse, int B,
-                             int S, int Hq, int Hkv, int hd, int causal) {
-    if (!qkv || !vt || !o || B < 1 || S < 1 || Hq < 1 || Hkv < 1) return SP_ERR_INVALID_ARG;
+extern "C" int spk_attention(void* stream, const uint16_t* qkv, uint16_t* o, float* lse, int B, int S, int Hq,
+                             int Hkv, int hd, int causal) {
+    if (!qkv || !o || B < 1 || S < 1 || Hq < 1 || Hkv < 1) return SP_ERR_INVALID_ARG;
     AttnShape a{B, S, Hq, Hkv, hd, causal, (Hq + 2 * Hkv) * hd};
-    hipError_t e = spk_launch_transpose_v((hipStream_t)stream, qkv, vt, a);
-    if (e != hipSuccess) return st(e);
-    return st(spk_launch_attention((hipStream_t)stream, qkv, vt, o, lse, a));
+    return st(spk_launch_attention((hipStream_t)stream, qkv, o, lse, a));
 }
 
 extern "C" int spk_kv_append(void* stream, const uint16_t* qkv, uint16_t* kt, uint16_t* v, int B, int S, int pos0,

@@ -41,14 +41,12 @@ int decoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
     const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, nqkv = nq + 2 * nkv;
     auto W = [&](int t) { return reinterpret_cast<const bf16_t*>(w + L.t[t].offset); };
     bf16_t *a = as_.a, *m = as_.m, *qkv = as_.qkv, *o = as_.o, *gu = as_.gu, *z = as_.z;
-    bf16_t* vt = e->wsp<bf16_t>(e->ws.vt);
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
     GemmArgs g;
     SP_HIP(e, spk_launch_norm(st, b.h_in, W(SP_T_G1), nullptr, a, T, dm, d.norm_eps));
     g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0, nullptr, T, nqkv, dm, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
-    SP_HIP(e, spk_launch_transpose_v(st, qkv, vt, as));
-    SP_HIP(e, spk_launch_attention(st, qkv, vt, o, b.lse, as));
+    SP_HIP(e, spk_launch_attention(st, qkv, o, b.lse, as));
     g = GemmArgs{o, nq, OP_KMAJOR, W(SP_T_WO), nq, OP_KMAJOR, b.h_mid, dm, b.h_in, dm, nullptr, T, dm, nq, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_G2), nullptr, m, T, dm, d.norm_eps));
@@ -82,14 +80,12 @@ int encoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
     const int nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, nqkv = nq + 2 * nkv;
     auto W = [&](int t) { return reinterpret_cast<const bf16_t*>(w + L.t[t].offset); };
     bf16_t *a = as_.a, *m = as_.m, *qkv = as_.qkv, *o = as_.o, *u = as_.gu, *z = as_.z;
-    bf16_t* vt = e->wsp<bf16_t>(e->ws.vt);
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
     GemmArgs g;
     SP_HIP(e, spk_launch_norm(st, b.h_in, W(SP_T_LN1_G), W(SP_T_LN1_B), a, T, dm, d.norm_eps));
     g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_E_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0, W(SP_T_BQKV), T, nqkv, dm, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
-    SP_HIP(e, spk_launch_transpose_v(st, qkv, vt, as));
-    SP_HIP(e, spk_launch_attention(st, qkv, vt, o, b.lse, as));
+    SP_HIP(e, spk_launch_attention(st, qkv, o, b.lse, as));
     g = GemmArgs{o, nq, OP_KMAJOR, W(SP_T_E_WO), nq, OP_KMAJOR, b.h_mid, dm, b.h_in, dm, W(SP_T_BO), T, dm, nq, e->gemm_tile};
     SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_LN2_G), W(SP_T_LN2_B), m, T, dm, d.norm_eps));

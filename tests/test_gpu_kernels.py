@@ -146,11 +146,10 @@ def test_attention(B, S, Hq, Hkv, hd, causal):
     nq, nk = Hq * hd, Hkv * hd
     q, k, v = qkv[:, :nq], qkv[:, nq:nq + nk], qkv[:, nq + nk:]
     ref = O.attention(q, k, v, B, S, sh)
-    vt = torch.zeros(sp.spk_attention_scratch_elems(B, S, Hkv, hd), dtype=torch.int16, device=DEV)
     o = torch.zeros((B * S, nq), dtype=torch.int16, device=DEV)
     lse = torch.zeros((B, Hq, S), dtype=torch.float32, device=DEV)
     qd = dev_u16(qb)
-    rc = sp.spk_attention(stream_ptr(), ptr(qd), ptr(vt), ptr(o), ptr(lse), B, S, Hq, Hkv, hd, causal)
+    rc = sp.spk_attention(stream_ptr(), ptr(qd), ptr(o), ptr(lse), B, S, Hq, Hkv, hd, causal)
     assert rc == sp.SP_OK
     sync()
     got = bf16_vals(host_u16(o))
@@ -171,8 +170,8 @@ def test_attention(B, S, Hq, Hkv, hd, causal):
 
 def test_attention_rejects_unsupported_head_dim():
     z = torch.zeros(1 << 16, dtype=torch.int16, device=DEV)
-    assert sp.spk_attention(stream_ptr(), ptr(z), ptr(z), ptr(z), None, 1, 8, 2, 2, 48, 1) == sp.SP_ERR_INVALID_ARG
-    assert sp.spk_attention(stream_ptr(), ptr(z), ptr(z), ptr(z), None, 1, 8, 3, 2, 64, 1) == sp.SP_ERR_INVALID_ARG
+    assert sp.spk_attention(stream_ptr(), ptr(z), ptr(z), None, 1, 8, 2, 2, 48, 1) == sp.SP_ERR_INVALID_ARG
+    assert sp.spk_attention(stream_ptr(), ptr(z), ptr(z), None, 1, 8, 3, 2, 64, 1) == sp.SP_ERR_INVALID_ARG
     sync()
 
 
@@ -250,10 +249,9 @@ def test_attention_backward(B, S, Hq, Hkv, hd, causal):
     q, k, v = qkv[:, :nq], qkv[:, nq:nq + nk], qkv[:, nq + nk:]
     dq, dk, dv = O._attention_bwd(dO, np.ascontiguousarray(q), np.ascontiguousarray(k), np.ascontiguousarray(v), B, S, sh)
     qd, dod = dev_u16(qb), dev_u16(dob)
-    vt = torch.zeros(sp.spk_attention_scratch_elems(B, S, Hkv, hd), dtype=torch.int16, device=DEV)
     o = torch.zeros((B * S, nq), dtype=torch.int16, device=DEV)
     lse = torch.zeros((B, Hq, S), dtype=torch.float32, device=DEV)
-    assert sp.spk_attention(stream_ptr(), ptr(qd), ptr(vt), ptr(o), ptr(lse), B, S, Hq, Hkv, hd, causal) == sp.SP_OK
+    assert sp.spk_attention(stream_ptr(), ptr(qd), ptr(o), ptr(lse), B, S, Hq, Hkv, hd, causal) == sp.SP_OK
     scratch = torch.zeros(sp.spk_attention_bwd_scratch_bytes(B, S, Hq, Hkv, hd), dtype=torch.uint8, device=DEV)
     dqkv = torch.zeros((B * S, nqkv), dtype=torch.int16, device=DEV)
     rc = sp.spk_attention_bwd(stream_ptr(), ptr(qd), ptr(o), ptr(dod), ptr(lse), ptr(scratch), ptr(dqkv),
