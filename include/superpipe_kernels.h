@@ -36,8 +36,9 @@ int spk_norm(void* stream, const float* h, const uint16_t* gain, const uint16_t*
  * a_form / w_form: 0 = contraction index contiguous (A[m*lda+k], W[n*ldw+k]),
  *                  1 = row index contiguous        (A[k*lda+m], W[k*ldw+n]).
  * tile: 0 = library heuristic; 1..4 force a block tile of the register-staged kernel (128x128, 128x256,
- *       256x256 with 4 waves, 256x256 with 8 waves), 5..7 of the LDS-DMA kernel (256x256, 128x256, 128x128;
- *       when an operand has form 1 the register-staged kernel of that shape runs instead).
+ *       256x256 with 4 waves, 256x256 with 8 waves), 5..8 of the LDS-DMA kernel (256x256, 128x256, 128x128,
+ *       256x192 -- the last not with epilogue 3; when an operand has form 1 a register-staged kernel runs
+ *       instead).
  * K % 64 == 0, N % 8 == 0. */
 int spk_gemm(void* stream, int epilogue, const uint16_t* A, int lda, int a_form, const uint16_t* W, int ldw,
              int w_form, void* C, int ldc, const float* R, int ldr, const uint16_t* bias, int M, int N, int K,

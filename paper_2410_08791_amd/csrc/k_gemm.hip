@@ -371,11 +371,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_kernel(GemmDev p) {
 // what the counts replace).
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
-template <int BM, int BN, int EPI, int WAVES>
+template <int BM, int BN, int EPI, int WAVES, int WM>
 __global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int WNC = WAVES / 2, WN = BN / WNC;
-    constexpr int TM = BM / 64, TN = WN / 32;
+    constexpr int WNC = WAVES / WM;              // wave grid: WM (m) x WNC (n)
+    constexpr int WMR = BM / WM, WN = BN / WNC;  // tile rows of A / of W per wave
+    constexpr int TM = WMR / 32, TN = WN / 32;   // 32x32 tiles per wave
+    static_assert(WMR % 32 == 0 && WN % 32 == 0, "whole MFMA tiles per wave");
     constexpr int A_BYTES = BM * ROW_BYTES, STAGE = (BM + BN) * ROW_BYTES;
     constexpr bool SWIGLU = (EPI == EPI_SWIGLU_BF16);
     constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
@@ -388,7 +390,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave & 1, wn = wave >> 1;
+    const int wm = wave % WM, wn = wave / WM;
     const int l32 = lane & 31, half = lane >> 5;
 
     int pid = xcd_remap(blockIdx.x, gridDim.x);
@@ -455,7 +457,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
     int foff[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) foff[ks] = l32 * ROW_BYTES + (((2 * ks + half) ^ sw) << 4);
-    const int a_base = wm * (BM / 2) * ROW_BYTES;
+    const int a_base = wm * WMR * ROW_BYTES;
     const int w_base = A_BYTES + wn * WN * ROW_BYTES;
 
     constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
@@ -529,18 +531,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
         if (NMFMA % NFRAG) __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA % NFRAG, 0);
     }
     __builtin_amdgcn_s_waitcnt(WAIT_VM0_LGKM0);   // drain the tail's idle loads
-    gemm_epilogue<EPI, TM, TN>(p, acc, m0 + wm * (BM / 2), SWIGLU ? n0 + wn * (WN / 2) : n0 + wn * WN, l32, half);
+    gemm_epilogue<EPI, TM, TN>(p, acc, m0 + wm * WMR, SWIGLU ? n0 + wn * (WN / 2) : n0 + wn * WN, l32, half);
 #undef SP_DMA_ISSUE
 #undef SP_DMA_ISSUE_R
 }
 
-template <int BM, int BN, int EPI, int WAVES>
+template <int BM, int BN, int EPI, int WAVES, int WM>
 hipError_t launch_dma(hipStream_t st, const GemmArgs& g) {
     constexpr int LDS = 2 * (BM + BN) * ROW_BYTES;
     constexpr int BN_OUT = (EPI == EPI_SWIGLU_BF16) ? BN / 2 : BN;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<BM, BN, EPI, WAVES>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<BM, BN, EPI, WAVES, WM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -551,7 +553,7 @@ hipError_t launch_dma(hipStream_t st, const GemmArgs& g) {
     d.M = g.M; d.N = g.N; d.K = g.K;
     d.tilesM = (g.M + BM - 1) / BM;
     d.tilesN = (g.N + BN_OUT - 1) / BN_OUT;
-    gemm_dma_kernel<BM, BN, EPI, WAVES><<<d.tilesM * d.tilesN, WAVES * 64, LDS, st>>>(d);
+    gemm_dma_kernel<BM, BN, EPI, WAVES, WM><<<d.tilesM * d.tilesN, WAVES * 64, LDS, st>>>(d);
     return hipGetLastError();
 }
 
@@ -581,14 +583,16 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
 
 // Tile ids: register-staged kernel 1 = 128x128, 2 = 128x256 (BM x BN), 3 = 256x256 (4 waves each),
 // 4 = 256x256 with 8 waves; LDS-DMA kernel (contraction-contiguous operands only) 5 = 256x256 and
-// 6 = 128x256 with 8 waves, 7 = 128x128 with 4 waves (two work-groups per CU).
+// 6 = 128x256 with 8 waves, 7 = 128x128 with 4 waves (two work-groups per CU), 8 = 256x192 with 8
+// waves in a 4 x 2 grid (not with the SwiGLU epilogue, which pairs tiles inside a wave).
 //
 // Choice (shapes only, so a stack's kernels never depend on the streaming window): the chip
 // runs 256 work-groups at a time (512 of tile 7), so a launch costs
 // ceil(tiles / concurrent) rounds of one tile's time; a tile's time is its area over a measured
 // relative efficiency (larger tiles move fewer operand bytes per MFMA).  Take the cheapest.
 struct TileCost { int id, bm, bn, concurrent; float eff; };
-constexpr TileCost kDmaTiles[] = {{5, 256, 256, 256, 1.00f}, {6, 128, 256, 256, 0.72f}, {7, 128, 128, 512, 0.70f}};
+constexpr TileCost kDmaTiles[] = {{5, 256, 256, 256, 1.00f}, {8, 256, 192, 256, 0.85f}, {6, 128, 256, 256, 0.72f},
+                                  {7, 128, 128, 512, 0.70f}};
 constexpr TileCost kRegTiles[] = {{4, 256, 256, 256, 1.00f}, {1, 128, 128, 512, 0.66f}};
 
 template <int NC>
@@ -597,12 +601,13 @@ int pick_tile(const TileCost (&cand)[NC], int M, int N, int epi) {
     float best_cost = 0.f;
     for (int c = 0; c < NC; ++c) {
         const TileCost& t = cand[c];
+        if (t.id == 8 && epi == EPI_SWIGLU_BF16) continue;
         const int bn_out = (epi == EPI_SWIGLU_BF16) ? t.bn / 2 : t.bn;
         const long tiles = (long)((M + t.bm - 1) / t.bm) * ((N + bn_out - 1) / bn_out);
         const long rounds = (tiles + t.concurrent - 1) / t.concurrent;
         // a round of the two-per-CU tile holds two tiles per CU
         const float cost = (float)rounds * (t.concurrent / 256) * (float)(t.bm * t.bn) / t.eff;
-        if (c == 0 || cost < best_cost) { best = t.id; best_cost = cost; }
+        if (c == 0 || cost < best_cost) { best = t.id; best_cost = cost; }   // candidate 0 takes every epilogue
     }
     return best;
 }
@@ -610,16 +615,18 @@ int pick_tile(const TileCost (&cand)[NC], int M, int N, int epi) {
 template <int EPI, int AFORM, int WFORM>
 hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
     constexpr bool DMA_OK = (AFORM == OP_KMAJOR && WFORM == OP_KMAJOR);
+    constexpr int NOSWIGLU = EPI == EPI_SWIGLU_BF16 ? EPI_BF16 : EPI;   // tile 8 has an odd tile count per wave
     int tile = g.tile ? g.tile : DMA_OK ? pick_tile(kDmaTiles, g.M, g.N, EPI) : pick_tile(kRegTiles, g.M, g.N, EPI);
-    if (!DMA_OK && tile >= 5 && tile <= 7) tile = tile == 5 ? 4 : tile == 6 ? 2 : 1;   // same shape, register-staged
+    if (!DMA_OK && tile >= 5 && tile <= 8) tile = tile == 6 ? 2 : tile == 7 ? 1 : 4;   // register-staged instead
     switch (tile) {
         case 1: return launch_one<128, 128, EPI, AFORM, WFORM, 4>(st, g);
         case 2: return launch_one<128, 256, EPI, AFORM, WFORM, 4>(st, g);
         case 3: return launch_one<256, 256, EPI, AFORM, WFORM, 4>(st, g);
         case 4: return launch_one<256, 256, EPI, AFORM, WFORM, 8>(st, g);
-        case 5: if (DMA_OK) return launch_dma<256, 256, EPI, 8>(st, g); break;
-        case 6: if (DMA_OK) return launch_dma<128, 256, EPI, 8>(st, g); break;
-        case 7: if (DMA_OK) return launch_dma<128, 128, EPI, 4>(st, g); break;
+        case 5: if (DMA_OK) return launch_dma<256, 256, EPI, 8, 2>(st, g); break;
+        case 6: if (DMA_OK) return launch_dma<128, 256, EPI, 8, 2>(st, g); break;
+        case 7: if (DMA_OK) return launch_dma<128, 128, EPI, 4, 2>(st, g); break;
+        case 8: if (DMA_OK && EPI != EPI_SWIGLU_BF16) return launch_dma<256, 192, NOSWIGLU, 8, 4>(st, g); break;
     }
     return hipErrorInvalidValue;
 }
