@@ -590,13 +590,14 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
 // runs 256 work-groups at a time (512 of tile 7), so a launch costs
 // ceil(tiles / concurrent) rounds of one tile's time; a tile's time is its area over a measured
 // relative efficiency (larger tiles move fewer operand bytes per MFMA).  Take the cheapest.
+// (Activation rows are contiguous in A, C and R, so a launch can be cut along M.)
 struct TileCost { int id, bm, bn, concurrent; float eff; };
 constexpr TileCost kDmaTiles[] = {{5, 256, 256, 256, 1.00f}, {8, 256, 192, 256, 0.85f}, {6, 128, 256, 256, 0.72f},
                                   {7, 128, 128, 512, 0.70f}};
 constexpr TileCost kRegTiles[] = {{4, 256, 256, 256, 1.00f}, {1, 128, 128, 512, 0.66f}};
 
 template <int NC>
-int pick_tile(const TileCost (&cand)[NC], int M, int N, int epi) {
+int pick_tile(const TileCost (&cand)[NC], int M, int N, int epi, float* cost_out = nullptr) {
     int best = cand[0].id;
     float best_cost = 0.f;
     for (int c = 0; c < NC; ++c) {
@@ -604,11 +605,14 @@ int pick_tile(const TileCost (&cand)[NC], int M, int N, int epi) {
         if (t.id == 8 && epi == EPI_SWIGLU_BF16) continue;
         const int bn_out = (epi == EPI_SWIGLU_BF16) ? t.bn / 2 : t.bn;
         const long tiles = (long)((M + t.bm - 1) / t.bm) * ((N + bn_out - 1) / bn_out);
-        const long rounds = (tiles + t.concurrent - 1) / t.concurrent;
-        // a round of the two-per-CU tile holds two tiles per CU
-        const float cost = (float)rounds * (t.concurrent / 256) * (float)(t.bm * t.bn) / t.eff;
+        // in units of "every CU busy with one tile": the two-per-CU tile fills a CU with two
+        long units = tiles / t.concurrent * (t.concurrent / 256);
+        const long rem = tiles % t.concurrent;
+        if (rem) units += rem <= 256 ? 1 : t.concurrent / 256;
+        const float cost = (float)units * (float)(t.bm * t.bn) / t.eff;
         if (c == 0 || cost < best_cost) { best = t.id; best_cost = cost; }   // candidate 0 takes every epilogue
     }
+    if (cost_out) *cost_out = best_cost;
     return best;
 }
 
@@ -616,7 +620,33 @@ template <int EPI, int AFORM, int WFORM>
 hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
     constexpr bool DMA_OK = (AFORM == OP_KMAJOR && WFORM == OP_KMAJOR);
     constexpr int NOSWIGLU = EPI == EPI_SWIGLU_BF16 ? EPI_BF16 : EPI;   // tile 8 has an odd tile count per wave
-    int tile = g.tile ? g.tile : DMA_OK ? pick_tile(kDmaTiles, g.M, g.N, EPI) : pick_tile(kRegTiles, g.M, g.N, EPI);
+    int tile = g.tile;
+    if (!tile && DMA_OK) {
+        float whole;
+        tile = pick_tile(kDmaTiles, g.M, g.N, EPI, &whole);
+        // A ragged last row of 256-row tiles can cost a whole extra round (ViT-H: 16448 tokens
+        // = 64 tiles + 64 rows, 1300 tiles = 5.08 rounds of 256).  When the model says so, the
+        // rows beyond the last multiple of 256 become a launch of their own with a small tile.
+        const int tail = g.M % 256, body = g.M - tail;
+        if (tail && body) {
+            float c_body, c_tail;
+            const int t_body = pick_tile(kDmaTiles, body, g.N, EPI, &c_body);
+            const int t_tail = pick_tile(kDmaTiles, tail, g.N, EPI, &c_tail);
+            if (c_body + c_tail < 0.95f * whole) {
+                constexpr size_t CSZ = (EPI == EPI_RESID_F32 || EPI == EPI_F32) ? 4 : 2;
+                GemmArgs a = g, b = g;
+                a.M = body; a.tile = t_body;
+                b.M = tail; b.tile = t_tail;
+                b.A = g.A + (size_t)body * g.lda;
+                b.C = static_cast<unsigned char*>(g.C) + (size_t)body * g.ldc * CSZ;
+                if (g.R) b.R = g.R + (size_t)body * g.ldr;
+                hipError_t e = launch_tile<EPI, AFORM, WFORM>(st, a);
+                return e != hipSuccess ? e : launch_tile<EPI, AFORM, WFORM>(st, b);
+            }
+        }
+    } else if (!tile) {
+        tile = pick_tile(kRegTiles, g.M, g.N, EPI);
+    }
     if (!DMA_OK && tile >= 5 && tile <= 8) tile = tile == 6 ? 2 : tile == 7 ? 1 : 4;   // register-staged instead
     switch (tile) {
         case 1: return launch_one<128, 128, EPI, AFORM, WFORM, 4>(st, g);

@@ -79,6 +79,29 @@ def test_gemm_kmajor(epi, M, N, K, tile):
     assert np.all(np.abs(got - ref) <= tol + 1e-6), float(np.max(np.abs(got - ref)))
 
 
+@pytest.mark.parametrize("epi", [sp.EPI_GELU_BF16, sp.EPI_RESID_F32])
+def test_gemm_ragged_rows_cut_off(epi):
+    """A shape whose last, ragged row of 256-row tiles would cost a whole extra round: the
+    library's own choice computes rows 1024.. in a second launch.  Every row must come out."""
+    M, N, K = 1088, 13312, 64
+    rng = np.random.default_rng(11 + epi)
+    Ab, A = rand_bf16(rng, (M, K))
+    Wb, W = rand_bf16(rng, (N, K), 0.1)
+    bias_b, bias = rand_bf16(rng, N, 0.5)
+    R = rng.standard_normal((M, N)).astype(np.float32)
+    f32out = epi == sp.EPI_RESID_F32
+    Cd = dev_f32(R) if f32out else torch.zeros((M, N), dtype=torch.int16, device=DEV)
+    Ad, Wd, bd = dev_u16(Ab), dev_u16(Wb), dev_u16(bias_b)
+    rc = sp.spk_gemm(stream_ptr(), epi, ptr(Ad), K, 0, ptr(Wd), K, 0, ptr(Cd), N,
+                     ptr(Cd) if f32out else None, N, ptr(bd), M, N, K, 0)
+    assert rc == sp.SP_OK
+    sync()
+    ref = gemm_ref(A, W, epi, R.astype(np.float64), bias, N)
+    got = Cd.cpu().numpy().astype(np.float64) if f32out else bf16_vals(host_u16(Cd))
+    tol = 2e-6 * np.sqrt(K) * np.max(np.abs(ref)) + (0 if f32out else BF16_EPS * np.abs(ref))
+    assert np.all(np.abs(got - ref) <= tol + 1e-6), float(np.max(np.abs(got - ref)))
+
+
 @pytest.mark.parametrize("tile", [1, 2, 3, 4, 6, 0])
 @pytest.mark.parametrize("M,N,K", [(200, 328, 128), (264, 520, 192)])
 def test_gemm_transposed_operands(M, N, K, tile):
