@@ -44,6 +44,11 @@ int spk_gemm(void* stream, int epilogue, const uint16_t* A, int lda, int a_form,
              int w_form, void* C, int ldc, const float* R, int ldr, const uint16_t* bias, int M, int N, int K,
              int tile);
 
+/* What tile = 0 resolves to for a shape (host-only query, nothing is launched; the choice depends on
+ * the shape alone, never on addresses or on the streaming window): out3 (host) = {tile id of rows
+ * [0, body_rows), body_rows, tile id of rows [body_rows, M) or 0 when body_rows == M}. */
+int spk_gemm_plan(int epilogue, int a_form, int w_form, int M, int N, int* out3);
+
 /* z bf16 [T,f] = silu(gu[:, :f]) * gu[:, f:]; gu bf16 [T,2f]; f % 8 == 0. */
 int spk_swiglu(void* stream, const uint16_t* gu, uint16_t* z, int T, int f);
 

@@ -616,36 +616,46 @@ int pick_tile(const TileCost (&cand)[NC], int M, int N, int epi, float* cost_out
     return best;
 }
 
+// The library's own choice for a shape: the tile, and when a ragged last row of 256-row tiles
+// would cost a whole extra round (ViT-H: 16448 tokens = 64 tiles + 64 rows, 1300 tiles = 5.08
+// rounds of 256) the rows beyond the last multiple of 256 become a launch of their own.
+GemmPlan plan_gemm(int epi, bool dma_ok, int M, int N) {
+    GemmPlan pl{0, M, 0};
+    if (!dma_ok) {
+        pl.tile = pick_tile(kRegTiles, M, N, epi);
+        return pl;
+    }
+    float whole;
+    pl.tile = pick_tile(kDmaTiles, M, N, epi, &whole);
+    const int tail = M % 256, body = M - tail;
+    if (tail && body) {
+        float c_body, c_tail;
+        const int t_body = pick_tile(kDmaTiles, body, N, epi, &c_body);
+        const int t_tail = pick_tile(kDmaTiles, tail, N, epi, &c_tail);
+        if (c_body + c_tail < 0.95f * whole) pl = GemmPlan{t_body, body, t_tail};
+    }
+    return pl;
+}
+
 template <int EPI, int AFORM, int WFORM>
 hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
     constexpr bool DMA_OK = (AFORM == OP_KMAJOR && WFORM == OP_KMAJOR);
     constexpr int NOSWIGLU = EPI == EPI_SWIGLU_BF16 ? EPI_BF16 : EPI;   // tile 8 has an odd tile count per wave
     int tile = g.tile;
-    if (!tile && DMA_OK) {
-        float whole;
-        tile = pick_tile(kDmaTiles, g.M, g.N, EPI, &whole);
-        // A ragged last row of 256-row tiles can cost a whole extra round (ViT-H: 16448 tokens
-        // = 64 tiles + 64 rows, 1300 tiles = 5.08 rounds of 256).  When the model says so, the
-        // rows beyond the last multiple of 256 become a launch of their own with a small tile.
-        const int tail = g.M % 256, body = g.M - tail;
-        if (tail && body) {
-            float c_body, c_tail;
-            const int t_body = pick_tile(kDmaTiles, body, g.N, EPI, &c_body);
-            const int t_tail = pick_tile(kDmaTiles, tail, g.N, EPI, &c_tail);
-            if (c_body + c_tail < 0.95f * whole) {
-                constexpr size_t CSZ = (EPI == EPI_RESID_F32 || EPI == EPI_F32) ? 4 : 2;
-                GemmArgs a = g, b = g;
-                a.M = body; a.tile = t_body;
-                b.M = tail; b.tile = t_tail;
-                b.A = g.A + (size_t)body * g.lda;
-                b.C = static_cast<unsigned char*>(g.C) + (size_t)body * g.ldc * CSZ;
-                if (g.R) b.R = g.R + (size_t)body * g.ldr;
-                hipError_t e = launch_tile<EPI, AFORM, WFORM>(st, a);
-                return e != hipSuccess ? e : launch_tile<EPI, AFORM, WFORM>(st, b);
-            }
+    if (!tile) {
+        const GemmPlan pl = plan_gemm(EPI, DMA_OK, g.M, g.N);
+        tile = pl.tile;
+        if (pl.body_rows < g.M) {
+            constexpr size_t CSZ = (EPI == EPI_RESID_F32 || EPI == EPI_F32) ? 4 : 2;
+            GemmArgs a = g, b = g;
+            a.M = pl.body_rows; a.tile = pl.tile;
+            b.M = g.M - pl.body_rows; b.tile = pl.tail_tile;
+            b.A = g.A + (size_t)pl.body_rows * g.lda;
+            b.C = static_cast<unsigned char*>(g.C) + (size_t)pl.body_rows * g.ldc * CSZ;
+            if (g.R) b.R = g.R + (size_t)pl.body_rows * g.ldr;
+            hipError_t e = launch_tile<EPI, AFORM, WFORM>(st, a);
+            return e != hipSuccess ? e : launch_tile<EPI, AFORM, WFORM>(st, b);
         }
-    } else if (!tile) {
-        tile = pick_tile(kRegTiles, g.M, g.N, EPI);
     }
     if (!DMA_OK && tile >= 5 && tile <= 8) tile = tile == 6 ? 2 : tile == 7 ? 1 : 4;   // register-staged instead
     switch (tile) {
@@ -662,6 +672,10 @@ hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
 }
 
 }  // namespace
+
+GemmPlan spk_gemm_plan_host(int epi, int a_form, int w_form, int M, int N) {
+    return plan_gemm(epi, a_form == OP_KMAJOR && w_form == OP_KMAJOR, M, N);
+}
 
 hipError_t spk_launch_gemm(hipStream_t st, int epi, const GemmArgs& g) {
     if (g.M <= 0 || g.N <= 0) return hipSuccess;

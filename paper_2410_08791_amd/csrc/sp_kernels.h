@@ -32,6 +32,10 @@ struct GemmArgs {
 // C[M,N] = sum_k A(m,k) W(n,k), bf16 operands, fp32 accumulate on MFMA.
 // Needs K % 64 == 0, N % 8 == 0, leading dimensions % 8 == 0, 16-byte aligned bases.
 hipError_t spk_launch_gemm(hipStream_t st, int epilogue, const GemmArgs& g);
+// What tile = 0 resolves to for a shape (host code, no launch): rows [0, body_rows) run with
+// `tile`, rows [body_rows, M) -- none when body_rows == M -- with `tail_tile`.
+struct GemmPlan { int tile, body_rows, tail_tile; };
+GemmPlan spk_gemm_plan_host(int epilogue, int a_form, int w_form, int M, int N);
 
 // out bf16 [T,d] = norm(h fp32 [T,d]); bias == nullptr -> RMSNorm, else LayerNorm.
 hipError_t spk_launch_norm(hipStream_t st, const float* h, const bf16_t* gain, const bf16_t* bias,

@@ -23,6 +23,14 @@ extern "C" int spk_gemm(void* stream, int epilogue, const uint16_t* A, int lda, 
     return st(spk_launch_gemm((hipStream_t)stream, epilogue, g));
 }
 
+extern "C" int spk_gemm_plan(int epilogue, int a_form, int w_form, int M, int N, int* out3) {
+    if (!out3 || epilogue < 0 || epilogue > 4 || a_form < 0 || a_form > 1 || w_form < 0 || w_form > 1 || M < 1 || N < 1)
+        return SP_ERR_INVALID_ARG;
+    const GemmPlan pl = spk_gemm_plan_host(epilogue, a_form, w_form, M, N);
+    out3[0] = pl.tile; out3[1] = pl.body_rows; out3[2] = pl.tail_tile;
+    return SP_OK;
+}
+
 extern "C" int spk_swiglu(void* stream, const uint16_t* gu, uint16_t* z, int T, int f) {
     if (!gu || !z) return SP_ERR_INVALID_ARG;
     return st(spk_launch_swiglu((hipStream_t)stream, gu, z, T, f));

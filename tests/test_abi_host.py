@@ -158,3 +158,40 @@ def test_create_argument_errors_without_a_device():
     assert sp.sp_destroy(fake) == sp.SP_ERR_STATE
     assert sp.sp_forward(fake, 16, 16, 1, 1) == sp.SP_ERR_STATE
     assert sp.sp_get_stats(fake, C.byref(sp.sp_stats())) == sp.SP_ERR_STATE
+
+
+def gemm_plan(epi, a_form, w_form, M, N):
+    out = (C.c_int * 3)()
+    assert sp.lib.spk_gemm_plan(epi, a_form, w_form, M, N, out) == sp.SP_OK
+    return tuple(out)
+
+
+def test_gemm_plan_is_a_function_of_the_shape_alone():
+    """What tile = 0 resolves to: valid ids, the whole of M covered, the SwiGLU epilogue never on
+    the tile that cannot pair gate and up rows, the operand forms the LDS-DMA kernel does not take
+    on the register-staged tiles, and the workloads' projections on the tiles their round counts
+    call for (256 work-groups run at a time)."""
+    for epi in range(5):
+        for M in (1, 8, 64, 200, 256, 300, 2048, 4096, 8192, 16448):
+            for N in (8, 128, 1280, 4096, 5120, 11008, 12288, 28672):
+                tile, body, tail_tile = gemm_plan(epi, 0, 0, M, N)
+                assert tile in (5, 6, 7, 8) and 0 < body <= M
+                assert (tail_tile == 0) == (body == M)
+                if body < M:
+                    assert body % 256 == 0 and M - body < 256 and tail_tile in (5, 6, 7, 8)
+                if epi == sp.EPI_SWIGLU_BF16:
+                    assert tile != 8 and tail_tile != 8
+                assert gemm_plan(epi, 0, 0, M, N) == (tile, body, tail_tile)
+                for forms in ((0, 1), (1, 1), (1, 0)):
+                    t, b, tt = gemm_plan(epi, forms[0], forms[1], M, N)
+                    assert t in (1, 4) and b == M and tt == 0
+    # llama7b, 2048 tokens: gate/up 8 x 86 = 688 tiles of 256x256; QKV 8 x 64 = 512 tiles of 256x192
+    # (two full rounds) instead of 384 of 256x256; O and down 16 x 16 = 256 tiles of 128x256 (one round)
+    assert gemm_plan(sp.EPI_SWIGLU_BF16, 0, 0, 2048, 11008) == (5, 2048, 0)
+    assert gemm_plan(sp.EPI_BF16, 0, 0, 2048, 12288) == (8, 2048, 0)
+    assert gemm_plan(sp.EPI_RESID_F32, 0, 0, 2048, 4096) == (6, 2048, 0)
+    # ViT-H, 16448 tokens = 64 x 256 + 64: the first MLP projection would take 1300 tiles = 5.08
+    # rounds; cut, it takes 1280 (5 rounds) plus a small launch for the last 64 rows
+    assert gemm_plan(sp.EPI_GELU_BF16, 0, 0, 16448, 5120) == (5, 16384, 7)
+    assert sp.lib.spk_gemm_plan(7, 0, 0, 8, 8, (C.c_int * 3)()) == sp.SP_ERR_INVALID_ARG
+    assert sp.lib.spk_gemm_plan(0, 0, 0, 0, 8, (C.c_int * 3)()) == sp.SP_ERR_INVALID_ARG
