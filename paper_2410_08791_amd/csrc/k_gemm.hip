@@ -349,6 +349,101 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_kernel(GemmDev p) {
     gemm_epilogue<EPI, TM, TN>(p, acc, m0 + wm * (BM / 2), SWIGLU ? n0 + wn * (WN / 2) : n0 + wn * WN, l32, half);
 }
 
+// Epilogue through LDS (used by the LDS-DMA kernel, whose LDS is idle once the k-loop ends).
+// Written straight from the accumulators a store instruction covers 32 rows x 16 or 32 bytes:
+// 2 M write requests of 16 bytes per round of 256 tiles, which the L2 takes ~9 us to absorb
+// (a fifth of the ViT-H first MLP projection).  Here the values (bias, GELU, SwiGLU applied)
+// are first laid out in LDS as the output tile, RP rows at a time (row stride + 16 bytes: a
+// wave's 32 rows spread over the banks), and then written with 16 bytes per lane, consecutive
+// lanes on consecutive bytes of a row: whole 128-byte lines.  The residual is read the same way.
+// acc[j][i]: tile (n tile j, m tile i) of a wave whose first tile row is wrow0 and first output
+// column inside the tile wcol0; lane layout as in gemm_epilogue.
+template <int EPI, int TM, int TN, int BM, int BN_OUT, int NT, int LDS_BYTES>
+__device__ __forceinline__ void gemm_epilogue_staged(const GemmDev& p, f32x16_t (&acc)[TN][TM], unsigned char* smem,
+                                                     int m0, int n0, int wrow0, int wcol0, int l32, int half) {
+    constexpr bool SWIGLU = (EPI == EPI_SWIGLU_BF16);
+    constexpr bool F32OUT = (EPI == EPI_RESID_F32 || EPI == EPI_F32);
+    constexpr int ESZ = F32OUT ? 4 : 2;
+    constexpr int ROWB = BN_OUT * ESZ, STRIDE = ROWB + 16;
+    constexpr int RP = BM * STRIDE <= LDS_BYTES ? BM : (BM / 2) * STRIDE <= LDS_BYTES ? BM / 2 : BM / 4;
+    static_assert(RP * STRIDE <= LDS_BYTES && RP % 32 == 0, "a pass of the output tile fits the LDS");
+    constexpr int TNO = SWIGLU ? TN / 2 : TN;
+    constexpr int CPR = ROWB / 16, CHUNKS = RP * CPR;     // 16-byte chunks per row / per pass
+    // the values of 4 consecutive columns (register group g of tile (j, i))
+    auto values = [&](int i, int j, int g, float (&v)[4]) {
+        const int nl = wcol0 + j * 32 + g * 8 + half * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (SWIGLU) {
+                const float gv = acc[j][i][g * 4 + e], uv = acc[j + TN / 2][i][g * 4 + e];
+                v[e] = gv * __builtin_amdgcn_rcpf(1.0f + __expf(-gv)) * uv;
+            } else {
+                v[e] = acc[j][i][g * 4 + e];
+            }
+        }
+        if (!SWIGLU && p.bias) {
+            const uint2 b = *reinterpret_cast<const uint2*>(p.bias + min(n0 + nl, p.N - 4));
+            v[0] += bf_lo(b.x); v[1] += bf_hi(b.x); v[2] += bf_lo(b.y); v[3] += bf_hi(b.y);
+        }
+        if (EPI == EPI_GELU_BF16) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
+        }
+    };
+    // bf16 outputs: every wave computes and packs all of its values first (the activation
+    // functions are the expensive part and must not be serialised by the passes below)
+    uint2 pk[F32OUT ? 1 : TM][F32OUT ? 1 : TNO][4];
+    if (!F32OUT) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TNO; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float v[4];
+                    values(i, j, g, v);
+                    pk[F32OUT ? 0 : i][F32OUT ? 0 : j][g] = make_uint2(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]));
+                }
+    }
+    __syncthreads();   // every wave is done with the operand stages, no load is in flight
+#pragma unroll
+    for (int pass = 0; pass < BM / RP; ++pass) {
+        if (pass) __syncthreads();   // the previous pass has been read out
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int r = wrow0 + i * 32;                 // wave-uniform
+            if (r / RP != pass) continue;
+            unsigned char* rowp = smem + (r - pass * RP + l32) * STRIDE;
+#pragma unroll
+            for (int j = 0; j < TNO; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int nl = wcol0 + j * 32 + g * 8 + half * 4;
+                    if (F32OUT) {
+                        float v[4];
+                        values(i, j, g, v);
+                        *reinterpret_cast<float4*>(rowp + nl * 4) = make_float4(v[0], v[1], v[2], v[3]);
+                    } else {
+                        *reinterpret_cast<uint2*>(rowp + nl * 2) = pk[F32OUT ? 0 : i][F32OUT ? 0 : j][g];
+                    }
+                }
+        }
+        __syncthreads();
+        for (int c = threadIdx.x; c < CHUNKS; c += NT) {
+            const int row = c / CPR, ch = c % CPR;
+            const int m = m0 + pass * RP + row, n = n0 + ch * (16 / ESZ);
+            if (m >= p.M || n >= p.N) continue;
+            u32x4_t v = *reinterpret_cast<const u32x4_t*>(smem + row * STRIDE + ch * 16);
+            if (EPI == EPI_RESID_F32) {
+                const float4 r = *reinterpret_cast<const float4*>(p.R + (size_t)m * p.ldr + n);
+                const float4 a = __builtin_bit_cast(float4, v);
+                v = __builtin_bit_cast(u32x4_t, make_float4(a.x + r.x, a.y + r.y, a.z + r.z, a.w + r.w));
+            }
+            *reinterpret_cast<u32x4_t*>(static_cast<unsigned char*>(p.C) + ((size_t)m * p.ldc + n) * ESZ) = v;
+        }
+    }
+}
+
 // ---- LDS-DMA kernel (both operands contraction-contiguous) ----------------------------------
 // Global loads write LDS directly (global_load_lds_dwordx4): no staging registers and no
 // ds_write instructions.  Measured on MI355X, LDS writes issued by the waves run at about
@@ -531,7 +626,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
         if (NMFMA % NFRAG) __builtin_amdgcn_sched_group_barrier(M_MFMA, NMFMA % NFRAG, 0);
     }
     __builtin_amdgcn_s_waitcnt(WAIT_VM0_LGKM0);   // drain the tail's idle loads
-    gemm_epilogue<EPI, TM, TN>(p, acc, m0 + wm * WMR, SWIGLU ? n0 + wn * (WN / 2) : n0 + wn * WN, l32, half);
+    gemm_epilogue_staged<EPI, TM, TN, BM, BN_OUT, WAVES * 64, 2 * STAGE>(p, acc, smem, m0, n0, wm * WMR,
+                                                                         SWIGLU ? wn * (WN / 2) : wn * WN, l32, half);
 #undef SP_DMA_ISSUE
 #undef SP_DMA_ISSUE_R
 }
@@ -641,12 +737,14 @@ template <int EPI, int AFORM, int WFORM>
 hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
     constexpr bool DMA_OK = (AFORM == OP_KMAJOR && WFORM == OP_KMAJOR);
     constexpr int NOSWIGLU = EPI == EPI_SWIGLU_BF16 ? EPI_BF16 : EPI;   // tile 8 has an odd tile count per wave
+    constexpr size_t CSZ = (EPI == EPI_RESID_F32 || EPI == EPI_F32) ? 4 : 2;
+    // the LDS-DMA kernel writes C (and reads R) in 16-byte pieces of a row
+    const bool dma = DMA_OK && (g.ldc * CSZ) % 16 == 0;
     int tile = g.tile;
     if (!tile) {
-        const GemmPlan pl = plan_gemm(EPI, DMA_OK, g.M, g.N);
+        const GemmPlan pl = plan_gemm(EPI, dma, g.M, g.N);
         tile = pl.tile;
         if (pl.body_rows < g.M) {
-            constexpr size_t CSZ = (EPI == EPI_RESID_F32 || EPI == EPI_F32) ? 4 : 2;
             GemmArgs a = g, b = g;
             a.M = pl.body_rows; a.tile = pl.tile;
             b.M = g.M - pl.body_rows; b.tile = pl.tail_tile;
@@ -657,7 +755,7 @@ hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
             return e != hipSuccess ? e : launch_tile<EPI, AFORM, WFORM>(st, b);
         }
     }
-    if (!DMA_OK && tile >= 5 && tile <= 8) tile = tile == 6 ? 2 : tile == 7 ? 1 : 4;   // register-staged instead
+    if (!dma && tile >= 5 && tile <= 8) tile = tile == 6 ? 2 : tile == 7 ? 1 : 4;   // register-staged instead
     switch (tile) {
         case 1: return launch_one<128, 128, EPI, AFORM, WFORM, 4>(st, g);
         case 2: return launch_one<128, 256, EPI, AFORM, WFORM, 4>(st, g);
