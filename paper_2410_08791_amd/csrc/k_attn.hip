@@ -20,6 +20,7 @@ namespace {
 
 constexpr int QB = 128;   // queries per work-group
 constexpr int KB = 64;    // keys per LDS tile
+constexpr int PF = 3;     // fragment reads in flight ahead of the MFMA that uses them
 
 template <int HD>
 struct AttnCfg {
@@ -44,25 +45,34 @@ template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
                                                        bf16_t* __restrict__ o, float* __restrict__ lse,
                                                        int S, int Hq, int Hkv, int ld_qkv,
-                                                       int causal, float scale_log2e) {
+                                                       int causal, int paired, float scale_log2e) {
     typedef AttnCfg<HD> C;
     // two K tiles then two V tiles (double buffered)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    // Causal: late query blocks carry more key tiles.  Work-groups are dealt to the CUs in
-    // id order, two resident per CU, so every other batch of 256 ids walks the query blocks
-    // in the opposite direction: a CU then holds one heavy and one light block.
-    const int nqb = gridDim.x;
-    const int lin = blockIdx.x + nqb * (blockIdx.y + gridDim.y * blockIdx.z);
-    const int qb = !causal ? blockIdx.x : (((lin >> 8) & 1) ? blockIdx.x : nqb - 1 - blockIdx.x);
+    // Causal: query block i walks i + 1 key tiles of 128.  With `paired` a work-group takes the
+    // blocks nqb - 1 - i and i one after the other, so that every work-group has the same amount
+    // of work (gridDim.x = ceil(nqb / 2)); the launcher asks for that when it still leaves two
+    // work-groups per CU.  Otherwise one block per work-group: ids are dealt to the CUs in
+    // order, two resident per CU, and every other batch of 256 ids walks the query blocks in
+    // the opposite direction, so a CU holds one heavy and one light block.
+    const int nqb = (S + QB - 1) / QB;
     const int h = blockIdx.y, b = blockIdx.z;
     const int kvh = h / (Hq / Hkv);
+    const int bx = blockIdx.x;
+    const int lin = bx + (int)gridDim.x * (h + (int)gridDim.y * b);
+    const int nphase = (paired && nqb - 1 - bx != bx) ? 2 : 1;
+    const size_t tok0 = (size_t)b * S;
+    const bf16_t* kbase = qkv + tok0 * ld_qkv + (size_t)Hq * HD + (size_t)kvh * HD;
+    const bf16_t* vbase = kbase + (size_t)Hkv * HD;
+    for (int phase = 0; phase < nphase; ++phase) {
+    const int qb = paired ? (phase ? bx : nqb - 1 - bx)                          // heavy block first
+                          : (!causal || ((lin >> 8) & 1)) ? bx : nqb - 1 - bx;
     const int q0 = qb * QB;
     const int wq0 = q0 + wave * 32;          // this wave's first query
     const int qi = wq0 + l32;                // this lane's query
-    const size_t tok0 = (size_t)b * S;
 
     // Q fragments: B operand, column = query, 8 contiguous head_dim elements.
     bf16x8_t qf[C::NKS];
@@ -72,8 +82,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
 #pragma unroll
         for (int ks = 0; ks < C::NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16);
     }
-    const bf16_t* kbase = qkv + tok0 * ld_qkv + (size_t)Hq * HD + (size_t)kvh * HD;
-    const bf16_t* vbase = kbase + (size_t)Hkv * HD;
 
     f32x16_t oacc[C::NMT];
 #pragma unroll
@@ -145,19 +153,51 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
         // wave-uniform skips: nothing visible to this wave / no valid query in this wave
         if (!((causal && key0 > wq_last) || wq0 >= S)) {
 
-        // ---- S^T = K Q^T for two 32-key tiles
+        // ---- S^T = K Q^T for two 32-key tiles.  The K fragments are read PF steps ahead of the
+        //      MFMA that consumes them (scheduling hints keep the compiler from sinking a read
+        //      down to its use, which would expose the LDS latency before every MFMA), and
+        //      consecutive MFMAs alternate between the two tiles' accumulators.
         f32x16_t sacc[2];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int e = 0; e < 16; ++e) sacc[t][e] = 0.f;
+        {
+            constexpr int NQK = 2 * C::NKS;
+            bf16x8_t kf[NQK];
+            auto kread = [&](int st) {   // step st: tile st & 1, k-step st >> 1
+                kf[st] = *reinterpret_cast<const bf16x8_t*>(
+                    sK + ((st & 1) * 32 + l32) * C::K_STRIDE + ((st >> 1) * 2 + half) * 16);
+            };
 #pragma unroll
-            for (int ks = 0; ks < C::NKS; ++ks) {
-                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(
-                    sK + (t * 32 + l32) * C::K_STRIDE + (ks * 2 + half) * 16);
-                sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc[t], 0, 0, 0);
+            for (int st = 0; st < PF; ++st) kread(st);
+#pragma unroll
+            for (int st = 0; st < NQK; ++st) {
+                if (st + PF < NQK) kread(st + PF);
+                sacc[st & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st], qf[st >> 1], sacc[st & 1], 0, 0, 0);
+            }
+            // issue order: PF reads, then one read per MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);
+#pragma unroll
+            for (int st = 0; st < NQK; ++st) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (st + PF < NQK) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
         }
+        // V^T fragments of step st = (t, j, mt): tile mt of O^T, keys of (t, j)
+        constexpr int NPV = 4 * C::NMT;
+        typedef short s16x8_t __attribute__((ext_vector_type(8)));
+        s16x8_t vf[NPV];
+        auto vread = [&](int st) {
+            const int tj = st / C::NMT, mt = st % C::NMT;
+            const unsigned char* vp = sV + ((tj >> 1) * 32 + 16 * (tj & 1) + half * 4) * C::V_STRIDE + mt * 64 + v_lane_off;
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * C::V_STRIDE));
+            vf[st] = s16x8_t{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        };
+#pragma unroll
+        for (int st = 0; st < PF; ++st) vread(st);
+        asm volatile("" ::: "memory");
         // ---- mask, online softmax in base 2 on the raw scores (the scale is positive,
         //      so it commutes with max and is folded into the exponent's fma)
         const bool need_mask = (causal && key0 + KB - 1 > wq0) || (key0 + KB > S);
@@ -203,21 +243,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
         //      t*32 + 16j + {half*4 + 0..3, 8 + half*4 + 0..3}.  The transposing read works on
         //      groups of 16 lanes: lane s of a group points at key row (s>>2) of the step's four
         //      and at 4 head_dim elements, and receives four consecutive keys of ITS element
-        //      (16 * (group & 1) + s within the 32-row tile).
+        //      (16 * (group & 1) + s within the 32-row tile).  Fragments are read PF steps ahead
+        //      (the first PF before the softmax arithmetic above, which hides their latency);
+        //      consecutive MFMAs go to different 32-row tiles of O^T.
 #pragma unroll
-        for (int mt = 0; mt < C::NMT; ++mt)
+        for (int st = 0; st < NPV; ++st) {
+            if (st + PF < NPV) vread(st + PF);
+            const int tj = st / C::NMT, mt = st % C::NMT;
+            oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf[st]),
+                                                               pf[tj >> 1][tj & 1], oacc[mt], 0, 0, 0);
+        }
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const unsigned char* vp = sV + (t * 32 + 16 * j + half * 4) * C::V_STRIDE + mt * 64 + v_lane_off;
-                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
-                    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * C::V_STRIDE));
-                    typedef short s16x8_t __attribute__((ext_vector_type(8)));
-                    const s16x8_t both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, both),
-                                                                       pf[t][j], oacc[mt], 0, 0, 0);
-                }
+        for (int st = 0; st < NPV; ++st) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (st + PF < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
         }
         if (more) stash((kt + 1) & 1);
         __syncthreads();
@@ -241,11 +281,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
         if (lse && half == 0)
             lse[((size_t)b * Hq + h) * S + qi] = m_run * scale_log2e * 0.69314718055994530942f + logf(l_run);
     }
+    }   // phase
 }
 
 template <int HD>
 hipError_t launch_fwd(hipStream_t st, dim3 grid, const bf16_t* qkv, bf16_t* o, float* lse,
-                      const AttnShape& a, float sl2) {
+                      const AttnShape& a, int paired, float sl2) {
     typedef AttnCfg<HD> C;
     constexpr int LDS = 2 * (C::K_BYTES + C::V_BYTES);
     static bool attr_set = false;
@@ -255,7 +296,7 @@ hipError_t launch_fwd(hipStream_t st, dim3 grid, const bf16_t* qkv, bf16_t* o, f
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    attn_fwd_kernel<HD><<<grid, 256, LDS, st>>>(qkv, o, lse, a.S, a.Hq, a.Hkv, a.ld_qkv, a.causal, sl2);
+    attn_fwd_kernel<HD><<<grid, 256, LDS, st>>>(qkv, o, lse, a.S, a.Hq, a.Hkv, a.ld_qkv, a.causal, paired, sl2);
     return hipGetLastError();
 }
 
@@ -266,11 +307,13 @@ hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, bf16_t* o, fl
     if (a.Hkv <= 0 || a.Hq % a.Hkv || a.ld_qkv % 8 || a.B > 65535 || a.Hq > 65535) return hipErrorInvalidValue;
     if (((uintptr_t)qkv | (uintptr_t)o) & 15) return hipErrorInvalidValue;
     const float sl2 = 1.4426950408889634f / sqrtf((float)a.hd);
-    dim3 grid((a.S + QB - 1) / QB, a.Hq, a.B);
+    const int nqb = (a.S + QB - 1) / QB;
+    const int paired = a.causal && (long)((nqb + 1) / 2) * a.Hq * a.B >= 512;
+    dim3 grid(paired ? (nqb + 1) / 2 : nqb, a.Hq, a.B);
     switch (a.hd) {
-        case 64: return launch_fwd<64>(st, grid, qkv, o, lse, a, sl2);
-        case 80: return launch_fwd<80>(st, grid, qkv, o, lse, a, sl2);
-        case 128: return launch_fwd<128>(st, grid, qkv, o, lse, a, sl2);
+        case 64: return launch_fwd<64>(st, grid, qkv, o, lse, a, paired, sl2);
+        case 80: return launch_fwd<80>(st, grid, qkv, o, lse, a, paired, sl2);
+        case 128: return launch_fwd<128>(st, grid, qkv, o, lse, a, paired, sl2);
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
