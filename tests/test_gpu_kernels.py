@@ -79,6 +79,28 @@ def test_gemm_kmajor(epi, M, N, K, tile):
     assert np.all(np.abs(got - ref) <= tol + 1e-6), float(np.max(np.abs(got - ref)))
 
 
+def test_gemm_output_rows_not_16_byte_aligned():
+    """A bf16 output whose row stride is a multiple of 4 but not of 8 elements: the kernel that
+    writes 16-byte pieces of a row cannot take it, the library must fall back by itself (also
+    when one of that kernel's tiles is forced) and leave the padding columns alone."""
+    M, N, K, ldc = 300, 264, 128, 268
+    rng = np.random.default_rng(5)
+    Ab, A = rand_bf16(rng, (M, K))
+    Wb, W = rand_bf16(rng, (N, K), 0.1)
+    Ad, Wd = dev_u16(Ab), dev_u16(Wb)
+    ref = A @ W.T
+    for tile in (0, 5, 7):
+        Cd = torch.full((M, ldc), 0x7fc0, dtype=torch.int16, device=DEV)
+        rc = sp.spk_gemm(stream_ptr(), sp.EPI_BF16, ptr(Ad), K, 0, ptr(Wd), K, 0, ptr(Cd), ldc,
+                         None, 0, None, M, N, K, tile)
+        assert rc == sp.SP_OK
+        sync()
+        raw = host_u16(Cd)
+        got = bf16_vals(raw[:, :N])
+        assert np.all(np.abs(got - ref) <= BF16_EPS * np.abs(ref) + 2e-6 * np.sqrt(K) * np.max(np.abs(ref)))
+        assert np.all(raw[:, N:] == 0x7fc0)
+
+
 @pytest.mark.parametrize("epi", [sp.EPI_GELU_BF16, sp.EPI_RESID_F32])
 def test_gemm_ragged_rows_cut_off(epi):
     """A shape whose last, ragged row of 256-row tiles would cost a whole extra round: the
