@@ -7,9 +7,11 @@ weight budget, on one MI355X.
 
 Default workload = the LLaMA-7B-shaped stack (32 layers, d 4096, 32 heads x
 128, SwiGLU 11008, causal, batch 1 x seq 2048), bf16 weights in pinned host
-memory, HBM weight budget of 4 layer slots, window (k, p) = (2, 2).  A step is
-one pass of the whole hot path: sp_forward over the whole stack (every layer
-copied host-to-device once and computed once), or for the training workload
+memory, HBM weight budget of 4 layer slots; the window -- (k, p), pinned units,
+and whether a layer streams whole or as three units -- is chosen at that budget
+by the tuner plus a short measured comparison.  A step is one pass of the whole
+hot path: sp_forward over the whole stack (every layer that is not held in the
+budget copied host-to-device once, every layer computed once), or for the training workload
 one sp_forward_backward (forward, loss, backward with re-streamed weights and
 gradients streamed device-to-host).  Inputs are resident in HBM before the
 timed region.  Prints ONE JSON line.
@@ -68,6 +70,9 @@ def main():
     ap.add_argument("--pinned", type=int, default=None,
                     help="layers held in HBM for good (-1 = what the budget leaves after k+p); "
                          "default: k, p and this are chosen by the tuner and a short measured comparison")
+    ap.add_argument("--units", type=int, default=1, choices=(1, 3),
+                    help="units a layer streams as (3: attention block, first FFN projection, last FFN projection; "
+                         "k, p and --pinned then count units); only used when k, p or --pinned is given")
     ap.add_argument("--layers", type=int, default=None, help="run a prefix of the stack (debug)")
     ap.add_argument("--distinct-blobs", type=int, default=None,
                     help="generate only this many distinct layer blobs and cycle them (host RAM limit)")
@@ -143,11 +148,11 @@ def main():
     ceiling = copy_ceiling_gbps(torch)
     log(f"[bench] plain pinned H2D copy ceiling: {ceiling:.1f} GB/s")
 
-    def run(kk, pp, flags, steps, warmup, pinned=0):
+    def run(kk, pp, flags, steps, warmup, pinned=0, units=1):
         if training:
             flags |= sp.SP_FLAG_TRAINING | (sp.SP_FLAG_KEEP_ACTIVATIONS if args.keep_activations else 0)
         eng = sp.Engine(desc, blobs, kk, pp, budget_layers=budget_layers, budget_bytes=budget_bytes, flags=flags,
-                        pinned=pinned, frozen=args.frozen if training else 0)
+                        pinned=pinned, frozen=args.frozen if training else 0, units=units)
 
         pos = [S]
 
@@ -189,6 +194,7 @@ def main():
     tmode = (2 if args.keep_activations else 1) if training else 0
     grad_ms = gbytes / (ceiling * 1e6) if training else 0.0
     pinned = args.pinned if args.pinned is not None else 0
+    units = args.units
     tuned = None
     if args.k is None and args.p is None and args.pinned is None:
         # Window choice at the fixed budget (the paper's grid search, Sec. 4.2): the cost model
@@ -200,27 +206,32 @@ def main():
         tuned = {"k": tk, "p": tp, "pinned": tr, "modelled_ms_per_step": round(tms, 3),
                  "layer_cost_ms": {"copy": round(cost[0], 3), "fwd": round(cost[1], 3),
                                    "bwd": round(cost[2], 3), "grad": round(cost[3], 3)}}
-        cands = {(k, p, 0): None, (tk, tp, tr): None}
+        cands = {(k, p, 0, 1): None, (tk, tp, tr, 1): None}
+        if not training:
+            # the same budget with a layer streamed as three units: a double buffer of the largest
+            # unit, everything else the budget holds pinned (-1 = SP_PIN_AUTO)
+            cands[(1, 1, sp.SP_PIN_AUTO, 3)] = None
         for c in cands:
-            r = run(c[0], c[1], base_flags, 3, 1, pinned=c[2])
+            r = run(c[0], c[1], base_flags, 3, 1, pinned=c[2], units=c[3])
             cands[c] = max(r["ms_per_step"], r["wall_ms_per_step"])
-        tuned["measured_ms_per_step"] = {f"k={c[0]},p={c[1]},pinned={c[2]}": round(v, 3) for c, v in cands.items()}
-        k, p, pinned = min(cands, key=cands.get)
-        log(f"[bench] window: tuner proposes {tuned}; using k={k} p={p} pinned={pinned}")
+        tuned["measured_ms_per_step"] = {f"k={c[0]},p={c[1]},pinned={c[2]},units={c[3]}": round(v, 3)
+                                         for c, v in cands.items()}
+        k, p, pinned, units = min(cands, key=cands.get)
+        log(f"[bench] window: tuner proposes {tuned}; using k={k} p={p} pinned={pinned} units/layer={units}")
     # the timed region: only the dominant GEMM is bracketed by events (compute stream)
     main_run = run(k, p, base_flags | (0 if args.no_kernel_timing else sp.SP_FLAG_KERNEL_TIMING), args.steps,
-                   args.warmup, pinned=pinned)
+                   args.warmup, pinned=pinned, units=units)
     kst = main_run["stats"]
     # a second, short region with the per-layer trace on (timestamped fence events on the
     # copy stream cost a few percent of link rate, so it is kept out of `value`)
-    trace_run = run(k, p, base_flags | sp.SP_FLAG_TIMING, 3, 1, pinned=pinned)
+    trace_run = run(k, p, base_flags | sp.SP_FLAG_TIMING, 3, 1, pinned=pinned, units=units)
     st = trace_run["stats"]
     flags = base_flags | sp.SP_FLAG_TIMING
     ms = max(main_run["ms_per_step"], main_run["wall_ms_per_step"])   # host wall covers all streams
     tokens_s = T / (ms * 1e-3)
     h2d_gbps_wall = st.last_h2d_bytes / (ms * 1e-3) / 1e9
     h2d_gbps_busy = st.last_h2d_bytes / (st.copy_busy_ms * 1e-3) / 1e9 if st.copy_busy_ms > 0 else None
-    log(f"[bench] k={k} p={p} pinned={st.plan.n_pinned} slots={st.plan.n_slots}: {ms:.2f} ms/step, {tokens_s:.0f} tokens/s, "
+    log(f"[bench] units/layer={units} k={k} p={p} pinned={st.plan.n_pinned} slots={st.plan.n_slots}: {ms:.2f} ms/step, {tokens_s:.0f} tokens/s, "
         f"H2D {h2d_gbps_wall:.1f} GB/s over wall")
 
     # dominant kernel: the layer's largest GEMM (gate/up projection, or the first MLP GEMM)
@@ -291,14 +302,17 @@ def main():
         # decode runs are compared at the same position: against the sweep's first entry
         base = None if decoding else main_run["y"]
         A = sp.SP_PIN_AUTO
-        grid = ([(1, 1, 0), (1, 2, 0), (2, 1, 0), (2, 2, 0), (4, 1, 0), (4, 2, 0), (1, 1, A), (1, 2, A), (2, 1, A)]
-                if w.name == "llama7b" else sorted({(1, 1, 0), (w.k, w.p, 0), (1, 1, A), (k, p, pinned)}))
-        for kk, pp, rr in grid:
-            r = run(kk, pp, flags & ~sp.SP_FLAG_TIMING, 3, 1, pinned=rr)
+        grid = ([(1, 1, 0, 1), (1, 2, 0, 1), (2, 1, 0, 1), (2, 2, 0, 1), (4, 1, 0, 1), (4, 2, 0, 1), (1, 1, A, 1),
+                 (1, 2, A, 1), (2, 1, A, 1), (1, 1, A, 3)]
+                if w.name == "llama7b" else
+                sorted({(1, 1, 0, 1), (w.k, w.p, 0, 1), (1, 1, A, 1), (k, p, pinned, units)} |
+                       (set() if training else {(1, 1, A, 3)})))
+        for kk, pp, rr, uu in grid:
+            r = run(kk, pp, flags & ~sp.SP_FLAG_TIMING, 3, 1, pinned=rr, units=uu)
             m = max(r["ms_per_step"], r["wall_ms_per_step"])
             if base is None:
                 base = r["y"]
-            sweep.append({"k": kk, "p": pp, "pinned": int(r["stats"].plan.n_pinned),
+            sweep.append({"k": kk, "p": pp, "units_per_layer": uu, "pinned": int(r["stats"].plan.n_pinned),
                           "slots": int(r["stats"].plan.n_slots),
                           "tokens_per_s": round(T / (m * 1e-3), 1),
                           "bit_identical": bool(np.array_equal(r["y"], base))})
@@ -357,7 +371,8 @@ def main():
                                f"x{w.head_dim} ffn={w.d_ffn} causal={w.causal} batch {B} x seq {S}, "
                                + ("forward+backward (MSE)" if training else
                                   f"prompt, then decode of one token per sequence per step" if decoding else "forward"),
-                   "k": k, "p": p, "pinned_layers": int(st.plan.n_pinned), "n_slots": int(st.plan.n_slots),
+                   "units_per_layer": units, "k": k, "p": p, "n_pinned": int(st.plan.n_pinned),
+                   "pinned_layers": int(st.plan.n_pinned) // units, "n_slots": int(st.plan.n_slots),
                    "budget_layers": budget_layers,
                    "wrap_prefetch": wrap, "keep_activations": bool(training and args.keep_activations),
                    "frozen_layers": args.frozen if training else 0,

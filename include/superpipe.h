@@ -112,6 +112,16 @@ typedef struct {
     int32_t pinned_layers;      /* layers 0..n-1 that stay in HBM for the handle's life and are
                                    never re-copied; SP_PIN_AUTO = as many as the budget leaves
                                    after the k + p window; 0 = none (every layer streams)      */
+    int32_t units_per_layer;    /* 0 or 1: a layer is the unit that streams (the paper's partition at
+                                   the repeated-layer boundaries, Sec. 3.2.1).  3: a layer streams as
+                                   three units in blob order -- the attention block (first norm, QKV and
+                                   output projections), the first FFN projection (second norm, gate/up or
+                                   W1) and the last FFN projection (down or W2) -- and k, p,
+                                   pinned_layers and every per-layer figure of sp_plan / sp_stats count
+                                   UNITS.  The double buffer then costs two of the largest unit instead
+                                   of two layers and the budget pins more of the stack (pinned units are
+                                   stored at their own size).  Forward-only handles (no SP_FLAG_TRAINING);
+                                   results are bit-identical to layer units.                            */
 } sp_config;
 #define SP_PIN_AUTO (-1)
 
@@ -127,15 +137,19 @@ typedef struct {
  *   p_eff    = min(p, max(window - 1, 1)),  k_eff = max(window - p_eff, 1).
  * With n_pinned layers held, a steady-state pass copies L - n_pinned blobs
  * instead of L: on a link-bound stack that is the only way to go faster at a
- * fixed budget once the link is saturated. */
+ * fixed budget once the link is saturated.
+ * With units_per_layer = 3 the same policy runs over the 3 L units: slot_bytes is the
+ * largest unit, the window takes k + p such slots, and the pinned units 0, 1, ... take
+ * their own sizes while they fit (sp_make_plan_units). */
 typedef struct {
     int32_t n_slots, k_eff, p_eff;
-    int32_t fully_resident;     /* n_slots == n_layers */
-    uint64_t slot_bytes;        /* blob bytes rounded up to 4 KiB */
+    int32_t fully_resident;     /* n_slots == number of units */
+    uint64_t slot_bytes;        /* bytes of the largest unit (layer blob, or its largest part) rounded up to 4 KiB */
     uint64_t workspace_bytes;
-    uint64_t arena_bytes_used;  /* workspace + n_slots * slot_bytes (+ gradient slots) */
-    int32_t n_pinned;           /* of the n_slots, those holding layers 0..n_pinned-1 for good */
-    int32_t reserved_;
+    uint64_t arena_bytes_used;  /* workspace + pinned_bytes + (n_slots - n_pinned) * slot_bytes (+ gradient slots) */
+    int32_t n_pinned;           /* of the n_slots, those holding units 0..n_pinned-1 for good */
+    int32_t units_per_layer;    /* 1 or 3 */
+    uint64_t pinned_bytes;      /* what the pinned units occupy: each its own size rounded up to 4 KiB */
 } sp_plan;
 
 #define SP_MAX_TRACE_LAYERS 256
@@ -180,9 +194,17 @@ size_t sp_layer_grad_bytes(const sp_stack_desc* desc);
  * (saved layer inputs, backward scratch, gradient slots); 2 = training with
  * SP_FLAG_KEEP_ACTIVATIONS (one activation set per layer). */
 size_t sp_workspace_bytes(const sp_stack_desc* desc, int training);
-/* The slot-count policy above as a pure function. */
+/* The slot-count policy above as a pure function (layer units). */
 int sp_make_plan(const sp_stack_desc* desc, int k, int p, int pinned_layers, uint64_t budget_bytes,
                  int training, sp_plan* out);
+/* The same with units_per_layer in {1, 3} (k, p, pinned in units).  With 3 the pinned units take
+ * their own sizes: the window's k + p slots of the largest unit come first, then units 0, 1, ... are
+ * pinned while they fit; the stack counts as fully resident only if every unit fits a slot of the
+ * largest unit's size, otherwise at least one unit keeps streaming. */
+int sp_make_plan_units(const sp_stack_desc* desc, int units_per_layer, int k, int p, int pinned_units,
+                       uint64_t budget_bytes, int training, sp_plan* out);
+/* Byte range of part `part` (0 .. units_per_layer-1) inside a layer blob. */
+int sp_unit_range(const sp_stack_desc* desc, int units_per_layer, int part, uint64_t* offset, uint64_t* bytes);
 
 /* One step of the host-side schedule, for inspection and host-only tests.
  * sp_trace_schedule writes the ordered op list that `passes` consecutive calls

@@ -50,13 +50,13 @@ class sp_config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("resident_window_k", C.c_int32), ("prefetch_depth_p", C.c_int32),
                 ("gpu_budget_bytes", C.c_uint64), ("device_arena", C.c_void_p), ("compute_stream", C.c_void_p),
                 ("h2d_stream", C.c_void_p), ("d2h_stream", C.c_void_p), ("flags", C.c_uint32),
-                ("frozen_layers", C.c_int32), ("pinned_layers", C.c_int32)]
+                ("frozen_layers", C.c_int32), ("pinned_layers", C.c_int32), ("units_per_layer", C.c_int32)]
 
 
 class sp_plan(C.Structure):
     _fields_ = [("n_slots", C.c_int32), ("k_eff", C.c_int32), ("p_eff", C.c_int32), ("fully_resident", C.c_int32),
                 ("slot_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("arena_bytes_used", C.c_uint64),
-                ("n_pinned", C.c_int32), ("reserved_", C.c_int32)]
+                ("n_pinned", C.c_int32), ("units_per_layer", C.c_int32), ("pinned_bytes", C.c_uint64)]
 
 
 _F = C.c_float * SP_MAX_TRACE_LAYERS
@@ -94,6 +94,9 @@ _sig = {
     "sp_layer_grad_bytes": (C.c_size_t, [_P(sp_stack_desc)]),
     "sp_workspace_bytes": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
     "sp_make_plan": (C.c_int, [_P(sp_stack_desc), C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_int, _P(sp_plan)]),
+    "sp_make_plan_units": (C.c_int, [_P(sp_stack_desc), C.c_int, C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_int,
+                                     _P(sp_plan)]),
+    "sp_unit_range": (C.c_int, [_P(sp_stack_desc), C.c_int, C.c_int, _P(C.c_uint64), _P(C.c_uint64)]),
     "sp_trace_schedule": (C.c_int, [C.c_int] * 7 + [_P(sp_sched_op), C.c_int]),
     "sp_create": (C.c_int, [_P(C.c_void_p), _P(sp_stack_desc), _P(C.c_void_p), _P(sp_config)]),
     "sp_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
@@ -248,7 +251,7 @@ class Engine:
     """Owns an sp_handle plus the torch-allocated arena and streams it runs on."""
 
     def __init__(self, desc, blobs, k, p, budget_bytes=None, budget_layers=None, flags=0, device="cuda:0",
-                 pinned=0, frozen=0):
+                 pinned=0, frozen=0, units=1):
         import torch
         self.torch = torch
         self.desc = desc
@@ -272,7 +275,7 @@ class Engine:
         ptrs = (C.c_void_p * len(blobs))(*[b.data_ptr() for b in blobs])
         cfg = sp_config(C.sizeof(sp_config), k, p, self.budget_bytes, self.arena.data_ptr(),
                         self.compute.cuda_stream, self.h2d.cuda_stream,
-                        self.d2h.cuda_stream if training else None, flags, frozen, pinned)
+                        self.d2h.cuda_stream if training else None, flags, frozen, pinned, units)
         self.handle = C.c_void_p()
         rc = sp_create(C.byref(self.handle), C.byref(desc), ptrs, C.byref(cfg))
         if rc != SP_OK:

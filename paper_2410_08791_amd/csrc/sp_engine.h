@@ -17,6 +17,12 @@ struct sp_engine {
     sp::Scheduler sched;
     unsigned char* arena = nullptr;   // caller's device arena: [workspace | slot 0 | slot 1 | ...]
     unsigned char* slots = nullptr;
+    // A layer streams as `units` units (1 or 3).  Unit u = layer u / units, part u % units: bytes
+    // [unit_off[part], + unit_len[part]) of that layer's blob.  Slots 0..n_pinned-1 hold the pinned
+    // units at their own sizes, the ring slots follow at plan.slot_bytes each.
+    int units = 1, n_units = 0;
+    size_t unit_off[3] = {0, 0, 0}, unit_len[3] = {0, 0, 0};
+    std::vector<unsigned char*> slot_addr;
     hipStream_t compute = nullptr, h2d = nullptr, d2h = nullptr;
     std::vector<const void*> blobs;   // pinned host weight blobs (never written)
     // Cross-stream fences.  Every copy and every layer compute of a call records
@@ -70,7 +76,10 @@ struct KvLayer {
     int max_len = 0;
     int pos = -1;           // >= 0: one new token per sequence at this position (S == 1)
 };
-int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int S, const KvLayer* kv = nullptr);
+// parts: which of the layer's three blocks to run (bit 0 attention block, bit 1 second norm and
+// first FFN projection, bit 2 last FFN projection); w is where the layer blob's byte 0 would be.
+int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int S, const KvLayer* kv = nullptr,
+                     int parts = 7);
 // Training forward of layer l: reads its saved input, writes the next layer's.
 int sp_layer_forward_train(sp_engine* e, int layer, const unsigned char* w, int B, int S);
 // Recompute + backward of layer l; leaves dL/d(input) in the stream-gradient buffer

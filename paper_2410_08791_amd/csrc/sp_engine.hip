@@ -118,12 +118,16 @@ struct HipSink : SchedSink {
             SP_HIP(e, hipStreamWaitEvent(cs, e->layer_done[wait_layer], 0));
             dep = e->layer_done_idx[wait_layer];
         }
-        unsigned char* dst = e->slots + (size_t)slot * e->plan.slot_bytes;
+        // `layer` counts units: part q of layer `layer / units`
+        const int part = layer % e->units;
+        const size_t nbytes = e->unit_len[part];
+        unsigned char* dst = e->slot_addr[slot];
         if (e->flags & SP_FLAG_POISON) {
             // bf16 NaN pattern: a read of a slot before its copy lands shows up as NaN output
-            SP_HIP(e, spk_launch_fill_u32(cs, reinterpret_cast<uint32_t*>(dst), 0x7FC17FC1u, e->plan.slot_bytes / 4));
+            SP_HIP(e, spk_launch_fill_u32(cs, reinterpret_cast<uint32_t*>(dst), 0x7FC17FC1u, align_up(nbytes, kSlotAlign) / 4));
         }
-        SP_HIP(e, hipMemcpyAsync(dst, e->blobs[layer], e->lay.blob_bytes, hipMemcpyHostToDevice, cs));
+        SP_HIP(e, hipMemcpyAsync(dst, static_cast<const unsigned char*>(e->blobs[layer / e->units]) + e->unit_off[part],
+                                 nbytes, hipMemcpyHostToDevice, cs));
         hipEvent_t ev = e->copy_ev[e->ci];
         SP_HIP(e, hipEventRecord(ev, cs));
         e->layer_loaded[layer] = ev;
@@ -132,9 +136,9 @@ struct HipSink : SchedSink {
         e->tr_copy_dep[e->ci] = dep;
         e->ci++;
         e->stats_h2d_copies++;
-        e->stats_h2d_bytes += e->lay.blob_bytes;
+        e->stats_h2d_bytes += nbytes;
         e->call_h2d_copies++;
-        e->call_h2d_bytes += e->lay.blob_bytes;
+        e->call_h2d_bytes += nbytes;
         return SP_OK;
     }
 
@@ -153,16 +157,20 @@ struct HipSink : SchedSink {
             SP_HIP(e, hipStreamWaitEvent(st, e->layer_loaded[layer], 0));
             dep = e->layer_loaded_idx[layer];
         }
-        const unsigned char* w = e->slots + (size_t)slot * e->plan.slot_bytes;
+        // where byte 0 of the layer blob would lie (a unit slot holds only its part of it: the
+        // tensors the part's kernels touch all lie inside the slot)
+        const int part = layer % e->units, lyr = layer / e->units;
+        const int parts = e->units == 1 ? 7 : 1 << part;
+        const unsigned char* w = e->slot_addr[slot] - e->unit_off[part];
         if (dir > 0 && kv_cache) {
             KvLayer kv;
-            kv.kt = reinterpret_cast<bf16_t*>(kv_cache + (size_t)layer * kv_layer_bytes);
-            kv.v = reinterpret_cast<bf16_t*>(kv_cache + (size_t)layer * kv_layer_bytes + kv_layer_bytes / 2);
+            kv.kt = reinterpret_cast<bf16_t*>(kv_cache + (size_t)lyr * kv_layer_bytes);
+            kv.v = reinterpret_cast<bf16_t*>(kv_cache + (size_t)lyr * kv_layer_bytes + kv_layer_bytes / 2);
             kv.max_len = kv_max_len;
             kv.pos = kv_pos;
-            rc = sp_layer_forward(e, w, hbuf, B, S, &kv);
+            rc = sp_layer_forward(e, w, hbuf, B, S, &kv, parts);
         } else if (dir > 0)
-            rc = training_fwd ? sp_layer_forward_train(e, layer, w, B, S) : sp_layer_forward(e, w, hbuf, B, S);
+            rc = training_fwd ? sp_layer_forward_train(e, layer, w, B, S) : sp_layer_forward(e, w, hbuf, B, S, nullptr, parts);
         else
             rc = sp_layer_backward(e, layer, w, B, S);
         if (rc != SP_OK) return rc;
@@ -178,7 +186,7 @@ struct HipSink : SchedSink {
 };
 
 // ---- one decoder / encoder layer, forward, residual stream updated in place -------
-int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int S, const KvLayer* kv) {
+int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int S, const KvLayer* kv, int parts) {
     const sp_stack_desc& d = e->desc;
     const Layout& L = e->lay;
     hipStream_t st = e->compute;
@@ -194,57 +202,67 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
     GemmArgs g;
 
-    // b1: a = norm(h)
-    SP_HIP(e, spk_launch_norm(st, h, W(dec ? SP_T_G1 : SP_T_LN1_G), dec ? nullptr : W(SP_T_LN1_B), a, T, dm, d.norm_eps));
-    // b2: qkv = a Wqkv^T (+ b)
-    g = GemmArgs{a, dm, OP_KMAJOR, W(dec ? SP_T_WQKV : SP_T_E_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0,
-                 dec ? nullptr : W(SP_T_BQKV), T, nqkv, dm, e->gemm_tile};
-    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
-    // b3: attention.  With a cache the new keys/values are stored first; a decode step then
-    // attends its single query per sequence to the cached positions 0..pos.
-    if (kv)
-        SP_HIP(e, spk_launch_kv_append(st, qkv, nqkv, kv->kt, kv->v, B, S, kv->pos >= 0 ? kv->pos : 0, d.n_q_heads,
-                                       d.n_kv_heads, d.head_dim, kv->max_len));
-    if (kv && kv->pos >= 0) {
-        SP_HIP(e, spk_launch_decode_attention(st, qkv, nqkv, kv->kt, kv->v, o, nq, B, kv->pos + 1, kv->max_len,
-                                              d.n_q_heads, d.n_kv_heads, d.head_dim));
-    } else {
-        SP_HIP(e, spk_launch_attention(st, qkv, o, nullptr, as));
-    }
-    // b4: h += o Wo^T (+ b)
-    g = GemmArgs{o, nq, OP_KMAJOR, W(dec ? SP_T_WO : SP_T_E_WO), nq, OP_KMAJOR, h, dm, h, dm,
-                 dec ? nullptr : W(SP_T_BO), T, dm, nq, e->gemm_tile};
-    SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
-    // b5: a = norm(h)
-    SP_HIP(e, spk_launch_norm(st, h, W(dec ? SP_T_G2 : SP_T_LN2_G), dec ? nullptr : W(SP_T_LN2_B), a, T, dm, d.norm_eps));
-    // every 4th launch of the largest GEMM is bracketed: the two event records cost a gap
-    // on the stream, which on a compute-bound stack would show in the step time
-    const bool kt = !e->kt_begin.empty() && (e->kt_seen++ % 4 == 0);
-    const size_t kti = kt ? e->kt_count % e->kt_begin.size() : 0;
-    if (kt) {
-        SP_HIP(e, hipEventRecord(e->kt_begin[kti], st));
-        e->kt_m = T; e->kt_n = dec ? 2 * f : f; e->kt_k = dm;
-    }
-    if (dec) {
-        // b6+b7: z = silu(a Wg^T) * (a Wu^T), gate applied in the GEMM epilogue
-        if (e->fuse_swiglu) {
-            g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, z, f, nullptr, 0, nullptr, T, f, dm, e->gemm_tile};
-            SP_HIP(e, spk_launch_gemm(st, EPI_SWIGLU_BF16, g));
+    if (parts & 1) {
+        // b1: a = norm(h)
+        SP_HIP(e, spk_launch_norm(st, h, W(dec ? SP_T_G1 : SP_T_LN1_G), dec ? nullptr : W(SP_T_LN1_B), a, T, dm, d.norm_eps));
+        // b2: qkv = a Wqkv^T (+ b)
+        g = GemmArgs{a, dm, OP_KMAJOR, W(dec ? SP_T_WQKV : SP_T_E_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0,
+                     dec ? nullptr : W(SP_T_BQKV), T, nqkv, dm, e->gemm_tile};
+        SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+        // b3: attention.  With a cache the new keys/values are stored first; a decode step then
+        // attends its single query per sequence to the cached positions 0..pos.
+        if (kv)
+            SP_HIP(e, spk_launch_kv_append(st, qkv, nqkv, kv->kt, kv->v, B, S, kv->pos >= 0 ? kv->pos : 0, d.n_q_heads,
+                                           d.n_kv_heads, d.head_dim, kv->max_len));
+        if (kv && kv->pos >= 0) {
+            SP_HIP(e, spk_launch_decode_attention(st, qkv, nqkv, kv->kt, kv->v, o, nq, B, kv->pos + 1, kv->max_len,
+                                                  d.n_q_heads, d.n_kv_heads, d.head_dim));
         } else {
-            g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, gu, 2 * f, nullptr, 0, nullptr, T, 2 * f, dm, e->gemm_tile};
-            SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+            SP_HIP(e, spk_launch_attention(st, qkv, o, nullptr, as));
         }
-        if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
-        if (!e->fuse_swiglu) SP_HIP(e, spk_launch_swiglu(st, gu, z, T, f));
-        // b8: h += z Wd^T
-        g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_WD), f, OP_KMAJOR, h, dm, h, dm, nullptr, T, dm, f, e->gemm_tile};
+        // b4: h += o Wo^T (+ b)
+        g = GemmArgs{o, nq, OP_KMAJOR, W(dec ? SP_T_WO : SP_T_E_WO), nq, OP_KMAJOR, h, dm, h, dm,
+                     dec ? nullptr : W(SP_T_BO), T, dm, nq, e->gemm_tile};
         SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
-    } else {
-        g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_W1), dm, OP_KMAJOR, z, f, nullptr, 0, W(SP_T_B1), T, f, dm, e->gemm_tile};
-        SP_HIP(e, spk_launch_gemm(st, EPI_GELU_BF16, g));
-        if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
-        g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_W2), f, OP_KMAJOR, h, dm, h, dm, W(SP_T_B2), T, dm, f, e->gemm_tile};
-        SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+    }
+    if (parts & 2) {
+        // b5: a = norm(h)
+        SP_HIP(e, spk_launch_norm(st, h, W(dec ? SP_T_G2 : SP_T_LN2_G), dec ? nullptr : W(SP_T_LN2_B), a, T, dm, d.norm_eps));
+        // every 4th launch of the largest GEMM is bracketed: the two event records cost a gap
+        // on the stream, which on a compute-bound stack would show in the step time
+        const bool kt = !e->kt_begin.empty() && (e->kt_seen++ % 4 == 0);
+        const size_t kti = kt ? e->kt_count % e->kt_begin.size() : 0;
+        if (kt) {
+            SP_HIP(e, hipEventRecord(e->kt_begin[kti], st));
+            e->kt_m = T; e->kt_n = dec ? 2 * f : f; e->kt_k = dm;
+        }
+        if (dec) {
+            // b6+b7: z = silu(a Wg^T) * (a Wu^T), gate applied in the GEMM epilogue
+            if (e->fuse_swiglu) {
+                g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, z, f, nullptr, 0, nullptr, T, f, dm, e->gemm_tile};
+                SP_HIP(e, spk_launch_gemm(st, EPI_SWIGLU_BF16, g));
+            } else {
+                g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, gu, 2 * f, nullptr, 0, nullptr, T, 2 * f, dm,
+                             e->gemm_tile};
+                SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+            }
+            if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
+            if (!e->fuse_swiglu) SP_HIP(e, spk_launch_swiglu(st, gu, z, T, f));
+        } else {
+            g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_W1), dm, OP_KMAJOR, z, f, nullptr, 0, W(SP_T_B1), T, f, dm, e->gemm_tile};
+            SP_HIP(e, spk_launch_gemm(st, EPI_GELU_BF16, g));
+            if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
+        }
+    }
+    if (parts & 4) {
+        if (dec) {
+            // b8: h += z Wd^T
+            g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_WD), f, OP_KMAJOR, h, dm, h, dm, nullptr, T, dm, f, e->gemm_tile};
+            SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+        } else {
+            g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_W2), f, OP_KMAJOR, h, dm, h, dm, W(SP_T_B2), T, dm, f, e->gemm_tile};
+            SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+        }
     }
     return SP_OK;
 }
@@ -274,11 +292,14 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     if (desc->n_layers > 4096) return fail(nullptr, SP_ERR_INVALID_ARG, "n_layers > 4096");
     if (cfg->frozen_layers < 0 || cfg->frozen_layers > desc->n_layers || (cfg->frozen_layers && !training))
         return fail(nullptr, SP_ERR_INVALID_ARG, "frozen_layers must be in 0..n_layers and needs SP_FLAG_TRAINING");
+    const int units = cfg->units_per_layer ? cfg->units_per_layer : 1;
+    if (units != 1 && units != 3) return fail(nullptr, SP_ERR_INVALID_ARG, "units_per_layer must be 0, 1 or 3");
+    if (units != 1 && training) return fail(nullptr, SP_ERR_INVALID_ARG, "units_per_layer = 3 is for forward-only handles");
     sp_plan plan;
-    int rc = make_plan(desc, cfg->resident_window_k, cfg->prefetch_depth_p, cfg->pinned_layers, cfg->gpu_budget_bytes, mode,
-                       &plan);
+    int rc = make_plan(desc, units, cfg->resident_window_k, cfg->prefetch_depth_p, cfg->pinned_layers,
+                       cfg->gpu_budget_bytes, mode, &plan);
     if (rc == SP_ERR_BUDGET) {
-        return fail(nullptr, rc, "gpu_budget_bytes=%llu cannot hold the workspace (%llu) plus one layer slot (%llu)",
+        return fail(nullptr, rc, "gpu_budget_bytes=%llu cannot hold the workspace (%llu) plus one slot (%llu)",
                     (unsigned long long)cfg->gpu_budget_bytes, (unsigned long long)plan.workspace_bytes,
                     (unsigned long long)plan.slot_bytes);
     }
@@ -302,11 +323,23 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     make_workspace(desc, e->lay, mode, &e->ws);
     e->arena = static_cast<unsigned char*>(cfg->device_arena);
     e->slots = e->arena + e->ws.total;
+    e->units = units;
+    e->n_units = desc->n_layers * units;
+    for (int q = 0; q < units; ++q) unit_range(desc, e->lay, units, q, &e->unit_off[q], &e->unit_len[q]);
+    {
+        // pinned units first, each at its own size, then the ring of equal slots
+        unsigned char* at = e->slots;
+        e->slot_addr.resize(plan.n_slots);
+        for (int s = 0; s < plan.n_slots; ++s) {
+            e->slot_addr[s] = at;
+            at += s < plan.n_pinned ? align_up(e->unit_len[s % units], kSlotAlign) : plan.slot_bytes;
+        }
+    }
     e->compute = static_cast<hipStream_t>(cfg->compute_stream);
     e->h2d = static_cast<hipStream_t>(cfg->h2d_stream);
     e->d2h = static_cast<hipStream_t>(cfg->d2h_stream);
     e->blobs.assign(blobs, blobs + desc->n_layers);
-    const int L = desc->n_layers;
+    const int L = e->n_units;      // what the scheduler calls a layer: a unit
     const bool timing = cfg->flags & SP_FLAG_TIMING;
     // a call issues at most 2L + n_slots copies and 2L computes (forward + backward)
     e->copy_ev.assign((training ? 2 : 1) * L + plan.n_slots + 1, nullptr);

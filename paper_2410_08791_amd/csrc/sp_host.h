@@ -56,7 +56,9 @@ struct Workspace {
 // layer's activations (no recompute)
 void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Workspace* ws);
 
-int make_plan(const sp_stack_desc* d, int k, int p, int pinned, uint64_t budget, int training, sp_plan* out);
+// Byte range of part `part` of a layer blob when a layer streams as `units` units (1 or 3).
+int unit_range(const sp_stack_desc* d, const Layout& lay, int units, int part, size_t* off, size_t* len);
+int make_plan(const sp_stack_desc* d, int units, int k, int p, int pinned, uint64_t budget, int training, sp_plan* out);
 
 // ---- window scheduler --------------------------------------------------------
 // Decides, in host order, which layer is copied into which slot and when a

@@ -109,32 +109,69 @@ void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Wor
     ws->total = align_up(off, kSlotAlign);
 }
 
-int make_plan(const sp_stack_desc* d, int k, int p, int pinned, uint64_t budget, int training, sp_plan* out) {
+int unit_range(const sp_stack_desc* d, const Layout& lay, int units, int part, size_t* off, size_t* len) {
+    if (units == 1 && part == 0) { *off = 0; *len = lay.blob_bytes; return SP_OK; }
+    if (units != 3 || part < 0 || part > 2) return SP_ERR_INVALID_ARG;
+    // blob order: [attention block | second norm + first FFN projection | last FFN projection]
+    const bool dec = d->arch == SP_DECODER_SWIGLU_RMS;
+    const size_t cut1 = lay.t[dec ? SP_T_G2 : SP_T_LN2_G].offset, cut2 = lay.t[dec ? SP_T_WD : SP_T_W2].offset;
+    const size_t b[4] = {0, cut1, cut2, lay.blob_bytes};
+    *off = b[part];
+    *len = b[part + 1] - b[part];
+    return SP_OK;
+}
+
+int make_plan(const sp_stack_desc* d, int units, int k, int p, int pinned, uint64_t budget, int training, sp_plan* out) {
     if (!out) return SP_ERR_INVALID_ARG;
     memset(out, 0, sizeof(*out));
     Layout lay;
     int rc = make_layout(d, &lay);
     if (rc != SP_OK) return rc;
+    if (units == 0) units = 1;
+    if ((units != 1 && units != 3) || (units != 1 && training)) return SP_ERR_INVALID_ARG;
     if (k < 1 || p < 1 || pinned < SP_PIN_AUTO) return SP_ERR_INVALID_ARG;
     Workspace ws;
     make_workspace(d, lay, training, &ws);
-    out->slot_bytes = align_up(lay.blob_bytes, kSlotAlign);
+    size_t ubytes[3] = {0, 0, 0};      // each part's size in the arena
+    for (int q = 0; q < units; ++q) {
+        size_t off, len;
+        unit_range(d, lay, units, q, &off, &len);
+        ubytes[q] = align_up(len, kSlotAlign);
+        out->slot_bytes = std::max<uint64_t>(out->slot_bytes, ubytes[q]);
+    }
+    out->units_per_layer = units;
     out->workspace_bytes = ws.total;
     if (budget < ws.total + out->slot_bytes) return SP_ERR_BUDGET;
-    const int64_t L = d->n_layers;
-    const int64_t cap = std::min<int64_t>(L, (int64_t)std::min<uint64_t>((budget - ws.total) / out->slot_bytes, 1u << 30));
-    // the streaming window comes first; pinned layers take what the budget leaves
+    const int64_t L = (int64_t)d->n_layers * units;      // units in the stack
+    const uint64_t room = budget - ws.total;
+    const int64_t cap = std::min<int64_t>(L, (int64_t)std::min<uint64_t>(room / out->slot_bytes, 1u << 30));
+    // the streaming window comes first; pinned units take what the budget leaves
     const int64_t window = std::min<int64_t>((int64_t)k + p, cap);
-    int64_t r = pinned == SP_PIN_AUTO ? cap - window : std::min<int64_t>(pinned, cap - window);
+    uint64_t left = room - (uint64_t)window * out->slot_bytes, pinned_bytes = 0;
+    int64_t r = 0;
+    while (r < L && (pinned == SP_PIN_AUTO || r < pinned) && ubytes[r % units] <= left) {
+        left -= ubytes[r % units];
+        pinned_bytes += ubytes[r % units];
+        ++r;
+    }
     int64_t n = window + r;
-    if (n >= L) { n = L; r = 0; }       // everything fits: nothing streams, nothing to pin
+    if (n >= L) {
+        if ((uint64_t)L * out->slot_bytes <= room) {
+            n = L; r = 0; pinned_bytes = 0;        // everything fits uniform slots: nothing streams, nothing to pin
+        } else {
+            // fits only with the pinned units at their own sizes: keep one unit streaming
+            while (r > 0 && window + r >= L) { --r; pinned_bytes -= ubytes[r % units]; }
+            n = window + r;
+        }
+    }
     out->n_slots = (int)n;
     out->n_pinned = (int)r;
+    out->pinned_bytes = pinned_bytes;
     const int64_t ring = n - r;
     out->p_eff = (int)std::min<int64_t>(p, std::max<int64_t>(ring - 1, 1));
     out->k_eff = (int)std::max<int64_t>(ring - out->p_eff, 1);
     out->fully_resident = n == L;
-    out->arena_bytes_used = ws.total + (uint64_t)n * out->slot_bytes;
+    out->arena_bytes_used = ws.total + pinned_bytes + (uint64_t)ring * out->slot_bytes;
     return SP_OK;
 }
 
@@ -277,7 +314,26 @@ extern "C" size_t sp_workspace_bytes(const sp_stack_desc* desc, int training) {
 
 extern "C" int sp_make_plan(const sp_stack_desc* desc, int k, int p, int pinned_layers, uint64_t budget_bytes,
                             int training, sp_plan* out) {
-    return make_plan(desc, k, p, pinned_layers, budget_bytes, training, out);
+    return make_plan(desc, 1, k, p, pinned_layers, budget_bytes, training, out);
+}
+
+extern "C" int sp_make_plan_units(const sp_stack_desc* desc, int units_per_layer, int k, int p, int pinned_units,
+                                  uint64_t budget_bytes, int training, sp_plan* out) {
+    return make_plan(desc, units_per_layer, k, p, pinned_units, budget_bytes, training, out);
+}
+
+extern "C" int sp_unit_range(const sp_stack_desc* desc, int units_per_layer, int part, uint64_t* offset,
+                             uint64_t* bytes) {
+    Layout lay;
+    if (!offset || !bytes) return SP_ERR_INVALID_ARG;
+    int rc = make_layout(desc, &lay);
+    if (rc != SP_OK) return rc;
+    size_t off = 0, len = 0;
+    rc = unit_range(desc, lay, units_per_layer, part, &off, &len);
+    if (rc != SP_OK) return rc;
+    *offset = off;
+    *bytes = len;
+    return SP_OK;
 }
 
 namespace {
@@ -395,7 +451,7 @@ extern "C" int sp_autotune(const sp_stack_desc* desc, uint64_t budget_bytes, int
         for (int p = 1; p <= L; ++p) {
             for (int k = 1; k + p <= L + 1; ++k) {
                 sp_plan pl;
-                int rc = make_plan(desc, k, p, pin ? SP_PIN_AUTO : 0, budget_bytes, training, &pl);
+                int rc = make_plan(desc, 1, k, p, pin ? SP_PIN_AUTO : 0, budget_bytes, training, &pl);
                 if (rc != SP_OK) { if (rc_first == SP_OK) rc_first = rc; continue; }
                 bool seen = false;
                 for (const Cand& c : cands) seen = seen || (c.n == pl.n_slots && c.r == pl.n_pinned && c.p == pl.p_eff);

@@ -195,3 +195,52 @@ def test_gemm_plan_is_a_function_of_the_shape_alone():
     assert gemm_plan(sp.EPI_GELU_BF16, 0, 0, 16448, 5120) == (5, 16384, 7)
     assert sp.lib.spk_gemm_plan(7, 0, 0, 8, 8, (C.c_int * 3)()) == sp.SP_ERR_INVALID_ARG
     assert sp.lib.spk_gemm_plan(0, 0, 0, 0, 8, (C.c_int * 3)()) == sp.SP_ERR_INVALID_ARG
+
+
+def test_unit_ranges_and_the_plan_in_units():
+    """A layer streamed as three units: the parts tile the blob at tensor boundaries, the plan
+    with one unit per layer is sp_make_plan's, and at the llama7b budget of four layers the
+    window of two gate/up-sized slots leaves room to pin three whole layers instead of two."""
+    w = synth.WORKLOADS["llama7b"]
+    desc = sp.make_desc(w)
+    blob = sp.sp_layer_blob_bytes(C.byref(desc))
+    parts = []
+    for q in range(3):
+        off, n = C.c_uint64(), C.c_uint64()
+        assert sp.sp_unit_range(C.byref(desc), 3, q, C.byref(off), C.byref(n)) == sp.SP_OK
+        parts.append((off.value, n.value))
+    assert parts[0][0] == 0 and parts[1][0] == sp.sp_tensor_offset(C.byref(desc), 3)   # second norm gain
+    assert parts[2][0] == sp.sp_tensor_offset(C.byref(desc), 5)   # down projection
+    assert sum(n for _, n in parts) == blob
+    off, n = C.c_uint64(), C.c_uint64()
+    assert sp.sp_unit_range(C.byref(desc), 1, 0, C.byref(off), C.byref(n)) == sp.SP_OK and (off.value, n.value) == (0, blob)
+    assert sp.sp_unit_range(C.byref(desc), 2, 0, C.byref(off), C.byref(n)) == sp.SP_ERR_INVALID_ARG
+    assert sp.sp_unit_range(C.byref(desc), 3, 3, C.byref(off), C.byref(n)) == sp.SP_ERR_INVALID_ARG
+
+    ws = sp.sp_workspace_bytes(C.byref(desc), 0)
+    al = lambda v: (v + 4095) // 4096 * 4096  # noqa: E731
+    budget = ws + 4 * al(blob)
+    a, b = sp.sp_plan(), sp.sp_plan()
+    for k, p, pinned in [(1, 1, 0), (2, 2, 0), (1, 1, sp.SP_PIN_AUTO), (4, 2, 1), (40, 1, 0)]:
+        assert sp.sp_make_plan(C.byref(desc), k, p, pinned, budget, 0, C.byref(a)) == sp.SP_OK
+        assert sp.sp_make_plan_units(C.byref(desc), 1, k, p, pinned, budget, 0, C.byref(b)) == sp.SP_OK
+        assert bytes(a) == bytes(b) and a.units_per_layer == 1
+        assert a.pinned_bytes == a.n_pinned * a.slot_bytes
+    # layer units: 2 window slots + 2 pinned layers; three units per layer: 2 slots + 9 pinned units
+    assert sp.sp_make_plan(C.byref(desc), 1, 1, sp.SP_PIN_AUTO, budget, 0, C.byref(a)) == sp.SP_OK
+    assert (a.n_slots, a.n_pinned) == (4, 2)
+    assert sp.sp_make_plan_units(C.byref(desc), 3, 1, 1, sp.SP_PIN_AUTO, budget, 0, C.byref(b)) == sp.SP_OK
+    assert b.slot_bytes == al(max(n for _, n in parts)) and (b.n_slots, b.n_pinned) == (11, 9)
+    assert b.pinned_bytes == 3 * sum(al(n) for _, n in parts)
+    assert b.arena_bytes_used == ws + b.pinned_bytes + 2 * b.slot_bytes <= budget
+    assert not b.fully_resident and b.k_eff == 1 and b.p_eff == 1
+    # a stack that fits only with the units at their own sizes keeps one unit streaming
+    small = sp.make_desc(w, n_layers=2)
+    ws2 = sp.sp_workspace_bytes(C.byref(small), 0)
+    room = 2 * sum(al(n) for _, n in parts) + al(parts[1][1])
+    assert sp.sp_make_plan_units(C.byref(small), 3, 1, 1, sp.SP_PIN_AUTO, ws2 + room, 0, C.byref(b)) == sp.SP_OK
+    assert not b.fully_resident and b.n_slots == 5 and b.n_pinned == 3
+    assert sp.sp_make_plan_units(C.byref(small), 3, 8, 8, 0, ws2 + 6 * b.slot_bytes, 0, C.byref(b)) == sp.SP_OK
+    assert b.fully_resident and b.n_slots == 6 and b.n_pinned == 0 and b.pinned_bytes == 0
+    # training handles stream whole layers
+    assert sp.sp_make_plan_units(C.byref(desc), 3, 1, 1, 0, 10 * budget, 1, C.byref(b)) == sp.SP_ERR_INVALID_ARG

@@ -42,9 +42,9 @@ class Case:
                                                oracle_shape(self.w), dtype=dtype)
         return self._ref[dtype]
 
-    def run(self, k, p, flags=0, budget_layers=None, calls=1, budget_bytes=None, pinned=0):
+    def run(self, k, p, flags=0, budget_layers=None, calls=1, budget_bytes=None, pinned=0, units=1):
         eng = sp.Engine(self.desc, self.blobs, k, p, budget_layers=budget_layers, budget_bytes=budget_bytes,
-                        flags=flags, pinned=pinned)
+                        flags=flags, pinned=pinned, units=units)
         outs = []
         for _ in range(calls):
             y = torch.full_like(self.xd, float("nan"))
@@ -109,6 +109,66 @@ def test_pinned_layers_do_not_change_bits_and_save_copies():
         assert st.last_h2d_copies <= L - r
         if wrap:
             assert st.last_h2d_copies == L - r
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_encoder"])
+def test_three_units_per_layer_give_the_same_bits_with_a_smaller_window(name):
+    """A layer streamed as three units (attention block, first FFN projection, last FFN
+    projection): the double buffer holds two of the largest unit instead of two layers, pinned
+    units are stored at their own sizes, and nothing about the result changes."""
+    w = synth.WORKLOADS["tiny"].with_(n_layers=6)
+    if name == "tiny_encoder":
+        w = w.with_(arch="encoder", causal=False, head_dim=80, n_q_heads=4, n_kv_heads=4, d_model=320, seq=50)
+    c = Case(w)
+    L, U = 6, 3
+    (base,), st = c.run(8, 8)
+    assert st.plan.fully_resident and max_rel(base, c.ref()) <= TOL
+    blob = sp.sp_layer_blob_bytes(C.byref(c.desc))
+    rng = []
+    for q in range(U):
+        off, n = C.c_uint64(), C.c_uint64()
+        assert sp.sp_unit_range(C.byref(c.desc), U, q, C.byref(off), C.byref(n)) == sp.SP_OK
+        rng.append((off.value, n.value))
+    assert rng[0][0] == 0 and all(rng[q][0] + rng[q][1] == rng[q + 1][0] for q in range(U - 1))
+    assert rng[-1][0] + rng[-1][1] == blob
+    al = lambda n: (n + 4095) // 4096 * 4096  # noqa: E731
+    ws = sp.sp_workspace_bytes(C.byref(c.desc), 0)
+    for k, p, pinned, flags, budget_layers in [
+            (1, 1, 0, 0, None), (2, 1, 0, sp.SP_FLAG_POISON, None), (1, 2, 4, sp.SP_FLAG_WRAP_PREFETCH, None),
+            (1, 1, sp.SP_PIN_AUTO, sp.SP_FLAG_WRAP_PREFETCH | sp.SP_FLAG_POISON | sp.SP_FLAG_TIMING, 3),
+            (1, 1, sp.SP_PIN_AUTO, sp.SP_FLAG_NO_OVERLAP, 2), (30, 30, 0, 0, 6)]:
+        budget = None if budget_layers is None else ws + budget_layers * al(blob)
+        if budget is None:       # room for the window and the pinned units asked for
+            budget = ws + (k + p) * al(max(n for _, n in rng)) + sum(al(rng[u % U][1]) for u in range(max(pinned, 0)))
+        outs, st = c.run(k, p, flags=flags, calls=3, pinned=pinned, budget_bytes=budget, units=U)
+        for y in outs:
+            assert np.array_equal(y.view(np.uint32), base.view(np.uint32)), (k, p, pinned, flags)
+        pl = st.plan
+        assert pl.units_per_layer == U and pl.slot_bytes == al(max(n for _, n in rng))
+        assert pl.arena_bytes_used <= budget
+        assert pl.pinned_bytes == sum(al(rng[u % U][1]) for u in range(pl.n_pinned))
+        assert pl.arena_bytes_used == ws + pl.pinned_bytes + (pl.n_slots - pl.n_pinned) * pl.slot_bytes
+        if pl.fully_resident:
+            assert pl.n_slots == L * U and st.last_h2d_copies == 0
+            continue
+        # steady state with the wrap prefetch: exactly the units that are not pinned, at their sizes
+        if flags & sp.SP_FLAG_WRAP_PREFETCH:
+            assert st.last_h2d_copies == L * U - pl.n_pinned
+            assert st.last_h2d_bytes == sum(rng[u % U][1] for u in range(pl.n_pinned, L * U))
+        if flags & sp.SP_FLAG_TIMING:
+            assert st.n_timed == L * U
+    # the same 3-layer budget pins more of the stack in units: fewer bytes per pass
+    _, st1 = c.run(1, 1, flags=sp.SP_FLAG_WRAP_PREFETCH, calls=3, pinned=sp.SP_PIN_AUTO, budget_layers=3)
+    _, st3 = c.run(1, 1, flags=sp.SP_FLAG_WRAP_PREFETCH, calls=3, pinned=sp.SP_PIN_AUTO, budget_layers=3, units=U)
+    assert st3.last_h2d_bytes < st1.last_h2d_bytes
+
+
+def test_units_are_refused_for_training(tiny):
+    with pytest.raises(sp.SuperpipeError) as ei:
+        sp.Engine(tiny.desc, tiny.blobs, 1, 1, flags=sp.SP_FLAG_TRAINING, units=3)
+    assert ei.value.code == sp.SP_ERR_INVALID_ARG
+    with pytest.raises(sp.SuperpipeError):
+        sp.Engine(tiny.desc, tiny.blobs, 1, 1, units=2)
 
 
 def test_debug_and_comparator_modes_do_not_change_bits(tiny):
