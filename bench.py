@@ -202,15 +202,11 @@ def main():
         # a short measured run of both decides which one the timed region uses.
         probe = run(k, p, base_flags | sp.SP_FLAG_TIMING, 3, 1)
         cost = sp.layer_costs(probe["stats"], w.n_layers, training=training, grad_ms=grad_ms)
-        tk, tp, tr, tms = sp.autotune(desc, int(probe["budget"]), cost, wrap=wrap, training=tmode)
-        tuned = {"k": tk, "p": tp, "pinned": tr, "modelled_ms_per_step": round(tms, 3),
+        tu, tk, tp, tr, tms = sp.autotune_units(desc, int(probe["budget"]), cost, wrap=wrap, training=tmode)
+        tuned = {"units_per_layer": tu, "k": tk, "p": tp, "pinned": tr, "modelled_ms_per_step": round(tms, 3),
                  "layer_cost_ms": {"copy": round(cost[0], 3), "fwd": round(cost[1], 3),
                                    "bwd": round(cost[2], 3), "grad": round(cost[3], 3)}}
-        cands = {(k, p, 0, 1): None, (tk, tp, tr, 1): None}
-        if not training:
-            # the same budget with a layer streamed as three units: a double buffer of the largest
-            # unit, everything else the budget holds pinned (-1 = SP_PIN_AUTO)
-            cands[(1, 1, sp.SP_PIN_AUTO, 3)] = None
+        cands = {(k, p, 0, 1): None, (tk, tp, tr, tu): None}
         for c in cands:
             r = run(c[0], c[1], base_flags, 3, 1, pinned=c[2], units=c[3])
             cands[c] = max(r["ms_per_step"], r["wall_ms_per_step"])

@@ -251,6 +251,16 @@ int sp_autotune(const sp_stack_desc* desc, uint64_t budget_bytes, int training, 
                 const sp_layer_cost* cost, double tolerance, int* k_out, int* p_out, int* pinned_out,
                 double* ms_out);
 
+/* The same choice with the unit size included: the layer-unit proposal of sp_autotune against
+ * three units per layer (windows of 1..2 + 1..2 unit slots, the rest of the budget pinned).  A
+ * unit's copy is charged its share of the layer's bytes, its compute its share of the layer's
+ * arithmetic, each plus the measured fixed cost of one more copy / one more fenced compute
+ * operation; units are proposed only when the modelled time is better by more than `tolerance`.
+ * Training handles stream whole layers: *units_out = 1. */
+int sp_autotune_units(const sp_stack_desc* desc, uint64_t budget_bytes, int training, int wrap_prefetch,
+                      const sp_layer_cost* cost, double tolerance, int* units_out, int* k_out, int* p_out,
+                      int* pinned_out, double* ms_out);
+
 /* ---- the four calls ------------------------------------------------------ */
 
 /* Create an executor.  layer_host_blobs[n_layers]: host, pinned, each

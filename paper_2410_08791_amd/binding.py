@@ -87,6 +87,8 @@ _sig = {
     "sp_simulate_call_ms": (C.c_double, [C.c_int] * 7 + [_P(sp_layer_cost)]),
     "sp_autotune": (C.c_int, [_P(sp_stack_desc), C.c_uint64, C.c_int, C.c_int, _P(sp_layer_cost), C.c_double,
                               _P(C.c_int), _P(C.c_int), _P(C.c_int), _P(C.c_double)]),
+    "sp_autotune_units": (C.c_int, [_P(sp_stack_desc), C.c_uint64, C.c_int, C.c_int, _P(sp_layer_cost), C.c_double,
+                                    _P(C.c_int), _P(C.c_int), _P(C.c_int), _P(C.c_int), _P(C.c_double)]),
     "sp_num_tensors": (C.c_int, [_P(sp_stack_desc)]),
     "sp_tensor_offset": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
     "sp_tensor_elems": (C.c_size_t, [_P(sp_stack_desc), C.c_int]),
@@ -202,6 +204,18 @@ def autotune(desc, budget_bytes, cost, training=0, wrap=False, tolerance=0.02):
     if rc != SP_OK:
         raise SuperpipeError(rc, "sp_autotune")
     return k.value, p.value, r.value, ms.value
+
+
+def autotune_units(desc, budget_bytes, cost, training=0, wrap=False, tolerance=0.02):
+    """(units per layer, k, p, pinned units, modelled ms): sp_autotune's choice against a layer
+    streamed as three units."""
+    c = sp_layer_cost(*cost)
+    u, k, p, r, ms = C.c_int(), C.c_int(), C.c_int(), C.c_int(), C.c_double()
+    rc = sp_autotune_units(C.byref(desc), budget_bytes, int(training), int(wrap), C.byref(c), tolerance,
+                           C.byref(u), C.byref(k), C.byref(p), C.byref(r), C.byref(ms))
+    if rc != SP_OK:
+        raise SuperpipeError(rc, "sp_autotune_units")
+    return u.value, k.value, p.value, r.value, ms.value
 
 
 def layer_costs(st, n_layers, training=False, grad_ms=0.0):

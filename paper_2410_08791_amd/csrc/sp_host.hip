@@ -372,11 +372,27 @@ extern "C" int sp_trace_schedule(int n_layers, int n_slots, int n_pinned, int p_
 
 // ---- schedule cost model and window tuner ----------------------------------
 namespace {
+// Measured on MI355X: what one more copy / one more fenced compute operation costs when a layer
+// is cut into units (llama7b: 87 instead of 30 copies per pass, +1.4 ms; ViT-H: 96 instead of 32
+// computes, +4.3 ms).
+constexpr double kCopyFixedMs = 0.025, kComputeFixedMs = 0.06;
+
 // Plays the scheduler's decisions on three in-order streams (copy, compute, gradient
 // copy) with fixed per-layer durations; the same dependencies the engine expresses as
 // events become max() of end times here.
 struct SimSink : SchedSink {
     const sp_layer_cost& c;
+    // units > 1: op `layer` is unit q = layer % units of a layer; its copy takes the unit's share
+    // of the bytes, its compute the unit's share of the layer's time, each plus a fixed cost per
+    // extra operation (launch of a copy; the event wait in front of a compute)
+    int units = 1;
+    double copy_part[3] = {1, 0, 0}, fwd_part[3] = {1, 0, 0};
+    double copy_ms_of(int layer) const {
+        return units == 1 ? c.copy_ms : std::max(0.0, c.copy_ms - kCopyFixedMs) * copy_part[layer % units] + kCopyFixedMs;
+    }
+    double fwd_ms_of(int layer) const {
+        return units == 1 ? c.fwd_ms : c.fwd_ms * fwd_part[layer % units] + kComputeFixedMs;
+    }
     std::vector<double> loaded, done;
     double t_copy = 0, t_comp = 0, t_grad = 0, t_floor = 0;
     double gslot_free[kGradSlots] = {};
@@ -386,7 +402,7 @@ struct SimSink : SchedSink {
     int copy(int layer, int, int wait_layer) override {
         double b = std::max(t_copy, t_floor);
         if (wait_layer >= 0) b = std::max(b, done[wait_layer]);
-        t_copy = b + c.copy_ms;
+        t_copy = b + copy_ms_of(layer);
         loaded[layer] = t_copy;
         return SP_OK;
     }
@@ -394,7 +410,7 @@ struct SimSink : SchedSink {
         double b = std::max(t_comp, t_floor);
         if (fresh) b = std::max(b, loaded[layer]);
         if (dir > 0) {
-            t_comp = b + c.fwd_ms;
+            t_comp = b + fwd_ms_of(layer);
         } else {
             b = std::max(b, gslot_free[gs]);            // its gradient slot must have drained
             t_comp = b + c.bwd_ms;
@@ -409,10 +425,13 @@ struct SimSink : SchedSink {
 };
 
 double simulate(int L, int n_slots, int n_pinned, int p_eff, int training, int wrap, int calls,
-                const sp_layer_cost& c) {
+                const sp_layer_cost& c, int units = 1, const double* copy_part = nullptr,
+                const double* fwd_part = nullptr) {
     Scheduler sch;
     sch.reset(L, n_slots, p_eff, n_pinned);
     SimSink sink(c, L);
+    sink.units = units;
+    for (int q = 0; q < units && units > 1; ++q) { sink.copy_part[q] = copy_part[q]; sink.fwd_part[q] = fwd_part[q]; }
     double begin = 0, end = 0;
     for (int i = 0; i < calls; ++i) {
         // forward-only calls follow each other on the streams; a training step starts
@@ -475,5 +494,58 @@ extern "C" int sp_autotune(const sp_stack_desc* desc, uint64_t budget_bytes, int
     *k_out = std::max(pick->n - pick->r - pick->p, 1);
     *pinned_out = pick->r;
     if (ms_out) *ms_out = pick->ms;
+    return SP_OK;
+}
+
+// Shares of a layer's bytes and of its arithmetic that fall to each of the three units.
+static void unit_shares(const sp_stack_desc* d, const Layout& lay, double* copy_part, double* fwd_part) {
+    double flops[3];
+    const double T = 1.0, dm = d->d_model, f = d->d_ffn;
+    const double nq = (double)d->n_q_heads * d->head_dim, nkv = (double)d->n_kv_heads * d->head_dim;
+    const double S = d->max_seq;
+    flops[0] = 2 * T * dm * (nq + 2 * nkv) + 2 * T * nq * dm + 4 * T * S * nq * (d->causal ? 0.5 : 1.0);
+    flops[1] = 2 * T * dm * f * (d->arch == SP_DECODER_SWIGLU_RMS ? 2 : 1);
+    flops[2] = 2 * T * f * dm;
+    const double fsum = flops[0] + flops[1] + flops[2];
+    for (int q = 0; q < 3; ++q) {
+        size_t off, len;
+        unit_range(d, lay, 3, q, &off, &len);
+        copy_part[q] = (double)len / (double)lay.blob_bytes;
+        fwd_part[q] = flops[q] / fsum;
+    }
+}
+
+extern "C" int sp_autotune_units(const sp_stack_desc* desc, uint64_t budget_bytes, int training, int wrap_prefetch,
+                                 const sp_layer_cost* cost, double tolerance, int* units_out, int* k_out, int* p_out,
+                                 int* pinned_out, double* ms_out) {
+    if (!units_out) return SP_ERR_INVALID_ARG;
+    double ms1 = 0;
+    int rc = sp_autotune(desc, budget_bytes, training, wrap_prefetch, cost, tolerance, k_out, p_out, pinned_out, &ms1);
+    if (rc != SP_OK) return rc;
+    *units_out = 1;
+    if (ms_out) *ms_out = ms1;
+    if (training) return SP_OK;
+    Layout lay;
+    make_layout(desc, &lay);
+    double copy_part[3], fwd_part[3];
+    unit_shares(desc, lay, copy_part, fwd_part);
+    const int L = desc->n_layers * 3;
+    // in units only the smallest windows are of interest: what a larger one buys is bought more
+    // cheaply by pinning, which is what the rest of the budget does
+    double best = -1;
+    int bk = 0, bp = 0, br = 0;
+    for (int p = 1; p <= 2; ++p)
+        for (int k = 1; k <= 2; ++k) {
+            sp_plan pl;
+            if (make_plan(desc, 3, k, p, SP_PIN_AUTO, budget_bytes, 0, &pl) != SP_OK) continue;
+            if (pl.n_pinned >= pl.n_slots || pl.n_slots > L) continue;
+            const double ms = simulate(L, pl.n_slots, pl.n_pinned, pl.p_eff, 0, wrap_prefetch, 3, *cost, 3, copy_part,
+                                       fwd_part);
+            if (best < 0 || ms < best) { best = ms; bk = pl.k_eff; bp = pl.p_eff; br = pl.n_pinned; }
+        }
+    if (best >= 0 && best < ms1 * (1.0 - tolerance)) {      // worth the extra fences only when clearly faster
+        *units_out = 3; *k_out = bk; *p_out = bp; *pinned_out = br;
+        if (ms_out) *ms_out = best;
+    }
     return SP_OK;
 }

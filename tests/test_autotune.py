@@ -161,3 +161,35 @@ def test_tuner_budget_and_argument_errors():
         sp.autotune(desc, ws + 4 * slot, (1, 1, 0, 0), tolerance=-1.0)
     k, p, r = C.c_int(), C.c_int(), C.c_int()
     assert sp.sp_autotune(None, 1 << 40, 0, 0, None, 0.0, C.byref(k), C.byref(p), C.byref(r), None) == sp.SP_ERR_INVALID_ARG
+
+
+def test_tuner_over_unit_sizes():
+    """Three units per layer are proposed where they pay -- a link-bound stack whose budget then
+    holds a whole layer more -- and not on a compute-bound stack (the extra fences cost more than
+    nothing is gained), not within the tolerance, and never for training."""
+    import ctypes as C
+
+    def budget_of(w, desc, layers):
+        blob = (sp.sp_layer_blob_bytes(C.byref(desc)) + 4095) // 4096 * 4096
+        return sp.sp_workspace_bytes(C.byref(desc), 0) + layers * blob
+
+    w = synth.WORKLOADS["llama7b"]
+    desc = sp.make_desc(w)
+    cost = (7.116, 0.95, 0.0, 0.0)                 # measured per-layer copy / forward times, ms
+    k1, p1, r1, ms1 = sp.autotune(desc, budget_of(w, desc, 4), cost, wrap=True)
+    u, k, p, r, ms = sp.autotune_units(desc, budget_of(w, desc, 4), cost, wrap=True)
+    assert (k1, p1, r1) == (1, 1, 2) and (u, k, p, r) == (3, 1, 1, 9)
+    # 29 layers' bytes instead of 30, plus 25 us for each of the 57 extra copies
+    assert ms == pytest.approx(29 * 7.116 + 57 * 0.025 * 29 / 30, rel=0.01) and ms < ms1 * 0.98
+    assert 207.0 < ms < 209.0                      # measured on MI355X: 208.0 ms
+    # compute-bound: layer units stay
+    v = synth.WORKLOADS["vith"]
+    vdesc = sp.make_desc(v)
+    u, k, p, r, ms = sp.autotune_units(vdesc, budget_of(v, vdesc, 3), (0.71, 0.973, 0.0, 0.0), wrap=True)
+    assert u == 1 and (k, p, r) == sp.autotune(vdesc, budget_of(v, vdesc, 3), (0.71, 0.973, 0.0, 0.0), wrap=True)[:3]
+    # training: whole layers
+    t = synth.WORKLOADS["train1p3b"]
+    tdesc = sp.make_desc(t)
+    blob = (sp.sp_layer_blob_bytes(C.byref(tdesc)) + 4095) // 4096 * 4096
+    tb = sp.sp_workspace_bytes(C.byref(tdesc), 1) + 3 * blob
+    assert sp.autotune_units(tdesc, tb, (1.8, 1.0, 3.5, 3.5), training=1)[0] == 1
