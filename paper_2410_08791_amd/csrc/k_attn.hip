@@ -216,8 +216,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
 #pragma unroll
             for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[t][e]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);   // finite: key 0 is visible to every query
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
+        // The reference maximum m_run follows the true one lazily: it moves only when a score
+        // exceeds it by more than 2^8 in the exponent.  Probabilities are then at most 256
+        // instead of 1 (bf16 has the range, the denominator and O^T are fp32, and both carry the
+        // same reference), and the rescale of O^T below -- 16 multiplies per MFMA tile --
+        // becomes rare instead of running in nearly every tile.
+        const bool move = (mx - m_run) * scale_log2e > 8.0f;   // first tile: m_run = -inf, mx finite (key 0 is visible to every query)
+        const float m_new = move ? mx : m_run;
+        const float alpha = move ? __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e) : 1.0f;
         const float m_scaled = m_new * scale_log2e;
         m_run = m_new;
         float psum = 0.f;
@@ -233,7 +239,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
                     pf[t][j][e] = (__bf16)pv;
                 }
         l_run = l_run * alpha + psum;
-        if (__any(alpha != 1.0f)) {   // the running maximum moved for some query of the wave
+        if (__any(move)) {   // the reference moved for some query of the wave
 #pragma unroll
             for (int t = 0; t < C::NMT; ++t)
 #pragma unroll
