@@ -264,9 +264,10 @@ int sp_autotune_units(const sp_stack_desc* desc, uint64_t budget_bytes, int trai
 /* ---- the four calls ------------------------------------------------------ */
 
 /* Create an executor.  layer_host_blobs[n_layers]: host, pinned, each
- * sp_layer_blob_bytes long, caller-owned, must stay valid and UNMODIFIED until
- * sp_destroy (the library never writes them: the method leaves parameters untouched,
- * Sec. 1).  Entries may alias.  On failure *out is NULL. */
+ * sp_layer_blob_bytes long, caller-owned, must stay valid until sp_destroy and
+ * UNMODIFIED except as sp_weights_updated allows (the library never writes them:
+ * the method leaves parameters untouched, Sec. 1).  Entries may alias.  On failure
+ * *out is NULL. */
 int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* const* layer_host_blobs,
               const sp_config* cfg);
 
@@ -306,6 +307,26 @@ int sp_decode(sp_handle h, const float* x_dev, float* y_dev, void* kv_cache_dev,
  * has to wait for anyway before the weights of the next step exist). */
 int sp_forward_backward(sp_handle h, const float* x_dev, const float* target_dev, float* y_dev,
                         float* loss_dev, float* dx_dev, void* const* grad_host_blobs, int B, int S);
+
+/* A training LOOP (Sec. 3.3 runs forward and backward over the same streamed layers;
+ * between two steps the caller's optimizer rewrites the host weights).
+ *
+ * sp_wait_gradient blocks the host until `layer`'s gradient of the latest
+ * sp_forward_backward has landed in its grad_host_blobs entry.  Gradients land from
+ * the last layer down, so a host optimizer can update layer L-1 while the backward
+ * pass still works on the layers below.  SP_ERR_STATE for a layer that sends no
+ * gradient (frozen, or no step yet).
+ *
+ * sp_weights_updated tells the handle that the caller has rewritten
+ * layer_host_blobs[layer] (layer -1: every layer): a copy of it still in device
+ * memory is forgotten and the next pass streams the layer in again.  Host order
+ * only, no device work.  A layer's host blob may be rewritten (a) while none of the
+ * handle's passes is in flight, or (b) during a training step once
+ * sp_wait_gradient(layer) has returned: the step reads the layer for the last time
+ * before it sends that gradient.  Skipping the call leaves stale weights in use for
+ * as long as the layer stays resident. */
+int sp_wait_gradient(sp_handle h, int layer);
+int sp_weights_updated(sp_handle h, int layer);
 
 /* Counters and (with SP_FLAG_TIMING) per-layer timings.  Synchronises the
  * handle's streams when timing is on. */

@@ -113,6 +113,8 @@ _sig = {
     "spk_colsum_bf16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "sp_forward_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       _P(C.c_void_p), C.c_int, C.c_int]),
+    "sp_wait_gradient": (C.c_int, [C.c_void_p, C.c_int]),
+    "sp_weights_updated": (C.c_int, [C.c_void_p, C.c_int]),
     "sp_get_stats": (C.c_int, [C.c_void_p, _P(sp_stats)]),
     "sp_destroy": (C.c_int, [C.c_void_p]),
     "sp_last_error": (C.c_char_p, [C.c_void_p]),
@@ -321,6 +323,12 @@ class Engine:
         self._check(sp_forward_backward(self.handle, x.data_ptr(), target.data_ptr(),
                                         y.data_ptr() if y is not None else None, loss.data_ptr(),
                                         dx.data_ptr() if dx is not None else None, ptrs, B, S))
+
+    def wait_gradient(self, layer):
+        self._check(sp_wait_gradient(self.handle, layer))
+
+    def weights_updated(self, layer=-1):
+        self._check(sp_weights_updated(self.handle, layer))
 
     def sync(self):
         self.compute.synchronize()

@@ -47,6 +47,8 @@ struct sp_engine {
     hipEvent_t grad_ready[sp::kGradSlots] = {}, gslot_free[sp::kGradSlots] = {};
     char gslot_used[sp::kGradSlots] = {};
     int gslot_next = 0;
+    std::vector<hipEvent_t> grad_landed;        // per layer: its gradient copy of the latest step (d2h stream)
+    std::vector<char> grad_sent;                // per layer: that event has been recorded in the latest step
     hipEvent_t last_grad_copy = nullptr;        // gslot_free event of the most recently submitted gradient copy
     hipEvent_t t0 = nullptr;
     std::vector<hipEvent_t> kt_begin, kt_end;   // ring of event pairs around the largest GEMM

@@ -368,6 +368,11 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
         he = mk(&e->grad_ready[i], hipEventDisableTiming);
         if (he == hipSuccess) he = mk(&e->gslot_free[i], hipEventDisableTiming);
     }
+    if (training) {
+        e->grad_landed.assign(L, nullptr);
+        e->grad_sent.assign(L, 0);
+        for (int i = 0; i < L && he == hipSuccess; ++i) he = mk(&e->grad_landed[i], hipEventDisableTiming);
+    }
     if (he == hipSuccess && timing) he = mk(&e->t0, hipEventDefault);
     if (he == hipSuccess && (cfg->flags & (SP_FLAG_TIMING | SP_FLAG_KERNEL_TIMING))) {
         e->kt_begin.assign(2048, nullptr);
@@ -518,6 +523,7 @@ extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float*
         e->pass_pending = false;
     }
     if ((rc = begin_call(e)) != SP_OK) return rc;
+    std::fill(e->grad_sent.begin(), e->grad_sent.end(), 0);
     e->grad_blobs = grad_host_blobs;
     e->y_out = y_dev;
     if ((rc = sp_train_begin(e, x_dev, B, S)) != SP_OK) return rc;
@@ -535,6 +541,27 @@ extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float*
     SP_HIP(e, hipEventRecord(e->pass_end_d, e->d2h));
     e->pass_pending = true;
     e->calls++;
+    return SP_OK;
+}
+
+extern "C" int sp_wait_gradient(sp_handle e, int layer) {
+    if (!e) return SP_ERR_INVALID_ARG;
+    if (!is_live(e)) return fail(nullptr, SP_ERR_STATE, "handle is not live (destroyed or never created)");
+    if (!(e->flags & SP_FLAG_TRAINING)) return fail(e, SP_ERR_STATE, "handle was created without SP_FLAG_TRAINING");
+    if (layer < 0 || layer >= e->desc.n_layers) return fail(e, SP_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (!e->grad_sent[layer])
+        return fail(e, SP_ERR_STATE, "layer %d has no gradient on its way (frozen, or no training step since create)", layer);
+    SP_HIP(e, hipEventSynchronize(e->grad_landed[layer]));
+    return SP_OK;
+}
+
+extern "C" int sp_weights_updated(sp_handle e, int layer) {
+    if (!e) return SP_ERR_INVALID_ARG;
+    if (!is_live(e)) return fail(nullptr, SP_ERR_STATE, "handle is not live (destroyed or never created)");
+    const int L = e->desc.n_layers;
+    if (layer < -1 || layer >= L) return fail(e, SP_ERR_INVALID_ARG, "layer %d out of range", layer);
+    const int lo = layer < 0 ? 0 : layer, hi = layer < 0 ? L : layer + 1;
+    for (int u = lo * e->units; u < hi * e->units; ++u) e->sched.invalidate(u);
     return SP_OK;
 }
 
@@ -643,6 +670,7 @@ static int destroy_engine(sp_engine* e) {
     kill(e->pass_end_d);
     kill(e->t0);
     for (int i = 0; i < kGradSlots; ++i) { kill(e->grad_ready[i]); kill(e->gslot_free[i]); }
+    for (auto ev : e->grad_landed) kill(ev);
     (void)hipGetLastError();
     delete e;
     return SP_OK;

@@ -80,6 +80,9 @@ public:
     // (forward-only use) slots freed at the tail are refilled with the first layers.
     // lo: the pass covers layers lo..L-1 only (a backward pass that stops above frozen layers).
     int run_pass(int dir, bool wrap, SchedSink& sink, int lo = 0);
+    // The caller rewrote `layer`'s host copy: forget the device copy, the next pass fetches it again.
+    // The slot remembers its last user, so the new copy still waits for that compute.
+    void invalidate(int layer);
     int n_slots() const { return n_slots_; }
     int n_pinned() const { return n_pinned_; }
     const std::vector<int>& layer_slot() const { return layer_slot_; }

@@ -188,6 +188,16 @@ void Scheduler::reset(int n_layers, int n_slots, int group, int n_pinned) {
     fresh_.assign(n_layers, 0);
 }
 
+void Scheduler::invalidate(int layer) {
+    if (layer < 0 || layer >= n_layers_) return;
+    const int s = layer_slot_[layer];
+    if (s >= 0) {
+        slot_layer_[s] = -1;
+        layer_slot_[layer] = -1;
+    }
+    fresh_[layer] = 0;
+}
+
 int Scheduler::run_pass(int dir, bool wrap, SchedSink& sink, int lo) {
     const int L = n_layers_, N = n_slots_, R = n_pinned_;
     if (lo < 0 || lo > L) return SP_ERR_INVALID_ARG;

@@ -284,6 +284,8 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     SP_HIP(e, hipStreamWaitEvent(e->d2h, e->grad_ready[gs], 0));
     SP_HIP(e, hipMemcpyAsync(e->grad_blobs[layer], gslot, L.grad_bytes, hipMemcpyDeviceToHost, e->d2h));
     SP_HIP(e, hipEventRecord(e->gslot_free[gs], e->d2h));
+    SP_HIP(e, hipEventRecord(e->grad_landed[layer], e->d2h));
+    e->grad_sent[layer] = 1;
     e->last_grad_copy = e->gslot_free[gs];
     e->gslot_used[gs] = 1;
     e->stats_d2h_copies++;

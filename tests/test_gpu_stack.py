@@ -346,3 +346,36 @@ def test_cost_model_and_tuner_against_measurement(name, over):
     assert ms[(k, p, r)] <= 1.1 * min(ms.values())
     if cost[0] > 2 * cost[1]:       # copy-bound: pinned layers must pay off as the model says
         assert r == 4 and ms[(k, p, r)] < 0.8 * ms[(1, 1, 0)]
+
+
+@pytest.mark.parametrize("k,p,pinned,units", [(8, 8, 0, 1), (1, 1, 2, 1), (1, 1, 4, 3)])
+def test_rewritten_weights_are_streamed_in_again(k, p, pinned, units):
+    """sp_weights_updated: after the caller rewrote one layer's host blob, the next pass uses the
+    new weights (bit for bit a fresh handle's output) although the old copy was still resident;
+    the untouched layers stay where they are."""
+    w = synth.WORKLOADS["tiny"]
+    desc = sp.make_desc(w)
+    blobs, views = sp.pinned_blobs(w, desc)
+    xd = dev_f32(synth.make_input(w))
+
+    def fwd(eng):
+        y = torch.full_like(xd, float("nan"))
+        eng.forward(xd, y, w.batch, w.seq)
+        eng.sync()
+        return y.cpu().numpy()
+
+    eng = sp.Engine(desc, blobs, k, p, pinned=pinned, units=units)
+    y0 = fwd(eng)
+    before = eng.stats().h2d_copies
+    synth.fill_layer(views[1], w, 1, seed=w.seed + 1)     # layer 1 gets other weights
+    eng.weights_updated(1)
+    y1 = fwd(eng)
+    copies = eng.stats().h2d_copies - before
+    assert eng.destroy() == sp.SP_OK
+    fresh = sp.Engine(desc, blobs, 1, 1)
+    y2 = fwd(fresh)
+    assert fresh.destroy() == sp.SP_OK
+    assert not np.array_equal(y0, y1)
+    assert np.array_equal(y1.view(np.uint32), y2.view(np.uint32))
+    if k == 8:
+        assert copies == 1                                # only the rewritten layer crossed the link again

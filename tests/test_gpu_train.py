@@ -238,3 +238,85 @@ def test_vith_layer_shape_training():
     c = TrainCase(w)
     got = c.run(1, 1)
     check_against_oracle(got, c.oracle(np.float32), "vith x2 layers, batch 4 (fp32 oracle)")
+
+
+def _host_update(views_l, grads_l):
+    """A host 'optimizer' for the loop test: w <- bf16(w - 0.01 * g / max|g|) per tensor, so that
+    every tensor moves by about half its own spread whatever the gradient's scale."""
+    for n, v in views_l.items():
+        g = grads_l[n].reshape(v.shape)
+        m = float(np.abs(g).max())
+        if m > 0:
+            v[...] = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(v) - np.float32(0.01 / m) * g)
+
+
+@pytest.mark.parametrize("k,p,pinned,budget_layers", [(8, 8, 0, None), (1, 1, 1, None), (1, 1, 0, 1)])
+def test_training_loop_with_host_updates_between_steps(small, k, p, pinned, budget_layers):
+    """Two steps with the host rewriting the weights in between.  Each layer is updated as soon
+    as its own gradient has landed (from the last layer down) and the handle is told; the second
+    step must run on the new weights: bit for bit what a fresh handle computes from them, and
+    within the tolerance of the oracle on them.  The resident window (first case) is where stale
+    weights would otherwise stay in use."""
+    w, desc = small.w, small.desc
+    blobs, views = sp.pinned_blobs(w, desc)              # private weights: this test rewrites them
+    L = w.n_layers
+
+    def step(eng):
+        gblobs = [torch.full((small.gbytes,), 0xFF, dtype=torch.uint8).pin_memory() for _ in range(L)]
+        y, dx = torch.zeros_like(small.xd), torch.zeros_like(small.xd)
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        eng.forward_backward(small.xd, small.td, y, loss, dx, gblobs, w.batch, w.seq)
+        return gblobs, y, dx, loss
+
+    def collect(eng, gblobs, y, dx, loss):
+        eng.sync()
+        return dict(loss=float(loss.item()), dx=dx.cpu().numpy().reshape(w.tokens, -1),
+                    y=y.cpu().numpy().reshape(w.tokens, -1),
+                    grads=[{n: v.copy() for n, v in sp.grad_views(desc, g.numpy()).items()} for g in gblobs])
+
+    eng = sp.Engine(desc, blobs, k, p, flags=sp.SP_FLAG_TRAINING, pinned=pinned, budget_layers=budget_layers)
+    with pytest.raises(sp.SuperpipeError):
+        eng.wait_gradient(0)                             # no step yet
+    out = step(eng)
+    for l in reversed(range(L)):
+        eng.wait_gradient(l)
+        _host_update(views[l], sp.grad_views(desc, out[0][l].numpy()))
+        eng.weights_updated(l)
+    first = collect(eng, *out)
+    second = collect(eng, *step(eng))
+    with pytest.raises(sp.SuperpipeError):
+        eng.wait_gradient(L)
+    assert eng.destroy() == sp.SP_OK
+    assert not np.array_equal(first["y"], second["y"]) and second["loss"] != first["loss"]
+
+    fresh = sp.Engine(desc, blobs, 1, 2, flags=sp.SP_FLAG_TRAINING)
+    ref = collect(fresh, *step(fresh))
+    assert fresh.destroy() == sp.SP_OK
+    assert second["loss"] == ref["loss"]
+    assert np.array_equal(second["y"], ref["y"]) and np.array_equal(second["dx"], ref["dx"])
+    for gl, rl in zip(second["grads"], ref["grads"]):
+        for n in gl:
+            assert np.array_equal(gl[n], rl[n]), n
+    sh = O.StackShape(w.arch, L, w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim, w.d_ffn, w.causal, w.norm_eps)
+    check_against_oracle(second, O.stack_forward_backward(small.x, small.t, views, w.batch, w.seq, sh),
+                         f"second step after host updates (k={k}, p={p}, pinned={pinned})")
+
+
+def test_wait_gradient_refuses_frozen_layers_and_forward_handles(small):
+    w, desc = small.w, small.desc
+    eng = sp.Engine(desc, small.blobs, 1, 1, flags=sp.SP_FLAG_TRAINING, frozen=1)
+    gblobs = [torch.zeros(small.gbytes, dtype=torch.uint8, pin_memory=True) for _ in range(w.n_layers)]
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    eng.forward_backward(small.xd, small.td, None, loss, None, gblobs, w.batch, w.seq)
+    eng.wait_gradient(w.n_layers - 1)
+    eng.wait_gradient(1)
+    with pytest.raises(sp.SuperpipeError) as ei:
+        eng.wait_gradient(0)
+    assert ei.value.code == sp.SP_ERR_STATE
+    eng.sync()
+    assert eng.destroy() == sp.SP_OK
+    fwd = sp.Engine(desc, small.blobs, 1, 1)
+    with pytest.raises(sp.SuperpipeError) as ei:
+        fwd.wait_gradient(0)
+    assert ei.value.code == sp.SP_ERR_STATE
+    assert fwd.destroy() == sp.SP_OK
