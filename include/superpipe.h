@@ -223,6 +223,12 @@ typedef struct {
 } sp_sched_op;
 int sp_trace_schedule(int n_layers, int n_slots, int n_pinned, int p_eff, int training,
                       int wrap_prefetch, int passes, sp_sched_op* ops, int cap);
+/* The same with the caller rewriting host weights between calls: before every forward
+ * pass but the first, sp_weights_updated is applied to each of updated_layers[0..n_updated-1]
+ * (host, may be NULL when n_updated = 0). */
+int sp_trace_schedule_updated(int n_layers, int n_slots, int n_pinned, int p_eff, int training,
+                              int wrap_prefetch, int passes, const int* updated_layers, int n_updated,
+                              sp_sched_op* ops, int cap);
 
 /* Cost model of the schedule (host only).  Plays what sp_trace_schedule lists on
  * three in-order streams -- layer copies, layer computes, gradient copies --

@@ -100,6 +100,7 @@ _sig = {
                                      _P(sp_plan)]),
     "sp_unit_range": (C.c_int, [_P(sp_stack_desc), C.c_int, C.c_int, _P(C.c_uint64), _P(C.c_uint64)]),
     "sp_trace_schedule": (C.c_int, [C.c_int] * 7 + [_P(sp_sched_op), C.c_int]),
+    "sp_trace_schedule_updated": (C.c_int, [C.c_int] * 7 + [_P(C.c_int), C.c_int, _P(sp_sched_op), C.c_int]),
     "sp_create": (C.c_int, [_P(C.c_void_p), _P(sp_stack_desc), _P(C.c_void_p), _P(sp_config)]),
     "sp_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
     "sp_kv_cache_bytes": (C.c_size_t, [_P(sp_stack_desc), C.c_int, C.c_int]),
@@ -180,13 +181,17 @@ def plan(desc, k, p, budget, training=False, pinned=0):
     return rc, pl
 
 
-def trace_schedule(n_layers, n_slots, p_eff, training=False, wrap=False, passes=1, pinned=0, frozen=0):
+def trace_schedule(n_layers, n_slots, p_eff, training=False, wrap=False, passes=1, pinned=0, frozen=0,
+                   updated=()):
+    """updated: layers whose host weights the caller rewrites between calls."""
     training = int(bool(training)) + (frozen if training else 0)
-    n = sp_trace_schedule(n_layers, n_slots, pinned, p_eff, int(training), int(wrap), passes, None, 0)
+    upd = (C.c_int * max(1, len(updated)))(*updated)
+    args = (n_layers, n_slots, pinned, p_eff, int(training), int(wrap), passes, upd, len(updated))
+    n = sp_trace_schedule_updated(*args, None, 0)
     if n < 0:
         raise SuperpipeError(n, "sp_trace_schedule")
     ops = (sp_sched_op * n)()
-    sp_trace_schedule(n_layers, n_slots, pinned, p_eff, int(training), int(wrap), passes, ops, n)
+    sp_trace_schedule_updated(*args, ops, n)
     return [(o.kind, o.layer, o.slot, o.wait_layer, o.pass_) for o in ops]
 
 

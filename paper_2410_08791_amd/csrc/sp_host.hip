@@ -359,13 +359,16 @@ struct TraceSink : SchedSink {
 };
 }  // namespace
 
-extern "C" int sp_trace_schedule(int n_layers, int n_slots, int n_pinned, int p_eff, int training,
-                                 int wrap_prefetch, int passes, sp_sched_op* ops, int cap) {
+static int trace_schedule(int n_layers, int n_slots, int n_pinned, int p_eff, int training, int wrap_prefetch,
+                          int passes, const int* updated, int n_updated, sp_sched_op* ops, int cap) {
     // training > 1: backward passes stop after layer training - 1 (layers below are frozen)
     const int bwd_lo = training > 1 ? training - 1 : 0;
     if (n_layers < 1 || n_slots < 1 || n_slots > n_layers || n_pinned < 0 || n_pinned >= n_slots || p_eff < 1 ||
-        passes < 1 || cap < 0 || (cap && !ops) || training < 0 || bwd_lo > n_layers)
+        passes < 1 || cap < 0 || (cap && !ops) || training < 0 || bwd_lo > n_layers || n_updated < 0 ||
+        (n_updated && !updated))
         return SP_ERR_INVALID_ARG;
+    for (int i = 0; i < n_updated; ++i)
+        if (updated[i] < 0 || updated[i] >= n_layers) return SP_ERR_INVALID_ARG;
     Scheduler sch;
     sch.reset(n_layers, n_slots, p_eff, n_pinned);
     TraceSink sink;
@@ -374,10 +377,24 @@ extern "C" int sp_trace_schedule(int n_layers, int n_slots, int n_pinned, int p_
     for (int ps = 0; ps < passes; ++ps) {
         sink.pass = ps;
         const int dir = (training && (ps & 1)) ? -1 : +1;
+        if (dir > 0 && ps > 0)
+            for (int i = 0; i < n_updated; ++i) sch.invalidate(updated[i]);
         int rc = sch.run_pass(dir, !training && wrap_prefetch, sink, dir < 0 ? bwd_lo : 0);
         if (rc != SP_OK) return rc;
     }
     return sink.n;
+}
+
+extern "C" int sp_trace_schedule(int n_layers, int n_slots, int n_pinned, int p_eff, int training,
+                                 int wrap_prefetch, int passes, sp_sched_op* ops, int cap) {
+    return trace_schedule(n_layers, n_slots, n_pinned, p_eff, training, wrap_prefetch, passes, nullptr, 0, ops, cap);
+}
+
+extern "C" int sp_trace_schedule_updated(int n_layers, int n_slots, int n_pinned, int p_eff, int training,
+                                         int wrap_prefetch, int passes, const int* updated_layers, int n_updated,
+                                         sp_sched_op* ops, int cap) {
+    return trace_schedule(n_layers, n_slots, n_pinned, p_eff, training, wrap_prefetch, passes, updated_layers,
+                          n_updated, ops, cap);
 }
 
 // ---- schedule cost model and window tuner ----------------------------------

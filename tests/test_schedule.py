@@ -165,3 +165,47 @@ def test_trace_argument_errors():
     for pinned in (-1, 2, 3):
         with pytest.raises(sp.SuperpipeError):
             sp.trace_schedule(4, 2, 1, pinned=pinned)
+
+
+@pytest.mark.parametrize("training", [False, True])
+def test_rewritten_layers_cross_the_link_again_and_only_they(training):
+    """sp_weights_updated in the schedule: every pass after an update computes a rewritten layer
+    from a copy issued after the update; layers that were not rewritten keep their residency."""
+    per_call = 2 if training else 1
+    for L, N, p, pinned, upd in [(6, 6, 1, 0, [1, 4]), (6, 3, 1, 1, [0, 5]), (8, 4, 2, 2, [1, 2, 7]),
+                                 (5, 2, 1, 0, [0, 1, 2, 3, 4]), (4, 4, 1, 0, [])]:
+        calls = 3
+        plain = sp.trace_schedule(L, N, p, training=training, passes=calls * per_call, pinned=pinned)
+        ops = sp.trace_schedule(L, N, p, training=training, passes=calls * per_call, pinned=pinned, updated=upd)
+        for seed in range(3):
+            comp = simulate(ops, L, N, seed)
+            assert len(comp) == calls * per_call * L
+        # a rewritten layer: in each call after the first, its first compute is preceded by a copy
+        # of it issued in the same call
+        for call in range(1, calls):
+            first_pass = call * per_call
+            seen_copy = set()
+            checked = set()
+            for kind, layer, slot, wait, ps in ops:
+                if ps < first_pass or ps >= first_pass + per_call:
+                    continue
+                if kind == COPY:
+                    seen_copy.add(layer)
+                elif layer in upd and layer not in checked:
+                    assert layer in seen_copy, (L, N, upd, call, layer)
+                    checked.add(layer)
+            assert checked == set(upd)
+        n_copies = lambda o: sum(1 for k, *_ in o if k == COPY)
+        if N == L:
+            # resident: the plain schedule copies each layer once, updates add one copy per call
+            assert n_copies(plain) == L and n_copies(ops) == L + (calls - 1) * len(upd)
+        else:
+            assert n_copies(plain) <= n_copies(ops) <= n_copies(plain) + (calls - 1) * len(upd)
+
+
+def test_trace_with_updates_argument_errors():
+    import ctypes as C
+    bad = (C.c_int * 1)(9)
+    assert sp.sp_trace_schedule_updated(4, 2, 0, 1, 0, 0, 2, bad, 1, None, 0) == sp.SP_ERR_INVALID_ARG
+    assert sp.sp_trace_schedule_updated(4, 2, 0, 1, 0, 0, 2, None, 1, None, 0) == sp.SP_ERR_INVALID_ARG
+    assert sp.sp_trace_schedule_updated(4, 2, 0, 1, 0, 0, 2, None, 0, None, 0) > 0
