@@ -467,7 +467,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmDev& p, f32x16_t 
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 template <int BM, int BN, int EPI, int WAVES, int WM>
-__global__ __launch_bounds__(WAVES * 64) void gemm_dma_kernel(GemmDev p) {
+__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void gemm_dma_kernel(GemmDev p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int WNC = WAVES / WM;              // wave grid: WM (m) x WNC (n)
     constexpr int WMR = BM / WM, WN = BN / WNC;  // tile rows of A / of W per wave

@@ -11,8 +11,9 @@
 //                     kernels; record a "done" event
 // Those two event kinds are the only cross-stream edges (training adds the pair
 // that fences the two gradient slots against the device-to-host stream).  An event is always
-// recorded (in host order) before anything waits on it.  Nothing here blocks
-// the host, and no device memory is allocated.
+// recorded (in host order) before anything waits on it.  The host blocks only at
+// the run-ahead bound below, at the start of a training step that follows another,
+// and in sp_wait_gradient; no device memory is allocated.
 #include <hip/hip_runtime.h>
 #include <stdarg.h>
 #include <stdio.h>
