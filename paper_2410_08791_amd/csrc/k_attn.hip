@@ -14,6 +14,17 @@
 // fragments come out of the transposing LDS read ds_read_b64_tr_b16, which hands
 // a lane four consecutive keys of one head_dim element: no transposed copy of V
 // exists anywhere.
+//
+// K and V tiles go from global memory straight into LDS (global_load_lds_dwordx4,
+// issued one tile ahead into the other stage): no staging registers, no ds_write.  A wave
+// instruction lands 1 KiB contiguously, so rows cannot be padded against bank conflicts;
+// the 16-byte chunks of a row are XOR-swizzled instead, on the global side (which chunk a
+// lane fetches).  Rows are 2*head_dim bytes (head_dim 80: 192, the lanes that land in the
+// padding fetch a dummy chunk).  K rows: chunk ^ (row & 15) for 256-byte rows,
+// ^ ((row >> 1) & 7) for 128, ^ ((row >> 2) & 3) for 192 -- the 16 rows a ds_read_b128 serves
+// at a time then cover all banks.  V rows: the 64-byte block (one 32-element tile of O^T)
+// ^ (row & 3) for 256-byte rows, ^ ((row >> 1) & 1) for 128, none for 192 -- the four key
+// rows of a transposing read fall into different bank groups.
 #include "sp_kernels.h"
 
 namespace {
@@ -27,19 +38,21 @@ struct AttnCfg {
     static constexpr int NKS = HD / 16;             // MFMA k-steps over head_dim
     static constexpr int NMT = (HD + 31) / 32;      // 32-row tiles of O^T
     static constexpr int HDP = NMT * 32;
-    static constexpr int K_STRIDE = HD * 2 + 16;    // bytes per key row in LDS (padded)
-    // bytes per value row in LDS: at least HDP elements (the fragment reads of a padded
-    // head_dim stay inside the row) and = 64 mod 128, so that the four key rows a 16-lane
-    // group touches in one transposing read fall into different 64-byte bank groups
-    static constexpr int V_STRIDE = (HDP * 2 + 63) / 128 * 128 + 64;
-    static constexpr int K_BYTES = KB * K_STRIDE;
-    static constexpr int V_BYTES = KB * V_STRIDE;
-    static constexpr int CHUNKS_K = KB * (HD / 8);  // 16-byte chunks of a K tile
-    static constexpr int CHUNKS_V = CHUNKS_K;
+    static constexpr int ROWB = HD == 80 ? 192 : HD * 2;   // bytes per key / value row in LDS
+    static constexpr int CPR = HD / 8;                     // 16-byte chunks of a row that hold data
+    static constexpr int TILE_BYTES = KB * ROWB;           // one K or one V tile
+    static constexpr int STAGE = 2 * TILE_BYTES;           // K tile, then V tile
+    static constexpr int NLOAD = STAGE / 1024 / 4;         // load instructions per wave and stage
+    static_assert(STAGE % 4096 == 0 && TILE_BYTES % 1024 == 0, "whole load instructions per wave and per tile");
+    static_assert(HDP * 2 <= ROWB, "the fragment reads of a padded head_dim stay inside the row");
+    __device__ static int k_swz(int row) { return HD == 128 ? (row & 15) : HD == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+    // in 64-byte blocks
+    __device__ static int v_swz(int row) { return HD == 128 ? (row & 3) : HD == 64 ? ((row >> 1) & 1) : 0; }
 };
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr_a;
 
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
@@ -47,10 +60,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
                                                        int S, int Hq, int Hkv, int ld_qkv,
                                                        int causal, int paired, float scale_log2e) {
     typedef AttnCfg<HD> C;
-    // two K tiles then two V tiles (double buffered)
+    // two stages of {K tile, V tile}
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_attn[];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     // Causal: query block i walks i + 1 key tiles of 128.  With `paired` a work-group takes the
     // blocks nqb - 1 - i and i one after the other, so that every work-group has the same amount
@@ -67,6 +80,44 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
     const size_t tok0 = (size_t)b * S;
     const bf16_t* kbase = qkv + tok0 * ld_qkv + (size_t)Hq * HD + (size_t)kvh * HD;
     const bf16_t* vbase = kbase + (size_t)Hkv * HD;
+    // load assignment: instruction i of this wave lands at byte (wave * NLOAD + i) * 1024 + lane * 16
+    // of a stage; the lane fetches the chunk that the swizzle puts there
+    const bf16_t* ld_col[C::NLOAD];
+    int ld_row[C::NLOAD];
+#pragma unroll
+    for (int i = 0; i < C::NLOAD; ++i) {
+        const int off = (wave * C::NLOAD + i) * 1024 + lane * 16;
+        const bool isv = off >= C::TILE_BYTES;
+        const int rel = off - (isv ? C::TILE_BYTES : 0);
+        const int row = rel / C::ROWB, pos = (rel % C::ROWB) >> 4;
+        int c = isv ? pos ^ (C::v_swz(row) << 2) : pos ^ C::k_swz(row);
+        if (c >= C::CPR) c = 0;                       // padding of the 192-byte rows: any valid chunk
+        ld_row[i] = row;
+        ld_col[i] = (isv ? vbase : kbase) + c * 8;
+    }
+#if defined(__HIP_DEVICE_COMPILE__)
+#define SP_ATTN_ISSUE(kt_, stage_)                                                                             \
+    do {                                                                                                       \
+        _Pragma("unroll") for (int i_ = 0; i_ < C::NLOAD; ++i_)                                                \
+            __builtin_amdgcn_global_load_lds(ld_col[i_] + (size_t)min((kt_) * KB + ld_row[i_], S - 1) * ld_qkv, \
+                                             (lds_void_ptr_a)(smem_attn + (stage_) * C::STAGE +                \
+                                                              (wave * C::NLOAD + i_) * 1024), 16, 0, 0);      \
+    } while (0)
+#else
+#define SP_ATTN_ISSUE(kt_, stage_) ((void)ld_col, (void)ld_row)
+#endif
+    constexpr int WAIT_VM0 = (0 & 15) | (7 << 4) | (15 << 8) | (0 << 14);   // vmcnt 0, lgkmcnt untouched
+    // fragment addresses inside a tile (the swizzle terms depend on the lane only)
+    int kpos[C::NKS];
+#pragma unroll
+    for (int ks = 0; ks < C::NKS; ++ks) kpos[ks] = l32 * C::ROWB + (((2 * ks + half) ^ C::k_swz(l32)) << 4);
+    int vpos[C::NMT];
+    {
+        const int rowv = half * 4 + ((lane & 15) >> 2);
+#pragma unroll
+        for (int mt = 0; mt < C::NMT; ++mt)
+            vpos[mt] = rowv * C::ROWB + ((mt ^ C::v_swz(rowv)) << 6) + 32 * ((lane >> 4) & 1) + 8 * (lane & 3);
+    }
     for (int phase = 0; phase < nphase; ++phase) {
     const int qb = paired ? (phase ? bx : nqb - 1 - bx)                          // heavy block first
                           : (!causal || ((lin >> 8) & 1)) ? bx : nqb - 1 - bx;
@@ -90,66 +141,22 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
         for (int e = 0; e < 16; ++e) oacc[t][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // per-lane part of the V fragment address: key row (s>>2) of a step, elements
-    // 16 * ((lane>>4)&1) + 4 * (s&3) .. +3 of a 32-element tile, s = lane & 15
-    const int v_lane_off = ((lane & 15) >> 2) * C::V_STRIDE + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
-
     const int k_end = causal ? min(S, q0 + QB) : S;
     const int ntiles = (k_end + KB - 1) / KB;
     const int wq_last = wq0 + 31;
 
-    // Tile staging: global -> registers (issued one tile ahead) -> LDS buffer (kt+1)&1
-    // while buffer kt&1 is being consumed; one barrier per tile.
-    constexpr int NK = (C::CHUNKS_K + 255) / 256, NV = (C::CHUNKS_V + 255) / 256;
-    u32x4_t rk[NK], rv[NV];
-    auto fetch = [&](int key0) {
-#pragma unroll
-        for (int i = 0; i < NK; ++i) {
-            const int c = threadIdx.x + i * 256;
-            if (c < C::CHUNKS_K) {
-                const int r = c / (HD / 8), cc = c % (HD / 8);
-                rk[i] = *reinterpret_cast<const u32x4_t*>(kbase + (size_t)min(key0 + r, S - 1) * ld_qkv + cc * 8);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int c = threadIdx.x + i * 256;
-            if (c < C::CHUNKS_V) {
-                const int r = c / (HD / 8), cc = c % (HD / 8);
-                rv[i] = *reinterpret_cast<const u32x4_t*>(vbase + (size_t)min(key0 + r, S - 1) * ld_qkv + cc * 8);
-            }
-        }
-    };
-    auto stash = [&](int buf) {
-        unsigned char* dK = smem_attn + buf * C::K_BYTES;
-        unsigned char* dV = smem_attn + 2 * C::K_BYTES + buf * C::V_BYTES;
-#pragma unroll
-        for (int i = 0; i < NK; ++i) {
-            const int c = threadIdx.x + i * 256;
-            if (c < C::CHUNKS_K) {
-                const int r = c / (HD / 8), cc = c % (HD / 8);
-                *reinterpret_cast<u32x4_t*>(dK + r * C::K_STRIDE + cc * 16) = rk[i];
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int c = threadIdx.x + i * 256;
-            if (c < C::CHUNKS_V) {
-                const int r = c / (HD / 8), cc = c % (HD / 8);
-                *reinterpret_cast<u32x4_t*>(dV + r * C::V_STRIDE + cc * 16) = rv[i];
-            }
-        }
-    };
-    fetch(0);
-    stash(0);
+    // Tile kt+1 is loaded into stage (kt+1)&1 while stage kt&1 is consumed; one barrier per tile.
+    SP_ATTN_ISSUE(0, 0);
+    __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+    asm volatile("" ::: "memory");
     __syncthreads();
 
     for (int kt = 0; kt < ntiles; ++kt) {
         const int key0 = kt * KB;
         const bool more = kt + 1 < ntiles;
-        if (more) fetch(key0 + KB);
-        const unsigned char* sK = smem_attn + (kt & 1) * C::K_BYTES;
-        const unsigned char* sV = smem_attn + 2 * C::K_BYTES + (kt & 1) * C::V_BYTES;
+        if (more) SP_ATTN_ISSUE(kt + 1, (kt + 1) & 1);
+        const unsigned char* sK = smem_attn + (kt & 1) * C::STAGE;
+        const unsigned char* sV = sK + C::TILE_BYTES;
         // wave-uniform skips: nothing visible to this wave / no valid query in this wave
         if (!((causal && key0 > wq_last) || wq0 >= S)) {
 
@@ -166,8 +173,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
             constexpr int NQK = 2 * C::NKS;
             bf16x8_t kf[NQK];
             auto kread = [&](int st) {   // step st: tile st & 1, k-step st >> 1
-                kf[st] = *reinterpret_cast<const bf16x8_t*>(
-                    sK + ((st & 1) * 32 + l32) * C::K_STRIDE + ((st >> 1) * 2 + half) * 16);
+                kf[st] = *reinterpret_cast<const bf16x8_t*>(sK + (st & 1) * 32 * C::ROWB + kpos[st >> 1]);
             };
 #pragma unroll
             for (int st = 0; st < PF; ++st) kread(st);
@@ -190,9 +196,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
         s16x8_t vf[NPV];
         auto vread = [&](int st) {
             const int tj = st / C::NMT, mt = st % C::NMT;
-            const unsigned char* vp = sV + ((tj >> 1) * 32 + 16 * (tj & 1) + half * 4) * C::V_STRIDE + mt * 64 + v_lane_off;
+            const unsigned char* vp = sV + ((tj >> 1) * 32 + 16 * (tj & 1)) * C::ROWB + vpos[mt];
             const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
-            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * C::V_STRIDE));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * C::ROWB));
             vf[st] = s16x8_t{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         };
 #pragma unroll
@@ -265,7 +271,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
             if (st + PF < NPV) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
         }
-        if (more) stash((kt + 1) & 1);
+        // this wave's loads of tile kt+1 have landed; after the barrier every wave's have, and
+        // every wave is done reading stage kt&1
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+        asm volatile("" ::: "memory");
         __syncthreads();
     }
 
@@ -288,13 +297,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16_t* __restri
             lse[((size_t)b * Hq + h) * S + qi] = m_run * scale_log2e * 0.69314718055994530942f + logf(l_run);
     }
     }   // phase
+#undef SP_ATTN_ISSUE
 }
 
 template <int HD>
 hipError_t launch_fwd(hipStream_t st, dim3 grid, const bf16_t* qkv, bf16_t* o, float* lse,
                       const AttnShape& a, int paired, float sl2) {
     typedef AttnCfg<HD> C;
-    constexpr int LDS = 2 * (C::K_BYTES + C::V_BYTES);
+    constexpr int LDS = 2 * C::STAGE;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_kernel<HD>),
