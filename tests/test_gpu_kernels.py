@@ -184,6 +184,9 @@ def test_swiglu(T, f):
     (2, 64, 2, 1, 128, 0),
     (1, 1, 2, 2, 64, 1),        # a single token attends to itself
     (1, 129, 2, 2, 64, 1),      # one query past a block boundary
+    (2, 33, 2, 2, 80, 1),       # head_dim 80 (padded 192-byte LDS rows), causal, less than one key tile
+    (1, 1, 2, 1, 128, 0),
+    (11, 520, 16, 4, 128, 1),   # enough work-groups for the paired causal blocks; ragged last key tile
 ])
 def test_attention(B, S, Hq, Hkv, hd, causal):
     rng = np.random.default_rng(B + S + Hq + hd + causal)
