@@ -83,6 +83,9 @@ def main():
                     help="training: this many lowest layers get no weight gradients; no input gradient is "
                          "asked for, so the backward stops above them")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--paper-table", action="store_true",
+                    help="also time the paper's comparison rows (Sec. 4.2, Table 1): Standard (resident), "
+                         "Naive(k) and Superpipeline(k, k') at the paper's window settings")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="no event brackets around the dominant GEMM in the timed region (roofline fields read 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -148,10 +151,12 @@ def main():
     ceiling = copy_ceiling_gbps(torch)
     log(f"[bench] plain pinned H2D copy ceiling: {ceiling:.1f} GB/s")
 
-    def run(kk, pp, flags, steps, warmup, pinned=0, units=1):
+    def run(kk, pp, flags, steps, warmup, pinned=0, units=1, slots=None):
+        # slots: a budget of that many layer slots instead of the workload's own
         if training:
             flags |= sp.SP_FLAG_TRAINING | (sp.SP_FLAG_KEEP_ACTIVATIONS if args.keep_activations else 0)
-        eng = sp.Engine(desc, blobs, kk, pp, budget_layers=budget_layers, budget_bytes=budget_bytes, flags=flags,
+        eng = sp.Engine(desc, blobs, kk, pp, budget_layers=slots or budget_layers,
+                        budget_bytes=None if slots else budget_bytes, flags=flags,
                         pinned=pinned, frozen=args.frozen if training else 0, units=units)
 
         pos = [S]
@@ -318,6 +323,38 @@ def main():
                       "bit_identical": bool(np.array_equal(r["y"], base))})
         extra["sweep"] = sweep
         log("[bench] sweep: " + json.dumps(sweep))
+
+    if args.paper_table and not training:
+        # The paper's Table 1 (Sec. 4.2) on this machine.  Its k = layers on the GPU, k' = layers
+        # swapped per group: here k slots, of which k' are in flight.  Naive(k): k slots, loads and
+        # computes never overlap.  Standard: every layer resident (its copies happen in the warm-up).
+        L = w.n_layers
+        rows = []
+
+        def row(method, kk, kp, r):
+            m = max(r["ms_per_step"], r["wall_ms_per_step"])
+            rows.append({"method": method, "gpu_memory_gb": round(r["stats"].plan.arena_bytes_used / 1e9, 2),
+                         "ms_per_step": round(m, 2), "k": kk, "k_prime": kp,
+                         "bit_identical": bool(np.array_equal(r["y"], main_run["y"])) if not decoding else None})
+
+        row("Standard", None, None, run(L, L, 0, 3, 2, slots=L))
+        for kk in (1, 8, 15):
+            if kk < L:
+                row("Naive", kk, None, run(1, max(kk - 1, 1), sp.SP_FLAG_NO_OVERLAP, 3, 1, slots=kk))
+        for kk, kp in ((4, 2), (5, 3), (8, 3), (10, 2), (20, 6)):
+            if kk < L:
+                row("Superpipeline", kk, kp, run(kk - kp, kp, base_flags, 3, 1, slots=kk))
+        # the same budgets spent this build's way: a ring of two slots, the other slots pinned
+        for kk in (4, 8, 20):
+            if kk < L:
+                row("Superpipeline, k-2 layers pinned", kk, 1, run(1, 1, base_flags, 3, 1, pinned=sp.SP_PIN_AUTO, slots=kk))
+        extra["paper_table"] = rows
+        unit = "ms/token step" if decoding else "ms/forward"
+        log("[bench] | Method | GPU memory (GB) | Time (%s) | k | k' |" % unit)
+        log("[bench] |---|---|---|---|---|")
+        for r_ in rows:
+            log(f"[bench] | {r_['method']} | {r_['gpu_memory_gb']} | {r_['ms_per_step']} | "
+                f"{r_['k'] if r_['k'] else '-'} | {r_['k_prime'] if r_['k_prime'] else '-'} |")
 
     cpu = None
     if decoding:
