@@ -242,6 +242,7 @@ def main():
     achieved_tf = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     kname = ("gemm_dma_kernel<EPI_BF16> (first MLP projection, bias epilogue)" if training and w.arch == "encoder" else
              "gemm_dma_kernel<EPI_BF16> (gate/up projection)" if training else
+             "gemm_skinny_kernel<EPI_SWIGLU_BF16> (gate/up projection, one row per sequence)" if decoding else
              "gemm_dma_kernel<EPI_SWIGLU_BF16> (gate/up projection)" if w.arch == "decoder" else
              "gemm_dma_kernel<EPI_GELU_BF16> (first MLP projection)")
     roofline = {"bound": "mfma", "kernel": kname,

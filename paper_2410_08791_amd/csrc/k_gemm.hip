@@ -680,7 +680,8 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
 // Tile ids: register-staged kernel 1 = 128x128, 2 = 128x256 (BM x BN), 3 = 256x256 (4 waves each),
 // 4 = 256x256 with 8 waves; LDS-DMA kernel (contraction-contiguous operands only) 5 = 256x256 and
 // 6 = 128x256 with 8 waves, 7 = 128x128 with 4 waves (two work-groups per CU), 8 = 256x192 with 8
-// waves in a 4 x 2 grid (not with the SwiGLU epilogue, which pairs tiles inside a wave).
+// waves in a 4 x 2 grid (not with the SwiGLU epilogue, which pairs tiles inside a wave); 9 = the
+// weight-streaming kernel for at most 16 activation rows (k_gemm_skinny.hip).
 //
 // Choice (shapes only, so a stack's kernels never depend on the streaming window): the chip
 // runs 256 work-groups at a time (512 of tile 7), so a launch costs
@@ -719,6 +720,10 @@ GemmPlan plan_gemm(int epi, bool dma_ok, int M, int N) {
     GemmPlan pl{0, M, 0};
     if (!dma_ok) {
         pl.tile = pick_tile(kRegTiles, M, N, epi);
+        return pl;
+    }
+    if (M <= SPK_SKINNY_MAX_ROWS) {     // a decode step: nothing of W is re-used, stream it
+        pl.tile = 9;
         return pl;
     }
     float whole;
@@ -765,6 +770,7 @@ hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
         case 6: if (DMA_OK) return launch_dma<128, 256, EPI, 8, 2>(st, g); break;
         case 7: if (DMA_OK) return launch_dma<128, 128, EPI, 4, 2>(st, g); break;
         case 8: if (DMA_OK && EPI != EPI_SWIGLU_BF16) return launch_dma<256, 192, NOSWIGLU, 8, 4>(st, g); break;
+        case 9: if (DMA_OK) return spk_launch_gemm_skinny(st, EPI, g); break;
     }
     return hipErrorInvalidValue;
 }

@@ -26,12 +26,16 @@ struct GemmArgs {
     const float* R; int ldr;                // EPI_RESID_F32
     const bf16_t* bias;                     // [N] or nullptr
     int M, N, K;
-    int tile;                               // 0 = heuristic, else 1..7 = forced kernel and tile shape
+    int tile;                               // 0 = heuristic, else 1..9 = forced kernel and tile shape
 };
 
 // C[M,N] = sum_k A(m,k) W(n,k), bf16 operands, fp32 accumulate on MFMA.
 // Needs K % 64 == 0, N % 8 == 0, leading dimensions % 8 == 0, 16-byte aligned bases.
 hipError_t spk_launch_gemm(hipStream_t st, int epilogue, const GemmArgs& g);
+// The kernel for at most SPK_SKINNY_MAX_ROWS activation rows (tile id 9; both operands
+// contraction-contiguous): streams W once, 16 output columns per work-group.
+constexpr int SPK_SKINNY_MAX_ROWS = 16;
+hipError_t spk_launch_gemm_skinny(hipStream_t st, int epilogue, const GemmArgs& g);
 // What tile = 0 resolves to for a shape (host code, no launch): rows [0, body_rows) run with
 // `tile`, rows [body_rows, M) -- none when body_rows == M -- with `tail_tile`.
 struct GemmPlan { int tile, body_rows, tail_tile; };

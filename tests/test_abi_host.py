@@ -172,9 +172,13 @@ def test_gemm_plan_is_a_function_of_the_shape_alone():
     on the register-staged tiles, and the workloads' projections on the tiles their round counts
     call for (256 work-groups run at a time)."""
     for epi in range(5):
-        for M in (1, 8, 64, 200, 256, 300, 2048, 4096, 8192, 16448):
+        for M in (1, 8, 16, 17, 64, 200, 256, 300, 2048, 4096, 8192, 16448):
             for N in (8, 128, 1280, 4096, 5120, 11008, 12288, 28672):
                 tile, body, tail_tile = gemm_plan(epi, 0, 0, M, N)
+                if M <= 16:           # a decode step: the weight-streaming kernel
+                    assert (tile, body, tail_tile) == (9, M, 0)
+                    assert gemm_plan(epi, 0, 1, M, N)[0] in (1, 4)
+                    continue
                 assert tile in (5, 6, 7, 8) and 0 < body <= M
                 assert (tail_tile == 0) == (body == M)
                 if body < M:

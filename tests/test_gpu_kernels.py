@@ -79,6 +79,48 @@ def test_gemm_kmajor(epi, M, N, K, tile):
     assert np.all(np.abs(got - ref) <= tol + 1e-6), float(np.max(np.abs(got - ref)))
 
 
+@pytest.mark.parametrize("tile", [9, 0])
+@pytest.mark.parametrize("M,N,K", [(1, 8, 64), (8, 328, 4096), (16, 24, 320), (5, 1288, 1088), (13, 4096, 192)])
+@pytest.mark.parametrize("epi", [sp.EPI_BF16, sp.EPI_RESID_F32, sp.EPI_GELU_BF16, sp.EPI_SWIGLU_BF16, sp.EPI_F32])
+def test_gemm_few_rows_streams_the_weights(epi, M, N, K, tile):
+    """At most 16 activation rows (a decode step): the weight-streaming kernel, forced (tile 9) and
+    as the heuristic's choice; N not a multiple of the 16 columns of a work-group, K / 32 not a
+    multiple of the eight waves that share the contraction, M = 1 and M = 16."""
+    rng = np.random.default_rng(M + N * 3 + K * 5 + epi)
+    Ab, A = rand_bf16(rng, (M, K))
+    nw = 2 * N if epi == sp.EPI_SWIGLU_BF16 else N
+    Wb, W = rand_bf16(rng, (nw, K), 0.1)
+    bias_b, bias = (rand_bf16(rng, N, 0.5) if epi in (sp.EPI_GELU_BF16, sp.EPI_BF16, sp.EPI_RESID_F32) else (None, None))
+    R = rng.standard_normal((M, N)).astype(np.float32)
+    f32out = epi in (sp.EPI_RESID_F32, sp.EPI_F32)
+    # one guard row behind C: the kernel must not write past row M - 1
+    Cd = torch.full((M + 1, N), 7.0 if f32out else 7, dtype=torch.float32 if f32out else torch.int16, device=DEV)
+    if epi == sp.EPI_RESID_F32:
+        Cd[:M] = dev_f32(R)
+    Ad, Wd = dev_u16(Ab), dev_u16(Wb)
+    bd = dev_u16(bias_b) if bias_b is not None else None
+    rc = sp.spk_gemm(stream_ptr(), epi, ptr(Ad), K, 0, ptr(Wd), K, 0, ptr(Cd), N,
+                     ptr(Cd) if epi == sp.EPI_RESID_F32 else None, N, ptr(bd), M, N, K, tile)
+    assert rc == sp.SP_OK
+    sync()
+    ref = gemm_ref(A, W, epi, R.astype(np.float64), bias, N)
+    out = Cd.cpu()
+    assert bool((out[M] == 7).all())
+    got = out[:M].numpy().astype(np.float64) if f32out else bf16_vals(host_u16(out[:M].contiguous()))
+    scale = np.max(np.abs(ref))
+    tol = 2e-6 * np.sqrt(K) * scale + (0 if f32out else BF16_EPS * np.abs(ref))
+    assert np.all(np.abs(got - ref) <= tol + 1e-6), float(np.max(np.abs(got - ref)))
+
+
+def test_gemm_few_rows_kernel_refuses_what_it_cannot_take():
+    z = torch.zeros(1 << 16, dtype=torch.int16, device=DEV)
+    f = torch.zeros(1 << 14, dtype=torch.float32, device=DEV)
+    # 17 rows; an operand with the row index contiguous
+    assert sp.spk_gemm(stream_ptr(), sp.EPI_BF16, ptr(z), 64, 0, ptr(z), 64, 0, ptr(z), 64, None, 0, None, 17, 64, 64, 9) == sp.SP_ERR_INVALID_ARG
+    assert sp.spk_gemm(stream_ptr(), sp.EPI_F32, ptr(z), 64, 0, ptr(z), 64, 1, ptr(f), 64, None, 0, None, 8, 64, 64, 9) == sp.SP_ERR_INVALID_ARG
+    sync()
+
+
 def test_gemm_output_rows_not_16_byte_aligned():
     """A bf16 output whose row stride is a multiple of 4 but not of 8 elements: the kernel that
     writes 16-byte pieces of a row cannot take it, the library must fall back by itself (also
