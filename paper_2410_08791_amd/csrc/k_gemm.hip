@@ -681,7 +681,7 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
 // 4 = 256x256 with 8 waves; LDS-DMA kernel (contraction-contiguous operands only) 5 = 256x256 and
 // 6 = 128x256 with 8 waves, 7 = 128x128 with 4 waves (two work-groups per CU), 8 = 256x192 with 8
 // waves in a 4 x 2 grid (not with the SwiGLU epilogue, which pairs tiles inside a wave); 9 = the
-// weight-streaming kernel for at most 16 activation rows (k_gemm_skinny.hip).
+// weight-streaming kernel for at most 64 activation rows (k_gemm_skinny.hip).
 //
 // Choice (shapes only, so a stack's kernels never depend on the streaming window): the chip
 // runs 256 work-groups at a time (512 of tile 7), so a launch costs
@@ -732,7 +732,15 @@ GemmPlan plan_gemm(int epi, bool dma_ok, int M, int N) {
     if (tail && body) {
         float c_body, c_tail;
         const int t_body = pick_tile(kDmaTiles, body, N, epi, &c_body);
-        const int t_tail = pick_tile(kDmaTiles, tail, N, epi, &c_tail);
+        int t_tail;
+        if (tail <= SPK_SKINNY_MAX_ROWS) {
+            // the weight-streaming kernel in the units of pick_tile (a round of 256x256 tiles = 65536):
+            // N x K x 2 bytes at ~4.5 TB/s against 256 tiles x 2 x 65536 K flop at ~1.3 PFLOP/s, plus a launch
+            t_tail = 9;
+            c_tail = 1.13f * (float)N + 6000.f;
+        } else {
+            t_tail = pick_tile(kDmaTiles, tail, N, epi, &c_tail);
+        }
         if (c_body + c_tail < 0.95f * whole) pl = GemmPlan{t_body, body, t_tail};
     }
     return pl;

@@ -1,14 +1,16 @@
-// GEMM for at most 16 activation rows (a decode step: one token per sequence), both operands
-// contraction-contiguous:  C[M,N] = epilogue(sum_k A(m,k) W(n,k)),  M <= 16.
+// GEMM for at most 64 activation rows (a decode step: one token per sequence; the ragged last
+// rows of a long launch), both operands contraction-contiguous:
+// C[M,N] = epilogue(sum_k A(m,k) W(n,k)),  M <= 64.
 //
 // With so few rows the weight matrix is read once and nothing of it is re-used: the kernel is
 // bound by how fast W streams from HBM, and the 256-row tiles of the large kernels leave most of
 // the chip without work (N / 128 work-groups, one k-tile in flight each).  Here a work-group owns
 // 16 output columns and the whole contraction, split over its 8 waves; a wave issues its loads
 // straight from global memory, eight k-steps (8 x 1 KiB of W) in flight, and contracts with
-// v_mfma_f32_16x16x32_bf16: W rows as the A operand, the (up to 16) tokens as the B operand, so a
-// lane ends up with four consecutive output columns of one token.  The eight partial tiles are
-// summed through LDS in wave order (deterministic) by wave 0, which applies the epilogue.
+// v_mfma_f32_16x16x32_bf16: W rows as the A operand, 16 tokens as the B operand (one to four such
+// token tiles per W fragment), so a lane ends up with four consecutive output columns of one
+// token per tile.  The eight partial results are summed through LDS in wave order (deterministic)
+// by wave 0, which applies the epilogue.
 // N / 16 work-groups: 256 or more on every projection of the workloads.
 #include "sp_kernels.h"
 
@@ -16,7 +18,6 @@ namespace {
 
 constexpr int SK_WAVES = 8;
 constexpr int SK_COLS = 16;     // output columns per work-group
-constexpr int SK_UNROLL = 8;    // k-steps of 32 whose loads are issued before the first MFMA
 
 struct SkinnyDev {
     const bf16_t* A; const bf16_t* W; void* C; const float* R; const bf16_t* bias;
@@ -24,11 +25,14 @@ struct SkinnyDev {
     int M, N, K;
 };
 
-template <int EPI>
+// MT: token tiles of 16 rows (M <= 16 * MT)
+template <int EPI, int MT>
 __global__ __launch_bounds__(SK_WAVES * 64) void gemm_skinny_kernel(SkinnyDev p) {
     constexpr bool SWIGLU = (EPI == EPI_SWIGLU_BF16);
     constexpr int NACC = SWIGLU ? 2 : 1;
-    __shared__ f32x4_t part[NACC][SK_WAVES][64];
+    // k-steps of 32 whose loads are issued before the first MFMA
+    constexpr int SK_UNROLL = MT == 1 ? 8 : MT == 2 ? 6 : 4;
+    __shared__ f32x4_t part[NACC][MT][SK_WAVES][64];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -44,79 +48,96 @@ __global__ __launch_bounds__(SK_WAVES * 64) void gemm_skinny_kernel(SkinnyDev p)
     // columns that are never stored.
     const bf16_t* wp = p.W + (size_t)min(n0 + r, p.N - 1) * p.ldw + kb * 8;
     const bf16_t* wp2 = SWIGLU ? wp + (size_t)p.N * p.ldw : wp;   // the matching "up" rows
-    const bf16_t* xp = p.A + (size_t)min(r, p.M - 1) * p.lda + kb * 8;
-
-    f32x4_t acc[NACC];
+    const bf16_t* xp[MT];
 #pragma unroll
-    for (int a = 0; a < NACC; ++a) acc[a] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < MT; ++t) xp[t] = p.A + (size_t)min(t * 16 + r, p.M - 1) * p.lda + kb * 8;
+
+    f32x4_t acc[NACC][MT];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[a][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     int s = s0;
     for (; s + SK_UNROLL <= s1; s += SK_UNROLL) {
-        bf16x8_t wf[NACC][SK_UNROLL], xf[SK_UNROLL];
+        bf16x8_t wf[NACC][SK_UNROLL], xf[MT][SK_UNROLL];
 #pragma unroll
         for (int u = 0; u < SK_UNROLL; ++u) {
             wf[0][u] = *reinterpret_cast<const bf16x8_t*>(wp + (size_t)(s + u) * 32);
             if (SWIGLU) wf[NACC - 1][u] = *reinterpret_cast<const bf16x8_t*>(wp2 + (size_t)(s + u) * 32);
-            xf[u] = *reinterpret_cast<const bf16x8_t*>(xp + (size_t)(s + u) * 32);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) xf[t][u] = *reinterpret_cast<const bf16x8_t*>(xp[t] + (size_t)(s + u) * 32);
         }
 #pragma unroll
         for (int u = 0; u < SK_UNROLL; ++u)
 #pragma unroll
             for (int a = 0; a < NACC; ++a)
-                acc[a] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[a][u], xf[u], acc[a], 0, 0, 0);
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+                    acc[a][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[a][u], xf[t][u], acc[a][t], 0, 0, 0);
     }
     for (; s < s1; ++s) {
-        const bf16x8_t xf = *reinterpret_cast<const bf16x8_t*>(xp + (size_t)s * 32);
-        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(wp + (size_t)s * 32), xf,
-                                                         acc[0], 0, 0, 0);
-        if (SWIGLU)
-            acc[NACC - 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                *reinterpret_cast<const bf16x8_t*>(wp2 + (size_t)s * 32), xf, acc[NACC - 1], 0, 0, 0);
+        const bf16x8_t w0 = *reinterpret_cast<const bf16x8_t*>(wp + (size_t)s * 32);
+        const bf16x8_t w1 = *reinterpret_cast<const bf16x8_t*>(wp2 + (size_t)s * 32);
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const bf16x8_t xf = *reinterpret_cast<const bf16x8_t*>(xp[t] + (size_t)s * 32);
+            acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, xf, acc[0][t], 0, 0, 0);
+            if (SWIGLU) acc[NACC - 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, xf, acc[NACC - 1][t], 0, 0, 0);
+        }
     }
 
 #pragma unroll
-    for (int a = 0; a < NACC; ++a) part[a][wave][lane] = acc[a];
+    for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) part[a][t][wave][lane] = acc[a][t];
     __syncthreads();
     if (wave != 0) return;
 
-    // accumulator layout: lane -> token m = lane & 15, output columns n0 + 4 * (lane >> 4) + 0..3
-    f32x4_t sum[NACC];
+    // accumulator layout of token tile t: lane -> token m = 16 t + (lane & 15), output columns
+    // n0 + 4 * (lane >> 4) + 0..3
+    const int n = n0 + 4 * (lane >> 4);
+    if (n >= p.N) return;                    // N % 8 == 0: a group of four columns is inside or outside
 #pragma unroll
-    for (int a = 0; a < NACC; ++a) {
-        sum[a] = part[a][0][lane];
+    for (int t = 0; t < MT; ++t) {
+        const int m = t * 16 + (lane & 15);
+        if (m >= p.M) continue;
+        f32x4_t sum[NACC];
 #pragma unroll
-        for (int w = 1; w < SK_WAVES; ++w) sum[a] += part[a][w][lane];
-    }
-    const int m = lane & 15, n = n0 + 4 * (lane >> 4);
-    if (m >= p.M || n >= p.N) return;        // N % 8 == 0: a group of four columns is inside or outside
-    float v[4];
+        for (int a = 0; a < NACC; ++a) {
+            sum[a] = part[a][t][0][lane];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        if (SWIGLU) {
-            const float gv = sum[0][e], uv = sum[NACC - 1][e];
-            v[e] = gv * __builtin_amdgcn_rcpf(1.0f + __expf(-gv)) * uv;
+            for (int w = 1; w < SK_WAVES; ++w) sum[a] += part[a][t][w][lane];
+        }
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (SWIGLU) {
+                const float gv = sum[0][e], uv = sum[NACC - 1][e];
+                v[e] = gv * __builtin_amdgcn_rcpf(1.0f + __expf(-gv)) * uv;
+            } else {
+                v[e] = sum[0][e];
+            }
+        }
+        if (!SWIGLU && p.bias) {
+            const uint2 b = *reinterpret_cast<const uint2*>(p.bias + n);
+            v[0] += bf_lo(b.x); v[1] += bf_hi(b.x); v[2] += bf_lo(b.y); v[3] += bf_hi(b.y);
+        }
+        if (EPI == EPI_GELU_BF16) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
+        }
+        if (EPI == EPI_RESID_F32 || EPI == EPI_F32) {
+            float4 o = make_float4(v[0], v[1], v[2], v[3]);
+            if (EPI == EPI_RESID_F32) {
+                const float4 rr = *reinterpret_cast<const float4*>(p.R + (size_t)m * p.ldr + n);
+                o = make_float4(o.x + rr.x, o.y + rr.y, o.z + rr.z, o.w + rr.w);
+            }
+            *reinterpret_cast<float4*>(static_cast<float*>(p.C) + (size_t)m * p.ldc + n) = o;
         } else {
-            v[e] = sum[0][e];
+            *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n) =
+                make_uint2(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]));
         }
-    }
-    if (!SWIGLU && p.bias) {
-        const uint2 b = *reinterpret_cast<const uint2*>(p.bias + n);
-        v[0] += bf_lo(b.x); v[1] += bf_hi(b.x); v[2] += bf_lo(b.y); v[3] += bf_hi(b.y);
-    }
-    if (EPI == EPI_GELU_BF16) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
-    }
-    if (EPI == EPI_RESID_F32 || EPI == EPI_F32) {
-        float4 o = make_float4(v[0], v[1], v[2], v[3]);
-        if (EPI == EPI_RESID_F32) {
-            const float4 rr = *reinterpret_cast<const float4*>(p.R + (size_t)m * p.ldr + n);
-            o = make_float4(o.x + rr.x, o.y + rr.y, o.z + rr.z, o.w + rr.w);
-        }
-        *reinterpret_cast<float4*>(static_cast<float*>(p.C) + (size_t)m * p.ldc + n) = o;
-    } else {
-        *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n) =
-            make_uint2(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]));
     }
 }
 
@@ -126,7 +147,10 @@ hipError_t launch_skinny(hipStream_t st, const GemmArgs& g) {
     d.A = g.A; d.W = g.W; d.C = g.C; d.R = g.R; d.bias = g.bias;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc; d.ldr = g.ldr;
     d.M = g.M; d.N = g.N; d.K = g.K;
-    gemm_skinny_kernel<EPI><<<(g.N + SK_COLS - 1) / SK_COLS, SK_WAVES * 64, 0, st>>>(d);
+    const dim3 grid((g.N + SK_COLS - 1) / SK_COLS), block(SK_WAVES * 64);
+    if (g.M <= 16) gemm_skinny_kernel<EPI, 1><<<grid, block, 0, st>>>(d);
+    else if (g.M <= 32) gemm_skinny_kernel<EPI, 2><<<grid, block, 0, st>>>(d);
+    else gemm_skinny_kernel<EPI, 4><<<grid, block, 0, st>>>(d);
     return hipGetLastError();
 }
 

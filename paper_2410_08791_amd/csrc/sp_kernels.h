@@ -33,8 +33,9 @@ struct GemmArgs {
 // Needs K % 64 == 0, N % 8 == 0, leading dimensions % 8 == 0, 16-byte aligned bases.
 hipError_t spk_launch_gemm(hipStream_t st, int epilogue, const GemmArgs& g);
 // The kernel for at most SPK_SKINNY_MAX_ROWS activation rows (tile id 9; both operands
-// contraction-contiguous): streams W once, 16 output columns per work-group.
-constexpr int SPK_SKINNY_MAX_ROWS = 16;
+// contraction-contiguous): streams W once, 16 output columns per work-group, one to four tiles of
+// 16 rows per weight fragment.
+constexpr int SPK_SKINNY_MAX_ROWS = 64;
 hipError_t spk_launch_gemm_skinny(hipStream_t st, int epilogue, const GemmArgs& g);
 // What tile = 0 resolves to for a shape (host code, no launch): rows [0, body_rows) run with
 // `tile`, rows [body_rows, M) -- none when body_rows == M -- with `tail_tile`.

@@ -172,17 +172,18 @@ def test_gemm_plan_is_a_function_of_the_shape_alone():
     on the register-staged tiles, and the workloads' projections on the tiles their round counts
     call for (256 work-groups run at a time)."""
     for epi in range(5):
-        for M in (1, 8, 16, 17, 64, 200, 256, 300, 2048, 4096, 8192, 16448):
+        for M in (1, 8, 16, 17, 64, 65, 200, 256, 300, 2048, 4096, 8192, 16448):
             for N in (8, 128, 1280, 4096, 5120, 11008, 12288, 28672):
                 tile, body, tail_tile = gemm_plan(epi, 0, 0, M, N)
-                if M <= 16:           # a decode step: the weight-streaming kernel
+                if M <= 64:           # a decode step: the weight-streaming kernel
                     assert (tile, body, tail_tile) == (9, M, 0)
                     assert gemm_plan(epi, 0, 1, M, N)[0] in (1, 4)
                     continue
                 assert tile in (5, 6, 7, 8) and 0 < body <= M
                 assert (tail_tile == 0) == (body == M)
                 if body < M:
-                    assert body % 256 == 0 and M - body < 256 and tail_tile in (5, 6, 7, 8)
+                    assert body % 256 == 0 and M - body < 256 and tail_tile in (5, 6, 7, 8, 9)
+                    assert (tail_tile == 9) == (M - body <= 64)
                 if epi == sp.EPI_SWIGLU_BF16:
                     assert tile != 8 and tail_tile != 8
                 assert gemm_plan(epi, 0, 0, M, N) == (tile, body, tail_tile)
@@ -196,7 +197,7 @@ def test_gemm_plan_is_a_function_of_the_shape_alone():
     assert gemm_plan(sp.EPI_RESID_F32, 0, 0, 2048, 4096) == (6, 2048, 0)
     # ViT-H, 16448 tokens = 64 x 256 + 64: the first MLP projection would take 1300 tiles = 5.08
     # rounds; cut, it takes 1280 (5 rounds) plus a small launch for the last 64 rows
-    assert gemm_plan(sp.EPI_GELU_BF16, 0, 0, 16448, 5120) == (5, 16384, 7)
+    assert gemm_plan(sp.EPI_GELU_BF16, 0, 0, 16448, 5120) == (5, 16384, 9)
     assert sp.lib.spk_gemm_plan(7, 0, 0, 8, 8, (C.c_int * 3)()) == sp.SP_ERR_INVALID_ARG
     assert sp.lib.spk_gemm_plan(0, 0, 0, 0, 8, (C.c_int * 3)()) == sp.SP_ERR_INVALID_ARG
 

@@ -80,12 +80,14 @@ def test_gemm_kmajor(epi, M, N, K, tile):
 
 
 @pytest.mark.parametrize("tile", [9, 0])
-@pytest.mark.parametrize("M,N,K", [(1, 8, 64), (8, 328, 4096), (16, 24, 320), (5, 1288, 1088), (13, 4096, 192)])
+@pytest.mark.parametrize("M,N,K", [(1, 8, 64), (8, 328, 4096), (16, 24, 320), (5, 1288, 1088), (13, 4096, 192),
+                                   (17, 40, 448), (32, 328, 1280), (33, 72, 64), (64, 5128, 1280)])
 @pytest.mark.parametrize("epi", [sp.EPI_BF16, sp.EPI_RESID_F32, sp.EPI_GELU_BF16, sp.EPI_SWIGLU_BF16, sp.EPI_F32])
 def test_gemm_few_rows_streams_the_weights(epi, M, N, K, tile):
-    """At most 16 activation rows (a decode step): the weight-streaming kernel, forced (tile 9) and
-    as the heuristic's choice; N not a multiple of the 16 columns of a work-group, K / 32 not a
-    multiple of the eight waves that share the contraction, M = 1 and M = 16."""
+    """At most 64 activation rows (a decode step, the ragged last rows of a long launch): the
+    weight-streaming kernel, forced (tile 9) and as the heuristic's choice; N not a multiple of the
+    16 columns of a work-group, K / 32 not a multiple of the eight waves that share the
+    contraction, M at and next to the limits of its one, two and four 16-row tiles."""
     rng = np.random.default_rng(M + N * 3 + K * 5 + epi)
     Ab, A = rand_bf16(rng, (M, K))
     nw = 2 * N if epi == sp.EPI_SWIGLU_BF16 else N
@@ -115,8 +117,8 @@ def test_gemm_few_rows_streams_the_weights(epi, M, N, K, tile):
 def test_gemm_few_rows_kernel_refuses_what_it_cannot_take():
     z = torch.zeros(1 << 16, dtype=torch.int16, device=DEV)
     f = torch.zeros(1 << 14, dtype=torch.float32, device=DEV)
-    # 17 rows; an operand with the row index contiguous
-    assert sp.spk_gemm(stream_ptr(), sp.EPI_BF16, ptr(z), 64, 0, ptr(z), 64, 0, ptr(z), 64, None, 0, None, 17, 64, 64, 9) == sp.SP_ERR_INVALID_ARG
+    # 65 rows; an operand with the row index contiguous
+    assert sp.spk_gemm(stream_ptr(), sp.EPI_BF16, ptr(z), 64, 0, ptr(z), 64, 0, ptr(z), 64, None, 0, None, 65, 64, 64, 9) == sp.SP_ERR_INVALID_ARG
     assert sp.spk_gemm(stream_ptr(), sp.EPI_F32, ptr(z), 64, 0, ptr(z), 64, 1, ptr(f), 64, None, 0, None, 8, 64, 64, 9) == sp.SP_ERR_INVALID_ARG
     sync()
 
