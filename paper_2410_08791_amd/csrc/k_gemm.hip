@@ -681,7 +681,9 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
 // 4 = 256x256 with 8 waves; LDS-DMA kernel (contraction-contiguous operands only) 5 = 256x256 and
 // 6 = 128x256 with 8 waves, 7 = 128x128 with 4 waves (two work-groups per CU), 8 = 256x192 with 8
 // waves in a 4 x 2 grid (not with the SwiGLU epilogue, which pairs tiles inside a wave); 9 = the
-// weight-streaming kernel for at most 64 activation rows (k_gemm_skinny.hip).
+// weight-streaming kernel for at most 64 activation rows (k_gemm_skinny.hip); 10 = 256x320 of the
+// LDS-DMA kernel, 4 x 2 waves (not with SwiGLU): N = 1280 is four of its columns, so the ViT-H
+// projections back to d_model are one round of 256 work-groups once the ragged rows are cut off.
 //
 // Choice (shapes only, so a stack's kernels never depend on the streaming window): the chip
 // runs 256 work-groups at a time (512 of tile 7), so a launch costs
@@ -689,8 +691,8 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
 // relative efficiency (larger tiles move fewer operand bytes per MFMA).  Take the cheapest.
 // (Activation rows are contiguous in A, C and R, so a launch can be cut along M.)
 struct TileCost { int id, bm, bn, concurrent; float eff; };
-constexpr TileCost kDmaTiles[] = {{5, 256, 256, 256, 1.00f}, {8, 256, 192, 256, 0.85f}, {6, 128, 256, 256, 0.72f},
-                                  {7, 128, 128, 512, 0.70f}};
+constexpr TileCost kDmaTiles[] = {{5, 256, 256, 256, 1.00f}, {10, 256, 320, 256, 1.02f}, {8, 256, 192, 256, 0.85f},
+                                  {6, 128, 256, 256, 0.72f}, {7, 128, 128, 512, 0.70f}};
 constexpr TileCost kRegTiles[] = {{4, 256, 256, 256, 1.00f}, {1, 128, 128, 512, 0.66f}};
 
 template <int NC>
@@ -699,7 +701,7 @@ int pick_tile(const TileCost (&cand)[NC], int M, int N, int epi, float* cost_out
     float best_cost = 0.f;
     for (int c = 0; c < NC; ++c) {
         const TileCost& t = cand[c];
-        if (t.id == 8 && epi == EPI_SWIGLU_BF16) continue;
+        if ((t.id == 8 || t.id == 10) && epi == EPI_SWIGLU_BF16) continue;
         const int bn_out = (epi == EPI_SWIGLU_BF16) ? t.bn / 2 : t.bn;
         const long tiles = (long)((M + t.bm - 1) / t.bm) * ((N + bn_out - 1) / bn_out);
         // in units of "every CU busy with one tile": the two-per-CU tile fills a CU with two
@@ -741,7 +743,7 @@ GemmPlan plan_gemm(int epi, bool dma_ok, int M, int N) {
         } else {
             t_tail = pick_tile(kDmaTiles, tail, N, epi, &c_tail);
         }
-        if (c_body + c_tail < 0.95f * whole) pl = GemmPlan{t_body, body, t_tail};
+        if (c_body + c_tail < 0.97f * whole) pl = GemmPlan{t_body, body, t_tail};
     }
     return pl;
 }
@@ -768,7 +770,7 @@ hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
             return e != hipSuccess ? e : launch_tile<EPI, AFORM, WFORM>(st, b);
         }
     }
-    if (!dma && tile >= 5 && tile <= 8) tile = tile == 6 ? 2 : tile == 7 ? 1 : 4;   // register-staged instead
+    if (!dma && ((tile >= 5 && tile <= 8) || tile == 10)) tile = tile == 6 ? 2 : tile == 7 ? 1 : 4;   // register-staged instead
     switch (tile) {
         case 1: return launch_one<128, 128, EPI, AFORM, WFORM, 4>(st, g);
         case 2: return launch_one<128, 256, EPI, AFORM, WFORM, 4>(st, g);
@@ -779,6 +781,7 @@ hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
         case 7: if (DMA_OK) return launch_dma<128, 128, EPI, 4, 2>(st, g); break;
         case 8: if (DMA_OK && EPI != EPI_SWIGLU_BF16) return launch_dma<256, 192, NOSWIGLU, 8, 4>(st, g); break;
         case 9: if (DMA_OK) return spk_launch_gemm_skinny(st, EPI, g); break;
+        case 10: if (DMA_OK && EPI != EPI_SWIGLU_BF16) return launch_dma<256, 320, NOSWIGLU, 8, 4>(st, g); break;
     }
     return hipErrorInvalidValue;
 }

@@ -179,13 +179,13 @@ def test_gemm_plan_is_a_function_of_the_shape_alone():
                     assert (tile, body, tail_tile) == (9, M, 0)
                     assert gemm_plan(epi, 0, 1, M, N)[0] in (1, 4)
                     continue
-                assert tile in (5, 6, 7, 8) and 0 < body <= M
+                assert tile in (5, 6, 7, 8, 10) and 0 < body <= M
                 assert (tail_tile == 0) == (body == M)
                 if body < M:
-                    assert body % 256 == 0 and M - body < 256 and tail_tile in (5, 6, 7, 8, 9)
+                    assert body % 256 == 0 and M - body < 256 and tail_tile in (5, 6, 7, 8, 9, 10)
                     assert (tail_tile == 9) == (M - body <= 64)
                 if epi == sp.EPI_SWIGLU_BF16:
-                    assert tile != 8 and tail_tile != 8
+                    assert tile not in (8, 10) and tail_tile not in (8, 10)
                 assert gemm_plan(epi, 0, 0, M, N) == (tile, body, tail_tile)
                 for forms in ((0, 1), (1, 1), (1, 0)):
                     t, b, tt = gemm_plan(epi, forms[0], forms[1], M, N)
@@ -195,9 +195,13 @@ def test_gemm_plan_is_a_function_of_the_shape_alone():
     assert gemm_plan(sp.EPI_SWIGLU_BF16, 0, 0, 2048, 11008) == (5, 2048, 0)
     assert gemm_plan(sp.EPI_BF16, 0, 0, 2048, 12288) == (8, 2048, 0)
     assert gemm_plan(sp.EPI_RESID_F32, 0, 0, 2048, 4096) == (6, 2048, 0)
-    # ViT-H, 16448 tokens = 64 x 256 + 64: the first MLP projection would take 1300 tiles = 5.08
-    # rounds; cut, it takes 1280 (5 rounds) plus a small launch for the last 64 rows
-    assert gemm_plan(sp.EPI_GELU_BF16, 0, 0, 16448, 5120) == (5, 16384, 9)
+    # ViT-H, 16448 tokens = 64 x 256 + 64: the first MLP projection would take 1300 tiles of 256x256 =
+    # 5.08 rounds; cut, it takes 1024 tiles of 256x320 (4 rounds) plus a small launch for the last 64
+    # rows; the projections back to d_model = 1280 = 4 x 320 become exactly one round
+    assert gemm_plan(sp.EPI_GELU_BF16, 0, 0, 16448, 5120) == (10, 16384, 9)
+    assert gemm_plan(sp.EPI_RESID_F32, 0, 0, 16448, 1280) == (10, 16384, 9)
+    # llama70b QKV, 4096 x 10240: 512 tiles of 256x320 (two rounds) instead of 640 of 256x256 (2.5)
+    assert gemm_plan(sp.EPI_BF16, 0, 0, 4096, 10240) == (10, 4096, 0)
     assert sp.lib.spk_gemm_plan(7, 0, 0, 8, 8, (C.c_int * 3)()) == sp.SP_ERR_INVALID_ARG
     assert sp.lib.spk_gemm_plan(0, 0, 0, 0, 8, (C.c_int * 3)()) == sp.SP_ERR_INVALID_ARG
 
