@@ -69,7 +69,7 @@ int spk_kv_append(void* stream, const uint16_t* qkv, uint16_t* kt, uint16_t* v, 
 
 /* o bf16 [B, Hq*hd]: row b = softmax(q_b K^T / sqrt(hd)) V over the first n cached
  * positions of sequence b, q_b = the query part of row b of qkv bf16 [B, (Hq+2Hkv)*hd].
- * hd 64 or 128; max_len even, <= 32768; 1 <= n <= max_len. */
+ * hd 64 or 128; max_len a multiple of 8, <= 32768; kt and v 16-byte aligned; 1 <= n <= max_len. */
 int spk_decode_attention(void* stream, const uint16_t* qkv, const uint16_t* kt, const uint16_t* v, uint16_t* o,
                          int B, int n, int max_len, int Hq, int Hkv, int hd);
 

@@ -3,7 +3,7 @@
 // Cache of one layer (bf16):  Kt [B][Hkv][hd][max_len]   keys, position index contiguous
 //                             V  [B][Hkv][max_len][hd]   values, head dimension contiguous
 // Kt is stored transposed so that the score pass reads keys coalesced along the position
-// (one lane per key pair); V rows are read coalesced along the head dimension by the
+// (eight positions per lane); V rows are read coalesced along the head dimension by the
 // weighted sum.  Both passes read every cached byte once: the kernel is HBM-bound,
 // 4 n Hkv hd bytes per sequence for n cached positions.
 #include "sp_kernels.h"
@@ -34,38 +34,75 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const bf16_t* __restrict
 }
 
 // One work-group = one (query head, sequence): scores over n cached positions, softmax in
-// fp32, weighted sum of V.  Dynamic LDS: n_pad scores | HD query | 8 | 4*KPW*HD partial sums.
+// fp32, weighted sum of V.  Every load is 16 bytes per lane and eight or more are in flight
+// per lane: with one work-group per (head, sequence) the kernel is bound by memory latency,
+// not bandwidth (4-byte loads four deep took 34 us for 8 x 32 heads over 520 positions).
+// Scores: the cache is walked in chunks of 512 positions; a lane owns 8 consecutive positions
+// (one 16-byte piece of a Kt row), the four waves split the head dimension, and their partial
+// dot products meet in LDS.  Weighted sum: a lane owns 8 consecutive head-dimension elements
+// of a V row, a wave 512 / HD rows per step; the partial sums of the waves' row groups meet in
+// LDS.  Both reductions add in a fixed order.
+// Dynamic LDS (floats): n_pad probabilities | HD query | 8 | 4 x 512 score partials | 2048 output partials.
 template <int HD>
 __global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restrict__ qkv, int ld_qkv,
                                                           const bf16_t* __restrict__ kt, const bf16_t* __restrict__ v,
                                                           bf16_t* __restrict__ o, int ld_o, int n, int n_pad,
                                                           int max_len, int Hq, int Hkv, float scale) {
     extern __shared__ float smem[];
-    constexpr int KPW = 128 / HD;          // keys one wave handles per step of the weighted sum
+    constexpr int DW = HD / 4;             // head-dimension elements per wave in the score pass
+    constexpr int LPR = HD / 8;            // lanes per V row
+    constexpr int RPW = 64 / LPR;          // V rows per wave and step
     float* sc = smem;
     float* qs = sc + n_pad;
     float* red = qs + HD;
-    float* part = red + 8;                 // [4 * KPW][HD]
+    float* scp = red + 8;                  // [4][512]
+    float* part = scp + 4 * 512;           // [4 * RPW][HD]
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int hq = blockIdx.x, b = blockIdx.y, hk = hq / (Hq / Hkv);
     if (tid < HD) qs[tid] = bf2f(qkv[(size_t)b * ld_qkv + hq * HD + tid]) * scale;
     __syncthreads();
 
-    // scores: a thread owns key pairs (t, t+1), t = 2*tid + 512*j; max_len is even, so the
-    // pair's second key is inside the cache even when it is not among the n valid ones
-    const bf16_t* K = kt + (size_t)(b * Hkv + hk) * HD * max_len;
+    // scores.  max_len is a multiple of 8, so a lane's 8 positions lie inside the cache row even
+    // when some of them are not among the n valid ones (those are never stored).
+    const bf16_t* K = kt + (size_t)(b * Hkv + hk) * HD * max_len + (size_t)w * DW * max_len;
     float mx = -INFINITY;
-    for (int t = 2 * tid; t < n; t += 512) {
-        float a0 = 0.f, a1 = 0.f;
-#pragma unroll 16
-        for (int d = 0; d < HD; ++d) {
-            const uint32_t kk = *reinterpret_cast<const uint32_t*>(K + (size_t)d * max_len + t);
-            a0 = fmaf(qs[d], bf_lo(kk), a0);
-            a1 = fmaf(qs[d], bf_hi(kk), a1);
+    for (int c0 = 0; c0 < n; c0 += 512) {
+        const int t = c0 + lane * 8;
+        float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (t < n) {
+            // all of the lane's loads first, then the arithmetic (left to itself the compiler pairs
+            // every load with its use and waits for each in turn)
+            constexpr int DB = DW < 16 ? DW : 16;
+#pragma unroll
+            for (int d0 = 0; d0 < DW; d0 += DB) {
+                u32x4_t kk[DB];
+#pragma unroll
+                for (int d = 0; d < DB; ++d) kk[d] = *reinterpret_cast<const u32x4_t*>(K + (size_t)(d0 + d) * max_len + t);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int d = 0; d < DB; ++d) {
+                    const float q = qs[w * DW + d0 + d];
+                    a[0] = fmaf(q, bf_lo(kk[d][0]), a[0]); a[1] = fmaf(q, bf_hi(kk[d][0]), a[1]);
+                    a[2] = fmaf(q, bf_lo(kk[d][1]), a[2]); a[3] = fmaf(q, bf_hi(kk[d][1]), a[3]);
+                    a[4] = fmaf(q, bf_lo(kk[d][2]), a[4]); a[5] = fmaf(q, bf_hi(kk[d][2]), a[5]);
+                    a[6] = fmaf(q, bf_lo(kk[d][3]), a[6]); a[7] = fmaf(q, bf_hi(kk[d][3]), a[7]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        sc[t] = a0;
-        mx = fmaxf(mx, a0);
-        if (t + 1 < n) { sc[t + 1] = a1; mx = fmaxf(mx, a1); }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) scp[w * 512 + lane * 8 + e] = a[e];
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int i = tid * 2 + e;
+            if (c0 + i < n) {
+                const float sv = (scp[i] + scp[512 + i]) + (scp[1024 + i] + scp[1536 + i]);
+                sc[c0 + i] = sv;
+                mx = fmaxf(mx, sv);
+            }
+        }
+        __syncthreads();                   // scp is rewritten by the next chunk
     }
     mx = wave_max(mx);
     if (lane == 0) red[w] = mx;
@@ -79,25 +116,38 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const bf16_t* __restri
     }
     sum = block_sum_256(sum, red + 4);     // its barriers also publish the probabilities
 
-    // weighted sum: wave w, sub-group g take keys t = (w*KPW + g) + 4*KPW*j; a lane holds two
-    // adjacent head-dimension elements
+    // weighted sum: wave w, row group g take keys t = (w * RPW + g) + 4 * RPW * j
     const bf16_t* V = v + (size_t)(b * Hkv + hk) * max_len * HD;
-    const int g = lane / (HD / 2), dp = 2 * (lane % (HD / 2));
-    float o0 = 0.f, o1 = 0.f;
-#pragma unroll 4
-    for (int t = w * KPW + g; t < n; t += 4 * KPW) {
-        const uint32_t vv = *reinterpret_cast<const uint32_t*>(V + (size_t)t * HD + dp);
-        const float p = sc[t];
-        o0 = fmaf(p, bf_lo(vv), o0);
-        o1 = fmaf(p, bf_hi(vv), o1);
+    const int g = lane / LPR, dp = 8 * (lane % LPR);
+    float oa[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    constexpr int VB = 8;                  // V rows of a lane in flight
+    for (int t0 = w * RPW + g; t0 < n; t0 += VB * 4 * RPW) {
+        u32x4_t vv[VB];
+        float pr[VB];
+#pragma unroll
+        for (int j = 0; j < VB; ++j) {
+            const int t = t0 + j * 4 * RPW;
+            vv[j] = *reinterpret_cast<const u32x4_t*>(V + (size_t)min(t, n - 1) * HD + dp);
+            pr[j] = t < n ? sc[t] : 0.f;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < VB; ++j) {
+            const float p = pr[j];
+            oa[0] = fmaf(p, bf_lo(vv[j][0]), oa[0]); oa[1] = fmaf(p, bf_hi(vv[j][0]), oa[1]);
+            oa[2] = fmaf(p, bf_lo(vv[j][1]), oa[2]); oa[3] = fmaf(p, bf_hi(vv[j][1]), oa[3]);
+            oa[4] = fmaf(p, bf_lo(vv[j][2]), oa[4]); oa[5] = fmaf(p, bf_hi(vv[j][2]), oa[5]);
+            oa[6] = fmaf(p, bf_lo(vv[j][3]), oa[6]); oa[7] = fmaf(p, bf_hi(vv[j][3]), oa[7]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
-    part[(w * KPW + g) * HD + dp] = o0;
-    part[(w * KPW + g) * HD + dp + 1] = o1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[(w * RPW + g) * HD + dp + e] = oa[e];
     __syncthreads();
     if (tid < HD) {
         float acc = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4 * KPW; ++i) acc += part[i * HD + tid];
+        for (int i = 0; i < 4 * RPW; ++i) acc += part[i * HD + tid];
         o[(size_t)b * ld_o + hq * HD + tid] = f2bf(acc / sum);
     }
 }
@@ -106,7 +156,7 @@ template <int HD>
 hipError_t launch_decode(hipStream_t st, const bf16_t* qkv, int ld_qkv, const bf16_t* kt, const bf16_t* v, bf16_t* o,
                          int ld_o, int B, int n, int max_len, int Hq, int Hkv) {
     const int n_pad = (n + 3) / 4 * 4;
-    const size_t lds = ((size_t)n_pad + HD + 8 + 4 * (128 / HD) * HD) * sizeof(float);
+    const size_t lds = ((size_t)n_pad + HD + 8 + 4 * 512 + 2048) * sizeof(float);
     static size_t attr = 0;
     if (lds > 48 * 1024 && lds > attr) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_attn_kernel<HD>),
@@ -132,8 +182,8 @@ hipError_t spk_launch_kv_append(hipStream_t st, const bf16_t* qkv, int ld_qkv, b
 hipError_t spk_launch_decode_attention(hipStream_t st, const bf16_t* qkv, int ld_qkv, const bf16_t* kt,
                                        const bf16_t* v, bf16_t* o, int ld_o, int B, int n, int max_len, int Hq,
                                        int Hkv, int hd) {
-    if (B < 1 || n < 1 || n > max_len || (max_len & 1) || max_len > kDecodeMaxLen || Hkv < 1 || Hq % Hkv ||
-        ((uintptr_t)kt & 3) || ((uintptr_t)v & 3))
+    if (B < 1 || n < 1 || n > max_len || (max_len & 7) || max_len > kDecodeMaxLen || Hkv < 1 || Hq % Hkv ||
+        ((uintptr_t)kt & 15) || ((uintptr_t)v & 15))
         return hipErrorInvalidValue;
     if (hd == 128) return launch_decode<128>(st, qkv, ld_qkv, kt, v, o, ld_o, B, n, max_len, Hq, Hkv);
     if (hd == 64) return launch_decode<64>(st, qkv, ld_qkv, kt, v, o, ld_o, B, n, max_len, Hq, Hkv);

@@ -64,7 +64,7 @@ hipError_t spk_launch_attention(hipStream_t st, const bf16_t* qkv, bf16_t* o, fl
 hipError_t spk_launch_kv_append(hipStream_t st, const bf16_t* qkv, int ld_qkv, bf16_t* kt, bf16_t* v, int B, int S,
                                 int pos0, int Hq, int Hkv, int hd, int max_len);
 // o bf16 [B, ld_o] = softmax(q K^T / sqrt(hd)) V for one query per sequence (row b of qkv)
-// over the first n cached positions.  hd 64 or 128, max_len even and <= kDecodeMaxLen.
+// over the first n cached positions.  hd 64 or 128, max_len a multiple of 8 and <= kDecodeMaxLen, kt and v 16-byte aligned.
 hipError_t spk_launch_decode_attention(hipStream_t st, const bf16_t* qkv, int ld_qkv, const bf16_t* kt,
                                        const bf16_t* v, bf16_t* o, int ld_o, int B, int n, int max_len, int Hq,
                                        int Hkv, int hd);

@@ -4,4 +4,4 @@
 #define SPK_MSE_PARTS 1024        // partial sums of the loss reduction
 // decode attention keeps one fp32 score per cached position in LDS
 constexpr int kDecodeMaxLen = 32768;
-constexpr size_t kDecodeMaxLds = ((size_t)kDecodeMaxLen + 128 + 8 + 512) * 4;
+constexpr size_t kDecodeMaxLds = ((size_t)kDecodeMaxLen + 128 + 8 + 4 * 512 + 2048) * 4;
