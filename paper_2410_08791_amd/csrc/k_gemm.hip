@@ -365,8 +365,11 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmDev& p, f32x16_t 
     constexpr bool F32OUT = (EPI == EPI_RESID_F32 || EPI == EPI_F32);
     constexpr int ESZ = F32OUT ? 4 : 2;
     constexpr int ROWB = BN_OUT * ESZ, STRIDE = ROWB + 16;
-    constexpr int RP = BM * STRIDE <= LDS_BYTES ? BM : (BM / 2) * STRIDE <= LDS_BYTES ? BM / 2 : BM / 4;
-    static_assert(RP * STRIDE <= LDS_BYTES && RP % 32 == 0, "a pass of the output tile fits the LDS");
+    constexpr int BIAS_BYTES = BN_OUT * 2;                // the tile's bias values, staged behind the passes
+    constexpr int ROOM = LDS_BYTES - BIAS_BYTES;
+    constexpr int RP = BM * STRIDE <= ROOM ? BM : (BM / 2) * STRIDE <= ROOM ? BM / 2 : BM / 4;
+    static_assert(RP * STRIDE <= ROOM && RP % 32 == 0 && BIAS_BYTES % 16 == 0, "a pass of the output tile fits the LDS");
+    const bf16_t* sbias = reinterpret_cast<const bf16_t*>(smem + ROOM);
     constexpr int TNO = SWIGLU ? TN / 2 : TN;
     constexpr int CPR = ROWB / 16, CHUNKS = RP * CPR;     // 16-byte chunks per row / per pass
     // the values of 4 consecutive columns (register group g of tile (j, i))
@@ -382,7 +385,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmDev& p, f32x16_t 
             }
         }
         if (!SWIGLU && p.bias) {
-            const uint2 b = *reinterpret_cast<const uint2*>(p.bias + min(n0 + nl, p.N - 4));
+            const uint2 b = *reinterpret_cast<const uint2*>(sbias + nl);
             v[0] += bf_lo(b.x); v[1] += bf_hi(b.x); v[2] += bf_lo(b.y); v[3] += bf_hi(b.y);
         }
         if (EPI == EPI_GELU_BF16) {
@@ -390,6 +393,27 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmDev& p, f32x16_t 
             for (int e = 0; e < 4; ++e) v[e] = gelu_erf(v[e]);
         }
     };
+    __syncthreads();   // every wave is done with the operand stages, no load is in flight
+    // Barriers from here on order LDS traffic only (lgkmcnt): a __syncthreads() would also wait
+    // for the global stores of a pass to be acknowledged, several microseconds per pass with the
+    // matrix pipes idle.
+    constexpr int WAIT_LGKM0 = 15 | (7 << 4) | (0 << 8) | (3 << 14);   // vmcnt 63, expcnt 7, lgkmcnt 0
+    auto lds_barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    // The tile's bias values go through LDS once: fetched from global memory where they are used,
+    // every one of a lane's TM x TN x 4 little loads was waited for in turn (a cache round trip each).
+    if (!SWIGLU && p.bias) {
+        for (int c = threadIdx.x; c < BN_OUT / 8; c += NT) {
+            const int n = n0 + c * 8;
+            const u32x4_t b = n < p.N ? *reinterpret_cast<const u32x4_t*>(p.bias + n) : u32x4_t{0, 0, 0, 0};   // N % 8 == 0
+            *reinterpret_cast<u32x4_t*>(smem + ROOM + c * 16) = b;
+        }
+        lds_barrier();
+    }
     // bf16 outputs: every wave computes and packs all of its values first (the activation
     // functions are the expensive part and must not be serialised by the passes below)
     uint2 pk[F32OUT ? 1 : TM][F32OUT ? 1 : TNO][4];
@@ -405,10 +429,32 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmDev& p, f32x16_t 
                     pk[F32OUT ? 0 : i][F32OUT ? 0 : j][g] = make_uint2(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]));
                 }
     }
-    __syncthreads();   // every wave is done with the operand stages, no load is in flight
+    // A thread's residual loads of a pass are all issued before the first is used (one after the
+    // other, each waited for, they cost a memory round trip per 16 bytes), the first batch before
+    // the pass's LDS writes, so that its latency runs under those.
+    constexpr int ITER = (CHUNKS + NT - 1) / NT;
+    constexpr int SB = ITER > 6 ? (ITER + 1) / 2 : ITER;     // residual pieces in flight per thread
+    auto chunk_pos = [&](int pass, int it, int* row, int* ch, int* m, int* n) {
+        const int c = threadIdx.x + it * NT;
+        *row = c / CPR;
+        *ch = c % CPR;
+        *m = m0 + pass * RP + *row;
+        *n = n0 + *ch * (16 / ESZ);
+        return c < CHUNKS && *m < p.M && *n < p.N;
+    };
+    float4 rr[EPI == EPI_RESID_F32 ? SB : 1];
+    auto load_resid = [&](int pass, int it0) {
+#pragma unroll
+        for (int it = it0; it < it0 + SB && it < ITER; ++it) {
+            int row, ch, m, n;
+            const bool ok = chunk_pos(pass, it, &row, &ch, &m, &n);
+            rr[it - it0] = ok ? *reinterpret_cast<const float4*>(p.R + (size_t)m * p.ldr + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
 #pragma unroll
     for (int pass = 0; pass < BM / RP; ++pass) {
-        if (pass) __syncthreads();   // the previous pass has been read out
+        if (EPI == EPI_RESID_F32) load_resid(pass, 0);
+        if (pass) lds_barrier();     // the previous pass has been read out
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int r = wrow0 + i * 32;                 // wave-uniform
@@ -428,18 +474,23 @@ __device__ __forceinline__ void gemm_epilogue_staged(const GemmDev& p, f32x16_t 
                     }
                 }
         }
-        __syncthreads();
-        for (int c = threadIdx.x; c < CHUNKS; c += NT) {
-            const int row = c / CPR, ch = c % CPR;
-            const int m = m0 + pass * RP + row, n = n0 + ch * (16 / ESZ);
-            if (m >= p.M || n >= p.N) continue;
-            u32x4_t v = *reinterpret_cast<const u32x4_t*>(smem + row * STRIDE + ch * 16);
-            if (EPI == EPI_RESID_F32) {
-                const float4 r = *reinterpret_cast<const float4*>(p.R + (size_t)m * p.ldr + n);
-                const float4 a = __builtin_bit_cast(float4, v);
-                v = __builtin_bit_cast(u32x4_t, make_float4(a.x + r.x, a.y + r.y, a.z + r.z, a.w + r.w));
+        lds_barrier();
+#pragma unroll
+        for (int it0 = 0; it0 < ITER; it0 += SB) {
+            if (EPI == EPI_RESID_F32 && it0) load_resid(pass, it0);
+#pragma unroll
+            for (int it = it0; it < it0 + SB && it < ITER; ++it) {
+                int row, ch, m, n;
+                if (chunk_pos(pass, it, &row, &ch, &m, &n)) {
+                    u32x4_t v = *reinterpret_cast<const u32x4_t*>(smem + row * STRIDE + ch * 16);
+                    if (EPI == EPI_RESID_F32) {
+                        const float4 a = __builtin_bit_cast(float4, v);
+                        const float4 r = rr[it - it0];
+                        v = __builtin_bit_cast(u32x4_t, make_float4(a.x + r.x, a.y + r.y, a.z + r.z, a.w + r.w));
+                    }
+                    *reinterpret_cast<u32x4_t*>(static_cast<unsigned char*>(p.C) + ((size_t)m * p.ldc + n) * ESZ) = v;
+                }
             }
-            *reinterpret_cast<u32x4_t*>(static_cast<unsigned char*>(p.C) + ((size_t)m * p.ldc + n) * ESZ) = v;
         }
     }
 }
