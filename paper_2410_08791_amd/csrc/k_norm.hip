@@ -29,6 +29,23 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_kernel(const float* __restr
         const int idx = lane + i * SP_WAVE;
         if (idx < nv) v[i] = src[idx];
     }
+    // Gain and bias of the lane's columns: fetched here, behind the row's loads and ahead of the
+    // reductions, when the registers allow; fetched where they are used, each little load is
+    // waited for in turn (eight cache round trips at the end of a 1280-wide row).
+    constexpr bool PRE = VPL <= 8;
+    const uint2* g2 = reinterpret_cast<const uint2*>(gain);
+    const uint2* b2 = reinterpret_cast<const uint2*>(bias);
+    uint2 gv[PRE ? VPL : 1], bv[PRE ? VPL : 1];
+    if (PRE) {
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            const int idx = lane + i * SP_WAVE;
+            if (idx < nv) {
+                gv[i] = g2[idx];
+                if (LAYERNORM) bv[i] = b2[idx];
+            }
+        }
+    }
 #pragma unroll
     for (int i = 0; i < VPL; ++i) {
         const int idx = lane + i * SP_WAVE;
@@ -53,17 +70,15 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_kernel(const float* __restr
         r = rsqrtf(wave_sum(s) / (float)d + eps);
     }
     uint2* dst = reinterpret_cast<uint2*>(out + (size_t)row * d);
-    const uint2* g2 = reinterpret_cast<const uint2*>(gain);
-    const uint2* b2 = reinterpret_cast<const uint2*>(bias);
 #pragma unroll
     for (int i = 0; i < VPL; ++i) {
         const int idx = lane + i * SP_WAVE;
         if (idx < nv) {
-            const uint2 g = g2[idx];
+            const uint2 g = PRE ? gv[PRE ? i : 0] : g2[idx];
             float o0 = (v[i].x - mean) * r * bf_lo(g.x), o1 = (v[i].y - mean) * r * bf_hi(g.x);
             float o2 = (v[i].z - mean) * r * bf_lo(g.y), o3 = (v[i].w - mean) * r * bf_hi(g.y);
             if (LAYERNORM) {
-                const uint2 b = b2[idx];
+                const uint2 b = PRE ? bv[PRE ? i : 0] : b2[idx];
                 o0 += bf_lo(b.x); o1 += bf_hi(b.x); o2 += bf_lo(b.y); o3 += bf_hi(b.y);
             }
             dst[idx] = make_uint2(pack_bf2(o0, o1), pack_bf2(o2, o3));
@@ -95,6 +110,18 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_block_kernel(const float* _
                            : (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
         }
     }
+    // gain and bias of the thread's columns, fetched ahead of the reductions (see norm_kernel)
+    const uint2* g2 = reinterpret_cast<const uint2*>(gain);
+    const uint2* b2 = reinterpret_cast<const uint2*>(bias);
+    uint2 gv[NORM_BLOCK_MAXV], bv[NORM_BLOCK_MAXV];
+#pragma unroll
+    for (int i = 0; i < NORM_BLOCK_MAXV; ++i) {
+        const int idx = threadIdx.x + i * NORM_THREADS;
+        if (idx < nv) {
+            gv[i] = g2[idx];
+            if (LAYERNORM) bv[i] = b2[idx];
+        }
+    }
     float mean = 0.f, r;
     if (LAYERNORM) {
         mean = block_sum_256(s, red) / (float)d;
@@ -112,17 +139,15 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_block_kernel(const float* _
         r = rsqrtf(block_sum_256(s, red) / (float)d + eps);
     }
     uint2* dst = reinterpret_cast<uint2*>(out + (size_t)row * d);
-    const uint2* g2 = reinterpret_cast<const uint2*>(gain);
-    const uint2* b2 = reinterpret_cast<const uint2*>(bias);
 #pragma unroll
     for (int i = 0; i < NORM_BLOCK_MAXV; ++i) {
         const int idx = threadIdx.x + i * NORM_THREADS;
         if (idx < nv) {
-            const uint2 g = g2[idx];
+            const uint2 g = gv[i];
             float o0 = (v[i].x - mean) * r * bf_lo(g.x), o1 = (v[i].y - mean) * r * bf_hi(g.x);
             float o2 = (v[i].z - mean) * r * bf_lo(g.y), o3 = (v[i].w - mean) * r * bf_hi(g.y);
             if (LAYERNORM) {
-                const uint2 b = b2[idx];
+                const uint2 b = bv[i];
                 o0 += bf_lo(b.x); o1 += bf_hi(b.x); o2 += bf_lo(b.y); o3 += bf_hi(b.y);
             }
             dst[idx] = make_uint2(pack_bf2(o0, o1), pack_bf2(o2, o3));
