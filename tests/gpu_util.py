@@ -43,3 +43,21 @@ def stream_ptr():
 def max_rel(got, ref):
     """max |got - ref| / max |ref|  (the bound the benchmark spec is quoted in)."""
     return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - ref)) / np.max(np.abs(ref)))
+
+
+def stack_errs(got, ref, x):
+    """Errors of a stack (or layer) output `got` against the oracle's `ref`, both [T, d], for the
+    input x [T, d] of that stack:
+      out     = max |got - ref| / max |ref|          the bound the benchmark spec is quoted in
+      contrib = max |got - ref| / max |ref - x|      the same error against what the layers ADDED to
+                the residual stream -- with x ~ N(0,1) and weights ~ N(0,0.02) the identity path
+                dominates max |ref|, and a badly wrong sub-block would still pass `out`
+      fro     = ||got - ref||_F / ||ref - x||_F
+    """
+    got = np.asarray(got, dtype=np.float64).reshape(ref.shape)
+    ref = np.asarray(ref, dtype=np.float64)
+    x = np.asarray(x, dtype=np.float64).reshape(ref.shape)
+    d = np.abs(got - ref)
+    added = ref - x
+    return dict(out=float(d.max() / np.abs(ref).max()), contrib=float(d.max() / np.abs(added).max()),
+                fro=float(np.sqrt((d * d).sum() / (added * added).sum())))

@@ -1,0 +1,189 @@
+"""Parity at the workloads' REAL sizes and depths (the paper's claim is about the whole model,
+Sec. 4.2: outputs identical to the standard mode; the task's bound is max relative error 2e-2).
+
+Two kinds of check per workload, both at the full token count, i.e. in the launch configurations
+the benchmark times:
+
+layerwise  For sampled layers l (first, middle, last) the library computes h_l with the l-layer
+           prefix of the stack and then h_{l+1} with layer l alone; the oracle computes ONE layer
+           from that same h_l.  This meets the kernels' real launch plans and the activation
+           statistics deep in the stack at the cost of one oracle layer per sample.  One sample
+           also checks that "layer l alone on h_l" is bit for bit the (l+1)-layer prefix.
+full       The library runs the whole stack; its output is compared on sampled token rows with
+           the oracle's full-depth output stored under tests/golden/ (written by
+           tests/golden/make_full_depth_golden.py, which calls only oracle/), and its max |y| and
+           Frobenius norm over ALL tokens with the stored ones.
+
+Errors are reported against max |ref| (the bound's norm) and against what the layers added to the
+residual stream (max |ref - input|): the identity path dominates max |ref|.
+"""
+import ctypes as C
+import gc
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from oracle import stack_oracle as O  # noqa: E402
+from paper_2410_08791_amd import binding as sp  # noqa: E402
+from paper_2410_08791_amd import synth  # noqa: E402
+from tests.gpu_util import DEV, dev_f32, stack_errs  # noqa: E402
+
+TOL = 2e-2            # max |got - ref| / max |ref|: the task's bound
+# One layer against the oracle's layer on the same input, relative to what the layer adds: every
+# GEMM operand is rounded to bf16 once (relative step 2^-8, rms error 2^-9/sqrt(3) = 1.1e-3), a
+# sub-block chains three to four such roundings (normed input, q/k/v or the hidden activation,
+# probabilities, attention output) through contractions that average them, so the added term
+# carries an rms relative error of about 2-3e-3; the maximum over 1e7-1e8 elements against the
+# maximum of the added term itself stays below 2e-2.
+TOL_LAYER_CONTRIB = 2e-2
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+# host RAM: the 80-layer 70B-shaped stack cycles 16 distinct layers (27 GB pinned instead of
+# 137 GB), as the benchmark does; the stored oracle run uses the same cycling
+DISTINCT = {"llama70b": 16}
+
+_cache = {}
+
+
+def case(name):
+    """Pinned blobs of a workload (distinct layers only), one workload alive at a time."""
+    if name not in _cache:
+        _cache.clear()
+        gc.collect()
+        w = synth.WORKLOADS[name]
+        gpath = os.path.join(GOLDEN, f"full_depth_{name}.npz")
+        distinct = DISTINCT.get(name, w.n_layers)
+        if os.path.exists(gpath):
+            assert int(np.load(gpath)["distinct"]) == distinct
+        desc = sp.make_desc(w)
+        pool = synth.make_pool(16)
+        blobs, views = sp.pinned_blobs(w, desc, n_layers=min(distinct, w.n_layers), pool=pool)
+        pool.shutdown()
+        _cache[name] = (w, distinct, blobs, views)
+    return _cache[name]
+
+
+def forward(w, blobs, x, n_layers, flags=0):
+    """sp_forward over `blobs` (one per layer) at the workload's batch and sequence length."""
+    desc = sp.make_desc(w.with_(training=False), n_layers=n_layers)
+    eng = sp.Engine(desc, blobs, 1, 1, flags=flags)
+    xd = dev_f32(x)
+    y = torch.full_like(xd, float("nan"))
+    eng.forward(xd, y, w.batch, w.seq)
+    eng.sync()
+    assert eng.destroy() == sp.SP_OK
+    return y.cpu().numpy().reshape(w.tokens, w.d_model)
+
+
+def oracle_shape(w):
+    return O.StackShape(w.arch, 1, w.d_model, w.n_q_heads, w.n_kv_heads, w.head_dim, w.d_ffn, w.causal, w.norm_eps)
+
+
+LAYERWISE = {"llama7b": (0, 15, 31), "vith": (0, 31), "train1p3b": (0, 23), "llama70b": (17,)}
+
+
+@pytest.mark.parametrize("name,phase", [(n, ph) for n in ("llama7b", "vith", "train1p3b", "llama70b")
+                                        for ph in ("layerwise", "full")])
+def test_depth(name, phase):
+    w, distinct, blobs, views = case(name)
+    x = synth.make_input(w).reshape(w.tokens, w.d_model)
+    layer_blob = lambda l: blobs[l % distinct]  # noqa: E731
+    if phase == "layerwise":
+        worst = {}
+        for i, l in enumerate(LAYERWISE[name]):
+            print(f"{name}: layer {l} of {w.n_layers}, {w.tokens} tokens", flush=True)
+            h_l = x if l == 0 else forward(w, [layer_blob(j) for j in range(l)], x, l)
+            got = forward(w, [layer_blob(l)], h_l, 1)
+            if i == len(LAYERWISE[name]) - 1 and l > 0 and name != "llama70b":
+                # the decomposition itself: layer l alone on h_l == the (l+1)-layer prefix, bit for bit
+                pre = forward(w, [layer_blob(j) for j in range(l + 1)], x, l + 1, flags=sp.SP_FLAG_POISON)
+                assert np.array_equal(pre.view(np.uint32), got.view(np.uint32)), l
+            wl = {k: O.decode_bf16(v, np.float32) for k, v in views[l % distinct].items()}
+            ref = O.layer_forward(h_l.astype(np.float32), wl, w.batch, w.seq, oracle_shape(w))
+            e = stack_errs(got, ref, h_l)
+            print(f"{name}: layer {l}: max|h_l| {np.abs(h_l).max():.3f} max|added| {np.abs(ref - h_l).max():.3f}; "
+                  f"err/max|ref| {e['out']:.3e}, err/max|added| {e['contrib']:.3e}, "
+                  f"Frobenius err/added {e['fro']:.3e}", flush=True)
+            assert np.all(np.isfinite(got))
+            for k_, v in e.items():
+                worst[k_] = max(worst.get(k_, 0.0), v)
+        assert worst["out"] <= TOL, worst
+        assert worst["contrib"] <= TOL_LAYER_CONTRIB, worst
+        return
+    gpath = os.path.join(GOLDEN, f"full_depth_{name}.npz")
+    if not os.path.exists(gpath):
+        pytest.skip(f"{gpath} has not been written (tests/golden/make_full_depth_golden.py {name})")
+    g = np.load(gpath)
+    print(f"{name}: whole stack, {w.n_layers} layers ({distinct} distinct), {w.tokens} tokens", flush=True)
+    y = forward(w, [layer_blob(l) for l in range(w.n_layers)], x, w.n_layers)
+    assert np.all(np.isfinite(y))
+    rows = g["rows"]
+    d = np.abs(y[rows].astype(np.float64) - g["y_rows"].astype(np.float64))
+    err_out = float(d.max() / g["y_absmax"])
+    err_contrib = float(d.max() / g["dy_absmax"])
+    added = g["y_rows"].astype(np.float64) - x[rows]
+    fro = float(np.sqrt((d * d).sum() / (added * added).sum()))
+    absmax = float(np.abs(y).max())
+    yfro = float(np.sqrt((y.astype(np.float64) ** 2).sum()))
+    print(f"{name}: full depth on {len(rows)} sampled rows: err/max|ref| {err_out:.3e}, err/max|ref-x| "
+          f"{err_contrib:.3e}, Frobenius err/(ref-x) {fro:.3e}; max|y| {absmax:.4f} vs {float(g['y_absmax']):.4f}, "
+          f"||y|| {yfro:.2f} vs {float(g['y_fro']):.2f}", flush=True)
+    assert err_out <= TOL
+    assert abs(absmax - float(g["y_absmax"])) <= TOL * float(g["y_absmax"])
+    assert abs(yfro - float(g["y_fro"])) <= TOL * float(g["y_fro"])
+
+
+def test_train1p3b_full_depth_gradients():
+    """The training workload at its full size (24 layers, 8 x 1024 tokens): loss, sampled rows of
+    y and dx and sampled entries of every weight gradient against the stored full-depth oracle
+    run; every gradient tensor's Frobenius norm against the stored one."""
+    name = "train1p3b"
+    gpath = os.path.join(GOLDEN, f"full_depth_{name}.npz")
+    if not os.path.exists(gpath):
+        pytest.skip(f"{gpath} has not been written")
+    g = np.load(gpath)
+    w, distinct, blobs, _ = case(name)
+    desc = sp.make_desc(w)
+    gbytes = sp.sp_layer_grad_bytes(C.byref(desc))
+    xd, td = dev_f32(synth.make_input(w)), dev_f32(synth.make_input(w, "target"))
+    eng = sp.Engine(desc, blobs, w.k, w.p, flags=sp.SP_FLAG_TRAINING)
+    gblobs = [torch.zeros(gbytes, dtype=torch.uint8, pin_memory=True) for _ in range(w.n_layers)]
+    y, dx = torch.zeros_like(xd), torch.zeros_like(xd)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    print(f"{name}: training step at full size", flush=True)
+    eng.forward_backward(xd, td, y, loss, dx, gblobs, w.batch, w.seq)
+    eng.sync()
+    assert eng.destroy() == sp.SP_OK
+    rows = g["rows"]
+    yh = y.cpu().numpy().reshape(w.tokens, -1)
+    dxh = dx.cpu().numpy().reshape(w.tokens, -1)
+    e_y = float(np.abs(yh[rows] - g["y_rows"]).max() / g["y_absmax"])
+    e_dx = float(np.abs(dxh[rows] - g["dx_rows"]).max() / g["dx_absmax"])
+    e_loss = abs(float(loss.item()) - float(g["loss"])) / float(g["loss"])
+    from tests.golden.make_full_depth_golden import grad_sample_index
+    names = [n for n, _, _ in synth.tensor_specs(w)]
+    worst = ("", 0.0)
+    worst_fro = ("", 0.0)
+    for l in range(w.n_layers):
+        gv = sp.grad_views(desc, gblobs[l].numpy())
+        for ti, n in enumerate(names):
+            got = gv[n]
+            assert np.all(np.isfinite(got)), (l, n)
+            idx = grad_sample_index(got.size, l, ti)
+            e = float(np.abs(got[idx] - g["grad_samples"][l, ti, :idx.size]).max() / g["grad_absmax"][l, ti])
+            if e > worst[1]:
+                worst = (f"layer {l} {n}", e)
+            fr = float(np.sqrt((got.astype(np.float64) ** 2).sum()))
+            ef = abs(fr - g["grad_fro"][l, ti]) / g["grad_fro"][l, ti]
+            if ef > worst_fro[1]:
+                worst_fro = (f"layer {l} {n}", ef)
+    print(f"{name}: loss {float(loss.item()):.6f} vs {float(g['loss']):.6f} (rel {e_loss:.2e}); y rows {e_y:.3e}; "
+          f"dx rows {e_dx:.3e}; worst sampled gradient error {worst[0]} = {worst[1]:.3e}; worst gradient-norm "
+          f"error {worst_fro[0]} = {worst_fro[1]:.3e}", flush=True)
+    assert e_y <= TOL and e_dx <= TOL and e_loss <= TOL
+    assert worst[1] <= TOL, worst
+    assert worst_fro[1] <= TOL, worst_fro
