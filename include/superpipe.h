@@ -19,9 +19,26 @@
  *    the current HIP device.  The library allocates NO device memory: slots
  *    and workspace are carved from the caller's arena, so peak HBM use is
  *    arena_bytes_used <= gpu_budget_bytes by construction.
- *  - Calls only enqueue work.  Outputs are valid after the caller
- *    synchronises compute_stream (gradient blobs: d2h_stream).
- *  - One handle = one stack; calls on a handle must not overlap.
+ *  - Calls enqueue work and return; outputs are valid after the caller
+ *    synchronises compute_stream (gradient blobs: d2h_stream).  Three places
+ *    block the host, none for longer than the work already enqueued: (1) the
+ *    run-ahead bound -- when about 1400 kernel launches and event records of a
+ *    handle are still unfinished on its compute stream, the next layer's enqueue
+ *    waits until about 350 are left (every call kind; a deep stack reaches the
+ *    bound inside one call; beyond it this HIP runtime was measured to run whole
+ *    passes 30-60 % slower); (2) sp_forward_backward waits at entry for the
+ *    previous step's last gradient; (3) sp_wait_gradient, sp_get_stats with a
+ *    timing flag, and sp_destroy wait for what they name.
+ *  - Kernel and tile choice depend on the shapes in sp_stack_desc and on B, S only:
+ *    never on the window, the slot address or the process environment (the library
+ *    reads no environment variable).
+ *  - One handle = one stack; calls on a handle must not overlap.  Handles may be
+ *    used from different host threads, one thread at a time per handle.
+ *  - A call that fails after it has begun to enqueue a pass (SP_ERR_HIP from a copy,
+ *    launch or event call mid-pass) leaves the handle FAILED: slots may hold layers
+ *    whose copies were never issued, so every later call on it returns SP_ERR_STATE;
+ *    sp_last_error and sp_destroy keep working.  Argument errors (INVALID_ARG, SHAPE,
+ *    NOT_PINNED, STATE) are detected before anything is enqueued and leave the handle usable.
  */
 #ifndef SUPERPIPE_H
 #define SUPERPIPE_H
@@ -90,8 +107,15 @@ enum {
                                       workspace instead of recomputing them in the backward
                                       (the columns of Table 2 that train without gradient
                                       checkpointing): more HBM, about a quarter less compute */
-    SP_FLAG_KERNEL_TIMING = 1u << 5 /* bracket every 4th launch of the layer's largest GEMM with
+    SP_FLAG_KERNEL_TIMING = 1u << 5, /* bracket every 4th launch of the layer's largest GEMM with
                                       timed events on the compute stream (big_gemm_* in sp_stats) */
+    SP_FLAG_DELAY = 1u << 7        /* debug: pseudo-random delays of up to sp_config.delay_us each -- the
+                                      host sleeps between enqueues, and a one-wave kernel that idles for a
+                                      bounded time and exits runs in front of every layer copy (copy stream)
+                                      and every layer's kernels (compute stream).  The streams then drift
+                                      against each other in ways a fast run never shows; a missing fence
+                                      surfaces as changed output bits (with SP_FLAG_POISON: as NaN).
+                                      Results must not change (Sec. 4.2)                              */
 };
 
 typedef struct {
@@ -122,6 +146,8 @@ typedef struct {
                                    of two layers and the budget pins more of the stack (pinned units are
                                    stored at their own size).  Forward-only handles (no SP_FLAG_TRAINING);
                                    results are bit-identical to layer units.                            */
+    int32_t delay_us;           /* SP_FLAG_DELAY: upper bound of one injected delay, 1..20000 microseconds
+                                   (0 with the flag set = 200); ignored without the flag               */
 } sp_config;
 #define SP_PIN_AUTO (-1)
 
@@ -176,6 +202,9 @@ typedef struct {
     uint32_t big_gemm_launches;
     float big_gemm_ms_sum;
     int32_t big_gemm_m, big_gemm_n, big_gemm_k;   /* its shape: C[m,n] over k (n counts gate and up) */
+    int32_t n_ops;              /* SP_FLAG_TIMING: compute operations the most recent call issued (units, forward
+                                   then backward); the arrays above hold the first n_timed = min(n_ops,
+                                   SP_MAX_TRACE_LAYERS) of them, the busy/hidden/wall sums cover all n_ops */
 } sp_stats;
 
 /* ---- layout queries (host only, no device needed) ------------------------ */
@@ -277,8 +306,12 @@ int sp_autotune_units(const sp_stack_desc* desc, uint64_t budget_bytes, int trai
 int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* const* layer_host_blobs,
               const sp_config* cfg);
 
-/* y = stack(x).  x_dev, y_dev: dev, fp32 [B, S, d_model], may be the same
- * buffer.  1 <= B <= max_batch, 1 <= S <= max_seq. */
+/* y = stack(x): one forward pass of the streamed stack (Sec. 3.3: the layers execute in order
+ * while the window slides; Sec. 4.2: the result is that of the resident model).  Layers that are
+ * not on the device are copied in as their slots free up, each layer is computed as soon as its
+ * weights have landed.  x_dev, y_dev: dev, fp32 [B, S, d_model], may be the same buffer (y_dev
+ * holds the residual stream while the pass runs).  1 <= B <= max_batch, 1 <= S <= max_seq
+ * (SP_ERR_SHAPE otherwise); both 16-byte aligned.  Returns once the pass is enqueued. */
 int sp_forward(sp_handle h, const float* x_dev, float* y_dev, int B, int S);
 
 /* Autoregressive generation (the paper quotes its LLM results in ms per token,
@@ -305,7 +338,9 @@ int sp_decode(sp_handle h, const float* x_dev, float* y_dev, void* kv_cache_dev,
 /* One training step's device work (Sec. 3.3): forward, loss =
  * mean((y - target)^2), backward with each layer's weights re-streamed in
  * reverse order, fp32 weight gradients written (overwrite, not accumulate) to
- * grad_host_blobs[l] (host, pinned, sp_layer_grad_bytes each) over d2h_stream.
+ * grad_host_blobs[l] (host, pinned -- checked, SP_ERR_NOT_PINNED otherwise: from pageable
+ * memory the gradient copies would block the host and lose their overlap with the backward
+ * pass -- sp_layer_grad_bytes each) over d2h_stream.
  * loss_dev: dev, 1 fp32.  dx_dev: dev fp32 [B,S,d] or NULL.  y_dev may be NULL.
  * The call returns once the step is enqueued.  At most one training step is in
  * flight per handle: a call first blocks the host until the previous step's
@@ -334,12 +369,17 @@ int sp_forward_backward(sp_handle h, const float* x_dev, const float* target_dev
 int sp_wait_gradient(sp_handle h, int layer);
 int sp_weights_updated(sp_handle h, int layer);
 
-/* Counters and (with SP_FLAG_TIMING) per-layer timings.  Synchronises the
- * handle's streams when timing is on. */
+/* Counters and (with SP_FLAG_TIMING) per-layer timings of the most recent call: how many bytes
+ * crossed the link, how long each layer's copy and compute took and how much of the copy time lay
+ * under compute -- the quantities the paper's evaluation reports per configuration (Sec. 4.2:
+ * memory used and time per step for each k, k').  Synchronises the handle's streams when a timing
+ * flag is on, otherwise returns at once. */
 int sp_get_stats(sp_handle h, sp_stats* out);
 
-/* Waits for the handle's streams, destroys its events, frees host bookkeeping.
- * Frees nothing the caller allocated. */
+/* Ends the streaming of this stack (Sec. 3.2.2: when execution is over the partitions' device
+ * copies are given up; here the slots simply go back to the caller with the arena).  Waits for the
+ * handle's streams, destroys its events, frees host bookkeeping.  Frees nothing the caller
+ * allocated; the host weight blobs were never written.  Works on a FAILED handle. */
 int sp_destroy(sp_handle h);
 
 const char* sp_last_error(sp_handle h);

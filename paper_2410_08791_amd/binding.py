@@ -29,6 +29,7 @@ SP_DECODER_SWIGLU_RMS, SP_ENCODER_GELU_LN = 0, 1
 SP_FLAG_TRAINING, SP_FLAG_TIMING, SP_FLAG_POISON, SP_FLAG_NO_OVERLAP, SP_FLAG_WRAP_PREFETCH = 1, 2, 4, 8, 16
 SP_FLAG_KERNEL_TIMING = 32
 SP_FLAG_KEEP_ACTIVATIONS = 64
+SP_FLAG_DELAY = 128
 SP_PIN_AUTO = -1
 SP_MAX_TRACE_LAYERS = 256
 EPI_BF16, EPI_RESID_F32, EPI_GELU_BF16, EPI_SWIGLU_BF16, EPI_F32 = 0, 1, 2, 3, 4
@@ -50,7 +51,8 @@ class sp_config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("resident_window_k", C.c_int32), ("prefetch_depth_p", C.c_int32),
                 ("gpu_budget_bytes", C.c_uint64), ("device_arena", C.c_void_p), ("compute_stream", C.c_void_p),
                 ("h2d_stream", C.c_void_p), ("d2h_stream", C.c_void_p), ("flags", C.c_uint32),
-                ("frozen_layers", C.c_int32), ("pinned_layers", C.c_int32), ("units_per_layer", C.c_int32)]
+                ("frozen_layers", C.c_int32), ("pinned_layers", C.c_int32), ("units_per_layer", C.c_int32),
+                ("delay_us", C.c_int32)]
 
 
 class sp_plan(C.Structure):
@@ -70,7 +72,8 @@ class sp_stats(C.Structure):
                 ("comp_end_ms", _F), ("copy_busy_ms", C.c_float), ("copy_hidden_ms", C.c_float),
                 ("compute_busy_ms", C.c_float), ("wall_ms", C.c_float),
                 ("big_gemm_launches", C.c_uint32), ("big_gemm_ms_sum", C.c_float),
-                ("big_gemm_m", C.c_int32), ("big_gemm_n", C.c_int32), ("big_gemm_k", C.c_int32)]
+                ("big_gemm_m", C.c_int32), ("big_gemm_n", C.c_int32), ("big_gemm_k", C.c_int32),
+                ("n_ops", C.c_int32)]
 
 
 class sp_sched_op(C.Structure):
@@ -272,7 +275,7 @@ class Engine:
     """Owns an sp_handle plus the torch-allocated arena and streams it runs on."""
 
     def __init__(self, desc, blobs, k, p, budget_bytes=None, budget_layers=None, flags=0, device="cuda:0",
-                 pinned=0, frozen=0, units=1):
+                 pinned=0, frozen=0, units=1, delay_us=0):
         import torch
         self.torch = torch
         self.desc = desc
@@ -296,7 +299,7 @@ class Engine:
         ptrs = (C.c_void_p * len(blobs))(*[b.data_ptr() for b in blobs])
         cfg = sp_config(C.sizeof(sp_config), k, p, self.budget_bytes, self.arena.data_ptr(),
                         self.compute.cuda_stream, self.h2d.cuda_stream,
-                        self.d2h.cuda_stream if training else None, flags, frozen, pinned, units)
+                        self.d2h.cuda_stream if training else None, flags, frozen, pinned, units, delay_us)
         self.handle = C.c_void_p()
         rc = sp_create(C.byref(self.handle), C.byref(desc), ptrs, C.byref(cfg))
         if rc != SP_OK:

@@ -25,6 +25,7 @@
 // at a time then cover all banks.  V rows: the 64-byte block (one 32-element tile of O^T)
 // ^ (row & 3) for 256-byte rows, ^ ((row >> 1) & 1) for 128, none for 192 -- the four key
 // rows of a transposing read fall into different bank groups.
+#include "sp_common.h"
 #include "sp_kernels.h"
 
 namespace {
@@ -305,13 +306,9 @@ hipError_t launch_fwd(hipStream_t st, dim3 grid, const bf16_t* qkv, bf16_t* o, f
                       const AttnShape& a, int paired, float sl2) {
     typedef AttnCfg<HD> C;
     constexpr int LDS = 2 * C::STAGE;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_kernel<HD>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimitOnce lds_limit;
+    hipError_t e = lds_limit.set(reinterpret_cast<const void*>(attn_fwd_kernel<HD>), LDS);
+    if (e != hipSuccess) return e;
     attn_fwd_kernel<HD><<<grid, 256, LDS, st>>>(qkv, o, lse, a.S, a.Hq, a.Hkv, a.ld_qkv, a.causal, paired, sl2);
     return hipGetLastError();
 }

@@ -13,6 +13,7 @@
 // in bf16 are the B operands of dV^T = dO^T P and dK^T = Q^T dS.  The A operands
 // K^T, dO^T, Q^T are read out of the same token-row LDS tiles the score products use,
 // through the transposing LDS read: no transposed copies exist in memory.
+#include "sp_common.h"
 #include "sp_kernels.h"
 
 namespace {

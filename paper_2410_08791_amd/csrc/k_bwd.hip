@@ -3,6 +3,7 @@
 // the gain gradient), fp32 -> bf16 copies, rowsum(dO * O).  No atomics: every
 // reduction has a fixed order, so gradients are bit-identical from run to run
 // and across window settings.
+#include "sp_common.h"
 #include "sp_kernels.h"
 
 namespace {

@@ -2,6 +2,7 @@
 // bias gradients by the same deterministic two-stage reduction as RMSNorm), GELU and its
 // backward as element-wise passes, and column sums over tokens for the bias gradients of
 // the linear maps.  All HBM-bound: each reads and writes its operands once.
+#include "sp_common.h"
 #include "sp_kernels.h"
 
 namespace {

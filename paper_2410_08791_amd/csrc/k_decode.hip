@@ -6,6 +6,7 @@
 // (eight positions per lane); V rows are read coalesced along the head dimension by the
 // weighted sum.  Both passes read every cached byte once: the kernel is HBM-bound,
 // 4 n Hkv hd bytes per sequence for n cached positions.
+#include "sp_common.h"
 #include "sp_kernels.h"
 
 namespace {
@@ -157,12 +158,10 @@ hipError_t launch_decode(hipStream_t st, const bf16_t* qkv, int ld_qkv, const bf
                          int ld_o, int B, int n, int max_len, int Hq, int Hkv) {
     const int n_pad = (n + 3) / 4 * 4;
     const size_t lds = ((size_t)n_pad + HD + 8 + 4 * 512 + 2048) * sizeof(float);
-    static size_t attr = 0;
-    if (lds > 48 * 1024 && lds > attr) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_attn_kernel<HD>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDecodeMaxLds);
+    static LdsLimitOnce lds_limit;
+    if (lds > 48 * 1024) {
+        hipError_t e = lds_limit.set(reinterpret_cast<const void*>(decode_attn_kernel<HD>), (int)kDecodeMaxLds);
         if (e != hipSuccess) return e;
-        attr = kDecodeMaxLds;
     }
     decode_attn_kernel<HD><<<dim3(Hq, B), 256, lds, st>>>(qkv, ld_qkv, kt, v, o, ld_o, n, n_pad, max_len, Hq, Hkv,
                                                           1.0f / sqrtf((float)HD));

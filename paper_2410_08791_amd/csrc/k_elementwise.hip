@@ -1,5 +1,6 @@
 // Small HBM-bound kernels: SwiGLU gate, copies and fills.  16-byte accesses,
 // grid-stride loops sized to a few waves per SIMD.
+#include "sp_common.h"
 #include "sp_kernels.h"
 
 namespace {
@@ -39,6 +40,12 @@ __global__ __launch_bounds__(EW_THREADS) void fill_u32_kernel(uint32_t* __restri
         dst[i] = v;
 }
 
+// One wave that idles for a bounded number of sleep instructions and exits: a delay on a
+// stream (debug mode).  s_sleep 64 parks the wave for 64 x 64 clocks, about 2 us.
+__global__ __launch_bounds__(64) void spin_kernel(int iters) {
+    for (int i = 0; i < iters; ++i) __builtin_amdgcn_s_sleep(64);
+}
+
 inline int ew_grid(size_t items) {
     size_t g = (items + EW_THREADS - 1) / EW_THREADS;
     const size_t cap = 256 * 16;  // 16 work-groups per CU
@@ -67,5 +74,12 @@ hipError_t spk_launch_copy_f32(hipStream_t st, const float* src, float* dst, siz
 hipError_t spk_launch_fill_u32(hipStream_t st, uint32_t* dst, uint32_t v, size_t n) {
     if (n == 0) return hipSuccess;
     fill_u32_kernel<<<ew_grid(n), EW_THREADS, 0, st>>>(dst, v, n);
+    return hipGetLastError();
+}
+
+hipError_t spk_launch_spin(hipStream_t st, int micros) {
+    if (micros <= 0) return hipSuccess;
+    const int iters = std::min(micros, SPK_SPIN_MAX_US) / 2 + 1;     // bounded: the kernel always ends
+    spin_kernel<<<1, 64, 0, st>>>(iters);
     return hipGetLastError();
 }

@@ -23,6 +23,7 @@
 // GEMMs) is staged as it lies in memory (LDS row = contraction index) and read
 // with the transposing LDS load of gfx950 (ds_read_b64_tr_b16), which hands each
 // lane four consecutive contraction elements of one operand row.
+#include "sp_common.h"
 #include "sp_kernels.h"
 
 namespace {
@@ -687,13 +688,9 @@ template <int BM, int BN, int EPI, int WAVES, int WM>
 hipError_t launch_dma(hipStream_t st, const GemmArgs& g) {
     constexpr int LDS = 2 * (BM + BN) * ROW_BYTES;
     constexpr int BN_OUT = (EPI == EPI_SWIGLU_BF16) ? BN / 2 : BN;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dma_kernel<BM, BN, EPI, WAVES, WM>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimitOnce lds_limit;
+    hipError_t e = lds_limit.set(reinterpret_cast<const void*>(gemm_dma_kernel<BM, BN, EPI, WAVES, WM>), LDS);
+    if (e != hipSuccess) return e;
     GemmDev d;
     d.A = g.A; d.W = g.W; d.C = g.C; d.R = g.R; d.bias = g.bias;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc; d.ldr = g.ldr;
@@ -709,14 +706,10 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& g) {
     constexpr int LDS = 2 * ((AFORM == OP_KMAJOR ? BM * ROW_BYTES : TLayout<BM>::BYTES) +
                              (WFORM == OP_KMAJOR ? BN * ROW_BYTES : TLayout<BN>::BYTES));
     constexpr int BN_OUT = (EPI == EPI_SWIGLU_BF16) ? BN / 2 : BN;
-    static bool attr_set = false;  // per instantiation; a benign race sets it twice at worst
+    static LdsLimitOnce lds_limit;   // one per instantiation
     auto kern = gemm_kernel<BM, BN, EPI, AFORM, WFORM, WAVES>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    hipError_t e = lds_limit.set(reinterpret_cast<const void*>(kern), LDS);
+    if (e != hipSuccess) return e;
     GemmDev d;
     d.A = g.A; d.W = g.W; d.C = g.C; d.R = g.R; d.bias = g.bias;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc; d.ldr = g.ldr;

@@ -12,6 +12,7 @@
 // token per tile.  The eight partial results are summed through LDS in wave order (deterministic)
 // by wave 0, which applies the epilogue.
 // N / 16 work-groups: 256 or more on every projection of the workloads.
+#include "sp_common.h"
 #include "sp_kernels.h"
 
 namespace {

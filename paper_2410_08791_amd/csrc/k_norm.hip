@@ -4,6 +4,7 @@
 // no barrier.  Launches of few rows: one work-group per row (second kernel below).
 // A lane issues all of its 16-byte loads of the row at once (VPL of them, the
 // row stays in registers), and the row is written once as bf16.
+#include "sp_common.h"
 #include "sp_kernels.h"
 
 namespace {

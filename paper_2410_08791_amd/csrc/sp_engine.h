@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <set>
 #include <string>
 #include <vector>
 
@@ -30,7 +31,18 @@ struct sp_engine {
     // layer_loaded / layer_done point at the most recent one for a layer.  With
     // SP_FLAG_TIMING the events carry timestamps and double as the per-layer trace,
     // so tracing adds no operation to either stream.
+    // The two pools are rings twice as long as the most operations one call can issue, and a
+    // call continues where the previous one stopped: an event that an earlier call recorded --
+    // the copy of a layer prefetched for this call, the compute of a slot's last user -- is not
+    // recorded again before the call after the next, so a wait on such a handle binds to the
+    // operation it was taken for.  A handle is dropped once its one consumer stream has waited
+    // on it (that stream is in order, so later operations on it need no second wait); the
+    // layers held for good therefore keep no handle into the pool.
     std::vector<hipEvent_t> copy_ev, comp_ev;
+    size_t copy_base = 0, comp_base = 0;                 // ring position of the current call's op 0
+    hipEvent_t copy_event(int i) const { return copy_ev[(copy_base + (size_t)i) % copy_ev.size()]; }
+    hipEvent_t comp_event(int i) const { return comp_ev[(comp_base + (size_t)i) % comp_ev.size()]; }
+    int max_copies = 0, max_computes = 0;                // per call
     std::vector<hipEvent_t> layer_loaded, layer_done;
     std::vector<int> layer_loaded_idx, layer_done_idx;   // op index within the current call, -1 = earlier call
     int ci = 0, mi = 0;                                  // ops issued by the current call
@@ -58,9 +70,12 @@ struct sp_engine {
     // counters
     uint64_t calls = 0, stats_h2d_copies = 0, stats_h2d_bytes = 0, stats_d2h_copies = 0, stats_d2h_bytes = 0;
     uint64_t call_h2d_copies = 0, call_h2d_bytes = 0;
-    // kernel selection (fixed at create; never depends on the window or the slot)
-    int gemm_tile = 0;
-    bool fuse_swiglu = true;
+    // debug delays (SP_FLAG_DELAY): upper bound per delay and the running draw counter
+    int delay_us = 0;
+    uint32_t delay_seq = 0;
+    // a call failed after it began to enqueue: residency bookkeeping is ahead of the streams
+    bool failed = false;
+    std::set<const void*> grad_pinned_ok;       // gradient blobs already verified as pinned host memory
     // training call context
     void* const* grad_blobs = nullptr;
     float* y_out = nullptr;

@@ -18,6 +18,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
+#include <unistd.h>
 
 #include <algorithm>
 #include <mutex>
@@ -95,6 +96,21 @@ static int throttle_after(sp_engine* e, unsigned packets) {
     return SP_OK;
 }
 
+// ---- debug delays (SP_FLAG_DELAY) -----------------------------------------------------
+// Before an operation is enqueued the host sleeps and the operation's stream idles, each for a
+// pseudo-random time up to delay_us (a fixed sequence per handle): the two streams and the host
+// drift against each other, which a fast run never does.  The idling kernel is bounded and exits.
+static int delay_point(sp_engine* e, hipStream_t stream) {
+    if (!e->delay_us) return SP_OK;
+    uint32_t r = (e->delay_seq++ + 1u) * 2654435761u;
+    r ^= r >> 15; r *= 2246822519u; r ^= r >> 13;
+    const int host_us = (int)(r % (uint32_t)(e->delay_us + 1));
+    const int dev_us = (int)((r >> 11) % (uint32_t)(e->delay_us + 1));
+    if (r & 1) SP_HIP(e, spk_launch_spin(stream, dev_us));
+    if (r & 2) usleep((useconds_t)host_us);
+    return SP_OK;
+}
+
 // ---- the sink that enqueues real stream work -------------------------------------
 struct HipSink : SchedSink {
     sp_engine* e;
@@ -108,7 +124,9 @@ struct HipSink : SchedSink {
 
     int copy(int layer, int slot, int wait_layer) override {
         hipStream_t cs = e->h2d;
-        if (e->ci >= (int)e->copy_ev.size()) return sp_fail(e, SP_ERR_STATE, "copy event pool exhausted");
+        if (e->ci >= e->max_copies) return sp_fail(e, SP_ERR_STATE, "copy event pool exhausted");
+        int rc = delay_point(e, cs);
+        if (rc != SP_OK) return rc;
         int dep = -1;
         if (e->flags & SP_FLAG_NO_OVERLAP) {
             // Naive comparator: a copy starts only after everything enqueued for compute.
@@ -118,6 +136,7 @@ struct HipSink : SchedSink {
         } else if (wait_layer >= 0 && e->layer_done[wait_layer]) {
             SP_HIP(e, hipStreamWaitEvent(cs, e->layer_done[wait_layer], 0));
             dep = e->layer_done_idx[wait_layer];
+            e->layer_done[wait_layer] = nullptr;     // the copy stream is in order: one wait serves every later copy
         }
         // `layer` counts units: part q of layer `layer / units`
         const int part = layer % e->units;
@@ -129,7 +148,7 @@ struct HipSink : SchedSink {
         }
         SP_HIP(e, hipMemcpyAsync(dst, static_cast<const unsigned char*>(e->blobs[layer / e->units]) + e->unit_off[part],
                                  nbytes, hipMemcpyHostToDevice, cs));
-        hipEvent_t ev = e->copy_ev[e->ci];
+        hipEvent_t ev = e->copy_event(e->ci);
         SP_HIP(e, hipEventRecord(ev, cs));
         e->layer_loaded[layer] = ev;
         e->layer_loaded_idx[layer] = e->ci;
@@ -145,9 +164,10 @@ struct HipSink : SchedSink {
 
     int compute(int layer, int slot, int dir, bool /*fresh*/) override {
         hipStream_t st = e->compute;
-        if (e->mi >= (int)e->comp_ev.size()) return sp_fail(e, SP_ERR_STATE, "compute event pool exhausted");
+        if (e->mi >= e->max_computes) return sp_fail(e, SP_ERR_STATE, "compute event pool exhausted");
         int rc = throttle_before(e);
         if (rc != SP_OK) return rc;
+        if ((rc = delay_point(e, st)) != SP_OK) return rc;
         int dep = -1;
         if (e->flags & SP_FLAG_NO_OVERLAP) {
             // Naive comparator: compute starts only after every copy enqueued so far.
@@ -157,6 +177,7 @@ struct HipSink : SchedSink {
         } else if (e->layer_loaded[layer]) {
             SP_HIP(e, hipStreamWaitEvent(st, e->layer_loaded[layer], 0));
             dep = e->layer_loaded_idx[layer];
+            e->layer_loaded[layer] = nullptr;        // the compute stream is in order: later uses need no second wait
         }
         // where byte 0 of the layer blob would lie (a unit slot holds only its part of it: the
         // tensors the part's kernels touch all lie inside the slot)
@@ -175,7 +196,7 @@ struct HipSink : SchedSink {
         else
             rc = sp_layer_backward(e, layer, w, B, S);
         if (rc != SP_OK) return rc;
-        hipEvent_t ev = e->comp_ev[e->mi];
+        hipEvent_t ev = e->comp_event(e->mi);
         SP_HIP(e, hipEventRecord(ev, st));
         e->layer_done[layer] = ev;
         e->layer_done_idx[layer] = e->mi;
@@ -197,7 +218,6 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
     bf16_t* a = e->wsp<bf16_t>(e->ws.a);
     bf16_t* qkv = e->wsp<bf16_t>(e->ws.qkv);
     bf16_t* o = e->wsp<bf16_t>(e->ws.o);
-    bf16_t* gu = e->wsp<bf16_t>(e->ws.gu);
     bf16_t* z = e->wsp<bf16_t>(e->ws.z);
     const bool dec = d.arch == SP_DECODER_SWIGLU_RMS;
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
@@ -208,7 +228,7 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
         SP_HIP(e, spk_launch_norm(st, h, W(dec ? SP_T_G1 : SP_T_LN1_G), dec ? nullptr : W(SP_T_LN1_B), a, T, dm, d.norm_eps));
         // b2: qkv = a Wqkv^T (+ b)
         g = GemmArgs{a, dm, OP_KMAJOR, W(dec ? SP_T_WQKV : SP_T_E_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0,
-                     dec ? nullptr : W(SP_T_BQKV), T, nqkv, dm, e->gemm_tile};
+                     dec ? nullptr : W(SP_T_BQKV), T, nqkv, dm, 0};
         SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
         // b3: attention.  With a cache the new keys/values are stored first; a decode step then
         // attends its single query per sequence to the cached positions 0..pos.
@@ -223,7 +243,7 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
         }
         // b4: h += o Wo^T (+ b)
         g = GemmArgs{o, nq, OP_KMAJOR, W(dec ? SP_T_WO : SP_T_E_WO), nq, OP_KMAJOR, h, dm, h, dm,
-                     dec ? nullptr : W(SP_T_BO), T, dm, nq, e->gemm_tile};
+                     dec ? nullptr : W(SP_T_BO), T, dm, nq, 0};
         SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     }
     if (parts & 2) {
@@ -239,18 +259,11 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
         }
         if (dec) {
             // b6+b7: z = silu(a Wg^T) * (a Wu^T), gate applied in the GEMM epilogue
-            if (e->fuse_swiglu) {
-                g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, z, f, nullptr, 0, nullptr, T, f, dm, e->gemm_tile};
-                SP_HIP(e, spk_launch_gemm(st, EPI_SWIGLU_BF16, g));
-            } else {
-                g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, gu, 2 * f, nullptr, 0, nullptr, T, 2 * f, dm,
-                             e->gemm_tile};
-                SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
-            }
+            g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, z, f, nullptr, 0, nullptr, T, f, dm, 0};
+            SP_HIP(e, spk_launch_gemm(st, EPI_SWIGLU_BF16, g));
             if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
-            if (!e->fuse_swiglu) SP_HIP(e, spk_launch_swiglu(st, gu, z, T, f));
         } else {
-            g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_W1), dm, OP_KMAJOR, z, f, nullptr, 0, W(SP_T_B1), T, f, dm, e->gemm_tile};
+            g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_W1), dm, OP_KMAJOR, z, f, nullptr, 0, W(SP_T_B1), T, f, dm, 0};
             SP_HIP(e, spk_launch_gemm(st, EPI_GELU_BF16, g));
             if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
         }
@@ -258,10 +271,10 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
     if (parts & 4) {
         if (dec) {
             // b8: h += z Wd^T
-            g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_WD), f, OP_KMAJOR, h, dm, h, dm, nullptr, T, dm, f, e->gemm_tile};
+            g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_WD), f, OP_KMAJOR, h, dm, h, dm, nullptr, T, dm, f, 0};
             SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
         } else {
-            g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_W2), f, OP_KMAJOR, h, dm, h, dm, W(SP_T_B2), T, dm, f, e->gemm_tile};
+            g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_W2), f, OP_KMAJOR, h, dm, h, dm, W(SP_T_B2), T, dm, f, 0};
             SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
         }
     }
@@ -296,6 +309,8 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     const int units = cfg->units_per_layer ? cfg->units_per_layer : 1;
     if (units != 1 && units != 3) return fail(nullptr, SP_ERR_INVALID_ARG, "units_per_layer must be 0, 1 or 3");
     if (units != 1 && training) return fail(nullptr, SP_ERR_INVALID_ARG, "units_per_layer = 3 is for forward-only handles");
+    if ((cfg->flags & SP_FLAG_DELAY) && (cfg->delay_us < 0 || cfg->delay_us > SPK_SPIN_MAX_US))
+        return fail(nullptr, SP_ERR_INVALID_ARG, "delay_us must be in 0..%d", SPK_SPIN_MAX_US);
     sp_plan plan;
     int rc = make_plan(desc, units, cfg->resident_window_k, cfg->prefetch_depth_p, cfg->pinned_layers,
                        cfg->gpu_budget_bytes, mode, &plan);
@@ -342,13 +357,16 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     e->blobs.assign(blobs, blobs + desc->n_layers);
     const int L = e->n_units;      // what the scheduler calls a layer: a unit
     const bool timing = cfg->flags & SP_FLAG_TIMING;
-    // a call issues at most 2L + n_slots copies and 2L computes (forward + backward)
-    e->copy_ev.assign((training ? 2 : 1) * L + plan.n_slots + 1, nullptr);
-    e->comp_ev.assign((training ? 2 : 1) * L + 1, nullptr);
-    e->tr_copy_layer.assign(e->copy_ev.size(), -1);
-    e->tr_copy_dep.assign(e->copy_ev.size(), -1);
-    e->tr_comp_layer.assign(e->comp_ev.size(), -1);
-    e->tr_comp_dep.assign(e->comp_ev.size(), -1);
+    // a call issues at most 2L + n_slots copies and 2L computes (forward + backward); the event
+    // rings hold two calls' worth
+    e->max_copies = (training ? 2 : 1) * L + plan.n_slots + 1;
+    e->max_computes = (training ? 2 : 1) * L + 1;
+    e->copy_ev.assign(2 * (size_t)e->max_copies, nullptr);
+    e->comp_ev.assign(2 * (size_t)e->max_computes, nullptr);
+    e->tr_copy_layer.assign(e->max_copies, -1);
+    e->tr_copy_dep.assign(e->max_copies, -1);
+    e->tr_comp_layer.assign(e->max_computes, -1);
+    e->tr_comp_dep.assign(e->max_computes, -1);
     e->layer_loaded.assign(L, nullptr);
     e->layer_done.assign(L, nullptr);
     e->layer_loaded_idx.assign(L, -1);
@@ -390,10 +408,7 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     }
     const bool naive = cfg->flags & SP_FLAG_NO_OVERLAP;
     e->sched.reset(L, plan.n_slots, naive ? plan.n_slots - plan.n_pinned : plan.p_eff, plan.n_pinned);
-    e->fuse_swiglu = true;
-    e->gemm_tile = 0;
-    if (const char* t = getenv("SP_GEMM_TILE")) e->gemm_tile = atoi(t);
-    if (const char* t = getenv("SP_FUSE_SWIGLU")) e->fuse_swiglu = atoi(t) != 0;
+    if (cfg->flags & SP_FLAG_DELAY) e->delay_us = cfg->delay_us ? cfg->delay_us : 200;
     if (training) {
         // padded token rows of the GEMM-operand buffers must read as zero
         hipError_t fe = spk_launch_fill_u32(e->compute, reinterpret_cast<uint32_t*>(e->arena), 0u, e->ws.total / 4);
@@ -411,9 +426,21 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
     return SP_OK;
 }
 
+// A pass that fails after it began leaves the scheduler's residency ahead of what the streams
+// hold (a layer recorded as resident whose copy was never issued): the handle refuses further
+// passes.  The first error's text stays in front for sp_last_error.
+static int mark_failed(sp_engine* e, int rc) {
+    if (rc != SP_OK && !e->failed) {
+        e->failed = true;
+        e->error = "handle FAILED mid-pass (only sp_destroy is left): " + e->error;
+    }
+    return rc;
+}
+
 static int check_call(sp_engine* e, int B, int S) {
     if (!e) return SP_ERR_INVALID_ARG;
     if (!is_live(e)) return fail(nullptr, SP_ERR_STATE, "handle is not live (destroyed or never created)");
+    if (e->failed) return SP_ERR_STATE;          // e->error keeps the first failure's text
     if (B < 1 || S < 1 || B > e->desc.max_batch || S > e->desc.max_seq)
         return fail(e, SP_ERR_SHAPE, "B=%d S=%d outside 1..%d x 1..%d", B, S, e->desc.max_batch, e->desc.max_seq);
     return SP_OK;
@@ -421,10 +448,42 @@ static int check_call(sp_engine* e, int B, int S) {
 
 static int begin_call(sp_engine* e) {
     e->call_h2d_copies = e->call_h2d_bytes = 0;
+    e->copy_base = (e->copy_base + (size_t)e->ci) % e->copy_ev.size();
+    e->comp_base = (e->comp_base + (size_t)e->mi) % e->comp_ev.size();
     e->ci = e->mi = 0;
     std::fill(e->layer_loaded_idx.begin(), e->layer_loaded_idx.end(), -1);
     std::fill(e->layer_done_idx.begin(), e->layer_done_idx.end(), -1);
     if (e->flags & SP_FLAG_TIMING) SP_HIP(e, hipEventRecord(e->t0, e->compute));
+    return SP_OK;
+}
+
+// bytes of one layer's cache: keys and values, bf16
+static size_t kv_layer_bytes(const sp_stack_desc& d, int batch, int max_len) {
+    return (size_t)2 * batch * d.n_kv_heads * d.head_dim * max_len * sizeof(bf16_t);
+}
+
+// One forward pass, arguments already checked: from here on a failure leaves the handle FAILED.
+static int enqueue_forward(sp_engine* e, const float* x_dev, float* y_dev, int B, int S, void* kv_cache_dev,
+                           int max_len, int pos) {
+    int rc;
+    if ((rc = begin_call(e)) != SP_OK) return rc;
+    SP_HIP(e, spk_launch_copy_f32(e->compute, x_dev, y_dev, (size_t)B * S * e->desc.d_model));
+    HipSink sink(e);
+    sink.hbuf = y_dev;
+    sink.B = B;
+    sink.S = S;
+    if (kv_cache_dev) {
+        sink.kv_cache = static_cast<unsigned char*>(kv_cache_dev);
+        sink.kv_layer_bytes = kv_layer_bytes(e->desc, B, max_len);
+        sink.kv_max_len = max_len;
+        sink.kv_pos = pos;
+    }
+    const bool wrap = (e->flags & SP_FLAG_WRAP_PREFETCH) && !(e->flags & SP_FLAG_TRAINING);
+    if ((rc = e->sched.run_pass(+1, wrap, sink)) != SP_OK) {
+        if (e->error.empty()) sp_fail(e, rc, "scheduler refused the pass");
+        return rc;
+    }
+    e->calls++;
     return SP_OK;
 }
 
@@ -433,22 +492,7 @@ extern "C" int sp_forward(sp_handle e, const float* x_dev, float* y_dev, int B, 
     if (rc != SP_OK) return rc;
     if (!x_dev || !y_dev) return fail(e, SP_ERR_INVALID_ARG, "x_dev / y_dev is NULL");
     if (((uintptr_t)x_dev | (uintptr_t)y_dev) & 15) return fail(e, SP_ERR_INVALID_ARG, "x_dev / y_dev must be 16-byte aligned");
-    if ((rc = begin_call(e)) != SP_OK) return rc;
-    SP_HIP(e, spk_launch_copy_f32(e->compute, x_dev, y_dev, (size_t)B * S * e->desc.d_model));
-    HipSink sink(e);
-    sink.hbuf = y_dev;
-    sink.B = B;
-    sink.S = S;
-    const bool wrap = (e->flags & SP_FLAG_WRAP_PREFETCH) && !(e->flags & SP_FLAG_TRAINING);
-    rc = e->sched.run_pass(+1, wrap, sink);
-    if (rc != SP_OK) return rc;
-    e->calls++;
-    return SP_OK;
-}
-
-// bytes of one layer's cache: keys and values, bf16
-static size_t kv_layer_bytes(const sp_stack_desc& d, int batch, int max_len) {
-    return (size_t)2 * batch * d.n_kv_heads * d.head_dim * max_len * sizeof(bf16_t);
+    return mark_failed(e, enqueue_forward(e, x_dev, y_dev, B, S, nullptr, 0, -1));
 }
 
 extern "C" size_t sp_kv_cache_bytes(const sp_stack_desc* desc, int batch, int max_len) {
@@ -472,21 +516,7 @@ static int cached_forward(sp_engine* e, const float* x_dev, float* y_dev, void* 
         return fail(e, SP_ERR_SHAPE, "max_len=%d must be a multiple of 8 in 8..%d", max_len, kDecodeMaxLen);
     const int first = pos >= 0 ? pos : 0;
     if (first + S > max_len) return fail(e, SP_ERR_SHAPE, "positions %d..%d exceed max_len=%d", first, first + S - 1, max_len);
-    int rc;
-    if ((rc = begin_call(e)) != SP_OK) return rc;
-    SP_HIP(e, spk_launch_copy_f32(e->compute, x_dev, y_dev, (size_t)B * S * d.d_model));
-    HipSink sink(e);
-    sink.hbuf = y_dev;
-    sink.B = B;
-    sink.S = S;
-    sink.kv_cache = static_cast<unsigned char*>(kv_cache_dev);
-    sink.kv_layer_bytes = kv_layer_bytes(d, B, max_len);
-    sink.kv_max_len = max_len;
-    sink.kv_pos = pos;
-    rc = e->sched.run_pass(+1, (e->flags & SP_FLAG_WRAP_PREFETCH) != 0, sink);
-    if (rc != SP_OK) return rc;
-    e->calls++;
-    return SP_OK;
+    return mark_failed(e, enqueue_forward(e, x_dev, y_dev, B, S, kv_cache_dev, max_len, pos));
 }
 
 extern "C" int sp_prefill(sp_handle e, const float* x_dev, float* y_dev, void* kv_cache_dev, int B, int S,
@@ -504,6 +534,9 @@ extern "C" int sp_decode(sp_handle e, const float* x_dev, float* y_dev, void* kv
     return cached_forward(e, x_dev, y_dev, kv_cache_dev, B, 1, pos, max_len);
 }
 
+static int enqueue_training_step(sp_engine* e, const float* x_dev, const float* target_dev, float* y_dev,
+                                 float* loss_dev, float* dx_dev, void* const* grad_host_blobs, int B, int S);
+
 extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float* target_dev, float* y_dev,
                                    float* loss_dev, float* dx_dev, void* const* grad_host_blobs, int B, int S) {
     int rc = check_call(e, B, S);
@@ -512,8 +545,24 @@ extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float*
     if (!x_dev || !target_dev || !loss_dev || !grad_host_blobs) return fail(e, SP_ERR_INVALID_ARG, "NULL argument");
     if (((uintptr_t)x_dev | (uintptr_t)target_dev | (uintptr_t)y_dev | (uintptr_t)dx_dev) & 15)
         return fail(e, SP_ERR_INVALID_ARG, "device tensors must be 16-byte aligned");
-    for (int l = 0; l < e->desc.n_layers; ++l)
-        if (!grad_host_blobs[l]) return fail(e, SP_ERR_INVALID_ARG, "grad_host_blobs[%d] is NULL", l);
+    for (int l = e->frozen; l < e->desc.n_layers; ++l) {
+        const void* gb = grad_host_blobs[l];
+        if (!gb) return fail(e, SP_ERR_INVALID_ARG, "grad_host_blobs[%d] is NULL", l);
+        if (e->grad_pinned_ok.count(gb)) continue;       // verified by an earlier step
+        hipPointerAttribute_t at;
+        hipError_t pe = hipPointerGetAttributes(&at, gb);
+        if (pe != hipSuccess || at.type != hipMemoryTypeHost) {
+            (void)hipGetLastError();
+            return fail(e, SP_ERR_NOT_PINNED, "grad_host_blobs[%d] is not pinned host memory", l);
+        }
+        e->grad_pinned_ok.insert(gb);
+    }
+    return mark_failed(e, enqueue_training_step(e, x_dev, target_dev, y_dev, loss_dev, dx_dev, grad_host_blobs, B, S));
+}
+
+static int enqueue_training_step(sp_engine* e, const float* x_dev, const float* target_dev, float* y_dev,
+                                 float* loss_dev, float* dx_dev, void* const* grad_host_blobs, int B, int S) {
+    int rc;
     // One training pass in flight: the host waits here until the previous pass has
     // delivered its last gradient.  Its consumer (the host-side optimizer) needs that
     // point anyway, and copies enqueued more than a pass ahead were measured to drop
@@ -548,6 +597,7 @@ extern "C" int sp_forward_backward(sp_handle e, const float* x_dev, const float*
 extern "C" int sp_wait_gradient(sp_handle e, int layer) {
     if (!e) return SP_ERR_INVALID_ARG;
     if (!is_live(e)) return fail(nullptr, SP_ERR_STATE, "handle is not live (destroyed or never created)");
+    if (e->failed) return SP_ERR_STATE;
     if (!(e->flags & SP_FLAG_TRAINING)) return fail(e, SP_ERR_STATE, "handle was created without SP_FLAG_TRAINING");
     if (layer < 0 || layer >= e->desc.n_layers) return fail(e, SP_ERR_INVALID_ARG, "layer %d out of range", layer);
     if (!e->grad_sent[layer])
@@ -559,6 +609,7 @@ extern "C" int sp_wait_gradient(sp_handle e, int layer) {
 extern "C" int sp_weights_updated(sp_handle e, int layer) {
     if (!e) return SP_ERR_INVALID_ARG;
     if (!is_live(e)) return fail(nullptr, SP_ERR_STATE, "handle is not live (destroyed or never created)");
+    if (e->failed) return SP_ERR_STATE;
     const int L = e->desc.n_layers;
     if (layer < -1 || layer >= L) return fail(e, SP_ERR_INVALID_ARG, "layer %d out of range", layer);
     const int lo = layer < 0 ? 0 : layer, hi = layer < 0 ? L : layer + 1;
@@ -599,8 +650,8 @@ extern "C" int sp_get_stats(sp_handle e, sp_stats* out) {
     // begins when its stream's previous op has ended and its dependency is met.
     const int nc = e->ci, nm = e->mi;
     std::vector<float> tc(nc), tm(nm), cb(nc), mb(nm);
-    for (int i = 0; i < nc; ++i) SP_HIP(e, hipEventElapsedTime(&tc[i], e->t0, e->copy_ev[i]));
-    for (int j = 0; j < nm; ++j) SP_HIP(e, hipEventElapsedTime(&tm[j], e->t0, e->comp_ev[j]));
+    for (int i = 0; i < nc; ++i) SP_HIP(e, hipEventElapsedTime(&tc[i], e->t0, e->copy_event(i)));
+    for (int j = 0; j < nm; ++j) SP_HIP(e, hipEventElapsedTime(&tm[j], e->t0, e->comp_event(j)));
     for (int i = 0; i < nc; ++i) {
         float b = i > 0 ? tc[i - 1] : std::min(0.f, tc[i]);
         const int dep = e->tr_copy_dep[i];
@@ -617,6 +668,7 @@ extern "C" int sp_get_stats(sp_handle e, sp_stats* out) {
     float tmin = 1e30f, tmax = -1e30f;
     const int n = std::min(nm, (int)SP_MAX_TRACE_LAYERS);
     out->n_timed = n;
+    out->n_ops = nm;
     for (int j = 0; j < nm; ++j) {
         comp[j] = {mb[j], tm[j]};
         out->compute_busy_ms += tm[j] - mb[j];

@@ -22,6 +22,8 @@ int validate_desc(const sp_stack_desc* d, const char** why) {
     else if (d->head_dim != 64 && d->head_dim != 80 && d->head_dim != 128) w = "head_dim must be 64, 80 or 128";
     else if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_q_heads % d->n_kv_heads) w = "n_kv_heads must divide n_q_heads";
     else if ((d->n_q_heads * d->head_dim) % 64) w = "n_q_heads*head_dim must be a multiple of 64";
+    // the fused q/k/v width is a contraction length of the backward pass (da = dqkv Wqkv)
+    else if (((d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim) % 64) w = "(n_q_heads + 2 n_kv_heads)*head_dim must be a multiple of 64";
     else if (d->d_ffn < 64 || d->d_ffn % 64) w = "d_ffn must be a multiple of 64";
     else if (d->max_batch < 1 || d->max_seq < 1) w = "max_batch/max_seq < 1";
     else if ((int64_t)d->max_batch * d->max_seq > (1 << 24)) w = "max_batch*max_seq too large";
@@ -78,7 +80,9 @@ void make_workspace(const sp_stack_desc* d, const Layout& lay, int training, Wor
     ws->a = take(Tp * dm * 2);
     ws->qkv = take(Tp * nqkv * 2);
     ws->o = take(Tp * nq * 2);
-    ws->gu = take(Tp * (d->arch == SP_DECODER_SWIGLU_RMS ? 2 * f : f) * 2);
+    // [gate | up] resp. the MLP pre-activation: only the backward needs them in memory (the
+    // forward applies SwiGLU / GELU in the producing GEMM's epilogue and stores z alone)
+    ws->gu = training ? take(Tp * (d->arch == SP_DECODER_SWIGLU_RMS ? 2 * f : f) * 2) : off;
     ws->z = take(Tp * f * 2);
     if (training) {
         ws->m = take(Tp * dm * 2);

@@ -1,10 +1,29 @@
 // Host-side launchers of the per-layer kernels (internal to the library).
 // Every launcher validates what its kernel and grid assume, enqueues on `st`
 // and returns the launch status; none synchronises or allocates.
+// Host declarations only: the device helpers live in sp_common.h, which the kernel sources
+// include themselves, so that the engine's host code builds against the HIP runtime API alone.
 #pragma once
-#include "sp_common.h"
-#include "sp_limits.h"
+#include <hip/hip_runtime.h>
+
 #include <algorithm>
+#include <mutex>
+
+#include "sp_limits.h"
+#include "sp_types.h"
+
+// Raises a kernel's dynamic-LDS limit once per process; safe when two host threads launch the
+// same kernel for the first time together.  Every call returns the status of that one attempt.
+struct LdsLimitOnce {
+    std::once_flag flag;
+    hipError_t status = hipSuccess;
+    hipError_t set(const void* kernel, int bytes) {
+        std::call_once(flag, [&] {
+            status = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        });
+        return status;
+    }
+};
 
 enum GemmEpilogue {
     EPI_BF16 = 0,        // C bf16 [M,N]  = acc (+ bias)
@@ -71,6 +90,8 @@ hipError_t spk_launch_decode_attention(hipStream_t st, const bf16_t* qkv, int ld
 
 hipError_t spk_launch_copy_f32(hipStream_t st, const float* src, float* dst, size_t n);
 hipError_t spk_launch_fill_u32(hipStream_t st, uint32_t* dst, uint32_t v, size_t n);
+// A one-wave kernel that idles for about `micros` microseconds (at most SPK_SPIN_MAX_US) and exits.
+hipError_t spk_launch_spin(hipStream_t st, int micros);
 
 // ---- backward ---------------------------------------------------------------------
 // loss = mean((y-t)^2) over n elements; dy = 2(y-t)/n as fp32 and as bf16.  part: SPK_MSE_PARTS floats.

@@ -44,13 +44,13 @@ int decoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
     GemmArgs g;
     SP_HIP(e, spk_launch_norm(st, b.h_in, W(SP_T_G1), nullptr, a, T, dm, d.norm_eps));
-    g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0, nullptr, T, nqkv, dm, e->gemm_tile};
+    g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0, nullptr, T, nqkv, dm, 0};
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
     SP_HIP(e, spk_launch_attention(st, qkv, o, b.lse, as));
-    g = GemmArgs{o, nq, OP_KMAJOR, W(SP_T_WO), nq, OP_KMAJOR, b.h_mid, dm, b.h_in, dm, nullptr, T, dm, nq, e->gemm_tile};
+    g = GemmArgs{o, nq, OP_KMAJOR, W(SP_T_WO), nq, OP_KMAJOR, b.h_mid, dm, b.h_in, dm, nullptr, T, dm, nq, 0};
     SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_G2), nullptr, m, T, dm, d.norm_eps));
-    g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, gu, 2 * f, nullptr, 0, nullptr, T, 2 * f, dm, e->gemm_tile};
+    g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, gu, 2 * f, nullptr, 0, nullptr, T, 2 * f, dm, 0};
     // every 4th launch of the largest GEMM is bracketed: the two event records cost a gap
     // on the stream, which on a compute-bound stack would show in the step time
     const bool kt = !e->kt_begin.empty() && (e->kt_seen++ % 4 == 0);
@@ -63,7 +63,7 @@ int decoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
     if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
     SP_HIP(e, spk_launch_swiglu(st, gu, z, T, f));
     if (b.h_out) {
-        g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_WD), f, OP_KMAJOR, b.h_out, dm, b.h_mid, dm, nullptr, T, dm, f, e->gemm_tile};
+        g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_WD), f, OP_KMAJOR, b.h_out, dm, b.h_mid, dm, nullptr, T, dm, f, 0};
         SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     }
     return SP_OK;
@@ -83,13 +83,13 @@ int encoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
     GemmArgs g;
     SP_HIP(e, spk_launch_norm(st, b.h_in, W(SP_T_LN1_G), W(SP_T_LN1_B), a, T, dm, d.norm_eps));
-    g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_E_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0, W(SP_T_BQKV), T, nqkv, dm, e->gemm_tile};
+    g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_E_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0, W(SP_T_BQKV), T, nqkv, dm, 0};
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
     SP_HIP(e, spk_launch_attention(st, qkv, o, b.lse, as));
-    g = GemmArgs{o, nq, OP_KMAJOR, W(SP_T_E_WO), nq, OP_KMAJOR, b.h_mid, dm, b.h_in, dm, W(SP_T_BO), T, dm, nq, e->gemm_tile};
+    g = GemmArgs{o, nq, OP_KMAJOR, W(SP_T_E_WO), nq, OP_KMAJOR, b.h_mid, dm, b.h_in, dm, W(SP_T_BO), T, dm, nq, 0};
     SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_LN2_G), W(SP_T_LN2_B), m, T, dm, d.norm_eps));
-    g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_W1), dm, OP_KMAJOR, u, f, nullptr, 0, W(SP_T_B1), T, f, dm, e->gemm_tile};
+    g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_W1), dm, OP_KMAJOR, u, f, nullptr, 0, W(SP_T_B1), T, f, dm, 0};
     const bool kt = !e->kt_begin.empty() && (e->kt_seen++ % 4 == 0);
     const size_t kti = kt ? e->kt_count % e->kt_begin.size() : 0;
     if (kt) {
@@ -100,7 +100,7 @@ int encoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
     if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
     SP_HIP(e, spk_launch_gelu(st, u, z, (size_t)T * f));
     if (b.h_out) {
-        g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_W2), f, OP_KMAJOR, b.h_out, dm, b.h_mid, dm, W(SP_T_B2), T, dm, f, e->gemm_tile};
+        g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_W2), f, OP_KMAJOR, b.h_out, dm, b.h_mid, dm, W(SP_T_B2), T, dm, f, 0};
         SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
     }
     return SP_OK;
@@ -214,18 +214,18 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     // ---- FFN.  dh is dL/d(layer output); dhb its bf16 copy.
     if (dec) {
         // dWd[d,f] = dh^T z       (contraction over tokens: both operands transposed on the way in)
-        g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_WD), f, nullptr, 0, nullptr, dm, f, Tp, e->gemm_tile};
+        g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_WD), f, nullptr, 0, nullptr, dm, f, Tp, 0};
         if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
         // dz[T,f] = dh Wd         (Wd is [d,f]: its row index f is contiguous)
-        g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_WD), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, e->gemm_tile};
+        g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_WD), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, 0};
         SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
         // [dg | du] in place over [g | u]
         SP_HIP(e, spk_launch_swiglu_bwd(st, dz, gu, T, f));
         // dWgu[2f,d] = dgu^T m
-        g = GemmArgs{gu, 2 * f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_WGU), dm, nullptr, 0, nullptr, 2 * f, dm, Tp, e->gemm_tile};
+        g = GemmArgs{gu, 2 * f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_WGU), dm, nullptr, 0, nullptr, 2 * f, dm, Tp, 0};
         if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
         // dm[T,d] = dgu Wgu  (fp32)
-        g = GemmArgs{gu, 2 * f, OP_KMAJOR, W(SP_T_WGU), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, 2 * f, e->gemm_tile};
+        g = GemmArgs{gu, 2 * f, OP_KMAJOR, W(SP_T_WGU), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, 2 * f, 0};
         SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
         // second norm: dh += d(rmsnorm)(h1) applied to dm; dg2
         SP_HIP(e, spk_launch_rmsnorm_bwd(st, da, h1, W(SP_T_G2), dh, dhb, part, G(SP_T_G2), T, dm, d.norm_eps));
@@ -233,19 +233,19 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
         bf16_t* u = gu;                     // pre-activation of the MLP, [T, f]
         if ((rc = bias_grad(dhb, dm, SP_T_B2)) != SP_OK) return rc;
         // dW2[d,f] = dh^T z
-        g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_W2), f, nullptr, 0, nullptr, dm, f, Tp, e->gemm_tile};
+        g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_W2), f, nullptr, 0, nullptr, dm, f, Tp, 0};
         if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
         // dz[T,f] = dh W2
-        g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_W2), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, e->gemm_tile};
+        g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_W2), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, 0};
         SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
         // du = dz gelu'(u), in place over u
         SP_HIP(e, spk_launch_gelu_bwd(st, dz, u, (size_t)T * f));
         if ((rc = bias_grad(u, f, SP_T_B1)) != SP_OK) return rc;
         // dW1[f,d] = du^T m
-        g = GemmArgs{u, f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_W1), dm, nullptr, 0, nullptr, f, dm, Tp, e->gemm_tile};
+        g = GemmArgs{u, f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_W1), dm, nullptr, 0, nullptr, f, dm, Tp, 0};
         if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
         // dm[T,d] = du W1  (fp32)
-        g = GemmArgs{u, f, OP_KMAJOR, W(SP_T_W1), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, f, e->gemm_tile};
+        g = GemmArgs{u, f, OP_KMAJOR, W(SP_T_W1), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, f, 0};
         SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
         // second norm: dh += d(layernorm)(h1) applied to dm; its gain and bias gradients
         SP_HIP(e, spk_launch_layernorm_bwd(st, da, h1, W(SP_T_LN2_G), dh, dhb, part, G(SP_T_LN2_G), G(SP_T_LN2_B), T,
@@ -255,20 +255,20 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     // ---- attention block.  dh is now dL/dh1.
     if (!dec && (rc = bias_grad(dhb, dm, SP_T_BO)) != SP_OK) return rc;
     // dWo[d,nq] = dh^T o
-    g = GemmArgs{dhb, dm, OP_RMAJOR, o, nq, OP_RMAJOR, G(t_wo), nq, nullptr, 0, nullptr, dm, nq, Tp, e->gemm_tile};
+    g = GemmArgs{dhb, dm, OP_RMAJOR, o, nq, OP_RMAJOR, G(t_wo), nq, nullptr, 0, nullptr, dm, nq, Tp, 0};
     if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
     // do[T,nq] = dh Wo
-    g = GemmArgs{dhb, dm, OP_KMAJOR, W(t_wo), nq, OP_RMAJOR, dob, nq, nullptr, 0, nullptr, T, nq, dm, e->gemm_tile};
+    g = GemmArgs{dhb, dm, OP_KMAJOR, W(t_wo), nq, OP_RMAJOR, dob, nq, nullptr, 0, nullptr, T, nq, dm, 0};
     SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
     SP_HIP(e, spk_launch_attn_delta(st, dob, o, delta, B, S, d.n_q_heads, d.head_dim));
     AttnBwdArgs ab{qkv, dob, lse, delta, dqkv};
     SP_HIP(e, spk_launch_attention_bwd(st, ab, as));
     if (!dec && (rc = bias_grad(dqkv, nqkv, SP_T_BQKV)) != SP_OK) return rc;
     // dWqkv[nqkv,d] = dqkv^T a
-    g = GemmArgs{dqkv, nqkv, OP_RMAJOR, a, dm, OP_RMAJOR, G(t_wqkv), dm, nullptr, 0, nullptr, nqkv, dm, Tp, e->gemm_tile};
+    g = GemmArgs{dqkv, nqkv, OP_RMAJOR, a, dm, OP_RMAJOR, G(t_wqkv), dm, nullptr, 0, nullptr, nqkv, dm, Tp, 0};
     if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
     // da[T,d] = dqkv Wqkv (fp32)
-    g = GemmArgs{dqkv, nqkv, OP_KMAJOR, W(t_wqkv), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, nqkv, e->gemm_tile};
+    g = GemmArgs{dqkv, nqkv, OP_KMAJOR, W(t_wqkv), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, nqkv, 0};
     SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
     // first norm: dh += d(norm)(x_l) applied to da; its parameter gradients.  dh is now
     // dL/d(layer input).

@@ -76,6 +76,30 @@ def test_bad_descs_are_rejected():
         rc, _ = sp.plan(d, 1, 1, 1 << 40)
         assert rc == sp.SP_ERR_INVALID_ARG, field
     assert sp.sp_layer_blob_bytes(None) == 0
+    # head_dim 80 with an odd number of key/value heads: the fused q/k/v width (a contraction
+    # length of the backward pass) is not a multiple of 64 -- refused at create, not mid-step
+    d = sp.make_desc(synth.WORKLOADS["vith"])
+    d.n_q_heads, d.n_kv_heads = 4, 1
+    assert sp.sp_layer_blob_bytes(C.byref(d)) == 0
+    d.n_kv_heads = 2
+    assert sp.sp_layer_blob_bytes(C.byref(d)) > 0
+
+
+def test_forward_workspace_holds_no_gate_up_buffer():
+    """SwiGLU / GELU are applied in the producing GEMM's epilogue: a forward-only handle reserves
+    the normed input, q/k/v, the attention output and z, nothing of width 2f."""
+    w = synth.WORKLOADS["llama7b"]
+    d = sp.make_desc(w)
+    T, dm, f = w.tokens, w.d_model, w.d_ffn
+    want = 2 * T * (dm + 3 * dm + dm + f)
+    got = sp.sp_workspace_bytes(C.byref(d), 0)
+    assert want <= got <= want + 5 * 4096
+    # and the 4-layer budget of the workload now pins a tenth unit
+    blob = sp.sp_layer_blob_bytes(C.byref(d))
+    slot = (blob + 4095) // 4096 * 4096
+    pl = sp.sp_plan()
+    assert sp.sp_make_plan_units(C.byref(d), 3, 1, 1, sp.SP_PIN_AUTO, got + 4 * slot, 0, C.byref(pl)) == sp.SP_OK
+    assert pl.arena_bytes_used <= got + 4 * slot
 
 
 def test_slot_count_policy():
@@ -143,6 +167,9 @@ def test_create_argument_errors_without_a_device():
     bad = sp.sp_config(C.sizeof(sp.sp_config), 1, 1, 1 << 30, 4097, None, 8, None, 0)       # misaligned arena
     assert sp.sp_create(C.byref(h), C.byref(d), ptrs, C.byref(bad)) == sp.SP_ERR_INVALID_ARG
     bad = sp.sp_config(C.sizeof(sp.sp_config), 1, 1, 1 << 30, 4096, None, None, None, 0)    # same streams
+    assert sp.sp_create(C.byref(h), C.byref(d), ptrs, C.byref(bad)) == sp.SP_ERR_INVALID_ARG
+    bad = sp.sp_config(C.sizeof(sp.sp_config), 1, 1, 1 << 30, 4096, None, 8, None, sp.SP_FLAG_DELAY)
+    bad.delay_us = 10 ** 6                                                                  # beyond the bound
     assert sp.sp_create(C.byref(h), C.byref(d), ptrs, C.byref(bad)) == sp.SP_ERR_INVALID_ARG
     bad = sp.sp_config(C.sizeof(sp.sp_config), 1, 1, 1 << 30, 4096, None, 8, None, sp.SP_FLAG_TRAINING)
     assert sp.sp_create(C.byref(h), C.byref(d), ptrs, C.byref(bad)) == sp.SP_ERR_INVALID_ARG  # no d2h stream

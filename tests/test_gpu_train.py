@@ -29,10 +29,10 @@ class TrainCase:
         self.gbytes = sp.sp_layer_grad_bytes(C.byref(self.desc))
 
     def run(self, k, p, calls=1, want_y=True, target=None, budget_layers=None, flags=0, pinned=0, frozen=0,
-            want_dx=True):
+            want_dx=True, delay_us=0):
         w = self.w
         eng = sp.Engine(self.desc, self.blobs, k, p, flags=sp.SP_FLAG_TRAINING | flags, budget_layers=budget_layers,
-                        pinned=pinned, frozen=frozen)
+                        pinned=pinned, frozen=frozen, delay_us=delay_us)
         gblobs = [torch.zeros(self.gbytes, dtype=torch.uint8, pin_memory=True) for _ in range(w.n_layers)]
         y = torch.zeros_like(self.xd) if want_y else None
         dx = torch.zeros_like(self.xd)
@@ -188,6 +188,34 @@ def test_zero_loss_gives_zero_gradients(small):
     got = small.run(2, 1, target=y)
     assert got["loss"] == 0.0 and not got["dx"].any()
     assert all(not g.any() for gl in got["grads"] for g in gl.values())
+
+
+def test_pageable_gradient_buffers_are_refused(small):
+    """Gradient blobs must be pinned: from pageable memory the device-to-host copies would block
+    the host and lose their overlap with the backward pass."""
+    w = small.w
+    eng = sp.Engine(small.desc, small.blobs, 1, 1, flags=sp.SP_FLAG_TRAINING)
+    good = [torch.zeros(small.gbytes, dtype=torch.uint8, pin_memory=True) for _ in range(w.n_layers)]
+    bad = list(good)
+    bad[1] = torch.zeros(small.gbytes, dtype=torch.uint8)          # pageable
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    with pytest.raises(sp.SuperpipeError) as ei:
+        eng.forward_backward(small.xd, small.td, None, loss, None, bad, w.batch, w.seq)
+    assert ei.value.code == sp.SP_ERR_NOT_PINNED
+    # an argument error leaves the handle usable
+    eng.forward_backward(small.xd, small.td, None, loss, None, good, w.batch, w.seq)
+    eng.sync()
+    assert np.isfinite(loss.item())
+    assert eng.destroy() == sp.SP_OK
+
+
+def test_training_with_injected_delays_gives_the_same_bits(small):
+    base = small.run(8, 8)
+    got = small.run(1, 1, calls=2, flags=sp.SP_FLAG_DELAY | sp.SP_FLAG_POISON, delay_us=300)
+    assert got["loss"] == base["loss"] and np.array_equal(got["dx"], base["dx"])
+    for gl, bl in zip(got["grads"], base["grads"]):
+        for n in gl:
+            assert np.array_equal(gl[n], bl[n]), n
 
 
 def test_forward_only_handle_refuses_training(small):
