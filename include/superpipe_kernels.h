@@ -89,6 +89,18 @@ int spk_swiglu_bwd(void* stream, const uint16_t* dz, uint16_t* gu, int T, int f)
 int spk_rmsnorm_bwd(void* stream, const float* da, const float* h, const uint16_t* gain, float* dh_io,
                     uint16_t* dh_bf16, float* scratch, float* dgain, int T, int d, float eps);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): spk_rmsnorm_bwd without the scratch argument.  The
+ * partial rows live in an array built into the library (4 MiB per device, held until the process
+ * ends), so the call allocates nothing; same kernels, same results as spk_rmsnorm_bwd.
+ * d % 4 == 0 and d <= spk_rmsnorm_bwd_static_max_d() (4096), else SP_ERR_SHAPE.  All calls on one
+ * device share the array: calls that overlap on one device (two streams, two threads) race;
+ * calls on one stream are ordered and safe.  The array keeps the previous call's contents and
+ * needs no clearing (every row read was written by the same call). */
+int spk_rmsnorm_bwd_static_max_d(void);
+int spk_rmsnorm_bwd_static(void* stream, const float* da, const float* h, const uint16_t* gain, float* dh_io,
+                           uint16_t* dh_bf16, float* dgain, int T, int d, float eps);
+
 /* Attention backward.  qkv as in spk_attention, o and lse its outputs, dO bf16 [B*S, Hq*hd].
  * dqkv bf16 (layout of qkv) receives dq, dk, dv.  scratch: spk_attention_bwd_scratch_bytes bytes
  * (the fp32 row sums of dO * O). */

@@ -132,6 +132,8 @@ _sig = {
     "spk_mse": (C.c_int, [C.c_void_p] * 7 + [C.c_size_t]),
     "spk_swiglu_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int]),
     "spk_rmsnorm_bwd": (C.c_int, [C.c_void_p] * 8 + [C.c_int, C.c_int, C.c_float]),
+    "spk_rmsnorm_bwd_static": (C.c_int, [C.c_void_p] * 7 + [C.c_int, C.c_int, C.c_float]),
+    "spk_rmsnorm_bwd_static_max_d": (C.c_int, []),
     "spk_attention_bwd_scratch_bytes": (C.c_size_t, [C.c_int] * 5),
     "spk_attention_bwd": (C.c_int, [C.c_void_p] * 7 + [C.c_int] * 6),
 }
