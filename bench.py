@@ -62,6 +62,42 @@ def overlap_metrics(copy_busy_ms, copy_hidden_ms, compute_busy_ms, wall_ms):
     return out
 
 
+def op_work(w, training):
+    """Algorithmic work of one step per operation kind of SP_FLAG_OP_TIMING: {name: (bound, amount)},
+    amount in FLOP for the contractions (2 M N K; attention 4 B Hq S^2 hd, half when causal, 10 for
+    its backward) and in bytes for the HBM-bound kernels (each operand read or written once)."""
+    T, L, d, f = w.tokens, w.n_layers, w.d_model, w.d_ffn
+    nq, nkv = w.n_q_heads * w.head_dim, w.n_kv_heads * w.head_dim
+    nqkv = nq + 2 * nkv
+    dec = w.arch == "decoder"
+    f1 = 2 * f if dec else f
+    attn = 4.0 * w.batch * w.n_q_heads * w.seq * w.seq * w.head_dim * (0.5 if w.causal else 1.0)
+    mats = d * nqkv + nq * d + d * f1 + f * d                 # matrix elements of a layer
+    fwd_passes = 2 if training else 1                         # the backward recomputes the layer
+    out = {
+        "norm": ("hbm", fwd_passes * L * 2 * T * 6.0 * d),
+        "gemm_qkv": ("mfma", fwd_passes * L * 2.0 * T * nqkv * d),
+        "attention": ("mfma", fwd_passes * L * attn),
+        "gemm_o": ("mfma", fwd_passes * L * 2.0 * T * d * nq),
+        "gemm_ffn1": ("mfma", fwd_passes * L * 2.0 * T * d * f1),
+        # forward pass only: the recompute stops before the last projection
+        "gemm_ffn2": ("mfma", L * 2.0 * T * f * d),
+        "copy": ("hbm", 8.0 * T * d * (2 if training else 1)),
+    }
+    if training:
+        out.update({
+            "act": ("hbm", fwd_passes * L * T * f * (6.0 if dec else 4.0)),
+            "loss": ("hbm", 14.0 * T * d),
+            "gemm_dw": ("mfma", L * 2.0 * T * mats),
+            "gemm_dx": ("mfma", L * 2.0 * T * mats),
+            "act_bwd": ("hbm", L * T * f * (10.0 if dec else 6.0)),
+            "norm_bwd": ("hbm", L * 2 * T * 18.0 * d),
+            "attention_bwd": ("mfma", L * 2.5 * attn),
+            "bias_grad": ("hbm", 0.0 if dec else L * 2.0 * T * (2 * d + nqkv + f)),
+        })
+    return out
+
+
 def copy_ceiling_gbps(torch, nbytes=1 << 30, reps=3):
     """Plain pinned hipMemcpyAsync host->device rate, measured in this run."""
     src = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
@@ -323,6 +359,32 @@ def measure(args, name, steps, warmup, ceiling, headline, blob_cache):
     if w.arch == "encoder":
         extra["images_per_s"] = round(B / (ms * 1e-3), 1)
 
+    if not decoding:
+        # Every kernel launch bracketed by HIP events on the compute stream (SP_FLAG_OP_TIMING), summed per
+        # operation kind over two steps: each op's time per step and what it reaches of its own bound.
+        # (The event records leave gaps between the kernels: this region's step time is not `value`.)
+        r = run(k, p, base_flags | sp.SP_FLAG_OP_TIMING, 2, 1, pinned=pinned, units=units)
+        ost = r["stats"]
+        work = op_work(w, training)
+        table = {}
+        for i, nm in enumerate(sp.SP_OP_NAMES):
+            if not ost.op_launches[i]:
+                continue
+            ms_op = ost.op_ms[i] / 2
+            row = {"ms_per_step": round(ms_op, 4), "launches_per_step": ost.op_launches[i] // 2}
+            if nm in work and work[nm][1] > 0 and ms_op > 0:
+                bound, amount = work[nm]
+                if bound == "mfma":
+                    row.update(bound="mfma", achieved_tflops=round(amount / ms_op / 1e9, 1),
+                               frac=round(amount / ms_op / 1e9 / PEAK_BF16_TFLOPS, 4))
+                else:
+                    row.update(bound="hbm", achieved_gbps=round(amount / ms_op / 1e6, 1),
+                               frac=round(amount / ms_op / 1e6 / 8000.0, 4))
+            table[nm] = row
+        extra["op_table"] = table
+        extra["op_table_kernel_ms_per_step"] = round(sum(v["ms_per_step"] for v in table.values()), 3)
+        log(f"[bench] {w.name} per-op (HIP events around every launch): " + json.dumps(table))
+
     if training and (args.host_update or not headline):
         # The training loop with a host optimizer between the steps (Sec. 3.3; Table 2's setting):
         # every layer's host weights rewritten after its gradient landed, then streamed in again.
@@ -478,7 +540,7 @@ def measure(args, name, steps, warmup, ceiling, headline, blob_cache):
 OTHER_KEYS = ("ms_per_step", "value", "unit", "steps", "config", "roofline", "peak_hbm_bytes", "budget_bytes",
               "h2d_gbps_over_wall", "h2d_frac_of_ceiling", "d2h_gbps_over_wall", "copy_hidden_frac",
               "copy_hidden_frac_bound", "overlap_efficiency", "copy_stream_idle_frac", "images_per_s", "ms_per_token",
-              "host_update_loop", "parity_sample", "parity_max_rel_err", "parity_err_over_added", "cpu_baseline")
+              "host_update_loop", "op_table", "op_table_kernel_ms_per_step", "parity_sample", "parity_max_rel_err", "parity_err_over_added", "cpu_baseline")
 
 
 def main():

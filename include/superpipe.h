@@ -109,6 +109,10 @@ enum {
                                       checkpointing): more HBM, about a quarter less compute */
     SP_FLAG_KERNEL_TIMING = 1u << 5, /* bracket every 4th launch of the layer's largest GEMM with
                                       timed events on the compute stream (big_gemm_* in sp_stats) */
+    SP_FLAG_OP_TIMING = 1u << 8,   /* bracket EVERY kernel launch of the layers with timed events on the compute
+                                      stream and sum the durations per operation kind (op_ms / op_launches in
+                                      sp_stats).  The event records leave gaps on the stream, so a pass runs
+                                      slower than without the flag; the per-kernel durations are what it is for */
     SP_FLAG_DELAY = 1u << 7        /* debug: pseudo-random delays of up to sp_config.delay_us each -- the
                                       host sleeps between enqueues, and a one-wave kernel that idles for a
                                       bounded time and exits runs in front of every layer copy (copy stream)
@@ -179,6 +183,25 @@ typedef struct {
 } sp_plan;
 
 #define SP_MAX_TRACE_LAYERS 256
+/* Operation kinds of SP_FLAG_OP_TIMING. */
+enum {
+    SP_OP_NORM = 0,        /* RMSNorm / LayerNorm, forward (and the backward pass's recompute)          */
+    SP_OP_GEMM_QKV = 1,    /* fused q/k/v projection                                                    */
+    SP_OP_ATTENTION = 2,   /* attention forward (with a cache: append + single-query attention)         */
+    SP_OP_GEMM_O = 3,      /* output projection + residual                                              */
+    SP_OP_GEMM_FFN1 = 4,   /* gate/up (SwiGLU in the epilogue when forward-only) or first MLP projection */
+    SP_OP_ACT = 5,         /* SwiGLU / GELU as a kernel of its own (training keeps the pre-activations) */
+    SP_OP_GEMM_FFN2 = 6,   /* down / second MLP projection + residual                                   */
+    SP_OP_LOSS = 7,        /* MSE loss and its gradient                                                 */
+    SP_OP_GEMM_DW = 8,     /* the weight-gradient GEMMs (contraction over tokens)                       */
+    SP_OP_GEMM_DX = 9,     /* the input-gradient GEMMs                                                  */
+    SP_OP_ACT_BWD = 10,    /* SwiGLU / GELU backward                                                    */
+    SP_OP_NORM_BWD = 11,   /* norm backward incl. its gain (and bias) gradient                          */
+    SP_OP_ATTENTION_BWD = 12, /* rowsum(dO * O), dq kernel, dk/dv kernel                               */
+    SP_OP_BIAS_GRAD = 13,  /* column sums for the bias gradients (encoder)                              */
+    SP_OP_COPY = 14,       /* copies and fills of activations (x -> y, padded rows)                     */
+    SP_N_OPS = 15
+};
 typedef struct {
     uint32_t struct_size;
     sp_plan plan;
@@ -202,6 +225,10 @@ typedef struct {
     uint32_t big_gemm_launches;
     float big_gemm_ms_sum;
     int32_t big_gemm_m, big_gemm_n, big_gemm_k;   /* its shape: C[m,n] over k (n counts gate and up) */
+    /* SP_FLAG_OP_TIMING: per operation kind (SP_OP_*), summed over the calls since the previous
+     * sp_get_stats: total duration and number of launches. */
+    float op_ms[16];
+    uint32_t op_launches[16];
     int32_t n_ops;              /* SP_FLAG_TIMING: compute operations the most recent call issued (units, forward
                                    then backward); the arrays above hold the first n_timed = min(n_ops,
                                    SP_MAX_TRACE_LAYERS) of them, the busy/hidden/wall sums cover all n_ops */

@@ -30,6 +30,9 @@ SP_FLAG_TRAINING, SP_FLAG_TIMING, SP_FLAG_POISON, SP_FLAG_NO_OVERLAP, SP_FLAG_WR
 SP_FLAG_KERNEL_TIMING = 32
 SP_FLAG_KEEP_ACTIVATIONS = 64
 SP_FLAG_DELAY = 128
+SP_FLAG_OP_TIMING = 256
+SP_OP_NAMES = ["norm", "gemm_qkv", "attention", "gemm_o", "gemm_ffn1", "act", "gemm_ffn2", "loss", "gemm_dw", "gemm_dx",
+               "act_bwd", "norm_bwd", "attention_bwd", "bias_grad", "copy"]
 SP_PIN_AUTO = -1
 SP_MAX_TRACE_LAYERS = 256
 EPI_BF16, EPI_RESID_F32, EPI_GELU_BF16, EPI_SWIGLU_BF16, EPI_F32 = 0, 1, 2, 3, 4
@@ -73,7 +76,7 @@ class sp_stats(C.Structure):
                 ("compute_busy_ms", C.c_float), ("wall_ms", C.c_float),
                 ("big_gemm_launches", C.c_uint32), ("big_gemm_ms_sum", C.c_float),
                 ("big_gemm_m", C.c_int32), ("big_gemm_n", C.c_int32), ("big_gemm_k", C.c_int32),
-                ("n_ops", C.c_int32)]
+                ("op_ms", C.c_float * 16), ("op_launches", C.c_uint32 * 16), ("n_ops", C.c_int32)]
 
 
 class sp_sched_op(C.Structure):

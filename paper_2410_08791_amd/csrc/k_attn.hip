@@ -247,7 +247,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_kernel(const bf16_t* __re
                                                                   (wave * C::NLOAD + i_) * 1024), 16, 0, 0);      \
     } while (0)
 #else
-#define SP_ATTN_ISSUE(kt_, stage_) ((void)ld_col, (void)ld_row, (void)ld_on)
+#define SP_ATTN_ISSUE(kt_, stage_) ((void)ld_col, (void)ld_row, (void)ld_on, (void)kbase)
 #endif
     constexpr int WAIT_VM0 = (0 & 15) | (7 << 4) | (15 << 8) | (0 << 14);   // vmcnt 0, lgkmcnt untouched
     if (C::ONES_ROW) {

@@ -55,8 +55,9 @@ template <> struct TokTile<64> { static constexpr int RS = 64 * 2 + 16; };
 // operand) and walks 64-key tiles.  K and V tiles sit in LDS as token rows: S^T = K Q^T and
 // dP^T = V dO^T read them straight, dQ^T += K^T dS^T reads K through the transposing LDS
 // read.  The next tile's rows are fetched into registers before the current one is computed.
+// (Two work-groups per CU: the kernel fits 256 registers at every head dimension.)
 template <int HD>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
                                                           const float* __restrict__ lse, const float* __restrict__ delta,
                                                           bf16_t* __restrict__ dqkv, int S, int Hq, int Hkv, int ld_qkv,
                                                           int causal, float scale, float scale_log2e) {
@@ -68,8 +69,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restri
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    const int qb = causal ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
-    const int h = blockIdx.y, b = blockIdx.z;
+    // work-group ids are dealt round-robin to the 8 XCDs: remapped so that an XCD works through a
+    // contiguous range of (batch, head, query block) and a head's keys and values are fetched
+    // through one L2
+    const int job = xcd_remap(blockIdx.x + (int)gridDim.x * (blockIdx.y + (int)gridDim.y * blockIdx.z),
+                              (int)(gridDim.x * gridDim.y * gridDim.z));
+    const int bx = job % (int)gridDim.x, h = (job / (int)gridDim.x) % (int)gridDim.y, b = job / (int)(gridDim.x * gridDim.y);
+    const int qb = causal ? gridDim.x - 1 - bx : bx;
     const int kvh = h / (Hq / Hkv);
     const int q0 = qb * 128, wq0 = q0 + wave * 32, qi = wq0 + l32;
     const size_t tok0 = (size_t)b * S;
@@ -150,7 +156,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restri
             for (int e = 0; e < 16; ++e) {
                 const int key = key0 + t * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
                 const bool ok = key < S && (!causal || key <= qi);
-                const float p = ok ? exp2f(s[e] * scale_log2e - lse_q) : 0.f;
+                const float p = ok ? __builtin_amdgcn_exp2f(fmaf(s[e], scale_log2e, -lse_q)) : 0.f;
                 dsf[t][e >> 3][e & 7] = (__bf16)(p * (dp[e] - delta_q));
             }
         }
@@ -184,8 +190,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restri
 // group.  Q and dO tiles sit in LDS once, as token rows: the score products read them
 // straight, dV^T += dO^T P and dK^T += Q^T dS read them through the transposing LDS read.
 // The next tile's rows are fetched into registers before the current tile is computed.
+// At head_dim 128 a wave holds dK^T and dV^T of its 32 keys (128 registers), its K and V
+// fragments (64) and the score / dP tiles: ~370 registers, one wave per SIMD; the smaller head
+// dimensions fit two.
 template <int HD>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
+__global__ __launch_bounds__(256, HD <= 80 ? 2 : 1) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dO,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16_t* __restrict__ dqkv, int S, int Hq, int Hkv,
                                                            int ld_qkv, int causal, float scale, float scale_log2e) {
@@ -198,9 +207,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    const int kvh = blockIdx.y, b = blockIdx.z;
+    // the same XCD-contiguous order as in the dq kernel: the key blocks of a head share its queries
+    const int job = xcd_remap(blockIdx.x + (int)gridDim.x * (blockIdx.y + (int)gridDim.y * blockIdx.z),
+                              (int)(gridDim.x * gridDim.y * gridDim.z));
+    const int bx = job % (int)gridDim.x, kvh = (job / (int)gridDim.x) % (int)gridDim.y, b = job / (int)(gridDim.x * gridDim.y);
     const int grp = Hq / Hkv;
-    const int k0 = blockIdx.x * 128, wk0 = k0 + wave * 32, kj = wk0 + l32;
+    const int k0 = bx * 128, wk0 = k0 + wave * 32, kj = wk0 + l32;
     const size_t tok0 = (size_t)b * S;
     const int ld_do = Hq * HD;
 
@@ -289,7 +301,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
                 const int r = (e >> 2) * 8 + half * 4 + (e & 3);
                 const int q = qs + r;
                 const bool ok = q < S && (!causal || kj <= q);
-                const float p = ok ? exp2f(s[e] * scale_log2e - s_lse[sub * 32 + r]) : 0.f;
+                const float p = ok ? __builtin_amdgcn_exp2f(fmaf(s[e], scale_log2e, -s_lse[sub * 32 + r])) : 0.f;
                 pf[e >> 3][e & 7] = (__bf16)p;
                 dsf[e >> 3][e & 7] = (__bf16)(p * (dp[e] - s_delta[sub * 32 + r]));
             }

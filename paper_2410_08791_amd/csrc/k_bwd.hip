@@ -140,6 +140,100 @@ __global__ __launch_bounds__(TH) void rmsnorm_bwd_kernel(const float* __restrict
     }
 }
 
+
+// The same for rows of at most 2048 elements with ONE WAVE PER ROW: a lane holds d/64 elements of
+// the row (at most eight float4), the two row sums are wave shuffles, and no barrier separates
+// the rows, so a work-group of eight waves keeps eight rows' loads in flight (the
+// row-per-work-group form above spends most of its time in its four barriers per row: 2.4 TB/s on
+// 8192 x 2048).  The waves' gain-gradient partials are added into LDS in wave order at the end:
+// one partial row per work-group.
+constexpr int NW_MAXV = 8;    // float4 per lane -> d <= 2048
+constexpr int NW_WAVES = 8;
+
+__global__ __launch_bounds__(NW_WAVES * 64) void rmsnorm_bwd_wave_kernel(
+    const float* __restrict__ da, const float* __restrict__ h, const bf16_t* __restrict__ gain, float* __restrict__ dh_io,
+    bf16_t* __restrict__ dhb, float* __restrict__ part, int T, int d, float eps) {
+    __shared__ float4 lds[64 * NW_MAXV];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nv = d >> 2;
+    float4 gacc[NW_MAXV], gv[NW_MAXV];
+#pragma unroll
+    for (int i = 0; i < NW_MAXV; ++i) {
+        gacc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int idx = lane + i * 64;
+        if (idx < nv) {
+            const uint2 g = reinterpret_cast<const uint2*>(gain)[idx];
+            gv[i] = make_float4(bf_lo(g.x), bf_hi(g.x), bf_lo(g.y), bf_hi(g.y));
+        }
+    }
+    for (int row = blockIdx.x * NW_WAVES + wave; row < T; row += gridDim.x * NW_WAVES) {
+        const float4* hp = reinterpret_cast<const float4*>(h + (size_t)row * d);
+        const float4* ap = reinterpret_cast<const float4*>(da + (size_t)row * d);
+        float4* op = reinterpret_cast<float4*>(dh_io + (size_t)row * d);
+        float4 hv[NW_MAXV], av[NW_MAXV], ov[NW_MAXV];
+#pragma unroll
+        for (int i = 0; i < NW_MAXV; ++i) {
+            const int idx = lane + i * 64;
+            if (idx < nv) { hv[i] = hp[idx]; av[i] = ap[idx]; ov[i] = op[idx]; }
+        }
+        float ss = 0.f, dot = 0.f;
+#pragma unroll
+        for (int i = 0; i < NW_MAXV; ++i) {
+            const int idx = lane + i * 64;
+            if (idx < nv) {
+                ss += (hv[i].x * hv[i].x + hv[i].y * hv[i].y) + (hv[i].z * hv[i].z + hv[i].w * hv[i].w);
+                dot += (av[i].x * gv[i].x * hv[i].x + av[i].y * gv[i].y * hv[i].y) +
+                       (av[i].z * gv[i].z * hv[i].z + av[i].w * gv[i].w * hv[i].w);
+            }
+        }
+        ss = wave_sum(ss);
+        dot = wave_sum(dot);
+        const float r = rsqrtf(ss / (float)d + eps);
+        const float c = r * r * r * dot / (float)d;
+        uint2* bp = reinterpret_cast<uint2*>(dhb + (size_t)row * d);
+#pragma unroll
+        for (int i = 0; i < NW_MAXV; ++i) {
+            const int idx = lane + i * 64;
+            if (idx < nv) {
+                float4 o = ov[i];
+                o.x += r * av[i].x * gv[i].x - hv[i].x * c;
+                o.y += r * av[i].y * gv[i].y - hv[i].y * c;
+                o.z += r * av[i].z * gv[i].z - hv[i].z * c;
+                o.w += r * av[i].w * gv[i].w - hv[i].w * c;
+                op[idx] = o;
+                bp[idx] = make_uint2(pack_bf2(o.x, o.y), pack_bf2(o.z, o.w));
+                gacc[i].x += av[i].x * hv[i].x * r;
+                gacc[i].y += av[i].y * hv[i].y * r;
+                gacc[i].z += av[i].z * hv[i].z * r;
+                gacc[i].w += av[i].w * hv[i].w * r;
+            }
+        }
+    }
+    // wave 0 stores its partial, waves 1 .. 7 add theirs one after the other: a fixed order
+    for (int w = 0; w < NW_WAVES; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int i = 0; i < NW_MAXV; ++i) {
+                float4 g = gacc[i];
+                if (w) {
+                    const float4 o = lds[i * 64 + lane];
+                    g.x += o.x; g.y += o.y; g.z += o.z; g.w += o.w;
+                }
+                lds[i * 64 + lane] = g;
+            }
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+        float4* pp = reinterpret_cast<float4*>(part + (size_t)blockIdx.x * d);
+#pragma unroll
+        for (int i = 0; i < NW_MAXV; ++i) {
+            const int idx = lane + i * 64;
+            if (idx < nv) pp[idx] = lds[i * 64 + lane];
+        }
+    }
+}
+
 __global__ __launch_bounds__(TH) void colsum_final_kernel(const float* __restrict__ part, int nparts, int d,
                                                           float* __restrict__ out) {
     __shared__ float lds[256];
@@ -206,8 +300,13 @@ hipError_t spk_launch_rmsnorm_bwd(hipStream_t st, const float* da, const float* 
                                   bf16_t* dhb, float* part, float* dgain, int T, int d, float eps) {
     if (T <= 0) return hipSuccess;
     if (d <= 0 || (d & 3) || d > TH * NB_MAXV * 4) return hipErrorInvalidValue;
-    const int nb = std::min(T, SPK_NORM_BWD_BLOCKS);
-    rmsnorm_bwd_kernel<<<nb, TH, 0, st>>>(da, h, gain, dh_io, dhb, part, T, d, eps);
+    // which form runs depends on the row length and the row count only
+    const bool per_wave = d <= 64 * NW_MAXV * 4 && T >= 4 * SPK_NORM_BWD_BLOCKS;   // enough rows for every wave
+    const int nb = per_wave ? SPK_NORM_BWD_BLOCKS : std::min(T, SPK_NORM_BWD_BLOCKS);
+    if (per_wave)
+        rmsnorm_bwd_wave_kernel<<<nb, NW_WAVES * 64, 0, st>>>(da, h, gain, dh_io, dhb, part, T, d, eps);
+    else
+        rmsnorm_bwd_kernel<<<nb, TH, 0, st>>>(da, h, gain, dh_io, dhb, part, T, d, eps);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     colsum_final_kernel<<<(d + 63) / 64, TH, 0, st>>>(part, nb, d, dgain);

@@ -70,6 +70,10 @@ struct sp_engine {
     // counters
     uint64_t calls = 0, stats_h2d_copies = 0, stats_h2d_bytes = 0, stats_d2h_copies = 0, stats_d2h_bytes = 0;
     uint64_t call_h2d_copies = 0, call_h2d_bytes = 0;
+    // SP_FLAG_OP_TIMING: event pairs around every kernel launch since the last sp_get_stats
+    std::vector<hipEvent_t> op_begin, op_end;
+    std::vector<unsigned char> op_tag;
+    size_t op_count = 0;
     // debug delays (SP_FLAG_DELAY): upper bound per delay and the running draw counter
     int delay_us = 0;
     uint32_t delay_seq = 0;
@@ -109,6 +113,19 @@ int sp_train_loss(sp_engine* e, const float* target_dev, float* loss_dev, int B,
 int sp_train_end(sp_engine* e, float* dx_dev, int B, int S);
 
 int sp_fail(sp_engine* e, int code, const char* fmt, ...);
+
+// A kernel launch of operation kind `tag`, bracketed by timed events when SP_FLAG_OP_TIMING is on
+// (until the pool of event pairs is used up; sp_get_stats empties it).
+#define SP_OP(e, tag, call)                                                       \
+    do {                                                                          \
+        const bool _t = (e)->op_count < (e)->op_begin.size();                     \
+        if (_t) SP_HIP((e), hipEventRecord((e)->op_begin[(e)->op_count], (e)->compute)); \
+        SP_HIP((e), call);                                                        \
+        if (_t) {                                                                 \
+            SP_HIP((e), hipEventRecord((e)->op_end[(e)->op_count], (e)->compute)); \
+            (e)->op_tag[(e)->op_count++] = (unsigned char)(tag);                  \
+        }                                                                         \
+    } while (0)
 
 #define SP_HIP(e, call)                                                                          \
     do {                                                                                         \

@@ -225,30 +225,30 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
 
     if (parts & 1) {
         // b1: a = norm(h)
-        SP_HIP(e, spk_launch_norm(st, h, W(dec ? SP_T_G1 : SP_T_LN1_G), dec ? nullptr : W(SP_T_LN1_B), a, T, dm, d.norm_eps));
+        SP_OP(e, SP_OP_NORM, spk_launch_norm(st, h, W(dec ? SP_T_G1 : SP_T_LN1_G), dec ? nullptr : W(SP_T_LN1_B), a, T, dm, d.norm_eps));
         // b2: qkv = a Wqkv^T (+ b)
         g = GemmArgs{a, dm, OP_KMAJOR, W(dec ? SP_T_WQKV : SP_T_E_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0,
                      dec ? nullptr : W(SP_T_BQKV), T, nqkv, dm, 0};
-        SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+        SP_OP(e, SP_OP_GEMM_QKV, spk_launch_gemm(st, EPI_BF16, g));
         // b3: attention.  With a cache the new keys/values are stored first; a decode step then
         // attends its single query per sequence to the cached positions 0..pos.
         if (kv)
-            SP_HIP(e, spk_launch_kv_append(st, qkv, nqkv, kv->kt, kv->v, B, S, kv->pos >= 0 ? kv->pos : 0, d.n_q_heads,
+            SP_OP(e, SP_OP_ATTENTION, spk_launch_kv_append(st, qkv, nqkv, kv->kt, kv->v, B, S, kv->pos >= 0 ? kv->pos : 0, d.n_q_heads,
                                            d.n_kv_heads, d.head_dim, kv->max_len));
         if (kv && kv->pos >= 0) {
-            SP_HIP(e, spk_launch_decode_attention(st, qkv, nqkv, kv->kt, kv->v, o, nq, B, kv->pos + 1, kv->max_len,
+            SP_OP(e, SP_OP_ATTENTION, spk_launch_decode_attention(st, qkv, nqkv, kv->kt, kv->v, o, nq, B, kv->pos + 1, kv->max_len,
                                                   d.n_q_heads, d.n_kv_heads, d.head_dim));
         } else {
-            SP_HIP(e, spk_launch_attention(st, qkv, o, nullptr, as));
+            SP_OP(e, SP_OP_ATTENTION, spk_launch_attention(st, qkv, o, nullptr, as));
         }
         // b4: h += o Wo^T (+ b)
         g = GemmArgs{o, nq, OP_KMAJOR, W(dec ? SP_T_WO : SP_T_E_WO), nq, OP_KMAJOR, h, dm, h, dm,
                      dec ? nullptr : W(SP_T_BO), T, dm, nq, 0};
-        SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+        SP_OP(e, SP_OP_GEMM_O, spk_launch_gemm(st, EPI_RESID_F32, g));
     }
     if (parts & 2) {
         // b5: a = norm(h)
-        SP_HIP(e, spk_launch_norm(st, h, W(dec ? SP_T_G2 : SP_T_LN2_G), dec ? nullptr : W(SP_T_LN2_B), a, T, dm, d.norm_eps));
+        SP_OP(e, SP_OP_NORM, spk_launch_norm(st, h, W(dec ? SP_T_G2 : SP_T_LN2_G), dec ? nullptr : W(SP_T_LN2_B), a, T, dm, d.norm_eps));
         // every 4th launch of the largest GEMM is bracketed: the two event records cost a gap
         // on the stream, which on a compute-bound stack would show in the step time
         const bool kt = !e->kt_begin.empty() && (e->kt_seen++ % 4 == 0);
@@ -260,11 +260,11 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
         if (dec) {
             // b6+b7: z = silu(a Wg^T) * (a Wu^T), gate applied in the GEMM epilogue
             g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, z, f, nullptr, 0, nullptr, T, f, dm, 0};
-            SP_HIP(e, spk_launch_gemm(st, EPI_SWIGLU_BF16, g));
+            SP_OP(e, SP_OP_GEMM_FFN1, spk_launch_gemm(st, EPI_SWIGLU_BF16, g));
             if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
         } else {
             g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_W1), dm, OP_KMAJOR, z, f, nullptr, 0, W(SP_T_B1), T, f, dm, 0};
-            SP_HIP(e, spk_launch_gemm(st, EPI_GELU_BF16, g));
+            SP_OP(e, SP_OP_GEMM_FFN1, spk_launch_gemm(st, EPI_GELU_BF16, g));
             if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
         }
     }
@@ -272,10 +272,10 @@ int sp_layer_forward(sp_engine* e, const unsigned char* w, float* h, int B, int 
         if (dec) {
             // b8: h += z Wd^T
             g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_WD), f, OP_KMAJOR, h, dm, h, dm, nullptr, T, dm, f, 0};
-            SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+            SP_OP(e, SP_OP_GEMM_FFN2, spk_launch_gemm(st, EPI_RESID_F32, g));
         } else {
             g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_W2), f, OP_KMAJOR, h, dm, h, dm, W(SP_T_B2), T, dm, f, 0};
-            SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+            SP_OP(e, SP_OP_GEMM_FFN2, spk_launch_gemm(st, EPI_RESID_F32, g));
         }
     }
     return SP_OK;
@@ -401,6 +401,16 @@ extern "C" int sp_create(sp_handle* out, const sp_stack_desc* desc, const void* 
             if (he == hipSuccess) he = mk(&e->kt_end[i], hipEventDefault);
         }
     }
+    if (he == hipSuccess && (cfg->flags & SP_FLAG_OP_TIMING)) {
+        // a training step of the deepest stacks in use launches about 3000 kernels
+        e->op_begin.assign(8192, nullptr);
+        e->op_end.assign(8192, nullptr);
+        e->op_tag.assign(8192, 0);
+        for (size_t i = 0; i < e->op_begin.size() && he == hipSuccess; ++i) {
+            he = mk(&e->op_begin[i], hipEventDefault);
+            if (he == hipSuccess) he = mk(&e->op_end[i], hipEventDefault);
+        }
+    }
     if (he != hipSuccess) {
         fail(nullptr, SP_ERR_HIP, "hipEventCreate failed: %s", hipGetErrorString(he));
         destroy_engine(e);
@@ -467,7 +477,7 @@ static int enqueue_forward(sp_engine* e, const float* x_dev, float* y_dev, int B
                            int max_len, int pos) {
     int rc;
     if ((rc = begin_call(e)) != SP_OK) return rc;
-    SP_HIP(e, spk_launch_copy_f32(e->compute, x_dev, y_dev, (size_t)B * S * e->desc.d_model));
+    SP_OP(e, SP_OP_COPY, spk_launch_copy_f32(e->compute, x_dev, y_dev, (size_t)B * S * e->desc.d_model));
     HipSink sink(e);
     sink.hbuf = y_dev;
     sink.B = B;
@@ -630,7 +640,7 @@ extern "C" int sp_get_stats(sp_handle e, sp_stats* out) {
     out->d2h_bytes = e->stats_d2h_bytes;
     out->last_h2d_copies = e->call_h2d_copies;
     out->last_h2d_bytes = e->call_h2d_bytes;
-    if (!(e->flags & (SP_FLAG_TIMING | SP_FLAG_KERNEL_TIMING)) || e->calls == 0) return SP_OK;
+    if (!(e->flags & (SP_FLAG_TIMING | SP_FLAG_KERNEL_TIMING | SP_FLAG_OP_TIMING)) || e->calls == 0) return SP_OK;
     SP_HIP(e, hipStreamSynchronize(e->h2d));
     SP_HIP(e, hipStreamSynchronize(e->compute));
     if (e->d2h) SP_HIP(e, hipStreamSynchronize(e->d2h));
@@ -645,6 +655,13 @@ extern "C" int sp_get_stats(sp_handle e, sp_stats* out) {
         out->big_gemm_m = e->kt_m; out->big_gemm_n = e->kt_n; out->big_gemm_k = e->kt_k;
         e->kt_count = 0;
     }
+    for (size_t i = 0; i < e->op_count; ++i) {
+        float ms = 0;
+        SP_HIP(e, hipEventElapsedTime(&ms, e->op_begin[i], e->op_end[i]));
+        out->op_ms[e->op_tag[i]] += ms;
+        out->op_launches[e->op_tag[i]]++;
+    }
+    e->op_count = 0;
     if (!(e->flags & SP_FLAG_TIMING)) return SP_OK;
     // Per-op trace of the most recent call from the fence events' timestamps.  An op
     // begins when its stream's previous op has ended and its dependency is met.
@@ -716,6 +733,8 @@ static int destroy_engine(sp_engine* e) {
     for (auto ev : e->comp_ev) kill(ev);
     for (auto ev : e->kt_begin) kill(ev);
     for (auto ev : e->kt_end) kill(ev);
+    for (auto ev : e->op_begin) kill(ev);
+    for (auto ev : e->op_end) kill(ev);
     kill(e->ev_sync_c);
     kill(e->ev_sync_h);
     for (auto ev : e->thr_ev) kill(ev);

@@ -43,13 +43,13 @@ int decoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
     bf16_t *a = as_.a, *m = as_.m, *qkv = as_.qkv, *o = as_.o, *gu = as_.gu, *z = as_.z;
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
     GemmArgs g;
-    SP_HIP(e, spk_launch_norm(st, b.h_in, W(SP_T_G1), nullptr, a, T, dm, d.norm_eps));
+    SP_OP(e, SP_OP_NORM, spk_launch_norm(st, b.h_in, W(SP_T_G1), nullptr, a, T, dm, d.norm_eps));
     g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0, nullptr, T, nqkv, dm, 0};
-    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
-    SP_HIP(e, spk_launch_attention(st, qkv, o, b.lse, as));
+    SP_OP(e, SP_OP_GEMM_QKV, spk_launch_gemm(st, EPI_BF16, g));
+    SP_OP(e, SP_OP_ATTENTION, spk_launch_attention(st, qkv, o, b.lse, as));
     g = GemmArgs{o, nq, OP_KMAJOR, W(SP_T_WO), nq, OP_KMAJOR, b.h_mid, dm, b.h_in, dm, nullptr, T, dm, nq, 0};
-    SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
-    SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_G2), nullptr, m, T, dm, d.norm_eps));
+    SP_OP(e, SP_OP_GEMM_O, spk_launch_gemm(st, EPI_RESID_F32, g));
+    SP_OP(e, SP_OP_NORM, spk_launch_norm(st, b.h_mid, W(SP_T_G2), nullptr, m, T, dm, d.norm_eps));
     g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_WGU), dm, OP_KMAJOR, gu, 2 * f, nullptr, 0, nullptr, T, 2 * f, dm, 0};
     // every 4th launch of the largest GEMM is bracketed: the two event records cost a gap
     // on the stream, which on a compute-bound stack would show in the step time
@@ -59,12 +59,12 @@ int decoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
         SP_HIP(e, hipEventRecord(e->kt_begin[kti], st));
         e->kt_m = T; e->kt_n = 2 * f; e->kt_k = dm;
     }
-    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+    SP_OP(e, SP_OP_GEMM_FFN1, spk_launch_gemm(st, EPI_BF16, g));
     if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
-    SP_HIP(e, spk_launch_swiglu(st, gu, z, T, f));
+    SP_OP(e, SP_OP_ACT, spk_launch_swiglu(st, gu, z, T, f));
     if (b.h_out) {
         g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_WD), f, OP_KMAJOR, b.h_out, dm, b.h_mid, dm, nullptr, T, dm, f, 0};
-        SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+        SP_OP(e, SP_OP_GEMM_FFN2, spk_launch_gemm(st, EPI_RESID_F32, g));
     }
     return SP_OK;
 }
@@ -82,13 +82,13 @@ int encoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
     bf16_t *a = as_.a, *m = as_.m, *qkv = as_.qkv, *o = as_.o, *u = as_.gu, *z = as_.z;
     AttnShape as{B, S, d.n_q_heads, d.n_kv_heads, d.head_dim, d.causal, nqkv};
     GemmArgs g;
-    SP_HIP(e, spk_launch_norm(st, b.h_in, W(SP_T_LN1_G), W(SP_T_LN1_B), a, T, dm, d.norm_eps));
+    SP_OP(e, SP_OP_NORM, spk_launch_norm(st, b.h_in, W(SP_T_LN1_G), W(SP_T_LN1_B), a, T, dm, d.norm_eps));
     g = GemmArgs{a, dm, OP_KMAJOR, W(SP_T_E_WQKV), dm, OP_KMAJOR, qkv, nqkv, nullptr, 0, W(SP_T_BQKV), T, nqkv, dm, 0};
-    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
-    SP_HIP(e, spk_launch_attention(st, qkv, o, b.lse, as));
+    SP_OP(e, SP_OP_GEMM_QKV, spk_launch_gemm(st, EPI_BF16, g));
+    SP_OP(e, SP_OP_ATTENTION, spk_launch_attention(st, qkv, o, b.lse, as));
     g = GemmArgs{o, nq, OP_KMAJOR, W(SP_T_E_WO), nq, OP_KMAJOR, b.h_mid, dm, b.h_in, dm, W(SP_T_BO), T, dm, nq, 0};
-    SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
-    SP_HIP(e, spk_launch_norm(st, b.h_mid, W(SP_T_LN2_G), W(SP_T_LN2_B), m, T, dm, d.norm_eps));
+    SP_OP(e, SP_OP_GEMM_O, spk_launch_gemm(st, EPI_RESID_F32, g));
+    SP_OP(e, SP_OP_NORM, spk_launch_norm(st, b.h_mid, W(SP_T_LN2_G), W(SP_T_LN2_B), m, T, dm, d.norm_eps));
     g = GemmArgs{m, dm, OP_KMAJOR, W(SP_T_W1), dm, OP_KMAJOR, u, f, nullptr, 0, W(SP_T_B1), T, f, dm, 0};
     const bool kt = !e->kt_begin.empty() && (e->kt_seen++ % 4 == 0);
     const size_t kti = kt ? e->kt_count % e->kt_begin.size() : 0;
@@ -96,12 +96,12 @@ int encoder_layer_keep(sp_engine* e, const unsigned char* w, const ActSet& as_, 
         SP_HIP(e, hipEventRecord(e->kt_begin[kti], st));
         e->kt_m = T; e->kt_n = f; e->kt_k = dm;
     }
-    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+    SP_OP(e, SP_OP_GEMM_FFN1, spk_launch_gemm(st, EPI_BF16, g));
     if (kt) { SP_HIP(e, hipEventRecord(e->kt_end[kti], st)); e->kt_count++; }
-    SP_HIP(e, spk_launch_gelu(st, u, z, (size_t)T * f));
+    SP_OP(e, SP_OP_ACT, spk_launch_gelu(st, u, z, (size_t)T * f));
     if (b.h_out) {
         g = GemmArgs{z, f, OP_KMAJOR, W(SP_T_W2), f, OP_KMAJOR, b.h_out, dm, b.h_mid, dm, W(SP_T_B2), T, dm, f, 0};
-        SP_HIP(e, spk_launch_gemm(st, EPI_RESID_F32, g));
+        SP_OP(e, SP_OP_GEMM_FFN2, spk_launch_gemm(st, EPI_RESID_F32, g));
     }
     return SP_OK;
 }
@@ -135,10 +135,10 @@ int sp_train_begin(sp_engine* e, const float* x_dev, int B, int S) {
             for (int set = 0; set < (bf.per_set ? n_sets : 1); ++set) {
                 uint32_t* p = reinterpret_cast<uint32_t*>(e->arena + (size_t)set * e->ws.set_stride + bf.off +
                                                           (size_t)T * bf.cols * 2);
-                SP_HIP(e, spk_launch_fill_u32(st, p, 0u, (size_t)(Tp - T) * bf.cols / 2));
+                SP_OP(e, SP_OP_COPY, spk_launch_fill_u32(st, p, 0u, (size_t)(Tp - T) * bf.cols / 2));
             }
     }
-    SP_HIP(e, spk_launch_copy_f32(st, x_dev, saved_input(e, 0, T), (size_t)T * d.d_model));
+    SP_OP(e, SP_OP_COPY, spk_launch_copy_f32(st, x_dev, saved_input(e, 0, T), (size_t)T * d.d_model));
     return SP_OK;
 }
 
@@ -157,8 +157,8 @@ int sp_train_loss(sp_engine* e, const float* target_dev, float* loss_dev, int B,
     const size_t n = (size_t)B * S * e->desc.d_model;
     float* dh = e->wsp<float>(e->ws.dh);
     const float* y = e->y_out ? e->y_out : dh;
-    SP_HIP(e, spk_launch_mse(e->compute, y, target_dev, dh, e->wsp<bf16_t>(e->ws.dhb), e->wsp<float>(e->ws.part),
-                             loss_dev, n));
+    SP_OP(e, SP_OP_LOSS, spk_launch_mse(e->compute, y, target_dev, dh, e->wsp<bf16_t>(e->ws.dhb), e->wsp<float>(e->ws.part),
+                                        loss_dev, n));
     return SP_OK;
 }
 
@@ -206,7 +206,7 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     // bias gradient of a linear map = column sums of its output gradient over the tokens
     auto bias_grad = [&](const bf16_t* dy, int n, int t) -> int {
         if (frozen) return SP_OK;
-        SP_HIP(e, spk_launch_colsum_bf16(st, dy, n, T, n, part, G(t)));
+        SP_OP(e, SP_OP_BIAS_GRAD, spk_launch_colsum_bf16(st, dy, n, T, n, part, G(t)));
         return SP_OK;
     };
     int rc;
@@ -215,40 +215,40 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     if (dec) {
         // dWd[d,f] = dh^T z       (contraction over tokens: both operands transposed on the way in)
         g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_WD), f, nullptr, 0, nullptr, dm, f, Tp, 0};
-        if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        if (!frozen) SP_OP(e, SP_OP_GEMM_DW, spk_launch_gemm(st, EPI_F32, g));
         // dz[T,f] = dh Wd         (Wd is [d,f]: its row index f is contiguous)
         g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_WD), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, 0};
-        SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+        SP_OP(e, SP_OP_GEMM_DX, spk_launch_gemm(st, EPI_BF16, g));
         // [dg | du] in place over [g | u]
-        SP_HIP(e, spk_launch_swiglu_bwd(st, dz, gu, T, f));
+        SP_OP(e, SP_OP_ACT_BWD, spk_launch_swiglu_bwd(st, dz, gu, T, f));
         // dWgu[2f,d] = dgu^T m
         g = GemmArgs{gu, 2 * f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_WGU), dm, nullptr, 0, nullptr, 2 * f, dm, Tp, 0};
-        if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        if (!frozen) SP_OP(e, SP_OP_GEMM_DW, spk_launch_gemm(st, EPI_F32, g));
         // dm[T,d] = dgu Wgu  (fp32)
         g = GemmArgs{gu, 2 * f, OP_KMAJOR, W(SP_T_WGU), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, 2 * f, 0};
-        SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        SP_OP(e, SP_OP_GEMM_DX, spk_launch_gemm(st, EPI_F32, g));
         // second norm: dh += d(rmsnorm)(h1) applied to dm; dg2
-        SP_HIP(e, spk_launch_rmsnorm_bwd(st, da, h1, W(SP_T_G2), dh, dhb, part, G(SP_T_G2), T, dm, d.norm_eps));
+        SP_OP(e, SP_OP_NORM_BWD, spk_launch_rmsnorm_bwd(st, da, h1, W(SP_T_G2), dh, dhb, part, G(SP_T_G2), T, dm, d.norm_eps));
     } else {
         bf16_t* u = gu;                     // pre-activation of the MLP, [T, f]
         if ((rc = bias_grad(dhb, dm, SP_T_B2)) != SP_OK) return rc;
         // dW2[d,f] = dh^T z
         g = GemmArgs{dhb, dm, OP_RMAJOR, z, f, OP_RMAJOR, G(SP_T_W2), f, nullptr, 0, nullptr, dm, f, Tp, 0};
-        if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        if (!frozen) SP_OP(e, SP_OP_GEMM_DW, spk_launch_gemm(st, EPI_F32, g));
         // dz[T,f] = dh W2
         g = GemmArgs{dhb, dm, OP_KMAJOR, W(SP_T_W2), f, OP_RMAJOR, dz, f, nullptr, 0, nullptr, T, f, dm, 0};
-        SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
+        SP_OP(e, SP_OP_GEMM_DX, spk_launch_gemm(st, EPI_BF16, g));
         // du = dz gelu'(u), in place over u
-        SP_HIP(e, spk_launch_gelu_bwd(st, dz, u, (size_t)T * f));
+        SP_OP(e, SP_OP_ACT_BWD, spk_launch_gelu_bwd(st, dz, u, (size_t)T * f));
         if ((rc = bias_grad(u, f, SP_T_B1)) != SP_OK) return rc;
         // dW1[f,d] = du^T m
         g = GemmArgs{u, f, OP_RMAJOR, m, dm, OP_RMAJOR, G(SP_T_W1), dm, nullptr, 0, nullptr, f, dm, Tp, 0};
-        if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        if (!frozen) SP_OP(e, SP_OP_GEMM_DW, spk_launch_gemm(st, EPI_F32, g));
         // dm[T,d] = du W1  (fp32)
         g = GemmArgs{u, f, OP_KMAJOR, W(SP_T_W1), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, f, 0};
-        SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+        SP_OP(e, SP_OP_GEMM_DX, spk_launch_gemm(st, EPI_F32, g));
         // second norm: dh += d(layernorm)(h1) applied to dm; its gain and bias gradients
-        SP_HIP(e, spk_launch_layernorm_bwd(st, da, h1, W(SP_T_LN2_G), dh, dhb, part, G(SP_T_LN2_G), G(SP_T_LN2_B), T,
+        SP_OP(e, SP_OP_NORM_BWD, spk_launch_layernorm_bwd(st, da, h1, W(SP_T_LN2_G), dh, dhb, part, G(SP_T_LN2_G), G(SP_T_LN2_B), T,
                                            dm, d.norm_eps));
     }
 
@@ -256,26 +256,26 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
     if (!dec && (rc = bias_grad(dhb, dm, SP_T_BO)) != SP_OK) return rc;
     // dWo[d,nq] = dh^T o
     g = GemmArgs{dhb, dm, OP_RMAJOR, o, nq, OP_RMAJOR, G(t_wo), nq, nullptr, 0, nullptr, dm, nq, Tp, 0};
-    if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    if (!frozen) SP_OP(e, SP_OP_GEMM_DW, spk_launch_gemm(st, EPI_F32, g));
     // do[T,nq] = dh Wo
     g = GemmArgs{dhb, dm, OP_KMAJOR, W(t_wo), nq, OP_RMAJOR, dob, nq, nullptr, 0, nullptr, T, nq, dm, 0};
-    SP_HIP(e, spk_launch_gemm(st, EPI_BF16, g));
-    SP_HIP(e, spk_launch_attn_delta(st, dob, o, delta, B, S, d.n_q_heads, d.head_dim));
+    SP_OP(e, SP_OP_GEMM_DX, spk_launch_gemm(st, EPI_BF16, g));
+    SP_OP(e, SP_OP_ATTENTION_BWD, spk_launch_attn_delta(st, dob, o, delta, B, S, d.n_q_heads, d.head_dim));
     AttnBwdArgs ab{qkv, dob, lse, delta, dqkv};
-    SP_HIP(e, spk_launch_attention_bwd(st, ab, as));
+    SP_OP(e, SP_OP_ATTENTION_BWD, spk_launch_attention_bwd(st, ab, as));
     if (!dec && (rc = bias_grad(dqkv, nqkv, SP_T_BQKV)) != SP_OK) return rc;
     // dWqkv[nqkv,d] = dqkv^T a
     g = GemmArgs{dqkv, nqkv, OP_RMAJOR, a, dm, OP_RMAJOR, G(t_wqkv), dm, nullptr, 0, nullptr, nqkv, dm, Tp, 0};
-    if (!frozen) SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    if (!frozen) SP_OP(e, SP_OP_GEMM_DW, spk_launch_gemm(st, EPI_F32, g));
     // da[T,d] = dqkv Wqkv (fp32)
     g = GemmArgs{dqkv, nqkv, OP_KMAJOR, W(t_wqkv), dm, OP_RMAJOR, da, dm, nullptr, 0, nullptr, T, dm, nqkv, 0};
-    SP_HIP(e, spk_launch_gemm(st, EPI_F32, g));
+    SP_OP(e, SP_OP_GEMM_DX, spk_launch_gemm(st, EPI_F32, g));
     // first norm: dh += d(norm)(x_l) applied to da; its parameter gradients.  dh is now
     // dL/d(layer input).
     if (dec)
-        SP_HIP(e, spk_launch_rmsnorm_bwd(st, da, x_l, W(SP_T_G1), dh, dhb, part, G(SP_T_G1), T, dm, d.norm_eps));
+        SP_OP(e, SP_OP_NORM_BWD, spk_launch_rmsnorm_bwd(st, da, x_l, W(SP_T_G1), dh, dhb, part, G(SP_T_G1), T, dm, d.norm_eps));
     else
-        SP_HIP(e, spk_launch_layernorm_bwd(st, da, x_l, W(SP_T_LN1_G), dh, dhb, part, G(SP_T_LN1_G), G(SP_T_LN1_B), T,
+        SP_OP(e, SP_OP_NORM_BWD, spk_launch_layernorm_bwd(st, da, x_l, W(SP_T_LN1_G), dh, dhb, part, G(SP_T_LN1_G), G(SP_T_LN1_B), T,
                                            dm, d.norm_eps));
 
     if (frozen) return SP_OK;
@@ -295,6 +295,6 @@ int sp_layer_backward(sp_engine* e, int layer, const unsigned char* w, int B, in
 
 int sp_train_end(sp_engine* e, float* dx_dev, int B, int S) {
     if (dx_dev)
-        SP_HIP(e, spk_launch_copy_f32(e->compute, e->wsp<float>(e->ws.dh), dx_dev, (size_t)B * S * e->desc.d_model));
+        SP_OP(e, SP_OP_COPY, spk_launch_copy_f32(e->compute, e->wsp<float>(e->ws.dh), dx_dev, (size_t)B * S * e->desc.d_model));
     return SP_OK;
 }

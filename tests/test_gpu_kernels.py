@@ -314,7 +314,9 @@ def test_swiglu_backward(T, f):
     assert np.all(np.abs(got - ref) <= BF16_EPS * np.abs(ref) + 1e-6)
 
 
-@pytest.mark.parametrize("T,d", [(300, 256), (37, 2048), (5, 8192), (700, 512)])
+@pytest.mark.parametrize("T,d", [(300, 256), (37, 2048), (5, 8192), (700, 512),
+                                 # 1024 rows and more of at most 2048 elements: one wave per row
+                                 (1501, 2048), (1100, 320), (1024, 64), (2050, 1280)])
 def test_rmsnorm_backward(T, d):
     rng = np.random.default_rng(T * 3 + d)
     da = rng.standard_normal((T, d)).astype(np.float32)

@@ -182,12 +182,19 @@ def test_debug_and_comparator_modes_do_not_change_bits(tiny):
     (base,), _ = tiny.run(8, 8)
     for flags in (sp.SP_FLAG_POISON, sp.SP_FLAG_NO_OVERLAP, sp.SP_FLAG_TIMING, sp.SP_FLAG_WRAP_PREFETCH,
                   sp.SP_FLAG_POISON | sp.SP_FLAG_WRAP_PREFETCH | sp.SP_FLAG_TIMING,
-                  sp.SP_FLAG_DELAY | sp.SP_FLAG_POISON, sp.SP_FLAG_DELAY | sp.SP_FLAG_POISON | sp.SP_FLAG_WRAP_PREFETCH):
+                  sp.SP_FLAG_DELAY | sp.SP_FLAG_POISON, sp.SP_FLAG_DELAY | sp.SP_FLAG_POISON | sp.SP_FLAG_WRAP_PREFETCH,
+                  sp.SP_FLAG_OP_TIMING):
         outs, st = tiny.run(1, 1, flags=flags, calls=3)
         for y in outs:
             assert np.array_equal(y.view(np.uint32), base.view(np.uint32)), flags
         if flags & sp.SP_FLAG_WRAP_PREFETCH:
             assert st.h2d_copies == 4 * 3 + 2 and st.last_h2d_copies == 4
+        if flags & sp.SP_FLAG_OP_TIMING:
+            # 4 layers x 3 calls: one launch of each projection per layer and call, two norms
+            ops = dict(zip(sp.SP_OP_NAMES, zip(st.op_launches, st.op_ms)))
+            assert ops["gemm_qkv"][0] == 12 and ops["norm"][0] == 24 and ops["attention"][0] == 12
+            assert ops["gemm_ffn1"][0] == 12 and ops["copy"][0] == 3 and ops["gemm_dw"][0] == 0
+            assert all(ms > 0 for n, ms in ops.values() if n)
         if flags & sp.SP_FLAG_TIMING:
             assert st.n_timed == 4 and st.n_ops == 4 and st.wall_ms > 0 and st.copy_busy_ms > 0
             assert 0 <= st.copy_hidden_ms <= st.copy_busy_ms + 1e-3
