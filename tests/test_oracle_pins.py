@@ -354,12 +354,24 @@ def test_zero_loss_gives_zero_gradients():
     assert all(not g.any() for gl in grads for g in gl.values())
 
 
-def test_float32_mode_tracks_float64():
+@pytest.mark.parametrize("arch,causal", [(O.DECODER, True), (O.ENCODER, False)])
+def test_float32_mode_tracks_float64(arch, causal):
+    """The float32 mode (the one the full-width GPU tests and the stored full-depth runs use) stays
+    within float32 rounding of the float64 mode, forward and backward, for both layer kinds; the
+    float64 mode is what the scalar-loop definitions and finite differences above pin."""
     B, S = 2, 8
-    sh = small_shape(O.DECODER, d=16, f=24, Hq=4, Hkv=4, hd=4)
+    sh = small_shape(arch, d=16, f=24, Hq=4, Hkv=2 if arch == O.DECODER else 4, hd=4, causal=causal)
     layers = [rand_layer(sh) for _ in range(sh.n_layers)]
     x = RNG.standard_normal((B, S, sh.d_model))
+    t = RNG.standard_normal((B, S, sh.d_model))
     y64 = O.stack_forward(x, layers, B, S, sh, dtype=np.float64)
     y32 = O.stack_forward(x, layers, B, S, sh, dtype=np.float32)
     assert y32.dtype == np.float32
     np.testing.assert_allclose(y32, y64, rtol=0, atol=2e-5 * np.max(np.abs(y64)))
+    _, l64, dx64, g64 = O.stack_forward_backward(x, t, layers, B, S, sh, dtype=np.float64)
+    _, l32, dx32, g32 = O.stack_forward_backward(x, t, layers, B, S, sh, dtype=np.float32)
+    assert abs(l32 - l64) <= 1e-5 * l64
+    np.testing.assert_allclose(dx32, dx64, rtol=0, atol=5e-5 * np.max(np.abs(dx64)))
+    for a, b in zip(g32, g64):
+        for n in b:
+            np.testing.assert_allclose(a[n], b[n], rtol=0, atol=5e-5 * np.max(np.abs(b[n])) + 1e-12, err_msg=n)
