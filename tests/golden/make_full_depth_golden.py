@@ -2,7 +2,10 @@
 """Writes tests/golden/full_depth_<workload>.npz: the CPU oracle's output of a WHOLE workload
 stack (every layer, full token count) on sampled token rows, plus per-layer norms.
 
-    python tests/golden/make_full_depth_golden.py llama7b vith llama70b train1p3b
+    python tests/golden/make_full_depth_golden.py [--checkpoint DIR] llama7b vith llama70b train1p3b
+
+With --checkpoint an inference run keeps its hidden state and per-layer norms in DIR after every
+layer and a later run with the same DIR resumes there (the 70B-shaped stack takes hours).
 
 This script calls only oracle/ and the seeded input generator (synth.py); nothing in the files it
 writes comes from the HIP path.  The full-depth runs take minutes to hours of CPU time (the 80-layer
@@ -63,7 +66,7 @@ def oracle_shape(w):
                         w.causal, w.norm_eps)
 
 
-def run(name, dtype=np.float32):
+def run(name, dtype=np.float32, ckpt_dir=None):
     w = synth.WORKLOADS[name]
     shape = oracle_shape(w)
     distinct = DISTINCT.get(name, w.n_layers)
@@ -74,12 +77,20 @@ def run(name, dtype=np.float32):
     if not w.training:
         h = x.astype(dtype)
         amax, fro = [], []
-        for l in range(w.n_layers):
+        ckpt = os.path.join(ckpt_dir, f"{name}_state.npz") if ckpt_dir else None
+        if ckpt and os.path.exists(ckpt):
+            with np.load(ckpt) as c:
+                h, amax, fro = c["h"].astype(dtype), list(c["amax"]), list(c["fro"])
+            print(f"[{name}] resumed after layer {len(amax)}", flush=True)
+        for l in range(len(amax), w.n_layers):
             wl = {k: O.decode_bf16(v, dtype) for k, v in synth.make_layer(w, l % distinct).items()}
             h = O.layer_forward(h, wl, w.batch, w.seq, shape)
             amax.append(float(np.max(np.abs(h))))
             fro.append(float(np.sqrt(np.sum(h.astype(np.float64) ** 2))))
             print(f"[{name}] layer {l + 1}/{w.n_layers}: max|h| {amax[-1]:.4g} ({time.time() - t0:.0f} s)", flush=True)
+            if ckpt:
+                np.savez(ckpt + ".tmp.npz", h=h, amax=np.array(amax), fro=np.array(fro))
+                os.replace(ckpt + ".tmp.npz", ckpt)
         y = h
     else:
         t = synth.make_input(w, "target")
@@ -111,5 +122,11 @@ def run(name, dtype=np.float32):
 
 
 if __name__ == "__main__":
-    for n in sys.argv[1:] or ["llama7b", "vith", "train1p3b", "llama70b"]:
-        run(n)
+    argv = sys.argv[1:]
+    ckpt_dir = None
+    if argv[:1] == ["--checkpoint"]:
+        ckpt_dir = argv[1]
+        os.makedirs(ckpt_dir, exist_ok=True)
+        argv = argv[2:]
+    for n in argv or ["llama7b", "vith", "train1p3b", "llama70b"]:
+        run(n, ckpt_dir=ckpt_dir)
