@@ -202,6 +202,13 @@ def measure(args, name, steps, warmup, ceiling, headline, blob_cache):
         # slots: a budget of that many layer slots instead of the workload's own
         if training:
             flags |= sp.SP_FLAG_TRAINING | (sp.SP_FLAG_KEEP_ACTIVATIONS if keep else 0)
+        # cross-check of the byte budget from outside the library: device memory torch hands out
+        # between here and the end of the timed steps (the arena is the only allocation; x, y, targets,
+        # the KV cache and the loss exist already), and the driver's free-memory figure
+        torch.cuda.synchronize()
+        torch.cuda.reset_peak_memory_stats()
+        alloc0 = torch.cuda.memory_allocated()
+        free0 = torch.cuda.mem_get_info()[0]
         eng = sp.Engine(desc, blobs, kk, pp, budget_layers=slots or budget_layers,
                         budget_bytes=None if slots else budget_bytes, flags=flags,
                         pinned=pinned, frozen=frozen, units=units)
@@ -246,10 +253,13 @@ def measure(args, name, steps, warmup, ceiling, headline, blob_cache):
         wall = time.perf_counter() - tw
         ms = e0.elapsed_time(e1)
         st = eng.stats()
+        torch_peak = torch.cuda.max_memory_allocated() - alloc0
+        driver_drop = free0 - torch.cuda.mem_get_info()[0]
         y = ((loss if frozen else dxd) if training else y1 if decoding else yd).cpu().numpy().copy()
         eng.destroy()
         return dict(ms_per_step=ms / steps, wall_ms_per_step=wall * 1e3 / steps, stats=st, y=y,
-                    budget=eng.budget_bytes, update_ms_per_step=upd_s[0] * 1e3 / steps)
+                    budget=eng.budget_bytes, update_ms_per_step=upd_s[0] * 1e3 / steps,
+                    torch_peak_bytes=int(torch_peak), driver_free_drop_bytes=int(driver_drop))
 
     wrap = not (headline and args.no_wrap) and not training
     base_flags = sp.SP_FLAG_WRAP_PREFETCH if wrap else 0
@@ -334,6 +344,13 @@ def measure(args, name, steps, warmup, ceiling, headline, blob_cache):
 
     extra = {
         "peak_hbm_bytes": int(st.plan.arena_bytes_used), "budget_bytes": int(main_run["budget"]),
+        # seen from outside the library over the timed run: torch's peak of newly allocated device
+        # bytes (the arena of budget_bytes + one 4 KiB alignment page; the library itself allocates
+        # nothing) and the drop of the driver's free-memory figure (torch's allocator rounds up and
+        # may reuse cached blocks, so this one only bounds it)
+        "hbm_cross_check": {"torch_max_memory_allocated_delta": main_run["torch_peak_bytes"],
+                            "driver_free_memory_drop": main_run["driver_free_drop_bytes"],
+                            "within_budget_plus_page": bool(main_run["torch_peak_bytes"] <= main_run["budget"] + 4096)},
         "h2d_gbps_over_wall": round(h2d_gbps_wall, 2),
         "h2d_gbps_while_copying": round(h2d_gbps_busy, 2) if h2d_gbps_busy else None,
         "h2d_ceiling_gbps": round(ceiling, 2),
@@ -537,7 +554,7 @@ def measure(args, name, steps, warmup, ceiling, headline, blob_cache):
 
 
 # what a short run of another workload contributes to the one JSON line
-OTHER_KEYS = ("ms_per_step", "value", "unit", "steps", "config", "roofline", "peak_hbm_bytes", "budget_bytes",
+OTHER_KEYS = ("ms_per_step", "value", "unit", "steps", "config", "roofline", "peak_hbm_bytes", "budget_bytes", "hbm_cross_check",
               "h2d_gbps_over_wall", "h2d_frac_of_ceiling", "d2h_gbps_over_wall", "copy_hidden_frac",
               "copy_hidden_frac_bound", "overlap_efficiency", "copy_stream_idle_frac", "images_per_s", "ms_per_token",
               "host_update_loop", "op_table", "op_table_kernel_ms_per_step", "parity_sample", "parity_max_rel_err", "parity_err_over_added", "cpu_baseline")
@@ -588,7 +605,14 @@ def main():
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    log(f"[bench] {torch.cuda.get_device_name(0)}; host cores {os.cpu_count()}")
+    prop = torch.cuda.get_device_properties(0)
+    try:
+        ram_gb = os.sysconf("SC_PAGE_SIZE") * os.sysconf("SC_PHYS_PAGES") / 1e9
+    except (ValueError, OSError):
+        ram_gb = float("nan")
+    log(f"[bench] {torch.cuda.get_device_name(0)}: {prop.multi_processor_count} CUs, "
+        f"{prop.total_memory / 1e9:.0f} GB, engine clock {getattr(prop, 'clock_rate', 0) / 1e3:.0f} MHz, "
+        f"HIP {torch.version.hip}; host cores {os.cpu_count()}, RAM {ram_gb:.0f} GB")
     ceiling = copy_ceiling_gbps(torch)
     log(f"[bench] plain pinned H2D copy ceiling: {ceiling:.1f} GB/s")
 

@@ -38,8 +38,11 @@ int spk_norm(void* stream, const float* h, const uint16_t* gain, const uint16_t*
  * tile: 0 = library heuristic; 1..4 force a block tile of the register-staged kernel (128x128, 128x256,
  *       256x256 with 4 waves, 256x256 with 8 waves), 5..8 of the LDS-DMA kernel (256x256, 128x256, 128x128,
  *       256x192 -- the last not with epilogue 3; when an operand has form 1 a register-staged kernel runs
- *       instead), 10 the 256x320 tile of the LDS-DMA kernel (not with epilogue 3), 9 the weight-streaming kernel for M <= 64 rows (both forms 0; the heuristic's choice
- *       for such M: a decode step reads every weight once and re-uses nothing).
+ *       instead), 10 the 256x320 tile of the LDS-DMA kernel (not with epilogue 3), 9 the weight-streaming
+ *       kernel for M <= 64 rows (both forms 0; the heuristic's choice for such M: a decode step reads every
+ *       weight once and re-uses nothing) with its own choice of rows per work-group, 11 / 12 / 13 the same
+ *       kernel with 16 / 32 / 64 rows per work-group (more rows than that become further work-groups on
+ *       the same 16 output columns).
  * K % 64 == 0, N % 8 == 0. */
 int spk_gemm(void* stream, int epilogue, const uint16_t* A, int lda, int a_form, const uint16_t* W, int ldw,
              int w_form, void* C, int ldc, const float* R, int ldr, const uint16_t* bias, int M, int N, int K,

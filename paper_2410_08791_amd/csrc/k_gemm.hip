@@ -826,6 +826,9 @@ hipError_t launch_tile(hipStream_t st, const GemmArgs& g) {
         case 8: if (DMA_OK && EPI != EPI_SWIGLU_BF16) return launch_dma<256, 192, NOSWIGLU, 8, 4>(st, g); break;
         case 9: if (DMA_OK) return spk_launch_gemm_skinny(st, EPI, g); break;
         case 10: if (DMA_OK && EPI != EPI_SWIGLU_BF16) return launch_dma<256, 320, NOSWIGLU, 8, 4>(st, g); break;
+        case 11: if (DMA_OK) return spk_launch_gemm_skinny(st, EPI, g, 16); break;
+        case 12: if (DMA_OK) return spk_launch_gemm_skinny(st, EPI, g, 32); break;
+        case 13: if (DMA_OK) return spk_launch_gemm_skinny(st, EPI, g, 64); break;
     }
     return hipErrorInvalidValue;
 }

@@ -5,13 +5,25 @@
 // With so few rows the weight matrix is read once and nothing of it is re-used: the kernel is
 // bound by how fast W streams from HBM, and the 256-row tiles of the large kernels leave most of
 // the chip without work (N / 128 work-groups, one k-tile in flight each).  Here a work-group owns
-// 16 output columns and the whole contraction, split over its 8 waves; a wave issues its loads
-// straight from global memory, eight k-steps (8 x 1 KiB of W) in flight, and contracts with
-// v_mfma_f32_16x16x32_bf16: W rows as the A operand, 16 tokens as the B operand (one to four such
-// token tiles per W fragment), so a lane ends up with four consecutive output columns of one
-// token per tile.  The eight partial results are summed through LDS in wave order (deterministic)
-// by wave 0, which applies the epilogue.
-// N / 16 work-groups: 256 or more on every projection of the workloads.
+// 16 output columns, 16 * MT activation rows and the whole contraction, split over its 8 waves; a
+// wave issues its loads straight from global memory, eight k-steps (8 x 1 KiB of W) in flight, and
+// contracts with v_mfma_f32_16x16x32_bf16: W rows as the A operand, 16 tokens as the B operand
+// (MT such token tiles per W fragment), so a lane ends up with four consecutive output columns of
+// one token per tile.  The eight partial results are summed through LDS in wave order
+// (deterministic) by wave 0, which applies the epilogue.
+//
+// More than 16 rows can be taken two ways: MT token tiles in one work-group (every W fragment
+// fetched once, N / 16 work-groups), or slices of 16 * MT rows in work-groups of their own.  The
+// slices of one column block sit next to each other in the dispatch order and on the same XCD, so
+// all but the first find the block in that XCD's L2 (counters: HBM reads are 1.3 x the weight
+// bytes with four slices, 1.1 x with one).  One slice is the faster form whenever N / 16 work-groups fill the
+// chip; N = 1280 (the ViT-H width) is 80 work-groups, a third of the CUs, and there two slices
+// of 32 rows win: 64 x 1280 x 5120 takes 26 -> 17 us, 64 x 1280 x 1280 10 -> 7 us.
+// (Measured and not kept: a ring of k-steps re-requested one by one instead of bursts of eight,
+// a contraction-index order that uses whole 128-byte lines per step pair, four waves instead of
+// eight -- all within 5 % of this form.  With one row tile the kernel streams W at 4.2-5.4 TB/s,
+// against 5.7 TB/s for the library's plain row-wise kernels; with 64 rows the L2-to-L1 traffic of
+// the re-read activation rows, 4 x the weight bytes, bounds it at ~1.4 TB/s of weights.)
 #include "sp_common.h"
 #include "sp_kernels.h"
 
@@ -24,9 +36,10 @@ struct SkinnyDev {
     const bf16_t* A; const bf16_t* W; void* C; const float* R; const bf16_t* bias;
     int lda, ldw, ldc, ldr;
     int M, N, K;
+    int slices;                 // work-groups per column block; slice i owns rows 16 * MT * i ..
 };
 
-// MT: token tiles of 16 rows (M <= 16 * MT)
+// MT: token tiles of 16 rows per work-group
 template <int EPI, int MT>
 __global__ __launch_bounds__(SK_WAVES * 64) void gemm_skinny_kernel(SkinnyDev p) {
     constexpr bool SWIGLU = (EPI == EPI_SWIGLU_BF16);
@@ -38,7 +51,12 @@ __global__ __launch_bounds__(SK_WAVES * 64) void gemm_skinny_kernel(SkinnyDev p)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 15, kb = lane >> 4;
-    const int n0 = blockIdx.x * SK_COLS;
+    // dispatch order: groups of 8 column blocks (one per XCD) x slices
+    const int per_group = 8 * p.slices;
+    const int in_group = blockIdx.x % per_group;
+    const int n0 = ((blockIdx.x / per_group) * 8 + (in_group & 7)) * SK_COLS;
+    const int m0 = (in_group >> 3) * (16 * MT);
+    if (n0 >= p.N) return;       // the last group may be short of column blocks (the whole work-group leaves)
 
     // this wave's share of the K / 32 contraction steps
     const int steps = p.K / 32;
@@ -51,7 +69,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void gemm_skinny_kernel(SkinnyDev p)
     const bf16_t* wp2 = SWIGLU ? wp + (size_t)p.N * p.ldw : wp;   // the matching "up" rows
     const bf16_t* xp[MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) xp[t] = p.A + (size_t)min(t * 16 + r, p.M - 1) * p.lda + kb * 8;
+    for (int t = 0; t < MT; ++t) xp[t] = p.A + (size_t)min(m0 + t * 16 + r, p.M - 1) * p.lda + kb * 8;
 
     f32x4_t acc[NACC][MT];
 #pragma unroll
@@ -95,13 +113,13 @@ __global__ __launch_bounds__(SK_WAVES * 64) void gemm_skinny_kernel(SkinnyDev p)
     __syncthreads();
     if (wave != 0) return;
 
-    // accumulator layout of token tile t: lane -> token m = 16 t + (lane & 15), output columns
-    // n0 + 4 * (lane >> 4) + 0..3
+    // accumulator layout of token tile t: lane -> token m = m0 + 16 t + (lane & 15), output
+    // columns n0 + 4 * (lane >> 4) + 0..3
     const int n = n0 + 4 * (lane >> 4);
     if (n >= p.N) return;                    // N % 8 == 0: a group of four columns is inside or outside
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
-        const int m = t * 16 + (lane & 15);
+        const int m = m0 + t * 16 + (lane & 15);
         if (m >= p.M) continue;
         f32x4_t sum[NACC];
 #pragma unroll
@@ -142,15 +160,22 @@ __global__ __launch_bounds__(SK_WAVES * 64) void gemm_skinny_kernel(SkinnyDev p)
     }
 }
 
+// rows_per_group: 0 = chosen here from the shape, else 16, 32 or 64 rows per work-group
 template <int EPI>
-hipError_t launch_skinny(hipStream_t st, const GemmArgs& g) {
+hipError_t launch_skinny(hipStream_t st, const GemmArgs& g, int rows_per_group) {
     SkinnyDev d;
     d.A = g.A; d.W = g.W; d.C = g.C; d.R = g.R; d.bias = g.bias;
     d.lda = g.lda; d.ldw = g.ldw; d.ldc = g.ldc; d.ldr = g.ldr;
     d.M = g.M; d.N = g.N; d.K = g.K;
-    const dim3 grid((g.N + SK_COLS - 1) / SK_COLS), block(SK_WAVES * 64);
-    if (g.M <= 16) gemm_skinny_kernel<EPI, 1><<<grid, block, 0, st>>>(d);
-    else if (g.M <= 32) gemm_skinny_kernel<EPI, 2><<<grid, block, 0, st>>>(d);
+    const int col_blocks = (g.N + SK_COLS - 1) / SK_COLS;
+    int rpg = rows_per_group;
+    if (!rpg) rpg = (g.M > 32 && col_blocks < 128) ? 32 : 64;
+    if (rpg > 32 && g.M <= 32) rpg = 32;
+    if (rpg > 16 && g.M <= 16) rpg = 16;
+    d.slices = (g.M + rpg - 1) / rpg;
+    const dim3 grid((col_blocks + 7) / 8 * 8 * d.slices), block(SK_WAVES * 64);
+    if (rpg == 16) gemm_skinny_kernel<EPI, 1><<<grid, block, 0, st>>>(d);
+    else if (rpg == 32) gemm_skinny_kernel<EPI, 2><<<grid, block, 0, st>>>(d);
     else gemm_skinny_kernel<EPI, 4><<<grid, block, 0, st>>>(d);
     return hipGetLastError();
 }
@@ -159,14 +184,15 @@ hipError_t launch_skinny(hipStream_t st, const GemmArgs& g) {
 
 // Shapes and alignment have been checked by spk_launch_gemm (K % 64 == 0, N % 8 == 0, leading
 // dimensions % 8 == 0 resp. % 4 == 0, 16-byte aligned bases); this launcher adds its own limits.
-hipError_t spk_launch_gemm_skinny(hipStream_t st, int epi, const GemmArgs& g) {
+hipError_t spk_launch_gemm_skinny(hipStream_t st, int epi, const GemmArgs& g, int rows_per_group) {
+    if (rows_per_group != 0 && rows_per_group != 16 && rows_per_group != 32 && rows_per_group != 64) return hipErrorInvalidValue;
     if (g.M < 1 || g.M > SPK_SKINNY_MAX_ROWS || g.a_form != OP_KMAJOR || g.w_form != OP_KMAJOR) return hipErrorInvalidValue;
     switch (epi) {
-        case EPI_BF16: return launch_skinny<EPI_BF16>(st, g);
-        case EPI_RESID_F32: return g.R ? launch_skinny<EPI_RESID_F32>(st, g) : hipErrorInvalidValue;
-        case EPI_GELU_BF16: return g.bias ? launch_skinny<EPI_GELU_BF16>(st, g) : hipErrorInvalidValue;
-        case EPI_SWIGLU_BF16: return !g.bias ? launch_skinny<EPI_SWIGLU_BF16>(st, g) : hipErrorInvalidValue;
-        case EPI_F32: return launch_skinny<EPI_F32>(st, g);
+        case EPI_BF16: return launch_skinny<EPI_BF16>(st, g, rows_per_group);
+        case EPI_RESID_F32: return g.R ? launch_skinny<EPI_RESID_F32>(st, g, rows_per_group) : hipErrorInvalidValue;
+        case EPI_GELU_BF16: return g.bias ? launch_skinny<EPI_GELU_BF16>(st, g, rows_per_group) : hipErrorInvalidValue;
+        case EPI_SWIGLU_BF16: return !g.bias ? launch_skinny<EPI_SWIGLU_BF16>(st, g, rows_per_group) : hipErrorInvalidValue;
+        case EPI_F32: return launch_skinny<EPI_F32>(st, g, rows_per_group);
     }
     return hipErrorInvalidValue;
 }

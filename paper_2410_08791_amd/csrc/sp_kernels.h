@@ -55,7 +55,7 @@ hipError_t spk_launch_gemm(hipStream_t st, int epilogue, const GemmArgs& g);
 // contraction-contiguous): streams W once, 16 output columns per work-group, one to four tiles of
 // 16 rows per weight fragment.
 constexpr int SPK_SKINNY_MAX_ROWS = 64;
-hipError_t spk_launch_gemm_skinny(hipStream_t st, int epilogue, const GemmArgs& g);
+hipError_t spk_launch_gemm_skinny(hipStream_t st, int epilogue, const GemmArgs& g, int rows_per_group = 0);
 // What tile = 0 resolves to for a shape (host code, no launch): rows [0, body_rows) run with
 // `tile`, rows [body_rows, M) -- none when body_rows == M -- with `tail_tile`.
 struct GemmPlan { int tile, body_rows, tail_tile; };

@@ -18,7 +18,7 @@ extern "C" int spk_norm(void* stream, const float* h, const uint16_t* gain, cons
 extern "C" int spk_gemm(void* stream, int epilogue, const uint16_t* A, int lda, int a_form, const uint16_t* W,
                         int ldw, int w_form, void* C, int ldc, const float* R, int ldr, const uint16_t* bias,
                         int M, int N, int K, int tile) {
-    if (a_form < 0 || a_form > 1 || w_form < 0 || w_form > 1 || tile < 0 || tile > 10) return SP_ERR_INVALID_ARG;
+    if (a_form < 0 || a_form > 1 || w_form < 0 || w_form > 1 || tile < 0 || tile > 13) return SP_ERR_INVALID_ARG;
     GemmArgs g{A, lda, a_form, W, ldw, w_form, C, ldc, R, ldr, bias, M, N, K, tile};
     return st(spk_launch_gemm((hipStream_t)stream, epilogue, g));
 }

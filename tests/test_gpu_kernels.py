@@ -79,14 +79,15 @@ def test_gemm_kmajor(epi, M, N, K, tile):
     assert np.all(np.abs(got - ref) <= tol + 1e-6), float(np.max(np.abs(got - ref)))
 
 
-@pytest.mark.parametrize("tile", [9, 0])
+@pytest.mark.parametrize("tile", [9, 0, 11, 12, 13])
 @pytest.mark.parametrize("M,N,K", [(1, 8, 64), (8, 328, 4096), (16, 24, 320), (5, 1288, 1088), (13, 4096, 192),
                                    (17, 40, 448), (32, 328, 1280), (33, 72, 64), (64, 5128, 1280)])
 @pytest.mark.parametrize("epi", [sp.EPI_BF16, sp.EPI_RESID_F32, sp.EPI_GELU_BF16, sp.EPI_SWIGLU_BF16, sp.EPI_F32])
 def test_gemm_few_rows_streams_the_weights(epi, M, N, K, tile):
     """At most 64 activation rows (a decode step, the ragged last rows of a long launch): the
-    weight-streaming kernel, forced (tile 9) and as the heuristic's choice; N not a multiple of the
-    16 columns of a work-group, K / 32 not a multiple of the eight waves that share the
+    weight-streaming kernel, forced (tile 9; 11-13 with 16, 32, 64 rows per work-group, the rest of
+    the rows in further work-groups) and as the heuristic's choice; N not a multiple of the
+    16 columns of a work-group nor of the 8 column blocks of a dispatch group, K / 32 not a multiple of the eight waves that share the
     contraction, M at and next to the limits of its one, two and four 16-row tiles."""
     rng = np.random.default_rng(M + N * 3 + K * 5 + epi)
     Ab, A = rand_bf16(rng, (M, K))
