@@ -505,7 +505,15 @@ def measure(args, name, steps, warmup, ceiling, headline, blob_cache):
             ts = synth.make_input(w, "target")[:cb]
             ref = O.stack_forward_backward(xs, ts, views[:n], cb, S, shape, dtype=np.float32)[0]
         else:
-            ref = O.stack_forward(xs, views, cb, S, shape, dtype=np.float32, n_layers=n)
+            # a deep sample runs as the oracle's own forward over consecutive groups of layers
+            # (the same composition as one call), so that a run of minutes reports where it is
+            ref, l0 = xs, 0
+            while l0 < n:
+                l1 = min(l0 + 4, n)
+                ref = O.stack_forward(ref, views[l0:l1], cb, S, shape, dtype=np.float32, n_layers=l1 - l0)
+                if n > 4:
+                    log(f"[bench] oracle: {l1} of {n} layers ({time.perf_counter() - t0:.0f} s)")
+                l0 = l1
         dt = time.perf_counter() - t0
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
         scale = (w.n_layers / n) * (B / cb)

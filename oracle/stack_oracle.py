@@ -38,6 +38,14 @@ bit patterns and widened exactly.  No intermediate is ever rounded to bf16:
 arithmetic is carried out in `dtype` (float32 as the benchmark spec of the
 oracle says; float64 for the pins and small parity cases).
 
+One optional departure, off by default: `operands="bf16"` rounds the operands
+of the dense contractions (normed activations, q/k/v, attention weights,
+attention output, SwiGLU/GELU output) to bfloat16, round-to-nearest-even,
+where a bf16 matrix pipeline has to; accumulation stays in `dtype`.  It answers
+one question without any device code: how far does "bf16 compute, fp32
+accumulate" alone move the output of a deep stack away from the exact result?
+The plain mode remains the reference every parity test compares against.
+
 Library primitives used as steps: numpy matmul, exp, sqrt, tanh-free erf
 (scipy.special.erf).  No blocking, fusion or reordering.
 """
@@ -72,6 +80,23 @@ def decode_bf16(a, dtype):
     if a.dtype == np.uint16:
         return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(dtype)
     return a.astype(dtype, copy=False)
+
+
+def round_bf16(x):
+    """Nearest bfloat16 (ties to even) of every element, returned in x's dtype.  Finite inputs."""
+    x = np.asarray(x)
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
+    return r.view(np.float32).astype(x.dtype, copy=False)
+
+
+def _operand(x, operands):
+    if operands is None:
+        return x
+    if operands == "bf16":
+        return round_bf16(x)
+    raise ValueError(operands)
 
 
 def _weights(layer, dtype):
@@ -137,7 +162,7 @@ def attention_probs(q, k, shape: StackShape):
     return softmax_rows(s)
 
 
-def attention(q, k, v, B, S, shape: StackShape):
+def attention(q, k, v, B, S, shape: StackShape, operands=None):
     """softmax(q k^T / sqrt(hd) + mask) v.  q [B*S, Hq*hd], k/v [B*S, Hkv*hd] -> [B*S, Hq*hd]."""
     Hq, Hkv, hd = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
     grp = Hq // Hkv
@@ -147,7 +172,7 @@ def attention(q, k, v, B, S, shape: StackShape):
         qb = q[sl].reshape(S, Hq, hd)
         kb = k[sl].reshape(S, Hkv, hd)
         vb = v[sl].reshape(S, Hkv, hd)
-        p = attention_probs(qb, kb, shape)
+        p = _operand(attention_probs(qb, kb, shape), operands)
         vx = np.repeat(vb, grp, axis=1)
         out[sl] = np.einsum("hij,jhd->ihd", p, vx).reshape(S, Hq * hd)
     return out
@@ -167,33 +192,35 @@ def _split_qkv(qkv, shape):
     return qkv[:, :nq], qkv[:, nq:nq + nk], qkv[:, nq + nk:nq + 2 * nk]
 
 
-def layer_forward(h, w, B, S, shape: StackShape, keep=False):
-    """One layer.  h [B*S, d].  Returns h_out (and the intermediates if keep)."""
+def layer_forward(h, w, B, S, shape: StackShape, keep=False, operands=None):
+    """One layer.  h [B*S, d].  Returns h_out (and the intermediates if keep).
+    operands: None = nothing is rounded; "bf16" = the contractions' operands are (module header)."""
     eps = shape.norm_eps
     f = shape.d_ffn
     c = {"h0": h}
+    rnd = lambda t: _operand(t, operands)
     if shape.arch == DECODER:
-        a = rmsnorm(h, w["g1"], eps)
-        qkv = linear(a, w["wqkv"])
+        a = rnd(rmsnorm(h, w["g1"], eps))
+        qkv = rnd(linear(a, w["wqkv"]))
         q, k, v = _split_qkv(qkv, shape)
-        o = attention(q, k, v, B, S, shape)
+        o = rnd(attention(q, k, v, B, S, shape, operands))
         h1 = h + linear(o, w["wo"])
-        m = rmsnorm(h1, w["g2"], eps)
+        m = rnd(rmsnorm(h1, w["g2"], eps))
         gu = linear(m, w["wgu"])
         g, u = gu[:, :f], gu[:, f:]
-        z = silu(g) * u
+        z = rnd(silu(g) * u)
         h2 = h1 + linear(z, w["wd"])
         if keep:
             c.update(a=a, q=q, k=k, v=v, o=o, h1=h1, m=m, g=g, u=u, z=z)
     elif shape.arch == ENCODER:
-        a = layernorm(h, w["ln1_g"], w["ln1_b"], eps)
-        qkv = linear(a, w["wqkv"], w["bqkv"])
+        a = rnd(layernorm(h, w["ln1_g"], w["ln1_b"], eps))
+        qkv = rnd(linear(a, w["wqkv"], w["bqkv"]))
         q, k, v = _split_qkv(qkv, shape)
-        o = attention(q, k, v, B, S, shape)
+        o = rnd(attention(q, k, v, B, S, shape, operands))
         h1 = h + linear(o, w["wo"], w["bo"])
-        m = layernorm(h1, w["ln2_g"], w["ln2_b"], eps)
+        m = rnd(layernorm(h1, w["ln2_g"], w["ln2_b"], eps))
         u = linear(m, w["w1"], w["b1"])
-        z = gelu(u)
+        z = rnd(gelu(u))
         h2 = h1 + linear(z, w["w2"], w["b2"])
         if keep:
             c.update(a=a, q=q, k=k, v=v, o=o, h1=h1, m=m, u=u, z=z)
@@ -202,12 +229,12 @@ def layer_forward(h, w, B, S, shape: StackShape, keep=False):
     return (h2, c) if keep else h2
 
 
-def stack_forward(x, layers, B, S, shape: StackShape, dtype=np.float32, n_layers=None):
+def stack_forward(x, layers, B, S, shape: StackShape, dtype=np.float32, n_layers=None, operands=None):
     """y = layer_{L-1}(... layer_0(x)).  x [B, S, d] or [B*S, d]; returns [B*S, d]."""
     h = np.asarray(x).reshape(B * S, shape.d_model).astype(dtype)
     L = shape.n_layers if n_layers is None else n_layers
     for l in range(L):
-        h = layer_forward(h, _weights(layers[l], dtype), B, S, shape)
+        h = layer_forward(h, _weights(layers[l], dtype), B, S, shape, operands=operands)
     return h
 
 

@@ -2,10 +2,15 @@
 """Writes tests/golden/full_depth_<workload>.npz: the CPU oracle's output of a WHOLE workload
 stack (every layer, full token count) on sampled token rows, plus per-layer norms.
 
-    python tests/golden/make_full_depth_golden.py [--checkpoint DIR] llama7b vith llama70b train1p3b
+    python tests/golden/make_full_depth_golden.py [--checkpoint DIR] [--legs plain,bf16] llama7b vith llama70b train1p3b
 
-With --checkpoint an inference run keeps its hidden state and per-layer norms in DIR after every
-layer and a later run with the same DIR resumes there (the 70B-shaped stack takes hours).
+Two forward legs: "plain" (nothing rounded: the reference) and "bf16" (the oracle's optional mode
+that rounds the contractions' operands to bf16; it measures, without any device code, how far
+bf16 compute alone moves the output of the deep stack).  With --checkpoint a leg keeps its hidden
+state and per-layer norms in DIR after every layer and a later run with the same DIR resumes
+there (the 70B-shaped stack takes hours per leg); --legs runs a subset (the file is written once
+the plain leg is complete; for a training workload `--legs bf16` adds the operand figures to a
+stored result).
 
 This script calls only oracle/ and the seeded input generator (synth.py); nothing in the files it
 writes comes from the HIP path.  The full-depth runs take minutes to hours of CPU time (the 80-layer
@@ -24,6 +29,10 @@ any intermediate):
     distinct    int              layer l uses the seeded weights of layer l % distinct
 Training workloads add: loss, dx_rows [R, d], dx_absmax, and per layer and weight tensor the
 gradient's absmax and Frobenius norm and 64 sampled entries (flat indices seeded per tensor).
+The bf16 leg adds: ops_y_rows [R, d] (its rows of y), ops_dev_all / ops_dev_rows (max |y_bf16 - y|
+over all elements / over the sampled rows, as a fraction of y_absmax), ops_dev_fro (Frobenius
+ratio), ops_rows_over_2e2 / ops_elems_over_2e2 (rows / elements whose deviation exceeds 2e-2 of
+y_absmax).
 """
 from __future__ import annotations
 
@@ -66,33 +75,70 @@ def oracle_shape(w):
                         w.causal, w.norm_eps)
 
 
-def run(name, dtype=np.float32, ckpt_dir=None):
+class Leg:
+    """One forward pass over the stack, resumable: hidden state and per-layer norms."""
+
+    def __init__(self, name, tag, operands, x, dtype, ckpt_dir):
+        self.tag, self.operands = tag, operands
+        self.h, self.amax, self.fro = x.astype(dtype), [], []
+        self.ckpt = os.path.join(ckpt_dir, f"{name}{'' if tag == 'plain' else '_' + tag}_state.npz") if ckpt_dir else None
+        if self.ckpt and os.path.exists(self.ckpt):
+            with np.load(self.ckpt) as c:
+                self.h, self.amax, self.fro = c["h"].astype(dtype), list(c["amax"]), list(c["fro"])
+            print(f"[{name}/{tag}] resumed after layer {len(self.amax)}", flush=True)
+
+    @property
+    def done(self):
+        return len(self.amax)
+
+    def step(self, wl, w, shape):
+        self.h = O.layer_forward(self.h, wl, w.batch, w.seq, shape, operands=self.operands)
+        self.amax.append(float(np.max(np.abs(self.h))))
+        self.fro.append(float(np.sqrt(np.sum(self.h.astype(np.float64) ** 2))))
+        if self.ckpt:
+            np.savez(self.ckpt + ".tmp.npz", h=self.h, amax=np.array(self.amax), fro=np.array(self.fro))
+            os.replace(self.ckpt + ".tmp.npz", self.ckpt)
+
+
+def forward_legs(name, w, shape, x, distinct, dtype, ckpt_dir, tags):
+    """Runs the requested forward legs layer by layer (weights of a layer are generated once for
+    all legs that are at that layer).  Returns {tag: Leg}; a leg not requested is still loaded
+    from its checkpoint if one exists, so that a later call can finish the job."""
+    legs = {t: Leg(name, t, None if t == "plain" else t, x, dtype, ckpt_dir)
+            for t in ("plain", "bf16") if t in tags or ckpt_dir}
+    t0 = time.time()
+    for l in range(w.n_layers):
+        todo = [g for t, g in legs.items() if t in tags and g.done == l]
+        if not todo:
+            continue
+        wl = {k: O.decode_bf16(v, dtype) for k, v in synth.make_layer(w, l % distinct).items()}
+        for g in todo:
+            g.step(wl, w, shape)
+            print(f"[{name}/{g.tag}] layer {l + 1}/{w.n_layers}: max|h| {g.amax[-1]:.4g} ({time.time() - t0:.0f} s)", flush=True)
+    return legs
+
+
+def operand_stats(y, yb, rows):
+    """How far rounding the contractions' operands to bf16 moves the oracle's own output."""
+    d = np.abs(yb.astype(np.float64) - y.astype(np.float64))
+    mx = float(np.max(np.abs(y)))
+    return dict(ops_y_rows=yb[rows].astype(np.float32), ops_dev_all=float(d.max() / mx),
+                ops_dev_rows=float(d[rows].max() / mx),
+                ops_dev_fro=float(np.sqrt((d ** 2).sum() / (y.astype(np.float64) ** 2).sum())),
+                ops_rows_over_2e2=int((d.max(axis=1) > 2e-2 * mx).sum()),
+                ops_elems_over_2e2=int((d > 2e-2 * mx).sum()))
+
+
+def run(name, dtype=np.float32, ckpt_dir=None, tags=("plain", "bf16")):
     w = synth.WORKLOADS[name]
     shape = oracle_shape(w)
     distinct = DISTINCT.get(name, w.n_layers)
     rows = sample_rows(w)
     x = synth.make_input(w).reshape(w.tokens, w.d_model)
+    path = os.path.join(HERE, f"full_depth_{name}.npz")
     out = {"rows": rows, "distinct": distinct}
     t0 = time.time()
-    if not w.training:
-        h = x.astype(dtype)
-        amax, fro = [], []
-        ckpt = os.path.join(ckpt_dir, f"{name}_state.npz") if ckpt_dir else None
-        if ckpt and os.path.exists(ckpt):
-            with np.load(ckpt) as c:
-                h, amax, fro = c["h"].astype(dtype), list(c["amax"]), list(c["fro"])
-            print(f"[{name}] resumed after layer {len(amax)}", flush=True)
-        for l in range(len(amax), w.n_layers):
-            wl = {k: O.decode_bf16(v, dtype) for k, v in synth.make_layer(w, l % distinct).items()}
-            h = O.layer_forward(h, wl, w.batch, w.seq, shape)
-            amax.append(float(np.max(np.abs(h))))
-            fro.append(float(np.sqrt(np.sum(h.astype(np.float64) ** 2))))
-            print(f"[{name}] layer {l + 1}/{w.n_layers}: max|h| {amax[-1]:.4g} ({time.time() - t0:.0f} s)", flush=True)
-            if ckpt:
-                np.savez(ckpt + ".tmp.npz", h=h, amax=np.array(amax), fro=np.array(fro))
-                os.replace(ckpt + ".tmp.npz", ckpt)
-        y = h
-    else:
+    if w.training and "plain" in tags:
         t = synth.make_input(w, "target")
         layers = [synth.make_layer(w, l % distinct) for l in range(w.n_layers)]
         y, loss, dx, grads = O.stack_forward_backward(x, t, layers, w.batch, w.seq, shape, dtype=dtype)
@@ -111,22 +157,55 @@ def run(name, dtype=np.float32, ckpt_dir=None):
                 idx = grad_sample_index(g.size, l, ti)
                 g_samples[l, ti, :idx.size] = g[idx]
         out.update(grad_absmax=g_absmax, grad_fro=g_fro, grad_samples=g_samples)
-        amax, fro = [float(np.max(np.abs(y)))], [float(np.sqrt(np.sum(y.astype(np.float64) ** 2)))]
-    out.update(y_rows=y[rows].astype(np.float32), y_absmax=float(np.max(np.abs(y))),
-               y_fro=float(np.sqrt(np.sum(y.astype(np.float64) ** 2))),
-               dy_absmax=float(np.max(np.abs(y - x.astype(dtype)))),
-               layer_absmax=np.array(amax), layer_fro=np.array(fro), seconds=time.time() - t0)
-    path = os.path.join(HERE, f"full_depth_{name}.npz")
+        del grads, layers
+        out.update(y_rows=y[rows].astype(np.float32), y_absmax=float(np.max(np.abs(y))),
+                   y_fro=float(np.sqrt(np.sum(y.astype(np.float64) ** 2))),
+                   dy_absmax=float(np.max(np.abs(y - x.astype(dtype)))),
+                   layer_absmax=np.array([float(np.max(np.abs(y)))]),
+                   layer_fro=np.array([float(np.sqrt(np.sum(y.astype(np.float64) ** 2)))]))
+        if "bf16" in tags:
+            # the operand-rounding leg is forward only (y, and through it the loss)
+            legs = forward_legs(name, w, shape, x, distinct, dtype, ckpt_dir, ("bf16",))
+            out.update(operand_stats(y, legs["bf16"].h, rows))
+    elif w.training:
+        # add the operand-rounding leg to a stored training result (its forward run twice here:
+        # the plain output is needed whole for the all-element figures)
+        with np.load(path) as old:
+            out = {k: old[k] for k in old.files}
+        legs = forward_legs(name, w, shape, x, distinct, dtype, ckpt_dir, ("plain", "bf16"))
+        np.testing.assert_array_equal(legs["plain"].h[rows].astype(np.float32), out["y_rows"])
+        out.update(operand_stats(legs["plain"].h, legs["bf16"].h, rows))
+    else:
+        legs = forward_legs(name, w, shape, x, distinct, dtype, ckpt_dir, tags)
+        if "plain" not in legs or legs["plain"].done < w.n_layers:
+            print(f"[{name}] the plain leg is not complete: nothing written; run again with it", flush=True)
+            return
+        g = legs["plain"]
+        y = g.h
+        out.update(y_rows=y[rows].astype(np.float32), y_absmax=float(np.max(np.abs(y))),
+                   y_fro=float(np.sqrt(np.sum(y.astype(np.float64) ** 2))),
+                   dy_absmax=float(np.max(np.abs(y - x.astype(dtype)))),
+                   layer_absmax=np.array(g.amax), layer_fro=np.array(g.fro))
+        if "bf16" in legs and legs["bf16"].done == w.n_layers:
+            out.update(operand_stats(y, legs["bf16"].h, rows))
+            print(f"[{name}] operands rounded to bf16 move the oracle's output by {out['ops_dev_all']:.3e} of its maximum "
+                  f"({out['ops_dev_rows']:.3e} on the sampled rows, Frobenius {out['ops_dev_fro']:.3e})", flush=True)
+    out["seconds"] = time.time() - t0
     np.savez(path, **out)
     print(f"[{name}] wrote {path} ({os.path.getsize(path)} bytes, {time.time() - t0:.0f} s)", flush=True)
 
 
 if __name__ == "__main__":
     argv = sys.argv[1:]
-    ckpt_dir = None
-    if argv[:1] == ["--checkpoint"]:
-        ckpt_dir = argv[1]
-        os.makedirs(ckpt_dir, exist_ok=True)
+    ckpt_dir, tags = None, ("plain", "bf16")
+    while argv and argv[0].startswith("--"):
+        if argv[0] == "--checkpoint":
+            ckpt_dir = argv[1]
+            os.makedirs(ckpt_dir, exist_ok=True)
+        elif argv[0] == "--legs":
+            tags = tuple(argv[1].split(","))
+        else:
+            raise SystemExit(f"unknown option {argv[0]}")
         argv = argv[2:]
     for n in argv or ["llama7b", "vith", "train1p3b", "llama70b"]:
-        run(n, ckpt_dir=ckpt_dir)
+        run(n, ckpt_dir=ckpt_dir, tags=tags)

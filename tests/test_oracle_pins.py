@@ -44,7 +44,25 @@ def bf_linear(x, w, b=None):
     return out
 
 
-def bf_attention(q, k, v, B, S, Hq, Hkv, hd, causal):
+def bf_round(x):
+    """Scalar nearest-bfloat16, ties to even, through the float32 bit pattern (struct, no numpy)."""
+    import struct
+    u = struct.unpack("<I", struct.pack("<f", x))[0]
+    top, rem = u >> 16, u & 0xFFFF
+    if rem > 0x8000 or (rem == 0x8000 and top & 1):
+        top += 1
+    return struct.unpack("<f", struct.pack("<I", (top << 16) & 0xFFFFFFFF))[0]
+
+
+def ident(x):
+    return x
+
+
+def rows(rnd, m):
+    return [[rnd(x) for x in r] for r in m]
+
+
+def bf_attention(q, k, v, B, S, Hq, Hkv, hd, causal, rnd=ident):
     T = B * S
     out = [[0.0] * (Hq * hd) for _ in range(T)]
     grp = Hq // Hkv
@@ -65,43 +83,43 @@ def bf_attention(q, k, v, B, S, Hq, Hkv, hd, causal):
                 for e in range(hd):
                     acc = 0.0
                     for jj, j in enumerate(keys):
-                        acc += ex[jj] / den * v[b * S + j][kvh * hd + e]
+                        acc += rnd(ex[jj] / den) * v[b * S + j][kvh * hd + e]
                     out[b * S + i][h * hd + e] = acc
     return out
 
 
-def bf_decoder_layer(h, w, B, S, sh):
+def bf_decoder_layer(h, w, B, S, sh, rnd=ident):
     d, f = sh.d_model, sh.d_ffn
     nq, nk = sh.n_q_heads * sh.head_dim, sh.n_kv_heads * sh.head_dim
-    a = bf_rmsnorm(h, w["g1"], sh.norm_eps)
-    qkv = bf_linear(a, w["wqkv"])
+    a = rows(rnd, bf_rmsnorm(h, w["g1"], sh.norm_eps))
+    qkv = rows(rnd, bf_linear(a, w["wqkv"]))
     q = [r[:nq] for r in qkv]
     k = [r[nq:nq + nk] for r in qkv]
     v = [r[nq + nk:] for r in qkv]
-    o = bf_attention(q, k, v, B, S, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.causal)
+    o = rows(rnd, bf_attention(q, k, v, B, S, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.causal, rnd))
     ow = bf_linear(o, w["wo"])
     h1 = [[h[t][i] + ow[t][i] for i in range(d)] for t in range(len(h))]
-    m = bf_rmsnorm(h1, w["g2"], sh.norm_eps)
+    m = rows(rnd, bf_rmsnorm(h1, w["g2"], sh.norm_eps))
     gu = bf_linear(m, w["wgu"])
-    z = [[(r[j] / (1.0 + math.exp(-r[j]))) * r[f + j] for j in range(f)] for r in gu]
+    z = [[rnd((r[j] / (1.0 + math.exp(-r[j]))) * r[f + j]) for j in range(f)] for r in gu]
     zw = bf_linear(z, w["wd"])
     return [[h1[t][i] + zw[t][i] for i in range(d)] for t in range(len(h))]
 
 
-def bf_encoder_layer(h, w, B, S, sh):
+def bf_encoder_layer(h, w, B, S, sh, rnd=ident):
     d = sh.d_model
     nq, nk = sh.n_q_heads * sh.head_dim, sh.n_kv_heads * sh.head_dim
-    a = bf_layernorm(h, w["ln1_g"], w["ln1_b"], sh.norm_eps)
-    qkv = bf_linear(a, w["wqkv"], w["bqkv"])
+    a = rows(rnd, bf_layernorm(h, w["ln1_g"], w["ln1_b"], sh.norm_eps))
+    qkv = rows(rnd, bf_linear(a, w["wqkv"], w["bqkv"]))
     q = [r[:nq] for r in qkv]
     k = [r[nq:nq + nk] for r in qkv]
     v = [r[nq + nk:] for r in qkv]
-    o = bf_attention(q, k, v, B, S, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, False)
+    o = rows(rnd, bf_attention(q, k, v, B, S, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, False, rnd))
     ow = bf_linear(o, w["wo"], w["bo"])
     h1 = [[h[t][i] + ow[t][i] for i in range(d)] for t in range(len(h))]
-    m = bf_layernorm(h1, w["ln2_g"], w["ln2_b"], sh.norm_eps)
+    m = rows(rnd, bf_layernorm(h1, w["ln2_g"], w["ln2_b"], sh.norm_eps))
     u = bf_linear(m, w["w1"], w["b1"])
-    z = [[0.5 * x * (1.0 + math.erf(x / math.sqrt(2.0))) for x in r] for r in u]
+    z = [[rnd(0.5 * x * (1.0 + math.erf(x / math.sqrt(2.0)))) for x in r] for r in u]
     zw = bf_linear(z, w["w2"], w["b2"])
     return [[h1[t][i] + zw[t][i] for i in range(d)] for t in range(len(h))]
 
@@ -225,7 +243,47 @@ def test_attention_special_cases():
     np.testing.assert_allclose(og, om, rtol=1e-14)
 
 
+def test_round_bf16_known_patterns():
+    """Nearest bfloat16, ties to even: values worked out by hand (spacing 2^-7 at 1.0)."""
+    cases = [(1.0, 1.0), (1.0 + 2.0 ** -8, 1.0),                      # tie, lower neighbour even
+             (1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -6),                  # tie, upper neighbour even
+             (1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 2.0 ** -7),         # just above the tie
+             (1.0 + 2.0 ** -8 - 2.0 ** -20, 1.0),                     # just below
+             (-(1.0 + 3 * 2.0 ** -8), -(1.0 + 2.0 ** -6)), (0.0, 0.0),
+             (0.1, 0.10009765625),                                    # 0x3DCD: 205 * 2^-11
+             (3.0e38, 226 * 2.0 ** 120),                              # spacing 2^120 there: 225.7 -> 226
+             (2.0 ** -130, 2.0 ** -130)]                              # a denormal with a bf16 pattern
+    x = np.array([c[0] for c in cases])
+    assert O.round_bf16(x).tolist() == [c[1] for c in cases]
+    assert O.round_bf16(x.astype(np.float32)).dtype == np.float32
+    assert [bf_round(c[0]) for c in cases] == [c[1] for c in cases]   # the scalar stand-in used below
+    r = RNG.standard_normal(4096) * np.exp(RNG.uniform(-20, 20, 4096))
+    q = O.round_bf16(r)
+    assert np.array_equal(O.round_bf16(q), q)                          # idempotent
+    assert np.all(np.abs(q - r) <= 2.0 ** -8 * np.abs(r) * (1 + 1e-6))  # half a step of 2^-7 at the bottom of a binade
+    assert np.all((q.astype(np.float32).view(np.uint32) & 0xFFFF) == 0)
+
+
 # ------------------------------------------------------------------ whole layer / stack
+@pytest.mark.parametrize("arch", [O.DECODER, O.ENCODER])
+def test_layer_with_bf16_operands_vs_scalar_composition(arch):
+    """operands="bf16": the scalar-loop layer with the scalar rounding at the six operand points
+    (normed activations twice, q/k/v, attention weights, attention output, activation output)."""
+    B, S = 2, 4
+    sh = small_shape(arch, causal=(arch == O.DECODER))
+    w = rand_layer(sh)
+    h = RNG.standard_normal((B * S, sh.d_model))
+    got = O.layer_forward(h, w, B, S, sh, operands="bf16")
+    bf = bf_decoder_layer if arch == O.DECODER else bf_encoder_layer
+    want = bf(h.tolist(), tolist(w), B, S, sh, rnd=bf_round)
+    np.testing.assert_allclose(got, want, rtol=1e-11, atol=1e-13)
+    plain = O.layer_forward(h, w, B, S, sh)
+    dev = np.max(np.abs(got - plain)) / np.max(np.abs(plain - h))
+    assert 1e-5 < dev < 2e-2, dev            # it does round, and by about what six roundings of 2^-9 give
+    st = O.stack_forward(h, [w, w], B, S, sh, dtype=np.float64, operands="bf16")
+    np.testing.assert_array_equal(st, O.layer_forward(got, w, B, S, sh, operands="bf16"))
+
+
 @pytest.mark.parametrize("arch", [O.DECODER, O.ENCODER])
 def test_layer_vs_scalar_composition(arch):
     B, S = 2, 4
