@@ -345,12 +345,15 @@ def measure(args, name, steps, warmup, ceiling, headline, blob_cache):
     extra = {
         "peak_hbm_bytes": int(st.plan.arena_bytes_used), "budget_bytes": int(main_run["budget"]),
         # seen from outside the library over the timed run: torch's peak of newly allocated device
-        # bytes (the arena of budget_bytes + one 4 KiB alignment page; the library itself allocates
-        # nothing) and the drop of the driver's free-memory figure (torch's allocator rounds up and
-        # may reuse cached blocks, so this one only bounds it)
+        # bytes -- one block, the arena of budget_bytes + a 4 KiB alignment page, which torch's
+        # allocator rounds up to a multiple of 2 MiB; the library itself allocates nothing -- and
+        # the drop of the driver's free-memory figure (0 when the allocator re-used a cached block
+        # of an earlier run, so this one only bounds it)
         "hbm_cross_check": {"torch_max_memory_allocated_delta": main_run["torch_peak_bytes"],
                             "driver_free_memory_drop": main_run["driver_free_drop_bytes"],
-                            "within_budget_plus_page": bool(main_run["torch_peak_bytes"] <= main_run["budget"] + 4096)},
+                            "arena_block_rounded_to_2MiB": int(-(-(main_run["budget"] + 4096) // (2 << 20)) * (2 << 20)),
+                            "only_the_arena_was_allocated": bool(
+                                main_run["torch_peak_bytes"] <= -(-(main_run["budget"] + 4096) // (2 << 20)) * (2 << 20))},
         "h2d_gbps_over_wall": round(h2d_gbps_wall, 2),
         "h2d_gbps_while_copying": round(h2d_gbps_busy, 2) if h2d_gbps_busy else None,
         "h2d_ceiling_gbps": round(ceiling, 2),
