@@ -8,7 +8,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 from oracle import stack_oracle as O  # noqa: E402
 from paper_2410_08791_amd import binding as sp  # noqa: E402
-from tests.gpu_util import (DEV, bf16_vals, dev_f32, dev_u16, host_u16, max_rel, ptr, rand_bf16,  # noqa: E402
+from tests.gpu_util import (DEV, bf16_vals, dev_f32, dev_u16, host_u16, ptr, rand_bf16,  # noqa: E402
                             stream_ptr)
 
 BF16_EPS = 2.0 ** -8     # half an ulp of bf16, relative
