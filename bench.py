@@ -423,6 +423,28 @@ def measure(args, name, steps, warmup, ceiling, headline, blob_cache):
                     "sp_wait_gradient(l), then sp_weights_updated(l)"}
         log(f"[bench] training loop with host updates: {json.dumps(extra['host_update_loop'])}")
 
+    # The timed run's own output against the oracle's stored run of the WHOLE stack at the full
+    # token count (tests/golden/, written by a script that calls only oracle/): sampled rows of y
+    # (of dx for a training step), at no extra cost.  Beside it, what the stored run says bf16
+    # operand rounding alone does to the oracle's own output on the same rows and over all elements.
+    gpath = os.path.join(ROOT, "tests", "golden", f"full_depth_{w.name}.npz")
+    if os.path.exists(gpath) and not decoding and not frozen and not (headline and args.layers):
+        with np.load(gpath) as g:
+            if int(g["distinct"]) == nb:
+                rows = g["rows"]
+                got = main_run["y"].reshape(w.tokens, -1)[rows].astype(np.float64)
+                ref = (g["dx_rows"] if training else g["y_rows"]).astype(np.float64)
+                rmax = float(g["dx_absmax"] if training else g["y_absmax"])
+                fd = {"compared": "dx" if training else "y", "rows": int(len(rows)), "layers": int(w.n_layers),
+                      "tokens": int(w.tokens), "max_rel_err": float(np.abs(got - ref).max() / rmax),
+                      "source": os.path.relpath(gpath, ROOT)}
+                if "ops_dev_rows" in g.files:
+                    fd["oracle_with_bf16_operands_vs_oracle"] = {
+                        "same_rows_of_y": float(g["ops_dev_rows"]), "all_elements_of_y": float(g["ops_dev_all"]),
+                        "frobenius": float(g["ops_dev_fro"])}
+                extra["parity_full_depth"] = fd
+                log(f"[bench] {w.name}: whole stack against the stored oracle run on {len(rows)} rows: {fd['max_rel_err']:.3e}")
+
     # window sweep at the same budget (+ the naive comparator); bits must not change
     if headline and not args.no_sweep:
         sweep = []
@@ -568,7 +590,7 @@ def measure(args, name, steps, warmup, ceiling, headline, blob_cache):
 OTHER_KEYS = ("ms_per_step", "value", "unit", "steps", "config", "roofline", "peak_hbm_bytes", "budget_bytes", "hbm_cross_check",
               "h2d_gbps_over_wall", "h2d_frac_of_ceiling", "d2h_gbps_over_wall", "copy_hidden_frac",
               "copy_hidden_frac_bound", "overlap_efficiency", "copy_stream_idle_frac", "images_per_s", "ms_per_token",
-              "host_update_loop", "op_table", "op_table_kernel_ms_per_step", "parity_sample", "parity_max_rel_err", "parity_err_over_added", "cpu_baseline")
+              "host_update_loop", "op_table", "op_table_kernel_ms_per_step", "parity_sample", "parity_max_rel_err", "parity_err_over_added", "parity_full_depth", "cpu_baseline")
 
 
 def main():
